@@ -1,0 +1,149 @@
+/*
+ * libals_gfx950 -- C ABI of the MI355X alternating-least-squares hot path.
+ *
+ * The library factorises a sparse rating matrix R (m x n, N_z stored entries)
+ * as R ~ X * Theta^T with X (m x f) and Theta (n x f), by the per-row
+ * normal-equation build and solve of the paper's Section 2:
+ *
+ *     A_u = sum_{v in Omega_u} theta_v theta_v^T + lambda * n_u * I      (get_hermitian, eq. (2))
+ *     b_u = sum_{v in Omega_u} r_uv theta_v                              (get_bias,      eq. (2))
+ *     x_u = A_u^-1 b_u                                                    (solve)
+ *
+ * for every row u (als_update_rows) and, with the roles of X and Theta
+ * swapped and the CSC of R in place of its CSR, for every column v
+ * (als_update_cols, eq. (3)).  Omega_u is the set of STORED entries of row u
+ * (a stored value 0 is an observation), n_u its size.
+ *
+ * Conventions that hold for every entry point
+ *   - "DEVICE" pointers are HIP device memory on the context's GPU, owned by
+ *     the caller, never freed or reallocated by the library.  "HOST" pointers
+ *     are ordinary host memory.
+ *   - Factor matrices are dense, row-major, f contiguous floats per row, the
+ *     base pointer 16-byte aligned.
+ *   - Sparse matrices are compressed rows: ptr has nrows+1 entries (int32 or
+ *     int64, see ptr_is_64), idx holds 0-based int32 column ids ascending and
+ *     duplicate-free inside a row, val the float ratings.
+ *   - Work is enqueued on the stream given at als_create and the call returns
+ *     without waiting, unless stated otherwise.
+ *   - Return value: ALS_OK (0) or a negative ALS_E* code; als_last_error gives
+ *     the text.  Nothing is printed, nothing aborts.
+ */
+#ifndef ALS_GFX950_H
+#define ALS_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ALS_OK 0
+#define ALS_EINVAL (-1)   /* bad argument: null pointer, unsupported f, negative lambda, inconsistent sizes */
+#define ALS_EHIP (-2)     /* a HIP runtime call failed (text in als_last_error)                              */
+#define ALS_ENUMERIC (-3) /* a kernel met a non-positive pivot or a non-finite value                         */
+#define ALS_ENOMEM (-4)   /* device or host allocation failed                                                */
+
+#define ALS_SOLVER_CHOLESKY 0 /* exact solve (the paper's LU baseline of Section 4.1; A_u is SPD)            */
+#define ALS_SOLVER_CG 1       /* Algorithm 1: cg_iters iterations warm-started from the current x_u          */
+
+#define ALS_F32 0
+#define ALS_BF16 1
+#define ALS_F16 2
+
+typedef struct als_ctx als_ctx; /* opaque; one per (device, stream); not thread-safe */
+
+/* A sparse matrix in compressed-row form, all arrays DEVICE memory.
+ * For als_update_cols pass the CSC of R as the compressed rows of R^T
+ * (nrows = n, ncols = m). */
+typedef struct als_sparse {
+    int64_t nrows, ncols, nnz;
+    const void *ptr;    /* nrows+1 offsets, int32 if ptr_is_64 == 0 else int64          */
+    int32_t ptr_is_64;
+    const int32_t *idx; /* nnz column ids                                              */
+    const float *val;   /* nnz ratings                                                 */
+} als_sparse;
+
+typedef struct als_config {
+    int32_t f;            /* number of latent features; supported: 16, 32, 64, 100, 128                 */
+    int32_t solver;       /* ALS_SOLVER_*                                                                */
+    int32_t cg_iters;     /* f_s of Algorithm 1 (used when solver == ALS_SOLVER_CG)                      */
+    float cg_eps;         /* epsilon of Algorithm 1: stop when sqrt(r^T r) < cg_eps; 0 = fixed f_s steps */
+    int32_t factor_dtype; /* ALS_F32: dtype of the factor matrix that is gathered                        */
+    int32_t herm_dtype;   /* ALS_F32: storage type of A_u where it is materialised (Section 4.2)         */
+    int32_t device;       /* HIP device ordinal                                                          */
+    void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */
+    int32_t chunk;        /* stored entries per work item; longer rows are split (0 = default 1024)      */
+    int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = default 32768)           */
+    int32_t profile;      /* 1: bracket every kernel with HIP events (see als_kernel_time)               */
+} als_config;
+
+/* Creates a context.  Allocates small bookkeeping only; work buffers are
+ * allocated with hipMalloc on first use and kept until als_destroy. */
+int als_create(als_ctx **out, const als_config *cfg);
+
+/* Frees everything the context allocated (waits for its stream first). NULL is allowed. */
+void als_destroy(als_ctx *ctx);
+
+/* Text of the last error recorded on this context ("" if none). Valid until the next call. */
+const char *als_last_error(const als_ctx *ctx);
+
+/* "Update X" (eq. (2)): for every row u of csr, builds A_u, b_u from Theta
+ * (DEVICE, ncols x f, config's factor_dtype) and writes x_u into X (DEVICE,
+ * nrows x f float).  With ALS_SOLVER_CG, X is also an input: row u of X is the
+ * warm start of Algorithm 1.  Rows with n_u = 0 get x_u = 0.  f must equal the
+ * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD). */
+int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X);
+
+/* "Update Theta" (eq. (3)): the same computation with csc = compressed columns
+ * of R (as compressed rows of R^T), X (DEVICE, m x f) gathered and Theta
+ * (DEVICE, n x f float) written (and warm start for CG). */
+int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, int f, float *Theta);
+
+/* Training RMSE over the stored entries, sqrt( sum (r_uv - x_u^T theta_v)^2 / N_z )
+ * (the metric of Section 5.2 applied to the set given).  X, Theta: DEVICE float.
+ * rmse_out: HOST double.  Blocks until the result is available. */
+int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out);
+
+/* get_hermitian / get_bias alone (Section 2, step (i)) for rows [row0, row0+nrows):
+ * A_out (DEVICE, nrows x f x f floats, full symmetric, lambda*n_u on the diagonal
+ * included) and b_out (DEVICE, nrows x f).  Meant for tests and breakdown runs. */
+int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f,
+                  int64_t row0, int64_t nrows, float *A_out, float *b_out);
+
+/* Load-balancing permutation (not in the paper, which maps one block per row):
+ * rows grouped by degree class, class(n_u) = 0 if n_u = 0 else
+ * min(1 + floor(log2 n_u), nclass-1); heaviest class first, original row order
+ * kept inside a class.  perm_out: DEVICE int32[nrows]; class_start_out: HOST
+ * int64[nclass+1] (rows of class c are perm[class_start[nclass-1-c] ..
+ * class_start[nclass-c])).  Blocks until done. */
+int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_out, int64_t *class_start_out);
+
+/* Compressed columns of R from its compressed rows (the CSC used by
+ * als_update_cols), rows ascending inside every column.  cptr_out: DEVICE,
+ * ncols+1 offsets of the same width as csr->ptr; cidx_out / cval_out: DEVICE,
+ * nnz entries.  Requires nnz < 2^31. */
+int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out);
+
+/* Waits for the stream and reports ALS_ENUMERIC if any kernel since the last
+ * call flagged a non-positive pivot or a non-finite value. */
+int als_synchronize(als_ctx *ctx);
+
+/* Kernel ids for als_kernel_time */
+#define ALS_K_HERMITIAN 0
+#define ALS_K_SOLVE 1
+#define ALS_K_RMSE 2
+#define ALS_K_PLAN 3
+#define ALS_K_COUNT 4
+
+/* With config.profile = 1: total milliseconds and number of launches of one
+ * kernel class since the last als_profile_reset, measured with HIP events on
+ * the context's stream.  Blocks until the recorded events have completed.
+ * ms_out / launches_out: HOST. */
+int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launches_out);
+int als_profile_reset(als_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALS_GFX950_H */

@@ -16,7 +16,20 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "als_oracle.c")
-_LIB = os.path.join(_HERE, "libals_oracle.so")
+
+
+def _cpu_tag() -> str:
+    """-march=native output only runs on a CPU with the same features: key the file name on them."""
+    import hashlib
+    try:
+        with open("/proc/cpuinfo") as fh:
+            flags = next((ln for ln in fh if ln.startswith("flags")), "")
+    except OSError:
+        flags = ""
+    return hashlib.sha1(flags.encode()).hexdigest()[:10]
+
+
+_LIB = os.path.join(_HERE, f"libals_oracle_{_cpu_tag()}.so")
 
 
 def build(force: bool = True) -> str:

@@ -1,0 +1,188 @@
+"""ctypes binding of libals_gfx950 (declared in include/als.h).
+
+Argument marshalling only: every step of the ALS path runs in the library's HIP
+kernels.  torch is used for device memory and the stream.  There is no CPU
+fallback: loading fails loudly when the built library is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
+SOLVER_CHOLESKY, SOLVER_CG = 0, 1
+F32, BF16, F16 = 0, 1, 2
+K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN = 0, 1, 2, 3
+
+EXPORTS = [
+    "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
+    "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
+    "als_profile_reset",
+]
+
+
+class AlsSparse(ctypes.Structure):
+    _fields_ = [("nrows", ctypes.c_int64), ("ncols", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("ptr", ctypes.c_void_p), ("ptr_is_64", ctypes.c_int32),
+                ("idx", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+class AlsConfig(ctypes.Structure):
+    _fields_ = [("f", ctypes.c_int32), ("solver", ctypes.c_int32), ("cg_iters", ctypes.c_int32),
+                ("cg_eps", ctypes.c_float), ("factor_dtype", ctypes.c_int32), ("herm_dtype", ctypes.c_int32),
+                ("device", ctypes.c_int32), ("stream", ctypes.c_void_p), ("chunk", ctypes.c_int32),
+                ("batch_slots", ctypes.c_int64), ("profile", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the in-tree library, building it first only if it was never built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, fl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    sp = ctypes.POINTER(AlsSparse)
+    lib.als_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(AlsConfig)]
+    lib.als_destroy.argtypes = [vp]
+    lib.als_destroy.restype = None
+    lib.als_last_error.argtypes = [vp]
+    lib.als_last_error.restype = ctypes.c_char_p
+    lib.als_update_rows.argtypes = [vp, sp, vp, fl, ctypes.c_int, vp]
+    lib.als_update_cols.argtypes = [vp, sp, vp, fl, ctypes.c_int, vp]
+    lib.als_rmse.argtypes = [vp, sp, vp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    lib.als_hermitian.argtypes = [vp, sp, vp, fl, ctypes.c_int, i64, i64, vp, vp]
+    lib.als_bin_rows.argtypes = [vp, sp, ctypes.c_int, vp, ctypes.POINTER(i64)]
+    lib.als_csr_to_csc.argtypes = [vp, sp, vp, vp, vp]
+    lib.als_synchronize.argtypes = [vp]
+    lib.als_kernel_time.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.als_profile_reset.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+class AlsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libals_gfx950 error {code}: {text}")
+        self.code = code
+
+
+class SparseMatrix:
+    """Device-resident compressed rows (torch tensors own the memory)."""
+
+    def __init__(self, nrows: int, ncols: int, ptr: torch.Tensor, idx: torch.Tensor, val: torch.Tensor):
+        assert ptr.is_cuda and idx.is_cuda and val.is_cuda
+        assert ptr.dtype in (torch.int32, torch.int64) and idx.dtype == torch.int32 and val.dtype == torch.float32
+        assert ptr.numel() == nrows + 1 and idx.numel() == val.numel()
+        self.nrows, self.ncols = int(nrows), int(ncols)
+        self.ptr, self.idx, self.val = ptr.contiguous(), idx.contiguous(), val.contiguous()
+        self.nnz = int(idx.numel())
+        self.desc = AlsSparse(self.nrows, self.ncols, self.nnz, self.ptr.data_ptr(),
+                              1 if ptr.dtype == torch.int64 else 0, self.idx.data_ptr(), self.val.data_ptr())
+
+    @staticmethod
+    def from_host(nrows, ncols, ptr, idx, val, device="cuda:0", ptr64: Optional[bool] = None) -> "SparseMatrix":
+        import numpy as np
+        nnz = int(ptr[-1])
+        if ptr64 is None:
+            ptr64 = nnz >= 2 ** 31
+        p = torch.from_numpy(np.ascontiguousarray(ptr, dtype=np.int64 if ptr64 else np.int32)).to(device)
+        i = torch.from_numpy(np.ascontiguousarray(idx, dtype=np.int32)).to(device)
+        v = torch.from_numpy(np.ascontiguousarray(val, dtype=np.float32)).to(device)
+        return SparseMatrix(nrows, ncols, p, i, v)
+
+
+class Als:
+    """One library context (als_create .. als_destroy) bound to a device and a stream."""
+
+    def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
+                 device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
+                 profile: bool = False):
+        self._lib = load_library()
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, F32, F32, device, stream, chunk, batch_slots,
+                             1 if profile else 0)
+        self._ctx = ctypes.c_void_p()
+        rc = self._lib.als_create(ctypes.byref(self._ctx), ctypes.byref(self.cfg))
+        if rc != ALS_OK:
+            self._ctx = ctypes.c_void_p()
+            raise AlsError(rc, "als_create failed (unsupported f / solver / dtype, or no such device)")
+        self.f = f
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx:
+            self._lib.als_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != ALS_OK:
+            raise AlsError(rc, self._lib.als_last_error(self._ctx).decode())
+
+    @staticmethod
+    def _factor(t: torch.Tensor, rows: int, f: int):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == (rows, f)
+        return t.data_ptr()
+
+    def update_rows(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, X: torch.Tensor):
+        self._check(self._lib.als_update_rows(self._ctx, ctypes.byref(csr.desc), self._factor(Theta, csr.ncols, self.f),
+                                              lam, self.f, self._factor(X, csr.nrows, self.f)))
+
+    def update_cols(self, csc: SparseMatrix, X: torch.Tensor, lam: float, Theta: torch.Tensor):
+        self._check(self._lib.als_update_cols(self._ctx, ctypes.byref(csc.desc), self._factor(X, csc.ncols, self.f),
+                                              lam, self.f, self._factor(Theta, csc.nrows, self.f)))
+
+    def rmse(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor) -> float:
+        out = ctypes.c_double()
+        self._check(self._lib.als_rmse(self._ctx, ctypes.byref(csr.desc), self._factor(X, csr.nrows, self.f),
+                                       self._factor(Theta, csr.ncols, self.f), self.f, ctypes.byref(out)))
+        return out.value
+
+    def hermitian(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, row0: int, nrows: int):
+        A = torch.empty((nrows, self.f, self.f), dtype=torch.float32, device=Theta.device)
+        b = torch.empty((nrows, self.f), dtype=torch.float32, device=Theta.device)
+        self._check(self._lib.als_hermitian(self._ctx, ctypes.byref(csr.desc), self._factor(Theta, csr.ncols, self.f),
+                                            lam, self.f, row0, nrows, A.data_ptr(), b.data_ptr()))
+        return A, b
+
+    def bin_rows(self, csr: SparseMatrix, nclass: int):
+        perm = torch.empty(csr.nrows, dtype=torch.int32, device=csr.idx.device)
+        start = (ctypes.c_int64 * (nclass + 1))()
+        self._check(self._lib.als_bin_rows(self._ctx, ctypes.byref(csr.desc), nclass, perm.data_ptr(), start))
+        return perm, list(start)
+
+    def csr_to_csc(self, csr: SparseMatrix) -> SparseMatrix:
+        dev = csr.idx.device
+        cptr = torch.empty(csr.ncols + 1, dtype=csr.ptr.dtype, device=dev)
+        cidx = torch.empty(csr.nnz, dtype=torch.int32, device=dev)
+        cval = torch.empty(csr.nnz, dtype=torch.float32, device=dev)
+        self._check(self._lib.als_csr_to_csc(self._ctx, ctypes.byref(csr.desc), cptr.data_ptr(), cidx.data_ptr(),
+                                             cval.data_ptr()))
+        return SparseMatrix(csr.ncols, csr.nrows, cptr, cidx, cval)
+
+    def synchronize(self):
+        self._check(self._lib.als_synchronize(self._ctx))
+
+    def kernel_time(self, kernel_id: int):
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        self._check(self._lib.als_kernel_time(self._ctx, kernel_id, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    def profile_reset(self):
+        self._check(self._lib.als_profile_reset(self._ctx))

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libals_gfx950.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/als.h"
+
+namespace als {
+
+// ---- geometry of one work item's output ("slot") --------------------------------------------
+// A_u is accumulated as 16x16 tiles of the lower triangle (tile row R >= tile column C) in the
+// register layout of v_mfma_f32_16x16x4_f32: lane l, register r of a tile holds the element
+// (row 4*(l/16)+r, column l%16).  A slot stores tile t = R(R+1)/2+C at float offset
+// (4t+r)*64 + l, followed by b_u padded to 16*NT floats.
+constexpr int tiles_1d(int F) { return (F + 15) / 16; }
+constexpr int tiles_tri(int F) { return tiles_1d(F) * (tiles_1d(F) + 1) / 2; }
+constexpr int slot_floats(int F) { return tiles_tri(F) * 256 + tiles_1d(F) * 16; }
+
+constexpr int kWave = 64;
+
+struct Plan {                     // per sparse matrix, built once and cached
+    const void *key_ptr = nullptr;
+    int64_t nrows = 0, nnz = 0;
+    int chunk = 0;
+    int32_t *perm = nullptr;      // DEVICE [nrows] rows grouped by degree class, heaviest first
+    int32_t *task_off = nullptr;  // DEVICE [nrows+1] first work item of the row at each perm position
+    int32_t *task_row = nullptr;  // DEVICE [ntasks]
+    int32_t *task_chunk = nullptr;// DEVICE [ntasks]
+    int32_t *task_off_host = nullptr; // HOST copy of task_off
+    int64_t ntasks = 0;
+};
+
+// status word bits set by kernels
+constexpr int kStatusBadPivot = 1;
+constexpr int kStatusNonFinite = 2;
+
+// ---- launchers (each defined next to its kernels) --------------------------------------------
+hipError_t launch_hermitian(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+                            int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
+                            const float *val, const float *Theta, float *slots);
+
+hipError_t launch_solve(int f, int solver, int cg_iters, float cg_eps, bool ptr64, hipStream_t st,
+                        const int32_t *perm, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
+                        const void *ptr, const float *slots, float lambda, float *Xout, int *status);
+
+hipError_t launch_export_dense(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                               int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                               float lambda, int64_t row0, float *A_out, float *b_out);
+
+hipError_t launch_sse(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+                      int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
+                      const float *X, const float *Theta, double *partial, double *total);
+
+// plan.hip
+hipError_t plan_bin_rows(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, int nclass, int32_t *perm,
+                         int32_t *class_start_dev /*nclass+1*/, void **scratch, size_t *scratch_bytes);
+hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
+                      int32_t *task_off /*nrows+1*/, void **scratch, size_t *scratch_bytes);
+hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
+                     const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
+hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
+
+// transpose.hip
+hipError_t transpose_csr(bool ptr64, hipStream_t st, int64_t nrows, int64_t ncols, int64_t nnz, const void *ptr,
+                         const int32_t *idx, const float *val, void *cptr, int32_t *cidx, float *cval);
+
+inline bool supported_f(int f) { return f == 16 || f == 32 || f == 64 || f == 100 || f == 128; }
+
+}  // namespace als

@@ -1,0 +1,410 @@
+// C ABI of libals_gfx950 (see include/als.h): argument checks, the cached per-matrix plan, the
+// batch loop of an update half-sweep, error bookkeeping.  No arithmetic of the method lives here.
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "als_internal.h"
+
+using namespace als;
+
+namespace {
+constexpr int kPlanClasses = 24;
+constexpr int kMaxPlans = 4;
+
+struct TimedLaunch { hipEvent_t a, b; int kernel; };
+}  // namespace
+
+struct als_ctx {
+    als_config cfg;
+    hipStream_t stream = nullptr;
+    std::string err;
+    Plan plans[kMaxPlans];
+    int next_plan = 0;
+    float *slots = nullptr;
+    size_t slots_bytes = 0;
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+    int *status = nullptr;       // DEVICE status word
+    double *sse_partial = nullptr;
+    size_t sse_partial_bytes = 0;
+    double *sse_total = nullptr; // DEVICE
+    std::vector<TimedLaunch> timed;
+    std::vector<hipEvent_t> free_events;
+};
+
+namespace {
+
+int fail(als_ctx *ctx, int code, const std::string &msg) {
+    if (ctx) ctx->err = msg;
+    return code;
+}
+int fail_hip(als_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, e == hipErrorOutOfMemory ? ALS_ENOMEM : ALS_EHIP,
+                std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(ctx, expr)                                   \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return fail_hip(ctx, e_, #expr); \
+    } while (0)
+
+void free_plan(Plan &p) {
+    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk);
+    delete[] p.task_off_host;
+    p = Plan();
+}
+
+int check_sparse(als_ctx *ctx, const als_sparse *a) {
+    if (!a) return fail(ctx, ALS_EINVAL, "sparse matrix descriptor is null");
+    if (a->nrows < 0 || a->ncols < 0 || a->nnz < 0) return fail(ctx, ALS_EINVAL, "negative matrix size");
+    if (a->nrows > 0x7fffffff || a->ncols > 0x7fffffff) return fail(ctx, ALS_EINVAL, "more than 2^31-1 rows or columns");
+    if (!a->ptr) return fail(ctx, ALS_EINVAL, "ptr is null");
+    if (a->nnz > 0 && (!a->idx || !a->val)) return fail(ctx, ALS_EINVAL, "idx or val is null");
+    if (!a->ptr_is_64 && a->nnz > 0x7fffffff) return fail(ctx, ALS_EINVAL, "nnz >= 2^31 needs 64-bit ptr");
+    return ALS_OK;
+}
+
+hipEvent_t get_event(als_ctx *ctx) {
+    if (!ctx->free_events.empty()) {
+        hipEvent_t e = ctx->free_events.back();
+        ctx->free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct Timed {   // brackets one launch with events when profiling is on
+    als_ctx *ctx; int kernel; hipEvent_t a = nullptr, b = nullptr;
+    Timed(als_ctx *c, int k) : ctx(c), kernel(k) {
+        if (ctx->cfg.profile) {
+            a = get_event(ctx); b = get_event(ctx);
+            if (a && b) hipEventRecord(a, ctx->stream);
+        }
+    }
+    ~Timed() {
+        if (a && b) {
+            hipEventRecord(b, ctx->stream);
+            ctx->timed.push_back({a, b, kernel});
+        }
+    }
+};
+
+// Finds or builds the plan of a matrix: degree-class permutation, work items.
+int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
+    for (auto &p : ctx->plans)
+        if (p.key_ptr == a->ptr && p.nrows == a->nrows && p.nnz == a->nnz && p.chunk == ctx->cfg.chunk) {
+            *out = &p;
+            return ALS_OK;
+        }
+    Plan &p = ctx->plans[ctx->next_plan];
+    ctx->next_plan = (ctx->next_plan + 1) % kMaxPlans;
+    if (p.key_ptr) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        free_plan(p);
+    }
+    Timed timed(ctx, ALS_K_PLAN);
+    const int64_t m = a->nrows;
+    const bool p64 = a->ptr_is_64 != 0;
+    HIP_TRY(ctx, hipMalloc(&p.perm, sizeof(int32_t) * (size_t)(m > 0 ? m : 1)));
+    HIP_TRY(ctx, hipMalloc(&p.task_off, sizeof(int32_t) * (size_t)(m + 1)));
+    HIP_TRY(ctx, plan_bin_rows(p64, ctx->stream, m, a->ptr, kPlanClasses, p.perm, nullptr, &ctx->scratch,
+                               &ctx->scratch_bytes));
+    HIP_TRY(ctx, plan_tasks(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, &ctx->scratch,
+                            &ctx->scratch_bytes));
+    p.task_off_host = new (std::nothrow) int32_t[(size_t)m + 1];
+    if (!p.task_off_host) { free_plan(p); return fail(ctx, ALS_ENOMEM, "host allocation of the work-item offsets failed"); }
+    HIP_TRY(ctx, hipMemcpyAsync(p.task_off_host, p.task_off, sizeof(int32_t) * (size_t)(m + 1), hipMemcpyDeviceToHost,
+                                ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    p.ntasks = p.task_off_host[m];
+    HIP_TRY(ctx, hipMalloc(&p.task_row, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
+    HIP_TRY(ctx, hipMalloc(&p.task_chunk, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
+    HIP_TRY(ctx, plan_emit(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, p.task_row, p.task_chunk));
+    p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz; p.chunk = ctx->cfg.chunk;
+    *out = &p;
+    return ALS_OK;
+}
+
+int ensure_slots(als_ctx *ctx, int64_t nslots) {
+    const size_t need = (size_t)nslots * slot_floats(ctx->cfg.f) * sizeof(float);
+    if (ctx->slots_bytes >= need) return ALS_OK;
+    if (ctx->slots) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        HIP_TRY(ctx, hipFree(ctx->slots));
+        ctx->slots = nullptr; ctx->slots_bytes = 0;
+    }
+    HIP_TRY(ctx, hipMalloc(&ctx->slots, need));
+    ctx->slots_bytes = need;
+    return ALS_OK;
+}
+
+// One half-sweep: rows of `a` updated from the gathered factor `G` into `Out`.
+int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f, float *Out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, a);
+    if (rc != ALS_OK) return rc;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (!(lambda >= 0.f)) return fail(ctx, ALS_EINVAL, "lambda must be >= 0");
+    if (!Out || (a->nnz > 0 && !G)) return fail(ctx, ALS_EINVAL, "factor pointer is null");
+    if (a->nrows == 0) return ALS_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    Plan *p = nullptr;
+    rc = get_plan(ctx, a, &p);
+    if (rc != ALS_OK) return rc;
+    const int64_t cap = ctx->cfg.batch_slots;
+    const bool p64 = a->ptr_is_64 != 0;
+    const int32_t *off = p->task_off_host;
+    int64_t pos = 0;
+    const int64_t m = a->nrows;
+    // widest row decides the minimum number of slots
+    while (pos < m) {
+        // rows [pos, end): as many as fit in `cap` slots, at least one row
+        int64_t end = pos + 1;
+        {
+            int64_t lo = pos + 1, hi = m;   // largest end with off[end]-off[pos] <= cap
+            while (lo < hi) {
+                const int64_t mid = (lo + hi + 1) >> 1;
+                if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
+            }
+            end = lo;
+        }
+        const int64_t task0 = off[pos], ntasks = (int64_t)off[end] - off[pos];
+        rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1);
+        if (rc != ALS_OK) return rc;
+        {
+            Timed t(ctx, ALS_K_HERMITIAN);
+            HIP_TRY(ctx, launch_hermitian(f, p64, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
+                                          ctx->cfg.chunk, a->ptr, a->idx, a->val, (const float *)G, ctx->slots));
+        }
+        {
+            Timed t(ctx, ALS_K_SOLVE);
+            HIP_TRY(ctx, launch_solve(f, ctx->cfg.solver, ctx->cfg.cg_iters, ctx->cfg.cg_eps, p64, ctx->stream,
+                                      p->perm, p->task_off, pos, end - pos, task0, a->ptr, ctx->slots, lambda, Out,
+                                      ctx->status));
+        }
+        pos = end;
+    }
+    return ALS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int als_create(als_ctx **out, const als_config *cfg) {
+    if (!out || !cfg) return ALS_EINVAL;
+    *out = nullptr;
+    if (!supported_f(cfg->f)) return ALS_EINVAL;
+    if (cfg->solver != ALS_SOLVER_CHOLESKY && cfg->solver != ALS_SOLVER_CG) return ALS_EINVAL;
+    if (cfg->solver == ALS_SOLVER_CG && cfg->cg_iters < 0) return ALS_EINVAL;
+    if (cfg->factor_dtype != ALS_F32 || cfg->herm_dtype != ALS_F32) return ALS_EINVAL;
+    if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return ALS_EHIP;
+    als_ctx *ctx = new (std::nothrow) als_ctx();
+    if (!ctx) return ALS_ENOMEM;
+    ctx->cfg = *cfg;
+    if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 1024;
+    if (ctx->cfg.batch_slots == 0) ctx->cfg.batch_slots = 32768;
+    ctx->stream = (hipStream_t)cfg->stream;
+    if (hipSetDevice(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
+        hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
+        hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess) {
+        hipFree(ctx->status); hipFree(ctx->sse_total);
+        delete ctx;
+        return ALS_EHIP;
+    }
+    *out = ctx;
+    return ALS_OK;
+}
+
+void als_destroy(als_ctx *ctx) {
+    if (!ctx) return;
+    hipSetDevice(ctx->cfg.device);
+    hipStreamSynchronize(ctx->stream);
+    for (auto &p : ctx->plans) free_plan(p);
+    hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
+    hipFree(ctx->sse_total);
+    for (auto &t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
+    for (auto e : ctx->free_events) hipEventDestroy(e);
+    delete ctx;
+}
+
+const char *als_last_error(const als_ctx *ctx) { return ctx ? ctx->err.c_str() : "context is null"; }
+
+int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X) {
+    return update(ctx, csr, Theta, lambda, f, X);
+}
+
+int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, int f, float *Theta) {
+    return update(ctx, csc, X, lambda, f, Theta);
+}
+
+int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, csr);
+    if (rc != ALS_OK) return rc;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (!rmse_out || (csr->nnz > 0 && (!X || !Theta))) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (csr->nnz == 0) { *rmse_out = 0.0; return ALS_OK; }
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    Plan *p = nullptr;
+    rc = get_plan(ctx, csr, &p);
+    if (rc != ALS_OK) return rc;
+    const size_t need = sizeof(double) * (size_t)(p->ntasks > 0 ? p->ntasks : 1);
+    if (ctx->sse_partial_bytes < need) {
+        if (ctx->sse_partial) { HIP_TRY(ctx, hipStreamSynchronize(ctx->stream)); HIP_TRY(ctx, hipFree(ctx->sse_partial)); }
+        ctx->sse_partial = nullptr; ctx->sse_partial_bytes = 0;
+        HIP_TRY(ctx, hipMalloc(&ctx->sse_partial, need));
+        ctx->sse_partial_bytes = need;
+    }
+    {
+        Timed t(ctx, ALS_K_RMSE);
+        HIP_TRY(ctx, launch_sse(f, csr->ptr_is_64 != 0, ctx->stream, p->task_row, p->task_chunk, p->ntasks,
+                                ctx->cfg.chunk, csr->ptr, csr->idx, csr->val, X, Theta, ctx->sse_partial,
+                                ctx->sse_total));
+    }
+    double sse = 0.0;
+    HIP_TRY(ctx, hipMemcpyAsync(&sse, ctx->sse_total, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    *rmse_out = sqrt(sse / (double)csr->nnz);
+    return ALS_OK;
+}
+
+int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, int64_t row0,
+                  int64_t nrows, float *A_out, float *b_out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, csr);
+    if (rc != ALS_OK) return rc;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (row0 < 0 || nrows < 0 || row0 + nrows > csr->nrows) return fail(ctx, ALS_EINVAL, "row range outside the matrix");
+    if (!A_out || !b_out || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (nrows == 0) return ALS_OK;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    // a throw-away plan over the row range, in natural order
+    const bool p64 = csr->ptr_is_64 != 0;
+    int32_t *perm = nullptr, *task_off = nullptr, *task_row = nullptr, *task_chunk = nullptr;
+    auto cleanup = [&]() { hipFree(perm); hipFree(task_off); hipFree(task_row); hipFree(task_chunk); };
+    hipError_t e;
+    if ((e = hipMalloc(&perm, sizeof(int32_t) * (size_t)nrows)) != hipSuccess ||
+        (e = hipMalloc(&task_off, sizeof(int32_t) * (size_t)(nrows + 1))) != hipSuccess) {
+        cleanup();
+        return fail_hip(ctx, e, "hipMalloc");
+    }
+    std::vector<int32_t> off((size_t)nrows + 1);
+    if ((e = fill_iota(ctx->stream, perm, nrows, (int32_t)row0)) != hipSuccess ||
+        (e = plan_tasks(p64, ctx->stream, nrows, csr->ptr, perm, ctx->cfg.chunk, task_off, &ctx->scratch,
+                        &ctx->scratch_bytes)) != hipSuccess ||
+        (e = hipMemcpyAsync(off.data(), task_off, sizeof(int32_t) * (size_t)(nrows + 1), hipMemcpyDeviceToHost,
+                            ctx->stream)) != hipSuccess ||
+        (e = hipStreamSynchronize(ctx->stream)) != hipSuccess) {
+        cleanup();
+        return fail_hip(ctx, e, "plan of the row range");
+    }
+    const int64_t ntasks = off[(size_t)nrows];
+    if ((e = hipMalloc(&task_row, sizeof(int32_t) * (size_t)(ntasks > 0 ? ntasks : 1))) != hipSuccess ||
+        (e = hipMalloc(&task_chunk, sizeof(int32_t) * (size_t)(ntasks > 0 ? ntasks : 1))) != hipSuccess ||
+        (e = plan_emit(p64, ctx->stream, nrows, csr->ptr, perm, ctx->cfg.chunk, task_off, task_row, task_chunk)) !=
+            hipSuccess) {
+        cleanup();
+        return fail_hip(ctx, e, "work items of the row range");
+    }
+    rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1);
+    if (rc != ALS_OK) { cleanup(); return rc; }
+    {
+        Timed t(ctx, ALS_K_HERMITIAN);
+        e = launch_hermitian(f, p64, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
+                             csr->val, (const float *)Theta, ctx->slots);
+    }
+    if (e == hipSuccess)
+        e = launch_export_dense(f, p64, ctx->stream, perm, task_off, 0, nrows, 0, csr->ptr, ctx->slots, lambda, row0,
+                                A_out, b_out);
+    hipError_t e2 = hipStreamSynchronize(ctx->stream);
+    cleanup();
+    if (e != hipSuccess) return fail_hip(ctx, e, "get_hermitian launch");
+    if (e2 != hipSuccess) return fail_hip(ctx, e2, "get_hermitian");
+    return ALS_OK;
+}
+
+int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_out, int64_t *class_start_out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, csr);
+    if (rc != ALS_OK) return rc;
+    if (nclass < 2 || nclass > 64) return fail(ctx, ALS_EINVAL, "nclass must be in [2, 64]");
+    if (!perm_out || !class_start_out) return fail(ctx, ALS_EINVAL, "null pointer");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    int32_t *cs_dev = nullptr;
+    HIP_TRY(ctx, hipMalloc(&cs_dev, sizeof(int32_t) * 65));
+    hipError_t e = plan_bin_rows(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ptr, nclass, perm_out, cs_dev,
+                                 &ctx->scratch, &ctx->scratch_bytes);
+    int32_t cs[65];
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(cs, cs_dev, sizeof(int32_t) * (size_t)(nclass + 1), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    hipFree(cs_dev);
+    if (e != hipSuccess) return fail_hip(ctx, e, "als_bin_rows");
+    for (int c = 0; c <= nclass; ++c) class_start_out[c] = cs[c];
+    return ALS_OK;
+}
+
+int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, csr);
+    if (rc != ALS_OK) return rc;
+    if (csr->nnz > 0x7fffffff) return fail(ctx, ALS_EINVAL, "als_csr_to_csc needs nnz < 2^31");
+    if (!cptr_out || (csr->nnz > 0 && (!cidx_out || !cval_out))) return fail(ctx, ALS_EINVAL, "null pointer");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    hipError_t e = transpose_csr(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ncols, csr->nnz, csr->ptr,
+                                 csr->idx, csr->val, cptr_out, cidx_out, cval_out);
+    if (e != hipSuccess) return fail_hip(ctx, e, "als_csr_to_csc");
+    return ALS_OK;
+}
+
+int als_synchronize(als_ctx *ctx) {
+    if (!ctx) return ALS_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    int st = 0;
+    HIP_TRY(ctx, hipMemcpyAsync(&st, ctx->status, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (st != 0) {
+        HIP_TRY(ctx, hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream));
+        std::string msg;
+        if (st & kStatusBadPivot) msg += "non-positive pivot in the exact solver; ";
+        if (st & kStatusNonFinite) msg += "non-finite value in a solution; ";
+        return fail(ctx, ALS_ENUMERIC, msg);
+    }
+    return ALS_OK;
+}
+
+int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launches_out) {
+    if (!ctx || !ms_out || !launches_out) return ALS_EINVAL;
+    if (kernel_id < 0 || kernel_id >= ALS_K_COUNT) return fail(ctx, ALS_EINVAL, "unknown kernel id");
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    double ms = 0.0;
+    int64_t n = 0;
+    for (auto &t : ctx->timed)
+        if (t.kernel == kernel_id) {
+            float dt = 0.f;
+            HIP_TRY(ctx, hipEventElapsedTime(&dt, t.a, t.b));
+            ms += dt;
+            ++n;
+        }
+    *ms_out = ms;
+    *launches_out = n;
+    return ALS_OK;
+}
+
+int als_profile_reset(als_ctx *ctx) {
+    if (!ctx) return ALS_EINVAL;
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto &t : ctx->timed) { ctx->free_events.push_back(t.a); ctx->free_events.push_back(t.b); }
+    ctx->timed.clear();
+    return ALS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Batched RMSE (Section 5.2 metric): sum over stored entries of (r_uv - x_u^T theta_v)^2.
+// One wavefront per work item (the same row chunks as the update), 4 stored entries per step with
+// 16 lanes sharing one dot product; fp32 dots, fp64 accumulation of the squared errors, per-item
+// partial sums added in item order by a single block (deterministic).
+#include "als_internal.h"
+
+namespace als {
+
+template <int F, typename PtrT>
+__global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row,
+                                            const int32_t *__restrict__ task_chunk, int chunk,
+                                            const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                            const float *__restrict__ val, const float *__restrict__ X,
+                                            const float *__restrict__ Theta, double *__restrict__ partial) {
+    constexpr int NT = tiles_1d(F);
+    const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
+    const int64_t t = blockIdx.x;
+    const int row = task_row[t];
+    const int ch = task_chunk[t];
+    const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
+    const int64_t s0 = rs + (int64_t)ch * chunk;
+    const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
+    const int len = (int)(s1 - s0);
+    float xr[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) xr[q] = (16 * q + i < F) ? X[(int64_t)row * F + 16 * q + i] : 0.f;
+    double acc = 0.0;
+    for (int e0 = 0; e0 < len; e0 += 4) {
+        const int e = e0 + kq;
+        const bool ok = e < len;
+        const int c = idx[s0 + (ok ? e : len - 1)];
+        const float r = val[s0 + (ok ? e : len - 1)];
+        const float *p = Theta + (int64_t)c * F;
+        float d = 0.f;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            const int feat = 16 * q + i;
+            d = fmaf(xr[q], p[feat < F ? feat : F - 1], d);
+        }
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) d += __shfl_xor(d, o);
+        const float err = r - d;
+        if (ok && i == 0) acc += (double)err * (double)err;
+    }
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (lane == 0) partial[t] = acc;
+}
+
+__global__ __launch_bounds__(1024) void k_sum_partials(const double *__restrict__ partial, int64_t n,
+                                                       double *__restrict__ total) {
+    __shared__ double red[1024];
+    // each thread sums a contiguous range, then a fixed tree: the order never depends on timing
+    const int64_t per = (n + 1023) / 1024;
+    const int64_t a = per * threadIdx.x, b = (a + per < n) ? a + per : n;
+    double s = 0.0;
+    for (int64_t q = a; q < b; ++q) s += partial[q];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total = red[0];
+}
+
+template <int F, typename PtrT>
+static hipError_t sse_f(hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t ntasks, int chunk,
+                        const void *ptr, const int32_t *idx, const float *val, const float *X, const float *Theta,
+                        double *partial, double *total) {
+    if (ntasks > 0)
+        hipLaunchKernelGGL((k_sse<F, PtrT>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk, chunk,
+                           (const PtrT *)ptr, idx, val, X, Theta, partial);
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, partial, ntasks, total);
+    return hipGetLastError();
+}
+
+hipError_t launch_sse(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+                      int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
+                      const float *X, const float *Theta, double *partial, double *total) {
+#define CALL(FF)                                                                                               \
+    (ptr64 ? sse_f<FF, int64_t>(st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta, partial, total) \
+           : sse_f<FF, int32_t>(st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta, partial, total))
+    switch (f) {
+        case 16: return CALL(16);
+        case 32: return CALL(32);
+        case 64: return CALL(64);
+        case 100: return CALL(100);
+        case 128: return CALL(128);
+        default: return hipErrorInvalidValue;
+    }
+#undef CALL
+}
+
+}  // namespace als

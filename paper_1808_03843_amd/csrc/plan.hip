@@ -1,0 +1,241 @@
+// Load balancing of the per-row work (not in the paper, which launches one thread block per row
+// whatever its length, Section 3): rows are grouped by degree class, heaviest first, and rows
+// longer than `chunk` stored entries are split into several work items.  Integer work only; the
+// results are deterministic (stable counting sort built from ballots and prefix sums, no atomics).
+#include "als_internal.h"
+
+namespace als {
+
+// ---- exclusive prefix sum of int32, in place ---------------------------------------------------
+constexpr int kScanThreads = 256, kScanItems = 8, kScanBlock = kScanThreads * kScanItems;
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_block(int32_t *__restrict__ data, int64_t n,
+                                                             int32_t *__restrict__ block_sums) {
+    __shared__ int32_t wave_tot[kScanThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
+    int32_t v[kScanItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        v[q] = (base + q < n) ? data[base + q] : 0;
+        sum += v[q];
+    }
+    // inclusive scan of `sum` across the wavefront
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int32_t t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wave_tot[w] = inc;
+    __syncthreads();
+    int32_t woff = 0, total = 0;
+#pragma unroll
+    for (int q = 0; q < kScanThreads / 64; ++q) {
+        if (q < w) woff += wave_tot[q];
+        total += wave_tot[q];
+    }
+    int32_t run = woff + inc - sum;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q) {
+        if (base + q < n) data[base + q] = run;
+        run += v[q];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kScanThreads) void k_scan_add(int32_t *__restrict__ data, int64_t n,
+                                                           const int32_t *__restrict__ block_offsets) {
+    const int32_t off = block_offsets[blockIdx.x];
+    const int64_t base = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
+#pragma unroll
+    for (int q = 0; q < kScanItems; ++q)
+        if (base + q < n) data[base + q] += off;
+}
+
+static size_t scan_scratch_ints(int64_t n) {
+    size_t total = 0;
+    while (n > 1) {
+        n = (n + kScanBlock - 1) / kScanBlock;
+        total += (size_t)n;
+        if (n == 1) break;
+    }
+    return total + 1;
+}
+
+static hipError_t exclusive_scan(hipStream_t st, int32_t *data, int64_t n, int32_t *scratch) {
+    if (n <= 0) return hipSuccess;
+    const int64_t nb = (n + kScanBlock - 1) / kScanBlock;
+    hipLaunchKernelGGL(k_scan_block, dim3((unsigned)nb), dim3(kScanThreads), 0, st, data, n, scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || nb == 1) return e;
+    e = exclusive_scan(st, scratch, nb, scratch + nb);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_scan_add, dim3((unsigned)nb), dim3(kScanThreads), 0, st, data, n, scratch);
+    return hipGetLastError();
+}
+
+static hipError_t ensure_scratch(void **scratch, size_t *have, size_t need) {
+    if (*have >= need) return hipSuccess;
+    if (*scratch) {
+        hipError_t e = hipFree(*scratch);
+        if (e != hipSuccess) return e;
+        *scratch = nullptr;
+        *have = 0;
+    }
+    hipError_t e = hipMalloc(scratch, need);
+    if (e == hipSuccess) *have = need;
+    return e;
+}
+
+// ---- degree classes -----------------------------------------------------------------------------
+__device__ __forceinline__ int degree_class(int64_t n_u, int nclass) {
+    if (n_u <= 0) return 0;
+    const int c = 1 + (63 - __clzll((long long)n_u));
+    return c < nclass ? c : nclass - 1;
+}
+
+// counts[slot * nseg + seg] = rows of the 64-row segment whose class is nclass-1-slot
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_class_hist(const PtrT *__restrict__ ptr, int64_t nrows, int nclass,
+                                                    int64_t nseg, int32_t *__restrict__ counts) {
+    const int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (seg >= nseg) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = seg * 64 + lane;
+    const int slot = (row < nrows) ? nclass - 1 - degree_class((int64_t)ptr[row + 1] - (int64_t)ptr[row], nclass) : -1;
+    int32_t mine = 0;
+    for (int s = 0; s < nclass; ++s) {
+        const unsigned long long m = __ballot(slot == s);
+        if (lane == s) mine = __popcll(m);
+    }
+    if (lane < nclass) counts[(int64_t)lane * nseg + seg] = mine;
+}
+
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_class_scatter(const PtrT *__restrict__ ptr, int64_t nrows, int nclass,
+                                                       int64_t nseg, const int32_t *__restrict__ offsets,
+                                                       int32_t *__restrict__ perm) {
+    const int64_t seg = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (seg >= nseg) return;
+    const int lane = threadIdx.x & 63;
+    const int64_t row = seg * 64 + lane;
+    const int slot = (row < nrows) ? nclass - 1 - degree_class((int64_t)ptr[row + 1] - (int64_t)ptr[row], nclass) : -1;
+    unsigned long long same = 0;
+    for (int s = 0; s < nclass; ++s) {
+        const unsigned long long m = __ballot(slot == s);
+        if (slot == s) same = m;
+    }
+    if (slot >= 0) {
+        const int rank = __popcll(same & ((1ull << lane) - 1ull));
+        perm[offsets[(int64_t)slot * nseg + seg] + rank] = (int32_t)row;
+    }
+}
+
+__global__ void k_class_start(const int32_t *__restrict__ offsets, int nclass, int64_t nseg,
+                              int32_t *__restrict__ class_start) {
+    const int s = threadIdx.x;
+    if (s <= nclass) class_start[s] = offsets[(int64_t)s * nseg];  // entry nclass*nseg holds the total
+}
+
+__global__ void k_set_zero(int32_t *p) { *p = 0; }
+
+hipError_t plan_bin_rows(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, int nclass, int32_t *perm,
+                         int32_t *class_start_dev, void **scratch, size_t *scratch_bytes) {
+    if (nclass < 2 || nclass > 64) return hipErrorInvalidValue;
+    const int64_t nseg = (nrows + 63) / 64;
+    const int64_t ncount = (int64_t)nclass * nseg + 1;
+    const size_t need = (size_t)(ncount + scan_scratch_ints(ncount)) * sizeof(int32_t);
+    hipError_t e = ensure_scratch(scratch, scratch_bytes, need);
+    if (e != hipSuccess) return e;
+    int32_t *counts = (int32_t *)*scratch;
+    if (nseg > 0) {
+        const unsigned nb = (unsigned)((nseg + 3) / 4);
+        if (ptr64)
+            hipLaunchKernelGGL((k_class_hist<int64_t>), dim3(nb), dim3(256), 0, st, (const int64_t *)ptr, nrows,
+                               nclass, nseg, counts);
+        else
+            hipLaunchKernelGGL((k_class_hist<int32_t>), dim3(nb), dim3(256), 0, st, (const int32_t *)ptr, nrows,
+                               nclass, nseg, counts);
+    }
+    hipLaunchKernelGGL(k_set_zero, dim3(1), dim3(1), 0, st, counts + ncount - 1);
+    e = exclusive_scan(st, counts, ncount, counts + ncount);
+    if (e != hipSuccess) return e;
+    if (nseg > 0) {
+        const unsigned nb = (unsigned)((nseg + 3) / 4);
+        if (ptr64)
+            hipLaunchKernelGGL((k_class_scatter<int64_t>), dim3(nb), dim3(256), 0, st, (const int64_t *)ptr, nrows,
+                               nclass, nseg, counts, perm);
+        else
+            hipLaunchKernelGGL((k_class_scatter<int32_t>), dim3(nb), dim3(256), 0, st, (const int32_t *)ptr, nrows,
+                               nclass, nseg, counts, perm);
+    }
+    if (class_start_dev)
+        hipLaunchKernelGGL(k_class_start, dim3(1), dim3(128), 0, st, counts, nclass, nseg, class_start_dev);
+    return hipGetLastError();
+}
+
+// ---- work items -----------------------------------------------------------------------------------
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_count_items(const PtrT *__restrict__ ptr, const int32_t *__restrict__ perm,
+                                                     int64_t nrows, int chunk, int32_t *__restrict__ task_off) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i > nrows) return;
+    int32_t nt = 0;
+    if (i < nrows) {
+        const int row = perm[i];
+        const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+        nt = (int32_t)((n_u + chunk - 1) / chunk);
+    }
+    task_off[i] = nt;
+}
+
+hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
+                      int32_t *task_off, void **scratch, size_t *scratch_bytes) {
+    const size_t need = scan_scratch_ints(nrows + 1) * sizeof(int32_t);
+    hipError_t e = ensure_scratch(scratch, scratch_bytes, need);
+    if (e != hipSuccess) return e;
+    const unsigned nb = (unsigned)((nrows + 1 + 255) / 256);
+    if (ptr64)
+        hipLaunchKernelGGL((k_count_items<int64_t>), dim3(nb), dim3(256), 0, st, (const int64_t *)ptr, perm, nrows,
+                           chunk, task_off);
+    else
+        hipLaunchKernelGGL((k_count_items<int32_t>), dim3(nb), dim3(256), 0, st, (const int32_t *)ptr, perm, nrows,
+                           chunk, task_off);
+    return exclusive_scan(st, task_off, nrows + 1, (int32_t *)*scratch);
+}
+
+__global__ __launch_bounds__(256) void k_emit_items(const int32_t *__restrict__ perm,
+                                                    const int32_t *__restrict__ task_off, int64_t nrows,
+                                                    int32_t *__restrict__ task_row, int32_t *__restrict__ task_chunk) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nrows) return;
+    const int row = perm[i];
+    const int32_t a = task_off[i], b = task_off[i + 1];
+    for (int32_t t = a; t < b; ++t) {
+        task_row[t] = row;
+        task_chunk[t] = t - a;
+    }
+}
+
+hipError_t plan_emit(bool, hipStream_t st, int64_t nrows, const void *, const int32_t *perm, int,
+                     const int32_t *task_off, int32_t *task_row, int32_t *task_chunk) {
+    if (nrows <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_emit_items, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, st, perm, task_off, nrows,
+                       task_row, task_chunk);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ p, int64_t n, int32_t first) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = first + (int32_t)i;
+}
+
+hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_iota, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, first);
+    return hipGetLastError();
+}
+
+}  // namespace als

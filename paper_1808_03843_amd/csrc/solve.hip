@@ -1,0 +1,286 @@
+// Step (ii) of Section 2 ("solve"): x_u = A_u^-1 b_u for a batch of rows whose A_u, b_u were
+// accumulated into work-item slots by the get_hermitian kernel.  One workgroup per system.
+//   - exact: LDL^T factorisation of the bordered matrix [A b; b^T .] in LDS (the paper's exact
+//     baseline is a batched LU, Section 4.1; A_u is symmetric positive definite, so the
+//     symmetric factorisation gives the same solution with half the work),
+//   - approximate: Algorithm 1 (CGSolve), f_s iterations warm-started from the current x_u,
+//     each thread keeping one row of A_u in registers.
+// A row that was split into several work items has its partial Gram matrices summed here, in
+// work-item order (deterministic).
+#include "als_internal.h"
+
+namespace als {
+
+// tile index -> (tile row R, tile column C), R >= C
+__device__ __forceinline__ void tile_rc(int tile, int &R, int &C) {
+    int r = 0;
+    while ((r + 1) * (r + 2) / 2 <= tile) ++r;
+    R = r;
+    C = tile - r * (r + 1) / 2;
+}
+
+// Sums the slots of one row into a dense lower triangle As[row*LD + col] (col <= row < F) and
+// bs[0..F).  Adds reg to the diagonal.  Every thread of the block takes part.
+template <int F, int LD>
+__device__ __forceinline__ void load_system(const float *__restrict__ slots, int nslots, float reg, float *As,
+                                            float *bs) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
+    for (int o = threadIdx.x; o < NTILES * 256; o += blockDim.x) {
+        const int tile = o >> 8, r = (o >> 6) & 3, l = o & 63;
+        int R, C;
+        tile_rc(tile, R, C);
+        const int row = 16 * R + 4 * (l >> 4) + r, col = 16 * C + (l & 15);
+        if (row < F && col <= row) {
+            float v = 0.f;
+            for (int s = 0; s < nslots; ++s) v += slots[(int64_t)s * SLOT + o];
+            if (row == col) v += reg;
+            As[row * LD + col] = v;
+        }
+    }
+    for (int o = threadIdx.x; o < NT * 16; o += blockDim.x) {
+        if (o < F) {
+            float v = 0.f;
+            for (int s = 0; s < nslots; ++s) v += slots[(int64_t)s * SLOT + NTILES * 256 + o];
+            bs[o] = v;
+        }
+    }
+}
+
+// ---- exact solve -------------------------------------------------------------------------------
+// Right-looking LDL^T on the bordered matrix: row F of As holds b.  After eliminating column j,
+// As[i][j] (i > j) holds L[i][j]*d_j and As[F][j] holds z_j with L z = b; then x solves
+// L^T x = D^-1 z.  One barrier per column.
+template <int F, typename PtrT>
+__global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ perm,
+                                                    const int32_t *__restrict__ task_off, int64_t pos0,
+                                                    int64_t task0, const PtrT *__restrict__ ptr,
+                                                    const float *__restrict__ slots, float lambda,
+                                                    float *__restrict__ Xout, int *__restrict__ status) {
+    constexpr int LD = F + 1, SLOT = slot_floats(F);
+    __shared__ float As[(F + 1) * LD];
+    const int64_t pos = pos0 + blockIdx.x;
+    const int row = perm[pos];
+    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+    float *x = Xout + (int64_t)row * F;
+    if (n_u == 0) {
+        for (int q = threadIdx.x; q < F; q += blockDim.x) x[q] = 0.f;
+        return;
+    }
+    const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
+    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, As + F * LD);
+
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    bool bad = false;
+    for (int j = 0; j < F; ++j) {
+        __syncthreads();
+        float d = As[j * LD + j];
+        if (!(d > 0.f)) { bad = true; d = 1.f; }
+        const float invd = 1.f / d;
+        // rows i in (j, F] (row F is b), columns k in (j, min(i, F-1)]
+        for (int i = j + 1 + ty; i <= F; i += 16) {
+            const float lij = As[i * LD + j] * invd;
+            const int kmax = i < F ? i : F - 1;
+            for (int k = j + 1 + tx; k <= kmax; k += 16) As[i * LD + k] -= lij * As[k * LD + j];
+        }
+    }
+    __syncthreads();
+    if (bad && threadIdx.x == 0) atomicOr(status, kStatusBadPivot);
+    if (threadIdx.x >= 64) return;
+    // back substitution by one wavefront: lane l owns z_l and z_{l+64}
+    const int l = threadIdx.x;
+    float z0 = (l < F) ? As[F * LD + l] : 0.f;
+    float z1 = (l + 64 < F) ? As[F * LD + l + 64] : 0.f;
+    float x0 = 0.f, x1 = 0.f;
+    for (int k = F - 1; k >= 0; --k) {
+        const float zk = __shfl(k < 64 ? z0 : z1, k & 63);
+        float dk = As[k * LD + k];
+        if (!(dk > 0.f)) dk = 1.f;
+        const float xk = zk / dk;
+        if (l == (k & 63)) {
+            if (k < 64) x0 = xk; else x1 = xk;
+        }
+        // z_i -= (L[k][i] d_i) x_k for i < k
+        if (l < k) z0 -= As[k * LD + l] * xk;
+        if (l + 64 < k) z1 -= As[k * LD + l + 64] * xk;
+    }
+    if (l < F) {
+        x[l] = x0;
+        if (!isfinite(x0)) atomicOr(status, kStatusNonFinite);
+    }
+    if (l + 64 < F) {
+        x[l + 64] = x1;
+        if (!isfinite(x1)) atomicOr(status, kStatusNonFinite);
+    }
+}
+
+// ---- Algorithm 1 -------------------------------------------------------------------------------
+template <int NW>
+__device__ __forceinline__ float block_sum(float v, float *red) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (NW == 1) return v;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) s += red[w];
+    return s;
+}
+
+template <int F, typename PtrT>
+__global__ __launch_bounds__(128) void k_solve_cg(const int32_t *__restrict__ perm,
+                                                  const int32_t *__restrict__ task_off, int64_t pos0, int64_t task0,
+                                                  const PtrT *__restrict__ ptr, const float *__restrict__ slots,
+                                                  float lambda, int fs, float eps, float *__restrict__ Xout,
+                                                  int *__restrict__ status) {
+    constexpr int LD = F + 1, SLOT = slot_floats(F), NW = 2;
+    constexpr int FP = (F + 3) & ~3;
+    __shared__ float As[F * LD];
+    __shared__ float bs[FP];
+    __shared__ __attribute__((aligned(16))) float ps[FP];
+    __shared__ float red[NW];
+    const int64_t pos = pos0 + blockIdx.x;
+    const int row = perm[pos];
+    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+    float *xg = Xout + (int64_t)row * F;
+    const int i = threadIdx.x;
+    if (n_u == 0) {
+        if (i < F) xg[i] = 0.f;
+        return;
+    }
+    const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
+    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, bs);
+    const bool act = i < F;
+    float x = act ? xg[i] : 0.f;
+    if (i < FP) ps[i] = x;
+    __syncthreads();
+    // row i of the symmetric A in registers: A[i][j] = As[max][min]
+    float a[FP];
+#pragma unroll
+    for (int j = 0; j < FP; ++j) {
+        float v = 0.f;
+        if (act && j < F) v = (j <= i) ? As[i * LD + j] : As[j * LD + i];
+        a[j] = v;
+    }
+    auto matvec = [&]() {  // A * ps, this thread's row
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int j = 0; j < FP; j += 4) {
+            const float4 p4 = *reinterpret_cast<const float4 *>(&ps[j]);
+            s0 = fmaf(a[j], p4.x, s0);
+            s1 = fmaf(a[j + 1], p4.y, s1);
+            s2 = fmaf(a[j + 2], p4.z, s2);
+            s3 = fmaf(a[j + 3], p4.w, s3);
+        }
+        return (s0 + s1) + (s2 + s3);
+    };
+    // r = b - A x;  p = r;  rs_old = r^T r
+    float r = act ? bs[i] - matvec() : 0.f;
+    float p = r;
+    float rs_old = block_sum<NW>(r * r, red);
+    if (rs_old > 0.f) {
+        for (int it = 0; it < fs; ++it) {
+            __syncthreads();
+            if (i < FP) ps[i] = p;
+            __syncthreads();
+            const float ap = act ? matvec() : 0.f;
+            const float pap = block_sum<NW>(p * ap, red);
+            if (!(pap > 0.f) || !isfinite(pap)) break;
+            const float alpha = rs_old / pap;
+            x = fmaf(alpha, p, x);
+            r = fmaf(-alpha, ap, r);
+            const float rs_new = block_sum<NW>(r * r, red);
+            if (sqrtf(rs_new) < eps) break;
+            p = fmaf(rs_new / rs_old, p, r);
+            rs_old = rs_new;
+        }
+    }
+    if (act) {
+        xg[i] = x;
+        if (!isfinite(x)) atomicOr(status, kStatusNonFinite);
+    }
+}
+
+// ---- dense export (tests, breakdown runs) -----------------------------------------------------
+template <int F, typename PtrT>
+__global__ __launch_bounds__(256) void k_export_dense(const int32_t *__restrict__ perm,
+                                                      const int32_t *__restrict__ task_off, int64_t pos0,
+                                                      int64_t task0, const PtrT *__restrict__ ptr,
+                                                      const float *__restrict__ slots, float lambda, int64_t row0,
+                                                      float *__restrict__ A_out, float *__restrict__ b_out) {
+    constexpr int LD = F + 1, SLOT = slot_floats(F);
+    __shared__ float As[F * LD];
+    __shared__ float bs[F];
+    const int64_t pos = pos0 + blockIdx.x;
+    const int row = perm[pos];
+    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+    const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
+    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, bs);
+    __syncthreads();
+    float *A = A_out + (row - row0) * (int64_t)F * F;
+    for (int o = threadIdx.x; o < F * F; o += blockDim.x) {
+        const int r = o / F, c = o % F;
+        A[o] = (c <= r) ? As[r * LD + c] : As[c * LD + r];
+    }
+    for (int o = threadIdx.x; o < F; o += blockDim.x) b_out[(row - row0) * (int64_t)F + o] = bs[o];
+}
+
+template <int F, typename PtrT>
+static hipError_t solve_f(int solver, int cg_iters, float cg_eps, hipStream_t st, const int32_t *perm,
+                          const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0, const void *ptr,
+                          const float *slots, float lambda, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    dim3 grid((unsigned)npos);
+    if (solver == ALS_SOLVER_CG)
+        hipLaunchKernelGGL((k_solve_cg<F, PtrT>), grid, dim3(128), 0, st, perm, task_off, pos0, task0,
+                           (const PtrT *)ptr, slots, lambda, cg_iters, cg_eps, Xout, status);
+    else
+        hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(256), 0, st, perm, task_off, pos0, task0,
+                           (const PtrT *)ptr, slots, lambda, Xout, status);
+    return hipGetLastError();
+}
+
+#define ALS_DISPATCH_F(CALL)                       \
+    switch (f) {                                   \
+        case 16: return CALL(16);                  \
+        case 32: return CALL(32);                  \
+        case 64: return CALL(64);                  \
+        case 100: return CALL(100);                \
+        case 128: return CALL(128);                \
+        default: return hipErrorInvalidValue;      \
+    }
+
+hipError_t launch_solve(int f, int solver, int cg_iters, float cg_eps, bool ptr64, hipStream_t st,
+                        const int32_t *perm, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
+                        const void *ptr, const float *slots, float lambda, float *Xout, int *status) {
+#define CALL(FF)                                                                                                  \
+    (ptr64 ? solve_f<FF, int64_t>(solver, cg_iters, cg_eps, st, perm, task_off, pos0, npos, task0, ptr, slots,    \
+                                  lambda, Xout, status)                                                           \
+           : solve_f<FF, int32_t>(solver, cg_iters, cg_eps, st, perm, task_off, pos0, npos, task0, ptr, slots,    \
+                                  lambda, Xout, status))
+    ALS_DISPATCH_F(CALL)
+#undef CALL
+}
+
+template <int F, typename PtrT>
+static hipError_t export_f(hipStream_t st, const int32_t *perm, const int32_t *task_off, int64_t pos0, int64_t npos,
+                           int64_t task0, const void *ptr, const float *slots, float lambda, int64_t row0,
+                           float *A_out, float *b_out) {
+    if (npos <= 0) return hipSuccess;
+    hipLaunchKernelGGL((k_export_dense<F, PtrT>), dim3((unsigned)npos), dim3(256), 0, st, perm, task_off, pos0,
+                       task0, (const PtrT *)ptr, slots, lambda, row0, A_out, b_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_export_dense(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                               int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                               float lambda, int64_t row0, float *A_out, float *b_out) {
+#define CALL(FF)                                                                                                   \
+    (ptr64 ? export_f<FF, int64_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, row0, A_out, b_out) \
+           : export_f<FF, int32_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, row0, A_out, b_out))
+    ALS_DISPATCH_F(CALL)
+#undef CALL
+}
+
+}  // namespace als

@@ -1,0 +1,217 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+import workload as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _row_rel_err(x_gpu, x_ref):
+    num = np.linalg.norm(x_gpu.astype(np.float64) - x_ref, axis=1)
+    den = np.maximum(np.linalg.norm(x_ref, axis=1), 1e-30)
+    return num / den
+
+
+def _edge_matrix(n, f, seed, degrees):
+    """Rows with chosen degrees (0 allowed), distinct sorted columns, ratings 0..5 (stored zeros included)."""
+    rng = np.random.default_rng(seed)
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, int)])
+    val = rng.integers(0, 6, size=int(ptr[-1])).astype(np.float32)
+    return W.CSR(len(degrees), n, ptr, idx.astype(np.int32), val)
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_1808_03843_amd as pkg
+    return pkg
+
+
+# tolerance of the exact fp32 mode (per row, 2-norm relative): 1e-4
+TOL_EXACT = 1e-4
+
+
+@pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
+def test_hermitian_and_bias_match_oracle_on_edge_degrees(P, f):
+    n = 5000
+    degrees = [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 127, 255, 256, 257, 300, 1023, 1024, 1025, 2048, 2500, 4097, 0, 1]
+    a = _edge_matrix(n, f, 7, degrees)
+    Theta = W.random_factors(n, f, seed=3, scale=0.5)
+    lam = 0.05
+    als = P.Als(f, chunk=256)          # several work items per long row
+    sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    A, b = als.hermitian(sp, _dev(Theta), lam, 0, a.nrows)
+    A, b = A.cpu().numpy(), b.cpu().numpy()
+    for u, d in enumerate(degrees):
+        s, e = a.ptr[u], a.ptr[u + 1]
+        Ao, bo = oracle.normal_eq(a.idx[s:e], a.val[s:e], Theta, lam)
+        scale = max(np.abs(Ao).max(), 1e-30)
+        assert np.abs(A[u] - Ao).max() <= 2e-6 * scale * max(1, np.sqrt(d)), (u, d)
+        assert np.abs(b[u] - bo).max() <= 2e-6 * max(np.abs(bo).max(), 1e-30) * max(1, np.sqrt(d)) + 1e-30, (u, d)
+        assert np.array_equal(A[u], A[u].T)
+    als.close()
+
+
+@pytest.mark.parametrize("chunk", [64, 1024])
+def test_one_exact_sweep_on_tiny(P, chunk):
+    w = W.TINY
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY, chunk=chunk)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    X, T = _dev(X0), _dev(T0)
+    als.update_rows(csr, T, w.lam, X)
+    als.update_cols(csc, X, w.lam, T)
+    als.synchronize()
+    Xo = oracle.update_rows(a.ptr, a.idx, a.val, T0, w.lam)
+    To = oracle.update_rows(c.ptr, c.idx, c.val, Xo, w.lam)
+    ex, et = _row_rel_err(X.cpu().numpy(), Xo), _row_rel_err(T.cpu().numpy(), To)
+    print(f"tiny one sweep: max row rel err X {ex.max():.2e} Theta {et.max():.2e}")
+    assert ex.max() <= TOL_EXACT and et.max() <= TOL_EXACT
+    # RMSE through the library against the oracle's on the same (GPU-independent) factors
+    r_gpu = als.rmse(csr, _dev(Xo.astype(np.float32)), _dev(To.astype(np.float32)))
+    r_orc = oracle.rmse(a.ptr, a.idx, a.val, Xo.astype(np.float32), To.astype(np.float32))
+    assert abs(r_gpu - r_orc) <= 1e-5 * max(r_orc, 1e-30)
+    als.close()
+
+
+def test_exact_sweeps_follow_oracle_trajectory_on_tiny(P):
+    w = W.TINY
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    _, _, hist = oracle.als((a.ptr, a.idx, a.val), (c.ptr, c.idx, c.val), X0, T0, w.lam, w.sweeps)
+    als = P.Als(w.f)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    X, T = _dev(X0), _dev(T0)
+    for s in range(w.sweeps):
+        als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+        assert abs(als.rmse(csr, X, T) - hist[s]["rmse"]) <= 2e-4
+    als.synchronize()
+    als.close()
+
+
+def test_one_exact_sweep_f100_several_tiles_ragged_tails(P):
+    w = W.MID_SMALL
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY, chunk=512, batch_slots=4096)   # several batches, split rows
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    X, T = _dev(X0), _dev(T0)
+    als.update_rows(csr, T, w.lam, X)
+    als.update_cols(csc, X, w.lam, T)
+    als.synchronize()
+    Xo = oracle.update_rows(a.ptr, a.idx, a.val, T0, w.lam)
+    To = oracle.update_rows(c.ptr, c.idx, c.val, Xo, w.lam)
+    ex, et = _row_rel_err(X.cpu().numpy(), Xo), _row_rel_err(T.cpu().numpy(), To)
+    print(f"mid_small one sweep: X max {ex.max():.2e} p99.9 {np.quantile(ex, 0.999):.2e}; "
+          f"Theta max {et.max():.2e} p99.9 {np.quantile(et, 0.999):.2e}")
+    assert ex.max() <= TOL_EXACT and et.max() <= TOL_EXACT
+    fro = np.linalg.norm(X.cpu().numpy() - Xo) / np.linalg.norm(Xo)
+    assert fro <= TOL_EXACT
+    als.close()
+
+
+def test_cg_update_matches_double_precision_algorithm_1(P):
+    # same Algorithm 1, same warm start, same f_s: only fp32 rounding separates the two
+    w = W.MID_SMALL
+    a = W.generate(w)
+    _, T0 = W.init_factors(w)
+    Xw = W.random_factors(w.m, w.f, seed=5, scale=0.1)
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, chunk=512)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    X = _dev(Xw.copy())
+    als.update_rows(csr, _dev(T0), w.lam, X)
+    als.synchronize()
+    Xo = oracle.update_rows_cg(a.ptr, a.idx, a.val, T0, w.lam, Xw, fs=6)
+    err = _row_rel_err(X.cpu().numpy(), Xo)
+    print(f"cg(6) vs double Algorithm 1: max {err.max():.2e}")
+    assert err.max() <= 2e-3
+    als.close()
+
+
+def test_cg_ten_sweeps_rmse_within_tolerance_of_exact_oracle(P):
+    w = W.MID_SMALL
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    _, _, hist = oracle.als((a.ptr, a.idx, a.val), (c.ptr, c.idx, c.val), X0, T0, w.lam, w.sweeps)
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    X, T = _dev(X0), _dev(T0)
+    for _ in range(w.sweeps):
+        als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+    r = als.rmse(csr, X, T)
+    als.synchronize()
+    print(f"cg(6) 10 sweeps rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
+    assert abs(r - hist[-1]["rmse"]) <= 2e-3
+    als.close()
+
+
+def test_empty_rows_stored_zeros_and_int64_pointers(P):
+    f, n = 32, 300
+    degrees = [0, 0, 5, 1, 0, 40, 300, 0]
+    a = _edge_matrix(n, f, 11, degrees)
+    Theta = W.random_factors(n, f, seed=4, scale=0.4)
+    Xo = oracle.update_rows(a.ptr, a.idx, a.val, Theta, 0.1)
+    for ptr64 in (False, True):
+        als = P.Als(f)
+        sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, ptr64=ptr64)
+        X = torch.full((a.nrows, f), 7.0, device="cuda:0")
+        als.update_rows(sp, _dev(Theta), 0.1, X)
+        als.synchronize()
+        Xg = X.cpu().numpy()
+        assert not Xg[[0, 1, 4, 7]].any()
+        live = [2, 3, 5, 6]
+        assert _row_rel_err(Xg[live], Xo[live]).max() <= TOL_EXACT
+        als.close()
+
+
+def test_index_work_is_bit_exact(P):
+    for w in (W.TINY, W.SQUARE_SMALL):
+        a = W.generate(w)
+        als = P.Als(w.f)
+        for ptr64 in (False, True):
+            sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, ptr64=ptr64)
+            perm, start = als.bin_rows(sp, 12)
+            perm_o, start_o = oracle.bin_rows(a.ptr, 12)
+            assert np.array_equal(perm.cpu().numpy(), perm_o) and list(start_o) == start
+            t = als.csr_to_csc(sp)
+            cptr, cidx, cval = oracle.csr_to_csc(w.m, w.n, a.ptr, a.idx, a.val)
+            assert np.array_equal(t.ptr.cpu().numpy(), cptr)
+            assert np.array_equal(t.idx.cpu().numpy(), cidx)
+            assert np.array_equal(t.val.cpu().numpy(), cval)
+        als.close()
+
+
+def test_bad_arguments_are_errors_not_crashes(P):
+    with pytest.raises(P.AlsError):
+        P.Als(17)
+    als = P.Als(16)
+    a = W.generate(W.TINY)
+    sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    T = torch.zeros((a.ncols, 16), device="cuda:0")
+    X = torch.zeros((a.nrows, 16), device="cuda:0")
+    with pytest.raises(P.AlsError):
+        als.update_rows(sp, T, -1.0, X)
+    # lambda = 0 and a rank-deficient row: the exact solver must flag it, not hang or crash
+    als.update_rows(sp, T, 0.0, X)
+    with pytest.raises(P.AlsError) as ei:
+        als.synchronize()
+    assert ei.value.code == -3
+    als.close()
