@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the ALS hot path on one MI355X: seconds per sweep (X-update + Theta-update) at f = 100
+on the Netflix-shaped synthetic workload, with the get_hermitian roofline and the CPU oracle beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mid] [--solver cg|cholesky]
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, a_host, stride):
+    """The oracle's exact sweep timed on every `stride`-th row and column, scaled by stored entries."""
+    import numpy as np
+    import oracle
+    import workload as W
+    _, T0 = W.init_factors(w)
+    rows = np.arange(0, w.m, stride, dtype=np.int64)
+    nnz_rows = int((a_host.ptr[rows + 1] - a_host.ptr[rows]).sum())
+    t0 = time.perf_counter()
+    oracle.update_selected(rows, a_host.ptr, a_host.idx, a_host.val, T0, w.lam)
+    t_rows = time.perf_counter() - t0
+    # column side: the same kernel of work on a CSC slice; build it from the sampled columns only
+    c = W.transpose(a_host)
+    cols = np.arange(0, w.n, stride, dtype=np.int64)
+    nnz_cols = int((c.ptr[cols + 1] - c.ptr[cols]).sum())
+    Xs = W.random_factors(w.m, w.f, seed=9, scale=0.5)
+    t0 = time.perf_counter()
+    oracle.update_selected(cols, c.ptr, c.idx, c.val, Xs, w.lam)
+    t_cols = time.perf_counter() - t0
+    est = t_rows * (w.nnz / max(nnz_rows, 1)) + t_cols * (w.nnz / max(nnz_cols, 1))
+    return {"value": est, "unit": "s/sweep", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"exact fp64 oracle on every {stride}th row ({nnz_rows} entries, {t_rows:.2f} s) and every "
+                      f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="mid")
+    ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
+    ap.add_argument("--cg-iters", type=int, default=6)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--batch-slots", type=int, default=0)
+    ap.add_argument("--cpu-stride", type=int, default=8, help="oracle baseline on every k-th row/column; 0 = skip")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
+                 "path would shard). Run with --gpus 1.")
+
+    import numpy as np
+    import torch
+    import paper_1808_03843_amd as P
+    import workload as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    w = W.CONFIGS[args.workload]
+    dev = "cuda:0"
+    t0 = time.perf_counter()
+    a = W.generate(w)
+    log(f"[bench] generated {w.name}: {w.m} x {w.n}, {a.nnz} stored entries in {time.perf_counter() - t0:.1f} s")
+    solver = P.SOLVER_CG if args.solver == "cg" else P.SOLVER_CHOLESKY
+    als = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
+                profile=True)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, device=dev)
+    csc = als.csr_to_csc(csr)
+    X0, T0 = W.init_factors(w)
+    X, T = torch.from_numpy(X0).to(dev), torch.from_numpy(T0).to(dev)
+    del X0
+
+    def sweep():
+        als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+
+    for _ in range(args.warmup):
+        sweep()
+    torch.cuda.synchronize()
+    als.profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sweep()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    sec_per_sweep = elapsed / args.steps
+    herm_ms, herm_n = als.kernel_time(P.K_HERMITIAN)
+    solve_ms, solve_n = als.kernel_time(P.K_SOLVE)
+    als.synchronize()
+    rmse = als.rmse(csr, X, T)
+    log(f"[bench] {args.steps} sweeps in {elapsed:.3f} s; rmse {rmse:.5f}; hermitian {herm_ms / args.steps:.2f} ms "
+        f"and solve {solve_ms / args.steps:.2f} ms per sweep ({herm_n // args.steps} + {solve_n // args.steps} launches)")
+
+    # get_hermitian roofline: algorithmic flops = N_z * f * (f+1) per half-sweep (lower triangle, FMA = 2)
+    flops_per_sweep = 2.0 * w.nnz * w.f * (w.f + 1)
+    herm_s_per_sweep = herm_ms * 1e-3 / args.steps
+    achieved = flops_per_sweep / herm_s_per_sweep / 1e12
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "kernel": "k_hermitian", "launches_per_sweep": herm_n // args.steps,
+                "avg_launch_ms": herm_ms / max(herm_n, 1),
+                "flops_per_launch": flops_per_sweep / max(herm_n // args.steps, 1)}
+    out = {
+        "metric": "seconds per ALS sweep (X+Theta) at f=100", "value": sec_per_sweep, "unit": "s/sweep",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={w.nnz} f={w.f} lambda={w.lam}",
+                   "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
+                   "chunk": als.cfg.chunk or 1024, "batch_slots": als.cfg.batch_slots or 32768},
+        "hermitian_tflops": achieved, "hermitian_ms_per_sweep": herm_ms / args.steps,
+        "solve_ms_per_sweep": solve_ms / args.steps, "train_rmse": rmse,
+        "roofline": roofline,
+    }
+    if args.cpu_stride > 0:
+        log("[bench] timing the CPU oracle on a sample ...")
+        out["cpu_baseline"] = cpu_baseline(w, a, args.cpu_stride)
+    else:
+        out["cpu_baseline"] = None
+    als.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
