@@ -73,7 +73,8 @@ typedef struct als_config {
     int32_t herm_dtype;   /* ALS_F32: storage type of A_u where it is materialised (Section 4.2)         */
     int32_t device;       /* HIP device ordinal                                                          */
     void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */
-    int32_t chunk;        /* stored entries per work item; longer rows are split (0 = default 1024)      */
+    int32_t chunk;        /* stored entries per work item, a power of two in [64, 2^20]; longer rows are
+                             split (0 = default 1024)                                                    */
     int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = default 32768)           */
     int32_t profile;      /* 1: bracket every kernel with HIP events (see als_kernel_time)               */
 } als_config;
@@ -134,7 +135,8 @@ int als_synchronize(als_ctx *ctx);
 #define ALS_K_SOLVE 1
 #define ALS_K_RMSE 2
 #define ALS_K_PLAN 3
-#define ALS_K_COUNT 4
+#define ALS_K_FUSED 4 /* get_hermitian and Algorithm 1 in one kernel (rows shorter than chunk, CG solver) */
+#define ALS_K_COUNT 5
 
 /* With config.profile = 1: total milliseconds and number of launches of one
  * kernel class since the last als_profile_reset, measured with HIP events on

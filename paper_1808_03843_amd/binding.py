@@ -17,7 +17,7 @@ from . import build as _build
 ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
 SOLVER_CHOLESKY, SOLVER_CG = 0, 1
 F32, BF16, F16 = 0, 1, 2
-K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN = 0, 1, 2, 3
+K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED = 0, 1, 2, 3, 4
 
 EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",

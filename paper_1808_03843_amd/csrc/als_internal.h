@@ -28,6 +28,7 @@ struct Plan {                     // per sparse matrix, built once and cached
     int32_t *task_chunk = nullptr;// DEVICE [ntasks]
     int32_t *task_off_host = nullptr; // HOST copy of task_off
     int64_t ntasks = 0;
+    int64_t split_pos = 0;        // perm positions [0, split_pos): rows with >= chunk entries (slot path)
 };
 
 // status word bits set by kernels
@@ -38,6 +39,15 @@ constexpr int kStatusNonFinite = 2;
 hipError_t launch_hermitian(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
                             int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
                             const float *val, const float *Theta, float *slots);
+
+hipError_t launch_hermitian_cg(int f, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                               const void *ptr, const int32_t *idx, const float *val, const float *Theta,
+                               float lambda, int fs, float eps, float *Xout, int *status);
+hipError_t launch_solve_cg_wave(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                float lambda, int fs, float eps, float *Xout, int *status);
+hipError_t launch_reduce_slots(int f, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
+                               int64_t task0, float *slots);
 
 hipError_t launch_solve(int f, int solver, int cg_iters, float cg_eps, bool ptr64, hipStream_t st,
                         const int32_t *perm, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,

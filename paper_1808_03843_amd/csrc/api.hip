@@ -112,8 +112,21 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     const bool p64 = a->ptr_is_64 != 0;
     HIP_TRY(ctx, hipMalloc(&p.perm, sizeof(int32_t) * (size_t)(m > 0 ? m : 1)));
     HIP_TRY(ctx, hipMalloc(&p.task_off, sizeof(int32_t) * (size_t)(m + 1)));
-    HIP_TRY(ctx, plan_bin_rows(p64, ctx->stream, m, a->ptr, kPlanClasses, p.perm, nullptr, &ctx->scratch,
-                               &ctx->scratch_bytes));
+    int32_t *class_start_dev = nullptr;
+    HIP_TRY(ctx, hipMalloc(&class_start_dev, sizeof(int32_t) * (kPlanClasses + 1)));
+    hipError_t eb = plan_bin_rows(p64, ctx->stream, m, a->ptr, kPlanClasses, p.perm, class_start_dev, &ctx->scratch,
+                                  &ctx->scratch_bytes);
+    int32_t class_start[kPlanClasses + 1];
+    if (eb == hipSuccess)
+        eb = hipMemcpyAsync(class_start, class_start_dev, sizeof(class_start), hipMemcpyDeviceToHost, ctx->stream);
+    if (eb == hipSuccess) eb = hipStreamSynchronize(ctx->stream);
+    (void)hipFree(class_start_dev);
+    HIP_TRY(ctx, eb);
+    {   // rows with >= chunk = 2^j entries are the classes >= j+1, i.e. the first class_start[...] positions
+        int j = 0;
+        while ((1 << j) < ctx->cfg.chunk) ++j;
+        p.split_pos = class_start[kPlanClasses - 1 - j];
+    }
     HIP_TRY(ctx, plan_tasks(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, &ctx->scratch,
                             &ctx->scratch_bytes));
     p.task_off_host = new (std::nothrow) int32_t[(size_t)m + 1];
@@ -159,20 +172,20 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const int64_t cap = ctx->cfg.batch_slots;
     const bool p64 = a->ptr_is_64 != 0;
     const int32_t *off = p->task_off_host;
-    int64_t pos = 0;
     const int64_t m = a->nrows;
-    // widest row decides the minimum number of slots
-    while (pos < m) {
+    const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
+    // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
+    // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
+    const int64_t slot_rows = cg ? p->split_pos : m;
+    int64_t pos = 0;
+    while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
-        int64_t end = pos + 1;
-        {
-            int64_t lo = pos + 1, hi = m;   // largest end with off[end]-off[pos] <= cap
-            while (lo < hi) {
-                const int64_t mid = (lo + hi + 1) >> 1;
-                if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
-            }
-            end = lo;
+        int64_t lo = pos + 1, hi = slot_rows;   // largest end with off[end]-off[pos] <= cap
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
         }
+        const int64_t end = lo;
         const int64_t task0 = off[pos], ntasks = (int64_t)off[end] - off[pos];
         rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1);
         if (rc != ALS_OK) return rc;
@@ -183,11 +196,24 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         }
         {
             Timed t(ctx, ALS_K_SOLVE);
-            HIP_TRY(ctx, launch_solve(f, ctx->cfg.solver, ctx->cfg.cg_iters, ctx->cfg.cg_eps, p64, ctx->stream,
-                                      p->perm, p->task_off, pos, end - pos, task0, a->ptr, ctx->slots, lambda, Out,
-                                      ctx->status));
+            if (ntasks > end - pos)   // some row of the batch has several slots
+                HIP_TRY(ctx, launch_reduce_slots(f, ctx->stream, p->task_off, pos, end - pos, task0, ctx->slots));
+            if (cg)
+                HIP_TRY(ctx, launch_solve_cg_wave(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
+                                                  a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
+                                                  Out, ctx->status));
+            else
+                HIP_TRY(ctx, launch_solve(f, ctx->cfg.solver, ctx->cfg.cg_iters, ctx->cfg.cg_eps, p64, ctx->stream,
+                                          p->perm, p->task_off, pos, end - pos, task0, a->ptr, ctx->slots, lambda,
+                                          Out, ctx->status));
         }
         pos = end;
+    }
+    if (slot_rows < m) {
+        Timed t(ctx, ALS_K_FUSED);
+        HIP_TRY(ctx, launch_hermitian_cg(f, p64, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
+                                         a->val, (const float *)G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
+                                         ctx->status));
     }
     return ALS_OK;
 }
@@ -204,6 +230,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (cfg->solver == ALS_SOLVER_CG && cfg->cg_iters < 0) return ALS_EINVAL;
     if (cfg->factor_dtype != ALS_F32 || cfg->herm_dtype != ALS_F32) return ALS_EINVAL;
     if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
+    if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return ALS_EHIP;
     als_ctx *ctx = new (std::nothrow) als_ctx();

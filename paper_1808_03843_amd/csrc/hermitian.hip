@@ -1,28 +1,23 @@
 // get_hermitian + get_bias (Section 2, step (i); Section 3): the gathered, batched SYRK
 //     A_u = sum_{v in Omega_u} theta_v theta_v^T,   b_u = sum_{v in Omega_u} r_uv theta_v
-// on the fp32 matrix cores of gfx950.
+// on the fp32 matrix cores of gfx950, and its fusion with the approximate solver (Section 4.1).
 //
 // One wavefront owns one work item (a row, or a chunk of a long row) and keeps the whole lower
 // triangle of A_u in MFMA accumulators: the paper keeps A_u in registers because it is the most
 // reused operand (Section 3, Solution 1); here "registers" are the 16x16 accumulator tiles of
-// v_mfma_f32_16x16x4_f32.  The K dimension of the MFMA runs over stored entries (4 per
-// instruction), M and N both index features, so the A operand of tile row R and the B operand of
-// tile column C are the same kind of register: lane l holds theta_{v(l/16)}[16*tile + l%16].
-// theta rows are gathered straight into those operand registers (no staging buffer): every
-// theta element is used by exactly one wavefront, so there is nothing to share through LDS, and a
-// register double buffer hides the gather latency.
-#include "als_internal.h"
+// v_mfma_f32_16x16x4_f32.  theta rows are gathered straight into the operand registers (no staging
+// buffer): every theta element is used by exactly one wavefront, so there is nothing to share
+// through LDS, and a register double buffer hides the gather latency.
+//
+//   k_hermitian        work items of long rows: the partial A_u, b_u go to a slot in memory.
+//   k_hermitian_cg     whole short rows: A_u never leaves the registers; the same wavefront runs
+//                      Algorithm 1 on the accumulator tiles and writes x_u (the paper flushes A_u to
+//                      global memory and reads it back in the solver, Section 3 and Observation 4).
+//   k_reduce_slots     sums the slots of a split row into its first slot, in slot order.
+//   k_solve_cg_wave    Algorithm 1 for rows whose A_u sits in a slot, one wavefront per row.
+#include "tiles.h"
 
 namespace als {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-// acc += a (16x4, one stored entry per 16 lanes) * b (4x16).  Written as an in-place instruction on
-// an accumulation register so that the 112 accumulators of f = 100 stay where they are across
-// the loop (the builtin form let the register allocator shuffle them through copies).
-__device__ __forceinline__ void mfma_16x16x4(v4f &acc, float a, float b) {
-    asm("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
 
 template <int F, typename PtrT>
 __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
@@ -32,16 +27,13 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
                                                   float *__restrict__ slots) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
     const int lane = threadIdx.x;
-    const int i = lane & 15;   // feature inside a tile
-    const int kq = lane >> 4;  // which of the 4 stored entries of a step
     const int64_t t = blockIdx.x;
     const int row = task_row[task0 + t];
     const int ch = task_chunk[task0 + t];
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
     const int64_t s0 = rs + (int64_t)ch * chunk;
     const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);
-    const int nsteps = (len + 3) >> 2;
+    const int len = (int)(s1 - s0);   // >= 1: rows without entries have no work items
 
     v4f acc[NTILES];
 #pragma unroll
@@ -49,71 +41,8 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
     float bacc[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) bacc[q] = 0.f;
+    accumulate_tiles<F, false>(idx, val, Theta, s0, len, acc, bacc);
 
-    // Software pipeline, every load unconditional (addresses clamped into the work item, the
-    // values masked when they are consumed) so that the loop body is straight-line code:
-    //   iteration s issues the (column id, rating) loads of step s+2, the theta gathers of
-    //   step s+1, and runs the MFMAs of step s.
-    const bool last_tile_ok = (16 * (NT - 1) + i) < F;
-    const int fclamp = last_tile_ok ? 16 * (NT - 1) + i : F - 1;
-    auto entry = [&](int step) {  // stored entry of this lane in a step, clamped
-        const int e = 4 * step + kq;
-        return e < len ? e : len - 1;
-    };
-    auto gather = [&](int c, float (&g)[NT]) {
-        const float *p = Theta + (int64_t)c * F;
-#pragma unroll
-        for (int q = 0; q < NT - 1; ++q) g[q] = p[16 * q + i];
-        g[NT - 1] = p[fclamp];
-    };
-
-    float gn[NT];
-    int cn2;
-    float rn, rn2;
-    {
-        const int e0 = entry(0);
-        const int c0 = idx[s0 + e0];
-        rn = val[s0 + e0];
-        const int e1 = entry(1);
-        cn2 = idx[s0 + e1];
-        rn2 = val[s0 + e1];
-        gather(c0, gn);
-    }
-    for (int s = 0; s < nsteps; ++s) {
-        // (1) column id / rating of step s+2
-        const int e2 = entry(s + 2);
-        const int c_far = idx[s0 + e2];
-        const float r_far = val[s0 + e2];
-        // Keeps the two loads above in this iteration: without it the compiler folds the
-        // loop-carried value into a load at the top of the NEXT iteration, which puts a full
-        // memory latency in front of every gather.
-        asm volatile("" ::: "memory");
-        // (2) operands of step s (loaded one iteration ago), masked
-        const bool ok = (4 * s + kq) < len;
-        float g[NT];
-#pragma unroll
-        for (int q = 0; q < NT - 1; ++q) g[q] = ok ? gn[q] : 0.f;
-        g[NT - 1] = (ok && last_tile_ok) ? gn[NT - 1] : 0.f;
-        const float r = ok ? rn : 0.f;
-        // (3) gathers of step s+1
-        gather(cn2, gn);
-        rn = rn2;
-        cn2 = c_far;
-        rn2 = r_far;
-        // (4) MFMAs of step s, kept behind the loads issued above
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
-#pragma unroll
-        for (int R = 0; R < NT; ++R)
-#pragma unroll
-            for (int C = 0; C <= R; ++C)
-                mfma_16x16x4(acc[R * (R + 1) / 2 + C], g[R], g[C]);
-    }
-
-    // The MFMAs above are opaque to the compiler's hazard recogniser: leave the matrix pipeline
-    // time to retire the last accumulator writes before they are read (8 passes = 32 cycles + margin).
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
     float *out = slots + t * (int64_t)SLOT;
 #pragma unroll
     for (int q = 0; q < NTILES; ++q)
@@ -121,39 +50,206 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
         for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
 #pragma unroll
     for (int q = 0; q < NT; ++q) {
-        float v = bacc[q];
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        if (kq == 0) out[NTILES * 256 + 16 * q + i] = v;
+        const float v = colsum4(bacc[q]);
+        if (lane < 16) out[NTILES * 256 + 16 * q + lane] = v;
     }
 }
 
+// x (column layout) <-> memory
 template <int F>
-static hipError_t launch_f(bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                           int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
-                           const float *val, const float *Theta, float *slots) {
+__device__ __forceinline__ void load_vec(const float *__restrict__ src, float (&x)[tiles_1d(F)]) {
+    const int c = threadIdx.x & 15;
+#pragma unroll
+    for (int q = 0; q < tiles_1d(F); ++q) x[q] = (16 * q + c < F) ? src[16 * q + c] : 0.f;
+}
+template <int F>
+__device__ __forceinline__ void store_vec(float *__restrict__ dst, const float (&x)[tiles_1d(F)], int *status) {
+    const int lane = threadIdx.x & 63;
+    bool bad = false;
+#pragma unroll
+    for (int q = 0; q < tiles_1d(F); ++q)
+        if (lane < 16 && 16 * q + lane < F) {
+            dst[16 * q + lane] = x[q];
+            bad |= !isfinite(x[q]);
+        }
+    if (bad) atomicOr(status, kStatusNonFinite);
+}
+
+template <int F, typename PtrT>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3 : 2, F <= 100 ? 3 : 2))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
+                                                     const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                     const float *__restrict__ val, const float *__restrict__ Theta,
+                                                     float lambda, int fs, float eps, float *__restrict__ Xout,
+                                                     int *__restrict__ status) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F);
+    const int lane = threadIdx.x;
+    const int row = perm[pos0 + blockIdx.x];
+    const int64_t s0 = (int64_t)ptr[row];
+    const int len = (int)((int64_t)ptr[row + 1] - s0);
+    float *xg = Xout + (int64_t)row * F;
+    if (len == 0) {   // no observation: x_u = 0
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16 && 16 * q + lane < F) xg[16 * q + lane] = 0.f;
+        return;
+    }
+    v4f acc[NTILES];
+#pragma unroll
+    for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    float b[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) b[q] = 0.f;
+    accumulate_tiles<F, true>(idx, val, Theta, s0, len, acc, b);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) b[q] = colsum4(b[q]);
+    add_diagonal<F>(acc, lambda * (float)len);
+    float x[NT];
+    load_vec<F>(xg, x);
+    cg_tiles<F>(acc, b, x, fs, eps);
+    store_vec<F>(xg, x, status);
+}
+
+template <int F, typename PtrT>
+__global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict__ perm,
+                                                      const int32_t *__restrict__ task_off, int64_t pos0,
+                                                      int64_t task0, const PtrT *__restrict__ ptr,
+                                                      const float *__restrict__ slots, float lambda, int fs,
+                                                      float eps, float *__restrict__ Xout, int *__restrict__ status) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
+    const int lane = threadIdx.x, c = lane & 15;
+    const int64_t pos = pos0 + blockIdx.x;
+    const int row = perm[pos];
+    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+    float *xg = Xout + (int64_t)row * F;
+    if (n_u == 0) {
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16 && 16 * q + lane < F) xg[16 * q + lane] = 0.f;
+        return;
+    }
+    const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;
+    v4f acc[NTILES];
+#pragma unroll
+    for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[q][r] = slot[(q * 4 + r) * 64 + lane];
+    float b[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 256 + 16 * q + c];
+    add_diagonal<F>(acc, lambda * (float)n_u);
+    float x[NT];
+    load_vec<F>(xg, x);
+    cg_tiles<F>(acc, b, x, fs, eps);
+    store_vec<F>(xg, x, status);
+}
+
+// slots[first] += slots[first+1] + ... (in slot order) for every row of the batch with several slots
+template <int F>
+__global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict__ task_off, int64_t pos0,
+                                                      int64_t task0, float *__restrict__ slots) {
+    constexpr int SLOT = slot_floats(F);
+    const int64_t pos = pos0 + blockIdx.x;
+    const int first = task_off[pos] - (int)task0, n = task_off[pos + 1] - task_off[pos];
+    if (n <= 1) return;
+    const int o = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (o >= SLOT) return;
+    float4 *dst = reinterpret_cast<float4 *>(slots + (int64_t)first * SLOT + o);
+    float4 v = *dst;
+#pragma unroll 8
+    for (int s = 1; s < n; ++s) {
+        const float4 w = *reinterpret_cast<const float4 *>(slots + (int64_t)(first + s) * SLOT + o);
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+    }
+    *dst = v;
+}
+
+#define ALS_FOR_F(CALL)                       \
+    switch (f) {                              \
+        case 16: return CALL(16);             \
+        case 32: return CALL(32);             \
+        case 64: return CALL(64);             \
+        case 100: return CALL(100);           \
+        case 128: return CALL(128);           \
+        default: return hipErrorInvalidValue; \
+    }
+
+template <int F, typename PtrT>
+static hipError_t herm_f(hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
+                         int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
+                         const float *Theta, float *slots) {
     if (ntasks <= 0) return hipSuccess;
-    dim3 grid((unsigned)ntasks), block(64);
-    if (ptr64)
-        hipLaunchKernelGGL((k_hermitian<F, int64_t>), grid, block, 0, st, task_row, task_chunk, task0, chunk,
-                           (const int64_t *)ptr, idx, val, Theta, slots);
-    else
-        hipLaunchKernelGGL((k_hermitian<F, int32_t>), grid, block, 0, st, task_row, task_chunk, task0, chunk,
-                           (const int32_t *)ptr, idx, val, Theta, slots);
+    hipLaunchKernelGGL((k_hermitian<F, PtrT>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk, task0,
+                       chunk, (const PtrT *)ptr, idx, val, Theta, slots);
     return hipGetLastError();
 }
 
 hipError_t launch_hermitian(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
                             int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
                             const float *val, const float *Theta, float *slots) {
-    switch (f) {
-        case 16: return launch_f<16>(ptr64, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
-        case 32: return launch_f<32>(ptr64, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
-        case 64: return launch_f<64>(ptr64, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
-        case 100: return launch_f<100>(ptr64, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
-        case 128: return launch_f<128>(ptr64, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
-        default: return hipErrorInvalidValue;
-    }
+#define CALL(FF)                                                                                              \
+    (ptr64 ? herm_f<FF, int64_t>(st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots) \
+           : herm_f<FF, int32_t>(st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots))
+    ALS_FOR_F(CALL)
+#undef CALL
+}
+
+template <int F, typename PtrT>
+static hipError_t herm_cg_f(hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
+                            const int32_t *idx, const float *val, const float *Theta, float lambda, int fs, float eps,
+                            float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    hipLaunchKernelGGL((k_hermitian_cg<F, PtrT>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
+                       (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_hermitian_cg(int f, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                               const void *ptr, const int32_t *idx, const float *val, const float *Theta,
+                               float lambda, int fs, float eps, float *Xout, int *status) {
+#define CALL(FF)                                                                                             \
+    (ptr64 ? herm_cg_f<FF, int64_t>(st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
+           : herm_cg_f<FF, int32_t>(st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
+    ALS_FOR_F(CALL)
+#undef CALL
+}
+
+template <int F, typename PtrT>
+static hipError_t solve_wave_f(hipStream_t st, const int32_t *perm, const int32_t *task_off, int64_t pos0,
+                               int64_t npos, int64_t task0, const void *ptr, const float *slots, float lambda, int fs,
+                               float eps, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off, pos0, task0,
+                       (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_solve_cg_wave(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                float lambda, int fs, float eps, float *Xout, int *status) {
+#define CALL(FF)                                                                                                   \
+    (ptr64 ? solve_wave_f<FF, int64_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+                                       status)                                                                     \
+           : solve_wave_f<FF, int32_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+                                       status))
+    ALS_FOR_F(CALL)
+#undef CALL
+}
+
+template <int F>
+static hipError_t reduce_f(hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
+                           float *slots) {
+    if (npos <= 0) return hipSuccess;
+    constexpr int SLOT = slot_floats(F);
+    hipLaunchKernelGGL((k_reduce_slots<F>), dim3((unsigned)npos, (SLOT / 4 + 255) / 256), dim3(256), 0, st, task_off,
+                       pos0, task0, slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_slots(int f, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
+                               int64_t task0, float *slots) {
+#define CALL(FF) reduce_f<FF>(st, task_off, pos0, npos, task0, slots)
+    ALS_FOR_F(CALL)
+#undef CALL
 }
 
 }  // namespace als

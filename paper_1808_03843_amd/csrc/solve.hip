@@ -1,12 +1,9 @@
-// Step (ii) of Section 2 ("solve"): x_u = A_u^-1 b_u for a batch of rows whose A_u, b_u were
-// accumulated into work-item slots by the get_hermitian kernel.  One workgroup per system.
-//   - exact: LDL^T factorisation of the bordered matrix [A b; b^T .] in LDS (the paper's exact
-//     baseline is a batched LU, Section 4.1; A_u is symmetric positive definite, so the
-//     symmetric factorisation gives the same solution with half the work),
-//   - approximate: Algorithm 1 (CGSolve), f_s iterations warm-started from the current x_u,
-//     each thread keeping one row of A_u in registers.
-// A row that was split into several work items has its partial Gram matrices summed here, in
-// work-item order (deterministic).
+// Step (ii) of Section 2 ("solve"), exact: x_u = A_u^-1 b_u for a batch of rows whose A_u, b_u were
+// accumulated into work-item slots by the get_hermitian kernel.  One workgroup per system: LDL^T
+// factorisation of the bordered matrix [A b; b^T .] in LDS (the paper's exact baseline is a batched
+// LU, Section 4.1; A_u is symmetric positive definite, so the symmetric factorisation gives the same
+// solution with half the work).  Algorithm 1, the approximate solver, lives with the get_hermitian
+// kernels because it runs on their accumulator tiles.
 #include "als_internal.h"
 
 namespace als {
@@ -66,8 +63,9 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
         for (int q = threadIdx.x; q < F; q += blockDim.x) x[q] = 0.f;
         return;
     }
-    const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
-    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, As + F * LD);
+    const int first = task_off[pos] - (int)task0;
+    // the slots of a split row have been summed into its first slot by k_reduce_slots
+    load_system<F, LD>(slots + (int64_t)first * SLOT, 1, lambda * (float)n_u, As, As + F * LD);
 
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     bool bad = false;
@@ -113,95 +111,6 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
     }
 }
 
-// ---- Algorithm 1 -------------------------------------------------------------------------------
-template <int NW>
-__device__ __forceinline__ float block_sum(float v, float *red) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    if (NW == 1) return v;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float s = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
-    return s;
-}
-
-template <int F, typename PtrT>
-__global__ __launch_bounds__(128) void k_solve_cg(const int32_t *__restrict__ perm,
-                                                  const int32_t *__restrict__ task_off, int64_t pos0, int64_t task0,
-                                                  const PtrT *__restrict__ ptr, const float *__restrict__ slots,
-                                                  float lambda, int fs, float eps, float *__restrict__ Xout,
-                                                  int *__restrict__ status) {
-    constexpr int LD = F + 1, SLOT = slot_floats(F), NW = 2;
-    constexpr int FP = (F + 3) & ~3;
-    __shared__ float As[F * LD];
-    __shared__ float bs[FP];
-    __shared__ __attribute__((aligned(16))) float ps[FP];
-    __shared__ float red[NW];
-    const int64_t pos = pos0 + blockIdx.x;
-    const int row = perm[pos];
-    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
-    float *xg = Xout + (int64_t)row * F;
-    const int i = threadIdx.x;
-    if (n_u == 0) {
-        if (i < F) xg[i] = 0.f;
-        return;
-    }
-    const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
-    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, bs);
-    const bool act = i < F;
-    float x = act ? xg[i] : 0.f;
-    if (i < FP) ps[i] = x;
-    __syncthreads();
-    // row i of the symmetric A in registers: A[i][j] = As[max][min]
-    float a[FP];
-#pragma unroll
-    for (int j = 0; j < FP; ++j) {
-        float v = 0.f;
-        if (act && j < F) v = (j <= i) ? As[i * LD + j] : As[j * LD + i];
-        a[j] = v;
-    }
-    auto matvec = [&]() {  // A * ps, this thread's row
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-        for (int j = 0; j < FP; j += 4) {
-            const float4 p4 = *reinterpret_cast<const float4 *>(&ps[j]);
-            s0 = fmaf(a[j], p4.x, s0);
-            s1 = fmaf(a[j + 1], p4.y, s1);
-            s2 = fmaf(a[j + 2], p4.z, s2);
-            s3 = fmaf(a[j + 3], p4.w, s3);
-        }
-        return (s0 + s1) + (s2 + s3);
-    };
-    // r = b - A x;  p = r;  rs_old = r^T r
-    float r = act ? bs[i] - matvec() : 0.f;
-    float p = r;
-    float rs_old = block_sum<NW>(r * r, red);
-    if (rs_old > 0.f) {
-        for (int it = 0; it < fs; ++it) {
-            __syncthreads();
-            if (i < FP) ps[i] = p;
-            __syncthreads();
-            const float ap = act ? matvec() : 0.f;
-            const float pap = block_sum<NW>(p * ap, red);
-            if (!(pap > 0.f) || !isfinite(pap)) break;
-            const float alpha = rs_old / pap;
-            x = fmaf(alpha, p, x);
-            r = fmaf(-alpha, ap, r);
-            const float rs_new = block_sum<NW>(r * r, red);
-            if (sqrtf(rs_new) < eps) break;
-            p = fmaf(rs_new / rs_old, p, r);
-            rs_old = rs_new;
-        }
-    }
-    if (act) {
-        xg[i] = x;
-        if (!isfinite(x)) atomicOr(status, kStatusNonFinite);
-    }
-}
-
 // ---- dense export (tests, breakdown runs) -----------------------------------------------------
 template <int F, typename PtrT>
 __global__ __launch_bounds__(256) void k_export_dense(const int32_t *__restrict__ perm,
@@ -232,11 +141,9 @@ static hipError_t solve_f(int solver, int cg_iters, float cg_eps, hipStream_t st
                           const float *slots, float lambda, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
     dim3 grid((unsigned)npos);
-    if (solver == ALS_SOLVER_CG)
-        hipLaunchKernelGGL((k_solve_cg<F, PtrT>), grid, dim3(128), 0, st, perm, task_off, pos0, task0,
-                           (const PtrT *)ptr, slots, lambda, cg_iters, cg_eps, Xout, status);
-    else
-        hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(256), 0, st, perm, task_off, pos0, task0,
+    (void)cg_iters; (void)cg_eps;
+    if (solver != ALS_SOLVER_CHOLESKY) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(256), 0, st, perm, task_off, pos0, task0,
                            (const PtrT *)ptr, slots, lambda, Xout, status);
     return hipGetLastError();
 }
