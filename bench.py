@@ -136,7 +136,7 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={w.nnz} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
-                   "chunk": chunk, "batch_slots": als.cfg.batch_slots or 32768},
+                   "chunk": chunk, "batch_slots": als.cfg.batch_slots or 131072},
         "hermitian_tflops": achieved, "hermitian_ms_per_sweep": (herm_ms + fused_ms) / K,
         "solve_ms_per_sweep": solve_ms / K, "train_rmse": rmse,
         "roofline": roofline,

@@ -47,8 +47,10 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.LIB
+    path = os.environ.get("ALS_LIBRARY", _build.LIB)   # ALS_LIBRARY: an alternative build, for tuning runs
     if not os.path.exists(path):
+        if path != _build.LIB:
+            raise FileNotFoundError(path)
         _build.build()
     lib = ctypes.CDLL(path)
     vp, i32, i64, fl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float

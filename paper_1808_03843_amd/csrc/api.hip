@@ -174,6 +174,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const int32_t *off = p->task_off_host;
     const int64_t m = a->nrows;
     const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
+    const bool wide = (uint64_t)a->ncols * (uint64_t)f * sizeof(float) >= (1ull << 32);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
     const int64_t slot_rows = cg ? p->split_pos : m;
@@ -191,7 +192,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         if (rc != ALS_OK) return rc;
         {
             Timed t(ctx, ALS_K_HERMITIAN);
-            HIP_TRY(ctx, launch_hermitian(f, p64, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
+            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
                                           ctx->cfg.chunk, a->ptr, a->idx, a->val, (const float *)G, ctx->slots));
         }
         {
@@ -211,7 +212,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     }
     if (slot_rows < m) {
         Timed t(ctx, ALS_K_FUSED);
-        HIP_TRY(ctx, launch_hermitian_cg(f, p64, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
+        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
                                          a->val, (const float *)G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
                                          ctx->status));
     }
@@ -237,7 +238,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (!ctx) return ALS_ENOMEM;
     ctx->cfg = *cfg;
     if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 1024;
-    if (ctx->cfg.batch_slots == 0) ctx->cfg.batch_slots = 32768;
+    if (ctx->cfg.batch_slots == 0) ctx->cfg.batch_slots = 131072;
     ctx->stream = (hipStream_t)cfg->stream;
     if (hipSetDevice(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
         hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
@@ -315,6 +316,7 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     // a throw-away plan over the row range, in natural order
     const bool p64 = csr->ptr_is_64 != 0;
+    const bool wide = (uint64_t)csr->ncols * (uint64_t)f * sizeof(float) >= (1ull << 32);
     int32_t *perm = nullptr, *task_off = nullptr, *task_row = nullptr, *task_chunk = nullptr;
     auto cleanup = [&]() { hipFree(perm); hipFree(task_off); hipFree(task_row); hipFree(task_chunk); };
     hipError_t e;
@@ -345,7 +347,7 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     if (rc != ALS_OK) { cleanup(); return rc; }
     {
         Timed t(ctx, ALS_K_HERMITIAN);
-        e = launch_hermitian(f, p64, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
+        e = launch_hermitian(f, p64, wide, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
                              csr->val, (const float *)Theta, ctx->slots);
     }
     if (e == hipSuccess)

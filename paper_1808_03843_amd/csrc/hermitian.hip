@@ -19,7 +19,23 @@
 
 namespace als {
 
-template <int F, typename PtrT>
+// gather pipeline depth (register sets of theta operands in flight per wavefront)
+#ifndef ALS_DEPTH_SLOTS
+#define ALS_DEPTH_SLOTS 3
+#endif
+#ifndef ALS_DEPTH_FUSED
+#define ALS_DEPTH_FUSED 2
+#endif
+constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
+
+// a value that is the same in every lane, moved to scalar registers
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+template <int F, typename PtrT, bool WIDE>
 __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
                                                   const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
@@ -38,10 +54,8 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
     v4f acc[NTILES];
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float bacc[NT];
-#pragma unroll
-    for (int q = 0; q < NT; ++q) bacc[q] = 0.f;
-    accumulate_tiles<F, false>(idx, val, Theta, s0, len, acc, bacc);
+    float b[NT];
+    accumulate_tiles<F, false, kDepthSlots, WIDE>(idx, val, Theta, uniform64(s0), len, acc, b);
 
     float *out = slots + t * (int64_t)SLOT;
 #pragma unroll
@@ -49,10 +63,8 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
 #pragma unroll
         for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
 #pragma unroll
-    for (int q = 0; q < NT; ++q) {
-        const float v = colsum4(bacc[q]);
-        if (lane < 16) out[NTILES * 256 + 16 * q + lane] = v;
-    }
+    for (int q = 0; q < NT; ++q)
+        if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
 }
 
 // x (column layout) <-> memory
@@ -75,7 +87,7 @@ __device__ __forceinline__ void store_vec(float *__restrict__ dst, const float (
     if (bad) atomicOr(status, kStatusNonFinite);
 }
 
-template <int F, typename PtrT>
+template <int F, typename PtrT, bool WIDE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3 : 2, F <= 100 ? 3 : 2))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
                                                      const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                      const float *__restrict__ val, const float *__restrict__ Theta,
@@ -97,11 +109,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-#pragma unroll
-    for (int q = 0; q < NT; ++q) b[q] = 0.f;
-    accumulate_tiles<F, true>(idx, val, Theta, s0, len, acc, b);
-#pragma unroll
-    for (int q = 0; q < NT; ++q) b[q] = colsum4(b[q]);
+    accumulate_tiles<F, true, kDepthFused, WIDE>(idx, val, Theta, uniform64(s0), len, acc, b);
     add_diagonal<F>(acc, lambda * (float)len);
     float x[NT];
     load_vec<F>(xg, x);
@@ -174,41 +182,49 @@ __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict_
     }
 
 template <int F, typename PtrT>
-static hipError_t herm_f(hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
+static hipError_t herm_f(bool wide, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
                          int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
                          const float *Theta, float *slots) {
     if (ntasks <= 0) return hipSuccess;
-    hipLaunchKernelGGL((k_hermitian<F, PtrT>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk, task0,
-                       chunk, (const PtrT *)ptr, idx, val, Theta, slots);
+    if (wide)
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, true>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row,
+                           task_chunk, task0, chunk, (const PtrT *)ptr, idx, val, Theta, slots);
+    else
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, false>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row,
+                           task_chunk, task0, chunk, (const PtrT *)ptr, idx, val, Theta, slots);
     return hipGetLastError();
 }
 
-hipError_t launch_hermitian(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                            int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
-                            const float *val, const float *Theta, float *slots) {
-#define CALL(FF)                                                                                              \
-    (ptr64 ? herm_f<FF, int64_t>(st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots) \
-           : herm_f<FF, int32_t>(st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots))
+hipError_t launch_hermitian(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+                            const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                            const int32_t *idx, const float *val, const float *Theta, float *slots) {
+#define CALL(FF)                                                                                                    \
+    (ptr64 ? herm_f<FF, int64_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots) \
+           : herm_f<FF, int32_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots))
     ALS_FOR_F(CALL)
 #undef CALL
 }
 
 template <int F, typename PtrT>
-static hipError_t herm_cg_f(hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
-                            const int32_t *idx, const float *val, const float *Theta, float lambda, int fs, float eps,
-                            float *Xout, int *status) {
+static hipError_t herm_cg_f(bool wide, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                            const void *ptr, const int32_t *idx, const float *val, const float *Theta, float lambda,
+                            int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    hipLaunchKernelGGL((k_hermitian_cg<F, PtrT>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
-                       (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
+    if (wide)
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, true>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
+                           (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
+    else
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, false>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
+                           (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
-hipError_t launch_hermitian_cg(int f, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
-                               const void *ptr, const int32_t *idx, const float *val, const float *Theta,
-                               float lambda, int fs, float eps, float *Xout, int *status) {
-#define CALL(FF)                                                                                             \
-    (ptr64 ? herm_cg_f<FF, int64_t>(st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
-           : herm_cg_f<FF, int32_t>(st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
+hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
+                               int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                               const float *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
+#define CALL(FF)                                                                                                     \
+    (ptr64 ? herm_cg_f<FF, int64_t>(wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
+           : herm_cg_f<FF, int32_t>(wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
     ALS_FOR_F(CALL)
 #undef CALL
 }

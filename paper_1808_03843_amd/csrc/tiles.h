@@ -1,6 +1,9 @@
 // Device code shared by the get_hermitian kernels: the gathered SYRK main loop on fp32 MFMA
 // accumulator tiles, and Algorithm 1 (CGSolve) run by one wavefront directly on those tiles.
 #pragma once
+#include <type_traits>
+#include <utility>
+
 #include "als_internal.h"
 
 namespace als {
@@ -23,81 +26,6 @@ __device__ __forceinline__ void mfma_16x16x4(v4f &acc, float a, float b) {
 // retire the last accumulator writes before they are read (8 passes = 32 cycles, plus margin).
 __device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
 
-// A_u (lower-triangle tiles) and b_u (per-lane partial sums, one stored entry slot kq per 16 lanes)
-// of the stored entries [s0, s0+len) of one row.  Section 2 step (i): get_hermitian and get_bias.
-//
-// Software pipeline with every load unconditional (addresses clamped into the work item, values
-// masked when consumed) so that the loop body is straight-line code: iteration s issues the
-// (column id, rating) loads of step s+2 and the theta gathers of step s+1, and runs the MFMAs of
-// step s.  Lane l supplies theta_{v(l/16)}[16*tile + l%16] both as the A operand of tile row
-// `tile` and as the B operand of tile column `tile`.
-template <int F, bool IN_VGPR>
-__device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
-                                                 const float *__restrict__ Theta, int64_t s0, int len,
-                                                 v4f (&acc)[tiles_tri(F)], float (&bacc)[tiles_1d(F)]) {
-    constexpr int NT = tiles_1d(F);
-    const int lane = threadIdx.x & 63;
-    const int i = lane & 15;   // feature inside a tile
-    const int kq = lane >> 4;  // which of the 4 stored entries of a step
-    const int nsteps = (len + 3) >> 2;
-    const bool last_tile_ok = (16 * (NT - 1) + i) < F;
-    const int fclamp = last_tile_ok ? 16 * (NT - 1) + i : F - 1;
-    auto entry = [&](int step) {  // stored entry of this lane in a step, clamped
-        const int e = 4 * step + kq;
-        return e < len ? e : len - 1;
-    };
-    auto gather = [&](int c, float (&g)[NT]) {
-        const float *p = Theta + (int64_t)c * F;
-#pragma unroll
-        for (int q = 0; q < NT - 1; ++q) g[q] = p[16 * q + i];
-        g[NT - 1] = p[fclamp];
-    };
-
-    float gn[NT];
-    int cn2;
-    float rn, rn2;
-    {
-        const int e0 = entry(0);
-        const int c0 = idx[s0 + e0];
-        rn = val[s0 + e0];
-        const int e1 = entry(1);
-        cn2 = idx[s0 + e1];
-        rn2 = val[s0 + e1];
-        gather(c0, gn);
-    }
-    for (int s = 0; s < nsteps; ++s) {
-        // (1) column id / rating of step s+2
-        const int e2 = entry(s + 2);
-        const int c_far = idx[s0 + e2];
-        const float r_far = val[s0 + e2];
-        // Keeps the two loads above in this iteration: without it the compiler folds the loop-carried
-        // value into a load at the top of the NEXT iteration, which puts a full memory latency in
-        // front of every gather.
-        asm volatile("" ::: "memory");
-        // (2) operands of step s (loaded one iteration ago), masked
-        const bool ok = (4 * s + kq) < len;
-        float g[NT];
-#pragma unroll
-        for (int q = 0; q < NT - 1; ++q) g[q] = ok ? gn[q] : 0.f;
-        g[NT - 1] = (ok && last_tile_ok) ? gn[NT - 1] : 0.f;
-        const float r = ok ? rn : 0.f;
-        // (3) gathers of step s+1
-        gather(cn2, gn);
-        rn = rn2;
-        cn2 = c_far;
-        rn2 = r_far;
-        // (4) MFMAs of step s, kept behind the loads issued above
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
-#pragma unroll
-        for (int R = 0; R < NT; ++R)
-#pragma unroll
-            for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[R * (R + 1) / 2 + C], g[R], g[C]);
-    }
-    mfma_drain();
-}
-
 // ---- cross-lane helpers -----------------------------------------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
@@ -119,6 +47,173 @@ __device__ __forceinline__ float colsum4(float v) {
 }
 __device__ __forceinline__ float bperm(int byte_addr, float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(byte_addr, __builtin_bit_cast(int, v)));
+}
+
+// A_u (lower-triangle tiles) and b_u of the stored entries [s0, s0+len) of one row (len >= 1).
+// Section 2 step (i): get_hermitian and get_bias.
+//
+// Lane l = (i = l%16, kq = l/16) supplies theta_{v(kq)}[16*tile + i] both as the A operand of tile
+// row `tile` and as the B operand of tile column `tile`; one step consumes 4 stored entries.
+//
+// When F is not a multiple of 16 the last tile has spare lanes: lane i = F%16 carries the rating
+// r_uv, so row F of the accumulated matrix is b_u and get_bias costs no instruction; lanes beyond
+// it carry a finite filler (a clamped theta element) whose rows and columns are zeroed at the end.
+// Otherwise b_u is accumulated with one FMA per tile and step.
+//
+// Software pipeline: a ring of D+1 operand register sets.  Step t runs its MFMAs directly on set
+// t mod (D+1) while the gathers of step t+D land in the set that step t-1 used, and the
+// (column id, rating) loads run two steps further ahead.  Every load is unconditional (entries
+// are clamped into the work item); only the last steps of a work item, which may hold fewer than
+// 4 entries, go through a masked copy of the operands.  The vector ALU shares the issue port with
+// the matrix pipeline, so the full steps carry almost no ALU work: addresses are a scalar base
+// plus a 32-bit lane offset (WIDE = false; the factor matrix must be smaller than 4 GiB).
+template <int F>
+struct TileGeom {
+    static constexpr int NT = tiles_1d(F);
+    static constexpr bool RIT = (F % 16) != 0;   // rating rides in the last tile
+    static constexpr int RI = F % 16;            // its lane
+};
+
+template <int F, bool IN_VGPR, int D, bool WIDE>
+__device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                 const float *__restrict__ Theta, int64_t s0, int len,
+                                                 v4f (&acc)[tiles_tri(F)], float (&b)[tiles_1d(F)]) {
+    constexpr int NT = TileGeom<F>::NT, NB = D + 1;
+    constexpr bool RIT = TileGeom<F>::RIT;
+    constexpr int RI = TileGeom<F>::RI;
+    const int lane = threadIdx.x & 63;
+    const int i = lane & 15;
+    const int kq = lane >> 4;
+    const int32_t *__restrict__ ib = idx + s0;   // wave-uniform bases
+    const float *__restrict__ vb = val + s0;
+    const int nsteps = (len + 3) >> 2;
+    const int nmain = ((len >> 2) / NB) * NB;    // full steps handled by the unmasked rounds
+    const int last = len - 1;
+    const uint32_t off0 = 4u * (uint32_t)i;
+    const uint32_t offl = 4u * (uint32_t)((16 * (NT - 1) + i < F) ? 16 * (NT - 1) + i : F - 1);
+    auto entry = [&](int step) -> uint32_t {   // this lane's stored entry of a step, clamped into the item
+        const int e = 4 * step + kq;
+        return (uint32_t)(e < last ? e : last);
+    };
+    auto gather = [&](int c, float (&g)[NT]) {
+        if constexpr (WIDE) {
+            const char *p = reinterpret_cast<const char *>(Theta + (int64_t)c * F);
+#pragma unroll
+            for (int q = 0; q < NT - 1; ++q) g[q] = *reinterpret_cast<const float *>(p + off0 + 64 * q);
+            g[NT - 1] = *reinterpret_cast<const float *>(p + offl);
+        } else {
+            const char *base = reinterpret_cast<const char *>(Theta);
+            const uint32_t rowoff = (uint32_t)c * (uint32_t)(4 * F);
+            const uint32_t o0 = rowoff + off0, ol = rowoff + offl;
+#pragma unroll
+            for (int q = 0; q < NT - 1; ++q) g[q] = *reinterpret_cast<const float *>(base + o0 + 64 * q);
+            g[NT - 1] = *reinterpret_cast<const float *>(base + ol);
+        }
+    };
+
+    // Rings with compile-time slots (step j lives in slot j mod NB), so that no register is ever
+    // moved: a move of a value that is still in flight would make the compiler wait for it.
+    //   gbuf/rbuf  operands and rating of a step, loaded D steps ahead
+    //   cbuf       column id of a step, loaded IDA steps before its gather is issued
+    constexpr int IDA = D >= 2 ? 2 : 1, K = D + IDA;
+    float gbuf[NB][NT];
+    float rbuf[NB];
+    int cbuf[NB];
+    float bacc[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) bacc[q] = 0.f;
+    // Prologue in the order of the loop body (far ids first, then the gathers, oldest step first): the
+    // compiler's wait-count bookkeeping merges both paths at the loop head, and any other order makes
+    // it drain the outstanding gathers at the top of every round.
+#pragma unroll
+    for (int j = D; j < K; ++j) cbuf[j % NB] = ib[entry(j)];
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        const uint32_t e = entry(d);
+        rbuf[d] = vb[e];
+        gather(ib[e], gbuf[d]);
+        asm volatile("" ::: "memory");
+    }
+
+    // one step; MASKED = the step may hold fewer than 4 entries (or none)
+    auto step = [&](auto dtag, auto mtag, int t) {
+        constexpr int d = decltype(dtag)::value;
+        constexpr bool MASKED = decltype(mtag)::value;
+        constexpr int dn = (d + D) % NB;
+        // (1) column id of step t+K
+        cbuf[(d + K) % NB] = ib[entry(t + K)];
+        // keeps the load above here: the compiler would otherwise fold the carried value into a load
+        // at its use, putting a full memory latency in front of a gather
+        asm volatile("" ::: "memory");
+        // (2) gathers and rating of step t+D into the set that step t-1 has finished with
+        gather(cbuf[dn], gbuf[dn]);
+        rbuf[dn] = vb[entry(t + D)];
+        __builtin_amdgcn_sched_barrier(0);
+        // (3) MFMAs of step t
+        float g[NT];
+        float r = rbuf[d];
+        if constexpr (MASKED) {
+            const bool ok = (4 * t + kq) < len;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) g[q] = ok ? gbuf[d][q] : 0.f;
+            r = ok ? r : 0.f;
+        } else {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) g[q] = gbuf[d][q];
+        }
+        if constexpr (RIT) {
+            g[NT - 1] = (i == RI) ? r : g[NT - 1];
+        } else {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
+        }
+        if constexpr (MASKED || (RIT && NT < 3)) {
+            // An operand written by the vector ALU must not be read by an MFMA in the next few cycles,
+            // and the compiler, to which the MFMAs are opaque, does not keep that distance: wait here,
+            // and tie every operand to the wait so that no MFMA can be moved in front of it.
+            asm volatile("s_nop 7" : "+v"(g[0]));
+#pragma unroll
+            for (int q = 1; q < NT; ++q) asm volatile("" : "+v"(g[q]), "+v"(g[0]));
+        }
+#pragma unroll
+        for (int R = 0; R < NT; ++R)
+#pragma unroll
+            for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[R * (R + 1) / 2 + C], g[R], g[C]);
+    };
+    auto round = [&](auto mtag, int s, int limit) {
+        [&]<int... d>(std::integer_sequence<int, d...>) {
+            ((s + d < limit ? step(std::integral_constant<int, d>{}, mtag, s + d) : void()), ...);
+        }(std::make_integer_sequence<int, NB>{});
+    };
+    for (int s = 0; s < nmain; s += NB) {
+        [&]<int... d>(std::integer_sequence<int, d...>) {
+            (step(std::integral_constant<int, d>{}, std::false_type{}, s + d), ...);
+        }(std::make_integer_sequence<int, NB>{});
+    }
+    round(std::true_type{}, nmain, nsteps);   // at most NB steps remain
+    mfma_drain();
+
+    // b_u in column layout, and the filler rows / columns of the last tile zeroed
+    const int c = i, g4 = kq;
+    if constexpr (RIT) {
+        const int src = 4 * (16 * (RI / 4) + c);   // lane (c, g = RI/4) holds row RI of the last tile row
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            const float v = bperm(src, acc[(NT - 1) * NT / 2 + T][RI % 4]);
+            b[T] = (T < NT - 1 || c < RI) ? v : 0.f;
+        }
+#pragma unroll
+        for (int T = 0; T < NT; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool keep = (4 * g4 + r < RI) && (T < NT - 1 || c < RI);
+                acc[(NT - 1) * NT / 2 + T][r] = keep ? acc[(NT - 1) * NT / 2 + T][r] : 0.f;
+            }
+    } else {
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = colsum4(bacc[q]);
+    }
 }
 
 // Algorithm 1 (CGSolve) on one system held by one wavefront.
