@@ -12,9 +12,30 @@ namespace als {
 // register layout of v_mfma_f32_16x16x4_f32: lane l, register r of a tile holds the element
 // (row 4*(l/16)+r, column l%16).  A slot stores tile t = R(R+1)/2+C at float offset
 // (4t+r)*64 + l, followed by b_u padded to 16*NT floats.
+//
+// Tile coordinates are "virtual" indices v = 16*tile + lane: the features are permuted so that a
+// lane can fetch the operands of several tiles with one wide load.  With N4 = F/64 16-byte loads,
+// N2 = (F%64)/32 8-byte loads and N1 4-byte loads per theta row,
+//   tiles 4q..4q+3      (q < N4)   lane i holds features 64q + 4i + (0..3)
+//   the next 2*N2 tiles            lane i holds features 64*N4 + 2i + (0..1)
+//   the last N1 tiles              lane i holds feature  64*N4 + 32*N2 + 16k + i
+// A symmetric permutation of the Gram matrix: the solvers work in virtual coordinates, and only
+// the code that reads or writes factor rows and dense matrices converts.
 constexpr int tiles_1d(int F) { return (F + 15) / 16; }
 constexpr int tiles_tri(int F) { return tiles_1d(F) * (tiles_1d(F) + 1) / 2; }
 constexpr int slot_floats(int F) { return tiles_tri(F) * 256 + tiles_1d(F) * 16; }
+constexpr int loads16(int F) { return F / 64; }
+constexpr int loads8(int F) { return (F % 64) / 32; }
+constexpr int loads4(int F) { return tiles_1d(F) - 4 * loads16(F) - 2 * loads8(F); }
+// feature held by lane i of tile t, or -1 (filler / rating lane)
+__host__ __device__ constexpr int feature_of(int F, int t, int i) {
+    if (t < 4 * loads16(F)) return 64 * (t / 4) + 4 * i + (t % 4);
+    t -= 4 * loads16(F);
+    if (t < 2 * loads8(F)) return 64 * loads16(F) + 2 * i + t;
+    t -= 2 * loads8(F);
+    const int f = 64 * loads16(F) + 32 * loads8(F) + 16 * t + i;
+    return f < F ? f : -1;
+}
 
 constexpr int kWave = 64;
 

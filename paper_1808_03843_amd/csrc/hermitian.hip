@@ -67,24 +67,33 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
         if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
 }
 
-// x (column layout) <-> memory
+// x (column layout, virtual coordinates) <-> a factor row in memory
 template <int F>
 __device__ __forceinline__ void load_vec(const float *__restrict__ src, float (&x)[tiles_1d(F)]) {
     const int c = threadIdx.x & 15;
 #pragma unroll
-    for (int q = 0; q < tiles_1d(F); ++q) x[q] = (16 * q + c < F) ? src[16 * q + c] : 0.f;
+    for (int q = 0; q < tiles_1d(F); ++q) {
+        const int ft = feature_of(F, q, c);
+        x[q] = ft >= 0 ? src[ft] : 0.f;
+    }
 }
 template <int F>
 __device__ __forceinline__ void store_vec(float *__restrict__ dst, const float (&x)[tiles_1d(F)], int *status) {
     const int lane = threadIdx.x & 63;
     bool bad = false;
 #pragma unroll
-    for (int q = 0; q < tiles_1d(F); ++q)
-        if (lane < 16 && 16 * q + lane < F) {
-            dst[16 * q + lane] = x[q];
+    for (int q = 0; q < tiles_1d(F); ++q) {
+        const int ft = feature_of(F, q, lane & 15);
+        if (lane < 16 && ft >= 0) {
+            dst[ft] = x[q];
             bad |= !isfinite(x[q]);
         }
+    }
     if (bad) atomicOr(status, kStatusNonFinite);
+}
+template <int F>
+__device__ __forceinline__ void store_zero_vec(float *__restrict__ dst) {
+    for (int q = threadIdx.x; q < F; q += 64) dst[q] = 0.f;
 }
 
 template <int F, typename PtrT, bool WIDE>
@@ -100,9 +109,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3
     const int len = (int)((int64_t)ptr[row + 1] - s0);
     float *xg = Xout + (int64_t)row * F;
     if (len == 0) {   // no observation: x_u = 0
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-            if (lane < 16 && 16 * q + lane < F) xg[16 * q + lane] = 0.f;
+        store_zero_vec<F>(xg);
         return;
     }
     v4f acc[NTILES];
@@ -130,9 +137,7 @@ __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict_
     const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
     float *xg = Xout + (int64_t)row * F;
     if (n_u == 0) {
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-            if (lane < 16 && 16 * q + lane < F) xg[16 * q + lane] = 0.f;
+        store_zero_vec<F>(xg);
         return;
     }
     const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;

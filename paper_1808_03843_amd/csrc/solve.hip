@@ -16,8 +16,8 @@ __device__ __forceinline__ void tile_rc(int tile, int &R, int &C) {
     C = tile - r * (r + 1) / 2;
 }
 
-// Sums the slots of one row into a dense lower triangle As[row*LD + col] (col <= row < F) and
-// bs[0..F).  Adds reg to the diagonal.  Every thread of the block takes part.
+// Sums the slots of one row into a dense lower triangle As[row*LD + col] (col <= row < F, feature
+// coordinates) and bs[0..F).  Adds reg to the diagonal.  Every thread of the block takes part.
 template <int F, int LD>
 __device__ __forceinline__ void load_system(const float *__restrict__ slots, int nslots, float reg, float *As,
                                             float *bs) {
@@ -26,19 +26,22 @@ __device__ __forceinline__ void load_system(const float *__restrict__ slots, int
         const int tile = o >> 8, r = (o >> 6) & 3, l = o & 63;
         int R, C;
         tile_rc(tile, R, C);
-        const int row = 16 * R + 4 * (l >> 4) + r, col = 16 * C + (l & 15);
-        if (row < F && col <= row) {
+        const int lr = 4 * (l >> 4) + r, lc = l & 15;          // position inside the tile
+        const int fr = feature_of(F, R, lr), fc = feature_of(F, C, lc);
+        if (fr >= 0 && fc >= 0 && (R > C || lc <= lr)) {        // each unordered pair once
             float v = 0.f;
             for (int s = 0; s < nslots; ++s) v += slots[(int64_t)s * SLOT + o];
-            if (row == col) v += reg;
-            As[row * LD + col] = v;
+            if (fr == fc) v += reg;
+            const int hi = fr > fc ? fr : fc, lo = fr > fc ? fc : fr;
+            As[hi * LD + lo] = v;
         }
     }
     for (int o = threadIdx.x; o < NT * 16; o += blockDim.x) {
-        if (o < F) {
+        const int ft = feature_of(F, o >> 4, o & 15);
+        if (ft >= 0) {
             float v = 0.f;
             for (int s = 0; s < nslots; ++s) v += slots[(int64_t)s * SLOT + NTILES * 256 + o];
-            bs[o] = v;
+            bs[ft] = v;
         }
     }
 }

@@ -89,25 +89,60 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     const int nsteps = (len + 3) >> 2;
     const int nmain = ((len >> 2) / NB) * NB;    // full steps handled by the unmasked rounds
     const int last = len - 1;
-    const uint32_t off0 = 4u * (uint32_t)i;
-    const uint32_t offl = 4u * (uint32_t)((16 * (NT - 1) + i < F) ? 16 * (NT - 1) + i : F - 1);
+    constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
+    // byte offset of this lane's last 4-byte load inside a theta row (clamped to the row: filler)
+    constexpr int base1 = 64 * N4 + 32 * N2;
+    const uint32_t offl = 4u * (uint32_t)((base1 + 16 * (N1 - 1) + i < F) ? base1 + 16 * (N1 - 1) + i : F - 1);
     auto entry = [&](int step) -> uint32_t {   // this lane's stored entry of a step, clamped into the item
         const int e = 4 * step + kq;
         return (uint32_t)(e < last ? e : last);
     };
+    // entry -> column id / rating: scalar base + 32-bit byte offset (a work item has < 2^30 entries)
+    auto load_id = [&](uint32_t e) { return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(ib) + 4u * e); };
+    auto load_rating = [&](uint32_t e) { return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(vb) + 4u * e); };
+    // one theta row -> operand registers, with the widest loads the feature permutation allows;
+    // addresses are (scalar base) + (32-bit lane offset) + (immediate) unless WIDE
+    const uint32_t lane16 = 16u * (uint32_t)i, lane8 = 256u * N4 + 8u * (uint32_t)i, lane4 = 4u * (uint32_t)(base1 + i);
     auto gather = [&](int c, float (&g)[NT]) {
         if constexpr (WIDE) {
             const char *p = reinterpret_cast<const char *>(Theta + (int64_t)c * F);
 #pragma unroll
-            for (int q = 0; q < NT - 1; ++q) g[q] = *reinterpret_cast<const float *>(p + off0 + 64 * q);
-            g[NT - 1] = *reinterpret_cast<const float *>(p + offl);
+            for (int q = 0; q < N4; ++q) {
+                const float4 v = *reinterpret_cast<const float4 *>(p + lane16 + 256 * q);
+                g[4 * q] = v.x; g[4 * q + 1] = v.y; g[4 * q + 2] = v.z; g[4 * q + 3] = v.w;
+            }
+            if constexpr (N2 > 0) {
+                const float2 v = *reinterpret_cast<const float2 *>(p + lane8);
+                g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
+            }
+#pragma unroll
+            for (int k = 0; k < N1 - 1; ++k) g[4 * N4 + 2 * N2 + k] = *reinterpret_cast<const float *>(p + lane4 + 64 * k);
+            if constexpr (N1 > 0) g[NT - 1] = *reinterpret_cast<const float *>(p + offl);
         } else {
             const char *base = reinterpret_cast<const char *>(Theta);
             const uint32_t rowoff = (uint32_t)c * (uint32_t)(4 * F);
-            const uint32_t o0 = rowoff + off0, ol = rowoff + offl;
+            if constexpr (N4 > 0) {
+                const uint32_t o = rowoff + lane16;
 #pragma unroll
-            for (int q = 0; q < NT - 1; ++q) g[q] = *reinterpret_cast<const float *>(base + o0 + 64 * q);
-            g[NT - 1] = *reinterpret_cast<const float *>(base + ol);
+                for (int q = 0; q < N4; ++q) {
+                    const float4 v = *reinterpret_cast<const float4 *>(base + o + 256 * q);
+                    g[4 * q] = v.x; g[4 * q + 1] = v.y; g[4 * q + 2] = v.z; g[4 * q + 3] = v.w;
+                }
+            }
+            if constexpr (N2 > 0) {
+                const uint32_t o = rowoff + lane8;
+                const float2 v = *reinterpret_cast<const float2 *>(base + o);
+                g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
+            }
+            if constexpr (N1 > 1) {
+                const uint32_t o = rowoff + lane4;
+#pragma unroll
+                for (int k = 0; k < N1 - 1; ++k) g[4 * N4 + 2 * N2 + k] = *reinterpret_cast<const float *>(base + o + 64 * k);
+            }
+            if constexpr (N1 > 0) {
+                const uint32_t o = rowoff + offl;
+                g[NT - 1] = *reinterpret_cast<const float *>(base + o);
+            }
         }
     };
 
@@ -126,13 +161,13 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     // compiler's wait-count bookkeeping merges both paths at the loop head, and any other order makes
     // it drain the outstanding gathers at the top of every round.
 #pragma unroll
-    for (int j = D; j < K; ++j) cbuf[j % NB] = ib[entry(j)];
+    for (int j = D; j < K; ++j) cbuf[j % NB] = load_id(entry(j));
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int d = 0; d < D; ++d) {
         const uint32_t e = entry(d);
-        rbuf[d] = vb[e];
-        gather(ib[e], gbuf[d]);
+        rbuf[d] = load_rating(e);
+        gather(load_id(e), gbuf[d]);
         asm volatile("" ::: "memory");
     }
 
@@ -142,13 +177,13 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         constexpr bool MASKED = decltype(mtag)::value;
         constexpr int dn = (d + D) % NB;
         // (1) column id of step t+K
-        cbuf[(d + K) % NB] = ib[entry(t + K)];
+        cbuf[(d + K) % NB] = load_id(entry(t + K));
         // keeps the load above here: the compiler would otherwise fold the carried value into a load
         // at its use, putting a full memory latency in front of a gather
         asm volatile("" ::: "memory");
         // (2) gathers and rating of step t+D into the set that step t-1 has finished with
         gather(cbuf[dn], gbuf[dn]);
-        rbuf[dn] = vb[entry(t + D)];
+        rbuf[dn] = load_rating(entry(t + D));
         __builtin_amdgcn_sched_barrier(0);
         // (3) MFMAs of step t
         float g[NT];
@@ -302,7 +337,7 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
     }
 }
 
-// adds reg to the diagonal entries (feature < F) of the diagonal tiles
+// adds reg to the diagonal entries of the diagonal tiles that belong to a feature
 template <int F>
 __device__ __forceinline__ void add_diagonal(v4f (&acc)[tiles_tri(F)], float reg) {
     constexpr int NT = tiles_1d(F);
@@ -311,7 +346,7 @@ __device__ __forceinline__ void add_diagonal(v4f (&acc)[tiles_tri(F)], float reg
     for (int R = 0; R < NT; ++R)
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            if (c == 4 * g + r && 16 * R + c < F) acc[R * (R + 1) / 2 + R][r] += reg;
+            if (c == 4 * g + r && feature_of(F, R, c) >= 0) acc[R * (R + 1) / 2 + R][r] += reg;
 }
 
 }  // namespace als
