@@ -1,0 +1,107 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times (default chunk and
+batch, CG(6) and exact): sampled rows / columns the oracle computes one by one, full-size RMSE, and the
+index work bit for bit.  Inputs are seeded and synthetic; no oracle input comes from the GPU."""
+import numpy as np
+import pytest
+
+import oracle
+import workload as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _sub_csr(a, rows):
+    deg = (a.ptr[rows + 1] - a.ptr[rows]).astype(np.int64)
+    ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    take = np.concatenate([np.arange(a.ptr[u], a.ptr[u + 1]) for u in rows] + [np.zeros(0, np.int64)])
+    return ptr, a.idx[take], a.val[take]
+
+
+def _sample_rows(a, rng, n_random, n_heavy, n_light):
+    deg = np.diff(a.ptr)
+    order = np.argsort(deg, kind="stable")
+    picks = np.concatenate([rng.choice(a.nrows, n_random, replace=False), order[-n_heavy:], order[:n_light]])
+    return np.unique(picks).astype(np.int64)
+
+
+def _rel(g, o):
+    return np.linalg.norm(g.astype(np.float64) - o, axis=1) / np.maximum(np.linalg.norm(o, axis=1), 1e-30)
+
+
+def _check_side(P, w, a, G_host, label, rng, n_random, n_heavy):
+    """One half-sweep on matrix `a` gathering G_host: CG(6) from a seeded warm start, then exact."""
+    rows = _sample_rows(a, rng, n_random, n_heavy, 8)
+    sptr, sidx, sval = _sub_csr(a, rows)
+    sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    G = _dev(G_host)
+    warm = W.random_factors(a.nrows, w.f, seed=77, scale=0.05)
+    # approximate mode: same Algorithm 1 in double on the sampled rows
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6)
+    out = _dev(warm.copy())
+    als.update_rows(sp, G, w.lam, out)
+    als.synchronize()
+    ref = oracle.update_rows_cg(sptr, sidx, sval, G_host, w.lam, warm[rows], fs=6)
+    err_cg = _rel(out[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
+    als.close()
+    # exact mode: per-row 1e-4
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY)
+    out = torch.zeros((a.nrows, w.f), device="cuda:0")
+    als.update_rows(sp, G, w.lam, out)
+    als.synchronize()
+    ref = oracle.update_rows(sptr, sidx, sval, G_host, w.lam)
+    got = out[torch.from_numpy(rows).cuda()].cpu().numpy()
+    err_ex = _rel(got, ref)
+    assert torch.isfinite(out).all().item()
+    als.close()
+    print(f"{w.name} {label}: {len(rows)} sampled rows (max degree {int((sptr[1:] - sptr[:-1]).max())}); "
+          f"CG(6) vs double Algorithm 1 max {err_cg.max():.2e}; exact max {err_ex.max():.2e}", flush=True)
+    assert err_cg.max() <= 2e-3
+    assert err_ex.max() <= 1e-4
+
+
+def _full_size(P, w, n_random, n_heavy):
+    rng = np.random.default_rng(w.seed + 5)
+    a = W.generate(w)
+    print(f"{w.name}: generated {a.nnz} entries", flush=True)
+    _, T0 = W.init_factors(w)
+    # index work, bit for bit
+    als = P.Als(w.f)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    perm, start = als.bin_rows(csr, 24)
+    perm_o, start_o = oracle.bin_rows(a.ptr, 24)
+    assert np.array_equal(perm.cpu().numpy(), perm_o) and list(start_o) == start
+    t = als.csr_to_csc(csr)
+    cptr, cidx, cval = oracle.csr_to_csc(w.m, w.n, a.ptr, a.idx, a.val)
+    assert np.array_equal(t.ptr.cpu().numpy(), cptr)
+    assert np.array_equal(t.idx.cpu().numpy(), cidx) and np.array_equal(t.val.cpu().numpy(), cval)
+    del t, perm
+    # RMSE at full size on seeded factors
+    Xs = W.random_factors(w.m, w.f, seed=21, scale=0.3)
+    Ts = W.random_factors(w.n, w.f, seed=22, scale=0.3)
+    r_gpu = als.rmse(csr, _dev(Xs), _dev(Ts))
+    r_orc = oracle.rmse(a.ptr, a.idx, a.val, Xs, Ts)
+    print(f"{w.name}: rmse gpu {r_gpu:.7f} oracle {r_orc:.7f}", flush=True)
+    assert abs(r_gpu - r_orc) <= 1e-5 * r_orc
+    als.close()
+    del csr
+    torch.cuda.empty_cache()
+    # row side from the initial Theta, column side from a seeded X (the oracle's input never comes from the GPU)
+    _check_side(P, w, a, T0, "rows", rng, n_random, n_heavy)
+    c = W.CSR(w.n, w.m, cptr, cidx, cval)
+    del a
+    _check_side(P, w, c, Xs, "cols", rng, max(n_random // 4, 16), max(n_heavy // 2, 2))
+
+
+def test_mid_full_size():
+    import paper_1808_03843_amd as P
+    _full_size(P, W.MID, n_random=300, n_heavy=6)
+
+
+def test_large_square_full_size():
+    import paper_1808_03843_amd as P
+    _full_size(P, W.LARGE_SQUARE, n_random=200, n_heavy=4)
