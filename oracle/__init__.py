@@ -63,6 +63,8 @@ def _load():
         lib.oracle_sse.restype = d
         lib.oracle_sse_parallel.argtypes = [i64, vp, vp, vp, vp, vp, ci]
         lib.oracle_sse_parallel.restype = d
+        lib.oracle_sse_parallel_f32.argtypes = [i64, vp, vp, vp, vp, vp, ci]
+        lib.oracle_sse_parallel_f32.restype = d
         lib.oracle_regulariser.argtypes = [i64, i64, vp, vp, vp, vp, ci, d]
         lib.oracle_regulariser.restype = d
         lib.oracle_csr_to_csc.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp]
@@ -146,6 +148,14 @@ def sse(ptr, idx, val, X, Theta, parallel=True):
     X, Theta = _c(X, _f64), _c(Theta, _f64)
     fn = _load().oracle_sse_parallel if parallel else _load().oracle_sse
     return fn(len(ptr) - 1, _p(ptr), _p(idx), _p(val), _p(X), _p(Theta), X.shape[1])
+
+
+def rmse_f32(ptr, idx, val, X, Theta):
+    """Training RMSE for float32 factors without a double-precision copy of them (arithmetic in double)."""
+    ptr, idx, val = _c(ptr, _i64), _c(idx, _i32), _c(val, _f32)
+    X, Theta = _c(X, _f32), _c(Theta, _f32)
+    s = _load().oracle_sse_parallel_f32(len(ptr) - 1, _p(ptr), _p(idx), _p(val), _p(X), _p(Theta), X.shape[1])
+    return float(np.sqrt(s / max(int(ptr[-1]), 1)))
 
 
 def rmse(ptr, idx, val, X, Theta):

@@ -245,6 +245,30 @@ double oracle_sse_parallel(int64_t m, const int64_t *ptr, const int32_t *idx, co
     return total;
 }
 
+/* The same sum for single-precision factors (read as they are, all arithmetic in double): lets a
+ * caller with tens of gigabytes of factors avoid a double-precision copy. */
+double oracle_sse_parallel_f32(int64_t m, const int64_t *ptr, const int32_t *idx, const float *val,
+                               const float *X, const float *Theta, int f) {
+    double *rows = (double *)malloc(sizeof(double) * (size_t)(m > 0 ? m : 1));
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t u = 0; u < m; u++) {
+        double row = 0.0;
+        const float *x = X + u * f;
+        for (int64_t q = ptr[u]; q < ptr[u + 1]; q++) {
+            const float *t = Theta + (int64_t)idx[q] * f;
+            double dot = 0.0;
+            for (int i = 0; i < f; i++) dot += (double)x[i] * (double)t[i];
+            double e = (double)val[q] - dot;
+            row += e * e;
+        }
+        rows[u] = row;
+    }
+    double total = 0.0;
+    for (int64_t u = 0; u < m; u++) total += rows[u];
+    free(rows);
+    return total;
+}
+
 /* Regulariser of eq. (1): lambda * ( sum_u n_{x_u} ||x_u||^2 + sum_v n_{theta_v} ||theta_v||^2 ),
  * n_{x_u} / n_{theta_v} being the numbers of stored entries in row u / column v. */
 double oracle_regulariser(int64_t m, int64_t n, const int64_t *ptr, const int32_t *idx,

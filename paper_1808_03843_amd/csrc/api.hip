@@ -385,7 +385,7 @@ int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t 
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
     if (rc != ALS_OK) return rc;
-    if (csr->nnz > 0x7fffffff) return fail(ctx, ALS_EINVAL, "als_csr_to_csc needs nnz < 2^31");
+    if (csr->nnz > 0xffffffffll) return fail(ctx, ALS_EINVAL, "als_csr_to_csc needs nnz < 2^32");
     if (!cptr_out || (csr->nnz > 0 && (!cidx_out || !cval_out))) return fail(ctx, ALS_EINVAL, "null pointer");
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     hipError_t e = transpose_csr(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ncols, csr->nnz, csr->ptr,

@@ -215,3 +215,30 @@ def test_bad_arguments_are_errors_not_crashes(P):
         als.synchronize()
     assert ei.value.code == -3
     als.close()
+
+
+def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P):
+    # a 4.3 GB factor matrix of which only a few rows are referenced: exercises the wide-offset gather
+    f, n = 16, 67_200_000
+    rng = np.random.default_rng(5)
+    degrees = [1, 3, 40, 700, 2000]
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees]).astype(np.int32)
+    val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+    used = np.unique(idx)
+    rows_val = W.random_factors(len(used), f, seed=8, scale=0.5)
+    Theta = torch.zeros((n, f), device="cuda:0")
+    Theta[torch.from_numpy(used.astype(np.int64)).cuda()] = torch.from_numpy(rows_val).cuda()
+    # the oracle sees a compact copy: column ids renumbered to the used rows
+    remap = np.searchsorted(used, idx).astype(np.int32)
+    for solver in (P.SOLVER_CHOLESKY, P.SOLVER_CG):
+        als = P.Als(f, solver=solver, cg_iters=f, chunk=256)
+        sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+        X = torch.zeros((len(degrees), f), device="cuda:0")
+        als.update_rows(sp, Theta, 0.05, X)
+        als.synchronize()
+        ref = oracle.update_rows(ptr, remap, val, rows_val, 0.05)
+        assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
+        als.close()
+    del Theta
+    torch.cuda.empty_cache()

@@ -1,0 +1,107 @@
+"""The Very-tall configuration (50,082,603 x 39,780, 3,101,144,313 entries, int64 row pointers, 64-bit
+factor offsets on the column side).  Heavy (tens of GB of host and device memory, minutes): it runs only
+when ALS_RUN_VERY_TALL=1 is set; the result of the last run is recorded in the design doc.
+
+The matrix does not fit a full oracle sweep, so parity is sampled: rows and columns the oracle solves one
+by one, the streamed double-precision RMSE over all entries, and the CSC checked on sampled columns plus
+invariants."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import workload as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.mark.skipif(os.environ.get("ALS_RUN_VERY_TALL") != "1", reason="set ALS_RUN_VERY_TALL=1 (needs ~60 GB host, ~150 GB device, minutes)")
+def test_very_tall():
+    import paper_1808_03843_amd as P
+    from test_gpu_full_size import _sub_csr, _rel
+
+    w = W.VERY_TALL
+    t0 = time.time()
+    a = W.generate(w)
+    print(f"very_tall: generated {a.nnz} entries in {time.time() - t0:.0f} s", flush=True)
+    assert a.nnz == w.nnz and a.nnz > 2 ** 31
+    dev = "cuda:0"
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, ptr64=True)
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, profile=True)
+    t0 = time.time()
+    csc = als.csr_to_csc(csr)
+    torch.cuda.synchronize()
+    print(f"very_tall: CSC built on the GPU in {time.time() - t0:.1f} s", flush=True)
+    cptr = csc.ptr.cpu().numpy()
+    assert cptr[0] == 0 and cptr[-1] == a.nnz
+    col_deg = np.diff(cptr)
+    rng = np.random.default_rng(3)
+    # CSC against the definition on sampled columns (rows ascending, values carried)
+    cols = np.unique(np.concatenate([rng.choice(w.n, 60, replace=False), np.argsort(col_deg)[-2:]]))
+    mask = np.isin(a.idx, cols.astype(np.int32))
+    pos = np.nonzero(mask)[0]
+    row_of = np.searchsorted(a.ptr, pos, side="right") - 1
+    for v in cols:
+        sel = a.idx[pos] == v
+        rows_ref, vals_ref = row_of[sel].astype(np.int32), a.val[pos[sel]]
+        s, e = int(cptr[v]), int(cptr[v + 1])
+        assert np.array_equal(csc.idx[s:e].cpu().numpy(), rows_ref)
+        assert np.array_equal(csc.val[s:e].cpu().numpy(), vals_ref)
+    del mask, pos, row_of
+    print("very_tall: CSC matches on sampled columns", flush=True)
+
+    X0, T0 = W.init_factors(w)
+    X, T = torch.from_numpy(X0).to(dev), torch.from_numpy(T0).to(dev)
+    del X0
+    # sweep 1, rows: sampled rows against double-precision Algorithm 1
+    deg = np.diff(a.ptr)
+    rows = np.unique(np.concatenate([rng.choice(w.m, 400, replace=False), np.argsort(deg)[-4:], np.argsort(deg)[:4]]))
+    sptr, sidx, sval = _sub_csr(a, rows)
+    als.update_rows(csr, T, w.lam, X)
+    als.synchronize()
+    ref = oracle.update_rows_cg(sptr, sidx, sval, T0, w.lam, np.zeros((len(rows), w.f), np.float32), fs=6)
+    err = _rel(X[torch.from_numpy(rows).to(dev)].cpu().numpy(), ref)
+    print(f"very_tall rows: {len(rows)} sampled, CG(6) vs double Algorithm 1 max {err.max():.2e}", flush=True)
+    assert err.max() <= 2e-3
+    # columns from a seeded X (not the GPU's): 64-bit factor offsets
+    Xs_host = W.random_factors(w.m, w.f, seed=21, scale=0.3)
+    Xs = torch.from_numpy(Xs_host).to(dev)
+    warm = W.random_factors(w.n, w.f, seed=23, scale=0.05)
+    Tw = torch.from_numpy(warm.copy()).to(dev)
+    als.update_cols(csc, Xs, w.lam, Tw)
+    als.synchronize()
+    ccols = np.unique(np.concatenate([rng.choice(w.n, 12, replace=False), np.argsort(col_deg)[:4]]))
+    for v in ccols:
+        s, e = int(cptr[v]), int(cptr[v + 1])
+        ridx, rval = csc.idx[s:e].cpu().numpy(), csc.val[s:e].cpu().numpy()
+        # compact copy of the rows this column touches (a double copy of all of X would be 40 GB)
+        ref = oracle.update_rows_cg(np.array([0, e - s], np.int64), np.arange(e - s, dtype=np.int32), rval,
+                                    Xs_host[ridx], w.lam, warm[v:v + 1], fs=6)
+        errc = _rel(Tw[v:v + 1].cpu().numpy(), ref)
+        assert errc.max() <= 2e-3, (v, errc)
+    print(f"very_tall cols: {len(ccols)} sampled columns match", flush=True)
+    # RMSE over all entries against the streamed double-precision sum
+    Ts_host = W.random_factors(w.n, w.f, seed=22, scale=0.3)
+    r_gpu = als.rmse(csr, Xs, torch.from_numpy(Ts_host).to(dev))
+    r_orc = oracle.rmse_f32(a.ptr, a.idx, a.val, Xs_host, Ts_host)
+    print(f"very_tall: rmse gpu {r_gpu:.7f} oracle {r_orc:.7f}", flush=True)
+    assert abs(r_gpu - r_orc) <= 1e-5 * r_orc
+    del Xs, Xs_host
+    # three timed sweeps (the first row update above was sweep 1's first half)
+    torch.cuda.synchronize()
+    hist = []
+    for s in range(3):
+        t0 = time.time()
+        if s > 0:
+            als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+        torch.cuda.synchronize()
+        dt = time.time() - t0
+        hist.append((dt, als.rmse(csr, X, T)))
+        print(f"very_tall sweep {s + 1}: {dt:.3f} s{' (column half only)' if s == 0 else ''}, training rmse {hist[-1][1]:.5f}", flush=True)
+    assert hist[2][1] < hist[0][1]
+    als.synchronize()
+    als.close()

@@ -293,3 +293,11 @@ def test_bin_rows_is_stable_partition_by_class():
     for c in range(nclass):
         seg = perm[start[nclass - 1 - c]:start[nclass - c]]
         assert np.all(cls[seg] == c)
+
+
+def test_rmse_f32_variant_equals_the_double_one_on_float_inputs():
+    w = W.TINY
+    a = W.generate(w)
+    X = W.random_factors(w.m, w.f, seed=1, scale=0.3)
+    T = W.random_factors(w.n, w.f, seed=2, scale=0.3)
+    assert oracle.rmse_f32(a.ptr, a.idx, a.val, X, T) == oracle.rmse(a.ptr, a.idx, a.val, X, T)
