@@ -69,7 +69,9 @@ typedef struct als_config {
     int32_t solver;       /* ALS_SOLVER_*                                                                */
     int32_t cg_iters;     /* f_s of Algorithm 1 (used when solver == ALS_SOLVER_CG)                      */
     float cg_eps;         /* epsilon of Algorithm 1: stop when sqrt(r^T r) < cg_eps; 0 = fixed f_s steps */
-    int32_t factor_dtype; /* ALS_F32: dtype of the factor matrix that is gathered                        */
+    int32_t factor_dtype; /* ALS_F32 / ALS_BF16 / ALS_F16: element type of the factor matrix that is GATHERED
+                             (Theta in als_update_rows, X in als_update_cols); widened to fp32 in registers,
+                             all arithmetic and the written factor stay fp32                            */
     int32_t herm_dtype;   /* ALS_F32: storage type of A_u where it is materialised (Section 4.2)         */
     int32_t device;       /* HIP device ordinal                                                          */
     void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */

@@ -109,11 +109,11 @@ class Als:
 
     def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
                  device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
-                 profile: bool = False):
+                 profile: bool = False, factor_dtype: int = F32):
         self._lib = load_library()
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
-        self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, F32, F32, device, stream, chunk, batch_slots,
+        self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, F32, device, stream, chunk, batch_slots,
                              1 if profile else 0)
         self._ctx = ctypes.c_void_p()
         rc = self._lib.als_create(ctypes.byref(self._ctx), ctypes.byref(self.cfg))
@@ -121,6 +121,7 @@ class Als:
             self._ctx = ctypes.c_void_p()
             raise AlsError(rc, "als_create failed (unsupported f / solver / dtype, or no such device)")
         self.f = f
+        self.factor_torch_dtype = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[factor_dtype]
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx:
@@ -138,16 +139,20 @@ class Als:
             raise AlsError(rc, self._lib.als_last_error(self._ctx).decode())
 
     @staticmethod
-    def _factor(t: torch.Tensor, rows: int, f: int):
-        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == (rows, f)
+    def _factor(t: torch.Tensor, rows: int, f: int, dtype=torch.float32):
+        assert t.is_cuda and t.dtype == dtype and t.is_contiguous() and tuple(t.shape) == (rows, f)
         return t.data_ptr()
 
+    def _gathered(self, t: torch.Tensor, rows: int):
+        """The factor matrix that is read (config's factor_dtype)."""
+        return self._factor(t, rows, self.f, self.factor_torch_dtype)
+
     def update_rows(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, X: torch.Tensor):
-        self._check(self._lib.als_update_rows(self._ctx, ctypes.byref(csr.desc), self._factor(Theta, csr.ncols, self.f),
+        self._check(self._lib.als_update_rows(self._ctx, ctypes.byref(csr.desc), self._gathered(Theta, csr.ncols),
                                               lam, self.f, self._factor(X, csr.nrows, self.f)))
 
     def update_cols(self, csc: SparseMatrix, X: torch.Tensor, lam: float, Theta: torch.Tensor):
-        self._check(self._lib.als_update_cols(self._ctx, ctypes.byref(csc.desc), self._factor(X, csc.ncols, self.f),
+        self._check(self._lib.als_update_cols(self._ctx, ctypes.byref(csc.desc), self._gathered(X, csc.ncols),
                                               lam, self.f, self._factor(Theta, csc.nrows, self.f)))
 
     def rmse(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor) -> float:
@@ -159,7 +164,7 @@ class Als:
     def hermitian(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, row0: int, nrows: int):
         A = torch.empty((nrows, self.f, self.f), dtype=torch.float32, device=Theta.device)
         b = torch.empty((nrows, self.f), dtype=torch.float32, device=Theta.device)
-        self._check(self._lib.als_hermitian(self._ctx, ctypes.byref(csr.desc), self._factor(Theta, csr.ncols, self.f),
+        self._check(self._lib.als_hermitian(self._ctx, ctypes.byref(csr.desc), self._gathered(Theta, csr.ncols),
                                             lam, self.f, row0, nrows, A.data_ptr(), b.data_ptr()))
         return A, b
 

@@ -58,13 +58,14 @@ constexpr int kStatusNonFinite = 2;
 
 // ---- launchers (each defined next to its kernels) --------------------------------------------
 // wide: the gathered factor matrix is 4 GiB or larger (64-bit lane addresses)
-hipError_t launch_hermitian(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+// et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16)
+hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
-                            const int32_t *idx, const float *val, const float *Theta, float *slots);
+                            const int32_t *idx, const float *val, const void *Theta, float *slots);
 
-hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
-                               int64_t npos, const void *ptr, const int32_t *idx, const float *val,
-                               const float *Theta, float lambda, int fs, float eps, float *Xout, int *status);
+hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm,
+                               int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                               const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
 hipError_t launch_solve_cg_wave(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);

@@ -174,7 +174,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const int32_t *off = p->task_off_host;
     const int64_t m = a->nrows;
     const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
-    const bool wide = (uint64_t)a->ncols * (uint64_t)f * sizeof(float) >= (1ull << 32);
+    const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
+    const bool wide = (uint64_t)a->ncols * (uint64_t)f * esize >= (1ull << 32);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
     const int64_t slot_rows = cg ? p->split_pos : m;
@@ -192,8 +193,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         if (rc != ALS_OK) return rc;
         {
             Timed t(ctx, ALS_K_HERMITIAN);
-            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
-                                          ctx->cfg.chunk, a->ptr, a->idx, a->val, (const float *)G, ctx->slots));
+            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
+                                          ctx->cfg.chunk, a->ptr, a->idx, a->val, G, ctx->slots));
         }
         {
             Timed t(ctx, ALS_K_SOLVE);
@@ -212,8 +213,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     }
     if (slot_rows < m) {
         Timed t(ctx, ALS_K_FUSED);
-        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
-                                         a->val, (const float *)G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
+        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
+                                         a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
                                          ctx->status));
     }
     return ALS_OK;
@@ -229,7 +230,8 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (!supported_f(cfg->f)) return ALS_EINVAL;
     if (cfg->solver != ALS_SOLVER_CHOLESKY && cfg->solver != ALS_SOLVER_CG) return ALS_EINVAL;
     if (cfg->solver == ALS_SOLVER_CG && cfg->cg_iters < 0) return ALS_EINVAL;
-    if (cfg->factor_dtype != ALS_F32 || cfg->herm_dtype != ALS_F32) return ALS_EINVAL;
+    if (cfg->factor_dtype != ALS_F32 && cfg->factor_dtype != ALS_BF16 && cfg->factor_dtype != ALS_F16) return ALS_EINVAL;
+    if (cfg->herm_dtype != ALS_F32) return ALS_EINVAL;
     if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
     if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;
     int ndev = 0;
@@ -316,7 +318,8 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     // a throw-away plan over the row range, in natural order
     const bool p64 = csr->ptr_is_64 != 0;
-    const bool wide = (uint64_t)csr->ncols * (uint64_t)f * sizeof(float) >= (1ull << 32);
+    const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
+    const bool wide = (uint64_t)csr->ncols * (uint64_t)f * esize >= (1ull << 32);
     int32_t *perm = nullptr, *task_off = nullptr, *task_row = nullptr, *task_chunk = nullptr;
     auto cleanup = [&]() { hipFree(perm); hipFree(task_off); hipFree(task_row); hipFree(task_chunk); };
     hipError_t e;
@@ -347,8 +350,8 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     if (rc != ALS_OK) { cleanup(); return rc; }
     {
         Timed t(ctx, ALS_K_HERMITIAN);
-        e = launch_hermitian(f, p64, wide, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
-                             csr->val, (const float *)Theta, ctx->slots);
+        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
+                             csr->val, Theta, ctx->slots);
     }
     if (e == hipSuccess)
         e = launch_export_dense(f, p64, ctx->stream, perm, task_off, 0, nrows, 0, csr->ptr, ctx->slots, lambda, row0,

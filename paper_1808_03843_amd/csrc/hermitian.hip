@@ -24,9 +24,14 @@ namespace als {
 #define ALS_DEPTH_SLOTS 3
 #endif
 #ifndef ALS_DEPTH_FUSED
-#define ALS_DEPTH_FUSED 2
+#define ALS_DEPTH_FUSED 3
+#endif
+#ifndef ALS_FUSED_WAVES
+#define ALS_FUSED_WAVES 2
 #endif
 constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
+// wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
+constexpr int fused_waves(int F) { return F <= 100 ? ALS_FUSED_WAVES : 2; }
 
 // a value that is the same in every lane, moved to scalar registers
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -35,11 +40,11 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-template <int F, typename PtrT, bool WIDE>
+template <int F, typename PtrT, bool WIDE, int ET>
 __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
                                                   const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                  const float *__restrict__ val, const float *__restrict__ Theta,
+                                                  const float *__restrict__ val, const void *__restrict__ Theta,
                                                   float *__restrict__ slots) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
     const int lane = threadIdx.x;
@@ -55,7 +60,7 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE>(idx, val, Theta, uniform64(s0), len, acc, b);
+    accumulate_tiles<F, false, kDepthSlots, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
 
     float *out = slots + t * (int64_t)SLOT;
 #pragma unroll
@@ -96,10 +101,10 @@ __device__ __forceinline__ void store_zero_vec(float *__restrict__ dst) {
     for (int q = threadIdx.x; q < F; q += 64) dst[q] = 0.f;
 }
 
-template <int F, typename PtrT, bool WIDE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3 : 2, F <= 100 ? 3 : 2))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
+template <int F, typename PtrT, bool WIDE, int ET>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F), fused_waves(F)))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
                                                      const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                     const float *__restrict__ val, const float *__restrict__ Theta,
+                                                     const float *__restrict__ val, const void *__restrict__ Theta,
                                                      float lambda, int fs, float eps, float *__restrict__ Xout,
                                                      int *__restrict__ status) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F);
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(F <= 100 ? 3
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, true, kDepthFused, WIDE>(idx, val, Theta, uniform64(s0), len, acc, b);
+    accumulate_tiles<F, true, kDepthFused, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
     add_diagonal<F>(acc, lambda * (float)len);
     float x[NT];
     load_vec<F>(xg, x);
@@ -186,50 +191,82 @@ __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict_
         default: return hipErrorInvalidValue; \
     }
 
-template <int F, typename PtrT>
-static hipError_t herm_f(bool wide, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
+// dispatch on the run-time switches that are template parameters of the kernels
+template <int F, typename PtrT, bool WIDE>
+static hipError_t herm_e(int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
                          int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
-                         const float *Theta, float *slots) {
-    if (ntasks <= 0) return hipSuccess;
-    if (wide)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, true>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row,
-                           task_chunk, task0, chunk, (const PtrT *)ptr, idx, val, Theta, slots);
+                         const void *Theta, float *slots) {
+    const dim3 grid((unsigned)ntasks), block(64);
+    const PtrT *p = (const PtrT *)ptr;
+    if (et == ALS_F32)
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, slots);
+    else if (et == ALS_BF16)
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, slots);
     else
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, false>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row,
-                           task_chunk, task0, chunk, (const PtrT *)ptr, idx, val, Theta, slots);
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, slots);
     return hipGetLastError();
 }
 
-hipError_t launch_hermitian(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+template <int F, typename PtrT>
+static hipError_t herm_f(bool wide, int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+                         int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
+                         const float *val, const void *Theta, float *slots) {
+    if (ntasks <= 0) return hipSuccess;
+    return wide ? herm_e<F, PtrT, true>(et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots)
+                : herm_e<F, PtrT, false>(et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
+}
+
+hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
-                            const int32_t *idx, const float *val, const float *Theta, float *slots) {
-#define CALL(FF)                                                                                                    \
-    (ptr64 ? herm_f<FF, int64_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots) \
-           : herm_f<FF, int32_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots))
+                            const int32_t *idx, const float *val, const void *Theta, float *slots) {
+#define CALL(FF)                                                                                                     \
+    (ptr64 ? herm_f<FF, int64_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,     \
+                                 slots)                                                                              \
+           : herm_f<FF, int32_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,     \
+                                 slots))
     ALS_FOR_F(CALL)
 #undef CALL
 }
 
-template <int F, typename PtrT>
-static hipError_t herm_cg_f(bool wide, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
-                            const void *ptr, const int32_t *idx, const float *val, const float *Theta, float lambda,
-                            int fs, float eps, float *Xout, int *status) {
-    if (npos <= 0) return hipSuccess;
-    if (wide)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, true>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
-                           (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
+template <int F, typename PtrT, bool WIDE>
+static hipError_t herm_cg_e(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
+                            const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
+                            float *Xout, int *status) {
+    const dim3 grid((unsigned)npos), block(64);
+    const PtrT *p = (const PtrT *)ptr;
+    if (et == ALS_F32)
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32>), grid, block, 0, st, perm, pos0, p, idx, val,
+                           Theta, lambda, fs, eps, Xout, status);
+    else if (et == ALS_BF16)
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16>), grid, block, 0, st, perm, pos0, p, idx, val,
+                           Theta, lambda, fs, eps, Xout, status);
     else
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, false>), dim3((unsigned)npos), dim3(64), 0, st, perm, pos0,
-                           (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16>), grid, block, 0, st, perm, pos0, p, idx, val,
+                           Theta, lambda, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
-hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
-                               int64_t npos, const void *ptr, const int32_t *idx, const float *val,
-                               const float *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
-#define CALL(FF)                                                                                                     \
-    (ptr64 ? herm_cg_f<FF, int64_t>(wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
-           : herm_cg_f<FF, int32_t>(wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
+template <int F, typename PtrT>
+static hipError_t herm_cg_f(bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                            const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
+                            int fs, float eps, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    return wide ? herm_cg_e<F, PtrT, true>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status)
+                : herm_cg_e<F, PtrT, false>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,
+                                            status);
+}
+
+hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm,
+                               int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                               const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
+#define CALL(FF)                                                                                                    \
+    (ptr64 ? herm_cg_f<FF, int64_t>(wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,    \
+                                    status)                                                                         \
+           : herm_cg_f<FF, int32_t>(wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,    \
+                                    status))
     ALS_FOR_F(CALL)
 #undef CALL
 }

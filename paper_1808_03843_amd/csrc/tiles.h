@@ -74,9 +74,23 @@ struct TileGeom {
     static constexpr int RI = F % 16;            // its lane
 };
 
-template <int F, bool IN_VGPR, int D, bool WIDE>
+// ET: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16).  16-bit elements are
+// fetched with loads of half the width and widened to fp32 in registers; the MFMAs stay fp32.
+__device__ __forceinline__ float bits_to_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+template <int ET>
+__device__ __forceinline__ float widen_lo(uint32_t w) {   // low 16 bits of w
+    if constexpr (ET == ALS_BF16) return bits_to_float(w << 16);
+    else return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xffffu));
+}
+template <int ET>
+__device__ __forceinline__ float widen_hi(uint32_t w) {   // high 16 bits of w
+    if constexpr (ET == ALS_BF16) return bits_to_float(w & 0xffff0000u);
+    else return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16));
+}
+
+template <int F, bool IN_VGPR, int D, bool WIDE, int ET>
 __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
-                                                 const float *__restrict__ Theta, int64_t s0, int len,
+                                                 const void *__restrict__ Theta, int64_t s0, int len,
                                                  v4f (&acc)[tiles_tri(F)], float (&b)[tiles_1d(F)]) {
     constexpr int NT = TileGeom<F>::NT, NB = D + 1;
     constexpr bool RIT = TileGeom<F>::RIT;
@@ -90,9 +104,9 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     const int nmain = ((len >> 2) / NB) * NB;    // full steps handled by the unmasked rounds
     const int last = len - 1;
     constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
-    // byte offset of this lane's last 4-byte load inside a theta row (clamped to the row: filler)
-    constexpr int base1 = 64 * N4 + 32 * N2;
-    const uint32_t offl = 4u * (uint32_t)((base1 + 16 * (N1 - 1) + i < F) ? base1 + 16 * (N1 - 1) + i : F - 1);
+    constexpr int base1 = 64 * N4 + 32 * N2;       // first feature fetched by the single-element loads
+    constexpr int ES = ET == ALS_F32 ? 4 : 2;       // bytes per element
+    constexpr int RW = ET == ALS_F32 ? NT : 2 * N4 + N2 + N1;   // 32-bit registers one gathered row needs
     auto entry = [&](int step) -> uint32_t {   // this lane's stored entry of a step, clamped into the item
         const int e = 4 * step + kq;
         return (uint32_t)(e < last ? e : last);
@@ -100,49 +114,72 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     // entry -> column id / rating: scalar base + 32-bit byte offset (a work item has < 2^30 entries)
     auto load_id = [&](uint32_t e) { return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(ib) + 4u * e); };
     auto load_rating = [&](uint32_t e) { return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(vb) + 4u * e); };
-    // one theta row -> operand registers, with the widest loads the feature permutation allows;
-    // addresses are (scalar base) + (32-bit lane offset) + (immediate) unless WIDE
-    const uint32_t lane16 = 16u * (uint32_t)i, lane8 = 256u * N4 + 8u * (uint32_t)i, lane4 = 4u * (uint32_t)(base1 + i);
-    auto gather = [&](int c, float (&g)[NT]) {
+    // One theta row -> raw registers, with the widest loads the feature permutation allows: 4, 2 and 1
+    // elements per lane.  Addresses are (scalar base) + (32-bit lane offset) + (immediate) unless WIDE.
+    const uint32_t lane_a = (uint32_t)(4 * ES) * (uint32_t)i;
+    const uint32_t lane_b = (uint32_t)(64 * ES * N4) + (uint32_t)(2 * ES) * (uint32_t)i;
+    const uint32_t lane_c = (uint32_t)ES * (uint32_t)(base1 + i);
+    const uint32_t lane_l = (uint32_t)ES * (uint32_t)((base1 + 16 * (N1 - 1) + i < F) ? base1 + 16 * (N1 - 1) + i : F - 1);
+    auto gather = [&](int c, uint32_t (&w)[RW]) {
+        const char *p;
+        uint32_t ro = 0;
         if constexpr (WIDE) {
-            const char *p = reinterpret_cast<const char *>(Theta + (int64_t)c * F);
+            p = reinterpret_cast<const char *>(Theta) + (int64_t)c * (ES * F);
+        } else {
+            p = reinterpret_cast<const char *>(Theta);
+            ro = (uint32_t)c * (uint32_t)(ES * F);
+        }
+        if constexpr (N4 > 0) {
+            const uint32_t o = ro + lane_a;
 #pragma unroll
             for (int q = 0; q < N4; ++q) {
-                const float4 v = *reinterpret_cast<const float4 *>(p + lane16 + 256 * q);
-                g[4 * q] = v.x; g[4 * q + 1] = v.y; g[4 * q + 2] = v.z; g[4 * q + 3] = v.w;
-            }
-            if constexpr (N2 > 0) {
-                const float2 v = *reinterpret_cast<const float2 *>(p + lane8);
-                g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
-            }
-#pragma unroll
-            for (int k = 0; k < N1 - 1; ++k) g[4 * N4 + 2 * N2 + k] = *reinterpret_cast<const float *>(p + lane4 + 64 * k);
-            if constexpr (N1 > 0) g[NT - 1] = *reinterpret_cast<const float *>(p + offl);
-        } else {
-            const char *base = reinterpret_cast<const char *>(Theta);
-            const uint32_t rowoff = (uint32_t)c * (uint32_t)(4 * F);
-            if constexpr (N4 > 0) {
-                const uint32_t o = rowoff + lane16;
-#pragma unroll
-                for (int q = 0; q < N4; ++q) {
-                    const float4 v = *reinterpret_cast<const float4 *>(base + o + 256 * q);
-                    g[4 * q] = v.x; g[4 * q + 1] = v.y; g[4 * q + 2] = v.z; g[4 * q + 3] = v.w;
+                if constexpr (ET == ALS_F32) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(p + o + 256 * q);
+                    w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
+                } else {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(p + o + 128 * q);
+                    w[2 * q] = v.x; w[2 * q + 1] = v.y;
                 }
             }
-            if constexpr (N2 > 0) {
-                const uint32_t o = rowoff + lane8;
-                const float2 v = *reinterpret_cast<const float2 *>(base + o);
-                g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
+        }
+        if constexpr (N2 > 0) {
+            const uint32_t o = ro + lane_b;
+            if constexpr (ET == ALS_F32) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(p + o);
+                w[4 * N4] = v.x; w[4 * N4 + 1] = v.y;
+            } else {
+                w[2 * N4] = *reinterpret_cast<const uint32_t *>(p + o);
             }
-            if constexpr (N1 > 1) {
-                const uint32_t o = rowoff + lane4;
+        }
+        constexpr int first1 = ET == ALS_F32 ? 4 * N4 + 2 * N2 : 2 * N4 + N2;
+        if constexpr (N1 > 1) {
+            const uint32_t o = ro + lane_c;
 #pragma unroll
-                for (int k = 0; k < N1 - 1; ++k) g[4 * N4 + 2 * N2 + k] = *reinterpret_cast<const float *>(base + o + 64 * k);
+            for (int k = 0; k < N1 - 1; ++k) {
+                if constexpr (ET == ALS_F32) w[first1 + k] = *reinterpret_cast<const uint32_t *>(p + o + 64 * k);
+                else w[first1 + k] = *reinterpret_cast<const unsigned short *>(p + o + 32 * k);
             }
-            if constexpr (N1 > 0) {
-                const uint32_t o = rowoff + offl;
-                g[NT - 1] = *reinterpret_cast<const float *>(base + o);
+        }
+        if constexpr (N1 > 0) {
+            const uint32_t o = ro + lane_l;
+            if constexpr (ET == ALS_F32) w[first1 + N1 - 1] = *reinterpret_cast<const uint32_t *>(p + o);
+            else w[first1 + N1 - 1] = *reinterpret_cast<const unsigned short *>(p + o);
+        }
+    };
+    // raw registers -> fp32 operands, one per tile
+    auto unpack = [&](const uint32_t (&w)[RW], float (&g)[NT]) {
+        if constexpr (ET == ALS_F32) {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) g[q] = bits_to_float(w[q]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < N4; ++q) {
+                g[4 * q] = widen_lo<ET>(w[2 * q]); g[4 * q + 1] = widen_hi<ET>(w[2 * q]);
+                g[4 * q + 2] = widen_lo<ET>(w[2 * q + 1]); g[4 * q + 3] = widen_hi<ET>(w[2 * q + 1]);
             }
+            if constexpr (N2 > 0) { g[4 * N4] = widen_lo<ET>(w[2 * N4]); g[4 * N4 + 1] = widen_hi<ET>(w[2 * N4]); }
+#pragma unroll
+            for (int k = 0; k < N1; ++k) g[4 * N4 + 2 * N2 + k] = widen_lo<ET>(w[2 * N4 + N2 + k]);
         }
     };
 
@@ -151,7 +188,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     //   gbuf/rbuf  operands and rating of a step, loaded D steps ahead
     //   cbuf       column id of a step, loaded IDA steps before its gather is issued
     constexpr int IDA = D >= 2 ? 2 : 1, K = D + IDA;
-    float gbuf[NB][NT];
+    uint32_t gbuf[NB][RW];
     float rbuf[NB];
     int cbuf[NB];
     float bacc[NT];
@@ -188,14 +225,12 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         // (3) MFMAs of step t
         float g[NT];
         float r = rbuf[d];
+        unpack(gbuf[d], g);
         if constexpr (MASKED) {
             const bool ok = (4 * t + kq) < len;
 #pragma unroll
-            for (int q = 0; q < NT; ++q) g[q] = ok ? gbuf[d][q] : 0.f;
+            for (int q = 0; q < NT; ++q) g[q] = ok ? g[q] : 0.f;
             r = ok ? r : 0.f;
-        } else {
-#pragma unroll
-            for (int q = 0; q < NT; ++q) g[q] = gbuf[d][q];
         }
         if constexpr (RIT) {
             g[NT - 1] = (i == RI) ? r : g[NT - 1];
@@ -203,7 +238,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
 #pragma unroll
             for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
         }
-        if constexpr (MASKED || (RIT && NT < 3)) {
+        if constexpr (MASKED || ET != ALS_F32 || (RIT && NT < 3)) {
             // An operand written by the vector ALU must not be read by an MFMA in the next few cycles,
             // and the compiler, to which the MFMAs are opaque, does not keep that distance: wait here,
             // and tie every operand to the wait so that no MFMA can be moved in front of it.

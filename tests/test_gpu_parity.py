@@ -242,3 +242,47 @@ def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P):
         als.close()
     del Theta
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_reduced_precision_factor_inputs(P, name):
+    """16-bit factor inputs, fp32 accumulate: same arithmetic as fp32 on the rounded values, and the
+    10-sweep training RMSE stays within the approximate-mode tolerance of the exact oracle."""
+    tdt, code = (torch.bfloat16, P.BF16) if name == "bf16" else (torch.float16, P.F16)
+    w = W.MID_SMALL
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    # (1) get_hermitian on rounded inputs against the oracle fed the same rounded values
+    T16 = _dev(T0).to(tdt)
+    T_rounded = T16.to(torch.float32).cpu().numpy()
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY, chunk=256, factor_dtype=code)
+    rows = [0, 1, 17, 500, 11999]
+    for u in rows:
+        A, b = als.hermitian(csr, T16, w.lam, u, 1)
+        s, e = a.ptr[u], a.ptr[u + 1]
+        Ao, bo = oracle.normal_eq(a.idx[s:e], a.val[s:e], T_rounded, w.lam)
+        d = e - s
+        assert np.abs(A[0].cpu().numpy() - Ao).max() <= 2e-6 * np.abs(Ao).max() * max(1, np.sqrt(d))
+        assert np.abs(b[0].cpu().numpy() - bo).max() <= 2e-6 * np.abs(bo).max() * max(1, np.sqrt(d))
+    # exact solve from the rounded Theta: per-row 1e-4 against the oracle on the same rounded values
+    X = _dev(X0)
+    als.update_rows(csr, T16, w.lam, X)
+    als.synchronize()
+    Xo = oracle.update_rows(a.ptr, a.idx, a.val, T_rounded, w.lam)
+    assert _row_rel_err(X.cpu().numpy(), Xo).max() <= TOL_EXACT
+    als.close()
+    # (2) approximate mode end to end: CG(6), 16-bit gathers, 10 sweeps
+    _, _, hist = oracle.als((a.ptr, a.idx, a.val), (c.ptr, c.idx, c.val), X0, T0, w.lam, w.sweeps)
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, factor_dtype=code)
+    X, T = _dev(X0), _dev(T0)
+    for _ in range(w.sweeps):
+        als.update_rows(csr, T.to(tdt), w.lam, X)
+        als.update_cols(csc, X.to(tdt), w.lam, T)
+    als.synchronize()
+    r = P.Als(w.f).rmse(csr, X, T)
+    print(f"{name} inputs, CG(6), 10 sweeps: rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
+    assert abs(r - hist[-1]["rmse"]) <= 2e-3
+    als.close()
