@@ -109,11 +109,11 @@ class Als:
 
     def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
                  device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
-                 profile: bool = False, factor_dtype: int = F32):
+                 profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32):
         self._lib = load_library()
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
-        self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, F32, device, stream, chunk, batch_slots,
+        self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, herm_dtype, device, stream, chunk, batch_slots,
                              1 if profile else 0)
         self._ctx = ctypes.c_void_p()
         rc = self._lib.als_create(ctypes.byref(self._ctx), ctypes.byref(self.cfg))

@@ -24,6 +24,9 @@ namespace als {
 constexpr int tiles_1d(int F) { return (F + 15) / 16; }
 constexpr int tiles_tri(int F) { return tiles_1d(F) * (tiles_1d(F) + 1) / 2; }
 constexpr int slot_floats(int F) { return tiles_tri(F) * 256 + tiles_1d(F) * 16; }
+// slot with the tiles stored as packed bf16 pairs (registers 2h, 2h+1 of a tile in one 32-bit word at
+// word offset (2t+h)*64 + l), b_u still fp32: the reduced-precision storage of Section 4.2
+constexpr int slot_words16(int F) { return tiles_tri(F) * 128 + tiles_1d(F) * 16; }
 constexpr int loads16(int F) { return F / 64; }
 constexpr int loads8(int F) { return (F % 64) / 32; }
 constexpr int loads4(int F) { return tiles_1d(F) - 4 * loads16(F) - 2 * loads8(F); }
@@ -59,17 +62,18 @@ constexpr int kStatusNonFinite = 2;
 // ---- launchers (each defined next to its kernels) --------------------------------------------
 // wide: the gathered factor matrix is 4 GiB or larger (64-bit lane addresses)
 // et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16)
-hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
+// s16: slots hold bf16 tiles (slot_words16) instead of fp32 tiles (slot_floats)
+hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots);
 
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
-hipError_t launch_solve_cg_wave(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
-hipError_t launch_reduce_slots(int f, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
+hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
                                int64_t task0, float *slots);
 
 hipError_t launch_solve(int f, int solver, int cg_iters, float cg_eps, bool ptr64, hipStream_t st,

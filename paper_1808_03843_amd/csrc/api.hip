@@ -143,8 +143,8 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     return ALS_OK;
 }
 
-int ensure_slots(als_ctx *ctx, int64_t nslots) {
-    const size_t need = (size_t)nslots * slot_floats(ctx->cfg.f) * sizeof(float);
+int ensure_slots(als_ctx *ctx, int64_t nslots, bool s16) {
+    const size_t need = (size_t)nslots * (s16 ? slot_words16(ctx->cfg.f) : slot_floats(ctx->cfg.f)) * sizeof(float);
     if (ctx->slots_bytes >= need) return ALS_OK;
     if (ctx->slots) {
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -174,6 +174,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const int32_t *off = p->task_off_host;
     const int64_t m = a->nrows;
     const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
+    const bool s16 = ctx->cfg.herm_dtype == ALS_BF16;
     const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
     const bool wide = (uint64_t)a->ncols * (uint64_t)f * esize >= (1ull << 32);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
@@ -189,19 +190,19 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         }
         const int64_t end = lo;
         const int64_t task0 = off[pos], ntasks = (int64_t)off[end] - off[pos];
-        rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1);
+        rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1, s16);
         if (rc != ALS_OK) return rc;
         {
             Timed t(ctx, ALS_K_HERMITIAN);
-            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
+            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, s16, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
                                           ctx->cfg.chunk, a->ptr, a->idx, a->val, G, ctx->slots));
         }
         {
             Timed t(ctx, ALS_K_SOLVE);
             if (ntasks > end - pos)   // some row of the batch has several slots
-                HIP_TRY(ctx, launch_reduce_slots(f, ctx->stream, p->task_off, pos, end - pos, task0, ctx->slots));
+                HIP_TRY(ctx, launch_reduce_slots(f, s16, ctx->stream, p->task_off, pos, end - pos, task0, ctx->slots));
             if (cg)
-                HIP_TRY(ctx, launch_solve_cg_wave(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
+                HIP_TRY(ctx, launch_solve_cg_wave(f, p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
             else
@@ -231,7 +232,9 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (cfg->solver != ALS_SOLVER_CHOLESKY && cfg->solver != ALS_SOLVER_CG) return ALS_EINVAL;
     if (cfg->solver == ALS_SOLVER_CG && cfg->cg_iters < 0) return ALS_EINVAL;
     if (cfg->factor_dtype != ALS_F32 && cfg->factor_dtype != ALS_BF16 && cfg->factor_dtype != ALS_F16) return ALS_EINVAL;
-    if (cfg->herm_dtype != ALS_F32) return ALS_EINVAL;
+    // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
+    // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
+    if (cfg->herm_dtype != ALS_F32 && !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG)) return ALS_EINVAL;
     if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
     if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;
     int ndev = 0;
@@ -346,11 +349,11 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
         cleanup();
         return fail_hip(ctx, e, "work items of the row range");
     }
-    rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1);
+    rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1, false);
     if (rc != ALS_OK) { cleanup(); return rc; }
     {
         Timed t(ctx, ALS_K_HERMITIAN);
-        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
+        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, false, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
                              csr->val, Theta, ctx->slots);
     }
     if (e == hipSuccess)

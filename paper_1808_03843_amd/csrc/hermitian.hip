@@ -40,13 +40,13 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-template <int F, typename PtrT, bool WIDE, int ET>
+template <int F, typename PtrT, bool WIDE, int ET, bool S16>
 __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
                                                   const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                   const float *__restrict__ val, const void *__restrict__ Theta,
                                                   float *__restrict__ slots) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     const int row = task_row[task0 + t];
@@ -63,13 +63,24 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
     accumulate_tiles<F, false, kDepthSlots, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
 
     float *out = slots + t * (int64_t)SLOT;
+    if constexpr (S16) {
+        uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
 #pragma unroll
-    for (int q = 0; q < NTILES; ++q)
+        for (int q = 0; q < NTILES; ++q)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
+            for (int h = 0; h < 2; ++h) out32[(q * 2 + h) * 64 + lane] = pack_bf16(acc[q][2 * h], acc[q][2 * h + 1]);
 #pragma unroll
-    for (int q = 0; q < NT; ++q)
-        if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16) out[NTILES * 128 + 16 * q + lane] = b[q];
+    } else {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
+    }
 }
 
 // x (column layout, virtual coordinates) <-> a factor row in memory
@@ -129,13 +140,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
     store_vec<F>(xg, x, status);
 }
 
-template <int F, typename PtrT>
+template <int F, typename PtrT, bool S16>
 __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict__ perm,
                                                       const int32_t *__restrict__ task_off, int64_t pos0,
                                                       int64_t task0, const PtrT *__restrict__ ptr,
                                                       const float *__restrict__ slots, float lambda, int fs,
                                                       float eps, float *__restrict__ Xout, int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     const int lane = threadIdx.x, c = lane & 15;
     const int64_t pos = pos0 + blockIdx.x;
     const int row = perm[pos];
@@ -147,13 +158,27 @@ __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict_
     }
     const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;
     v4f acc[NTILES];
-#pragma unroll
-    for (int q = 0; q < NTILES; ++q)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[q][r] = slot[(q * 4 + r) * 64 + lane];
     float b[NT];
+    if constexpr (S16) {
+        const uint32_t *slot32 = reinterpret_cast<const uint32_t *>(slot);
 #pragma unroll
-    for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 256 + 16 * q + c];
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t w = slot32[(q * 2 + h) * 64 + lane];
+                acc[q][2 * h] = bits_to_float(w << 16);
+                acc[q][2 * h + 1] = bits_to_float(w & 0xffff0000u);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 128 + 16 * q + c];
+    } else {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[q][r] = slot[(q * 4 + r) * 64 + lane];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 256 + 16 * q + c];
+    }
     add_diagonal<F>(acc, lambda * (float)n_u);
     float x[NT];
     load_vec<F>(xg, x);
@@ -162,16 +187,34 @@ __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict_
 }
 
 // slots[first] += slots[first+1] + ... (in slot order) for every row of the batch with several slots
-template <int F>
+template <int F, bool S16>
 __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict__ task_off, int64_t pos0,
                                                       int64_t task0, float *__restrict__ slots) {
-    constexpr int SLOT = slot_floats(F);
+    constexpr int SLOT = S16 ? slot_words16(F) : slot_floats(F);
+    constexpr int PACKED = S16 ? tiles_tri(F) * 128 : 0;   // words holding bf16 pairs (a multiple of 4)
     const int64_t pos = pos0 + blockIdx.x;
     const int first = task_off[pos] - (int)task0, n = task_off[pos + 1] - task_off[pos];
     if (n <= 1) return;
     const int o = (blockIdx.y * 256 + threadIdx.x) * 4;
     if (o >= SLOT) return;
     float4 *dst = reinterpret_cast<float4 *>(slots + (int64_t)first * SLOT + o);
+    if (o < PACKED) {   // sums in fp32, stored back as bf16
+        uint4 *dst32 = reinterpret_cast<uint4 *>(dst);
+        const uint4 w0 = *dst32;
+        float a[8] = {bits_to_float(w0.x << 16), bits_to_float(w0.x & 0xffff0000u), bits_to_float(w0.y << 16),
+                      bits_to_float(w0.y & 0xffff0000u), bits_to_float(w0.z << 16), bits_to_float(w0.z & 0xffff0000u),
+                      bits_to_float(w0.w << 16), bits_to_float(w0.w & 0xffff0000u)};
+#pragma unroll 4
+        for (int s = 1; s < n; ++s) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(slots + (int64_t)(first + s) * SLOT + o);
+            a[0] += bits_to_float(w.x << 16); a[1] += bits_to_float(w.x & 0xffff0000u);
+            a[2] += bits_to_float(w.y << 16); a[3] += bits_to_float(w.y & 0xffff0000u);
+            a[4] += bits_to_float(w.z << 16); a[5] += bits_to_float(w.z & 0xffff0000u);
+            a[6] += bits_to_float(w.w << 16); a[7] += bits_to_float(w.w & 0xffff0000u);
+        }
+        *dst32 = make_uint4(pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(a[4], a[5]), pack_bf16(a[6], a[7]));
+        return;
+    }
     float4 v = *dst;
 #pragma unroll 8
     for (int s = 1; s < n; ++s) {
@@ -192,40 +235,42 @@ __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict_
     }
 
 // dispatch on the run-time switches that are template parameters of the kernels
-template <int F, typename PtrT, bool WIDE>
+template <int F, typename PtrT, bool WIDE, bool S16>
 static hipError_t herm_e(int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
                          int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
                          const void *Theta, float *slots) {
     const dim3 grid((unsigned)ntasks), block(64);
     const PtrT *p = (const PtrT *)ptr;
     if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32, S16>), grid, block, 0, st, task_row, task_chunk, task0,
                            chunk, p, idx, val, Theta, slots);
     else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16, S16>), grid, block, 0, st, task_row, task_chunk, task0,
                            chunk, p, idx, val, Theta, slots);
     else
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16, S16>), grid, block, 0, st, task_row, task_chunk, task0,
                            chunk, p, idx, val, Theta, slots);
     return hipGetLastError();
 }
 
 template <int F, typename PtrT>
-static hipError_t herm_f(bool wide, int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                         int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
-                         const float *val, const void *Theta, float *slots) {
+static hipError_t herm_f(bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
+                         const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                         const int32_t *idx, const float *val, const void *Theta, float *slots) {
     if (ntasks <= 0) return hipSuccess;
-    return wide ? herm_e<F, PtrT, true>(et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots)
-                : herm_e<F, PtrT, false>(et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots);
+#define ARGS et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots
+    if (s16) return wide ? herm_e<F, PtrT, true, true>(ARGS) : herm_e<F, PtrT, false, true>(ARGS);
+    return wide ? herm_e<F, PtrT, true, false>(ARGS) : herm_e<F, PtrT, false, false>(ARGS);
+#undef ARGS
 }
 
-hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
+hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots) {
-#define CALL(FF)                                                                                                     \
-    (ptr64 ? herm_f<FF, int64_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,     \
-                                 slots)                                                                              \
-           : herm_f<FF, int32_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,     \
+#define CALL(FF)                                                                                                      \
+    (ptr64 ? herm_f<FF, int64_t>(wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, \
+                                 slots)                                                                               \
+           : herm_f<FF, int32_t>(wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, \
                                  slots))
     ALS_FOR_F(CALL)
 #undef CALL
@@ -272,40 +317,47 @@ hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t
 }
 
 template <int F, typename PtrT>
-static hipError_t solve_wave_f(hipStream_t st, const int32_t *perm, const int32_t *task_off, int64_t pos0,
+static hipError_t solve_wave_f(bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off, int64_t pos0,
                                int64_t npos, int64_t task0, const void *ptr, const float *slots, float lambda, int fs,
                                float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off, pos0, task0,
-                       (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+    if (s16)
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, true>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off,
+                           pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+    else
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off,
+                           pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
-hipError_t launch_solve_cg_wave(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status) {
 #define CALL(FF)                                                                                                   \
-    (ptr64 ? solve_wave_f<FF, int64_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+    (ptr64 ? solve_wave_f<FF, int64_t>(s16, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
                                        status)                                                                     \
-           : solve_wave_f<FF, int32_t>(st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+           : solve_wave_f<FF, int32_t>(s16, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
                                        status))
     ALS_FOR_F(CALL)
 #undef CALL
 }
 
 template <int F>
-static hipError_t reduce_f(hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
-                           float *slots) {
+static hipError_t reduce_f(bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
+                           int64_t task0, float *slots) {
     if (npos <= 0) return hipSuccess;
-    constexpr int SLOT = slot_floats(F);
-    hipLaunchKernelGGL((k_reduce_slots<F>), dim3((unsigned)npos, (SLOT / 4 + 255) / 256), dim3(256), 0, st, task_off,
-                       pos0, task0, slots);
+    if (s16)
+        hipLaunchKernelGGL((k_reduce_slots<F, true>), dim3((unsigned)npos, (slot_words16(F) / 4 + 255) / 256),
+                           dim3(256), 0, st, task_off, pos0, task0, slots);
+    else
+        hipLaunchKernelGGL((k_reduce_slots<F, false>), dim3((unsigned)npos, (slot_floats(F) / 4 + 255) / 256),
+                           dim3(256), 0, st, task_off, pos0, task0, slots);
     return hipGetLastError();
 }
 
-hipError_t launch_reduce_slots(int f, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
+hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
                                int64_t task0, float *slots) {
-#define CALL(FF) reduce_f<FF>(st, task_off, pos0, npos, task0, slots)
+#define CALL(FF) reduce_f<FF>(s16, st, task_off, pos0, npos, task0, slots)
     ALS_FOR_F(CALL)
 #undef CALL
 }

@@ -286,6 +286,14 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     }
 }
 
+// fp32 -> bf16 bits, round to nearest even; two values packed in one word (first in the low half)
+__device__ __forceinline__ uint32_t bf16_bits(float x) {
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
+
 // Algorithm 1 (CGSolve) on one system held by one wavefront.
 //   acc   lower-triangle tiles of the symmetric A (register layout of the 16x16 MFMA result:
 //         lane (c = l%16, g = l/16), register r of tile (R,C) is A[16R+4g+r][16C+c]); rows and

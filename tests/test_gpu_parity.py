@@ -286,3 +286,37 @@ def test_reduced_precision_factor_inputs(P, name):
     print(f"{name} inputs, CG(6), 10 sweeps: rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
     assert abs(r - hist[-1]["rmse"]) <= 2e-3
     als.close()
+
+
+def test_reduced_precision_storage_of_split_rows(P):
+    """Section 4.2: A_u stored in 16 bits where it is materialised (here: the partial Gram matrices of
+    split rows, bf16).  Approximate mode only; judged by the 10-sweep RMSE against the exact oracle."""
+    w = W.MID_SMALL
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    with pytest.raises(P.AlsError):
+        P.Als(w.f, solver=P.SOLVER_CHOLESKY, herm_dtype=P.BF16)     # exact mode keeps fp32
+    _, _, hist = oracle.als((a.ptr, a.idx, a.val), (c.ptr, c.idx, c.val), X0, T0, w.lam, w.sweeps)
+    # chunk 64: every row of this workload is split, so every A_u goes through bf16 slots
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, chunk=64, herm_dtype=P.BF16)
+    ref = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, chunk=64)
+    X, T = _dev(X0), _dev(T0)
+    X32 = _dev(X0)
+    als.update_rows(csr, T, w.lam, X)
+    ref.update_rows(csr, T, w.lam, X32)
+    dev = _row_rel_err(X.cpu().numpy(), X32.cpu().numpy().astype(np.float64))
+    print(f"bf16 slot storage: first half-sweep deviates from fp32 storage by max {dev.max():.2e} per row")
+    assert 0 < dev.max() <= 5e-2
+    als.update_cols(csc, X, w.lam, T)
+    for _ in range(w.sweeps - 1):
+        als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+    als.synchronize()
+    r = ref.rmse(csr, X, T)
+    print(f"bf16 slot storage, CG(6), 10 sweeps: rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
+    assert abs(r - hist[-1]["rmse"]) <= 2e-3
+    als.close()
+    ref.close()
