@@ -16,9 +16,12 @@ __device__ __forceinline__ void tile_rc(int tile, int &R, int &C) {
     C = tile - r * (r + 1) / 2;
 }
 
-// Sums the slots of one row into a dense lower triangle As[row*LD + col] (col <= row < F, feature
+// packed lower triangle: element (i, k), k <= i, at i(i+1)/2 + k
+__device__ __forceinline__ int tri(int i, int k) { return i * (i + 1) / 2 + k; }
+
+// Sums the slots of one row into a packed lower triangle As[tri(row, col)] (col <= row < F, feature
 // coordinates) and bs[0..F).  Adds reg to the diagonal.  Every thread of the block takes part.
-template <int F, int LD>
+template <int F>
 __device__ __forceinline__ void load_system(const float *__restrict__ slots, int nslots, float reg, float *As,
                                             float *bs) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
@@ -33,7 +36,7 @@ __device__ __forceinline__ void load_system(const float *__restrict__ slots, int
             for (int s = 0; s < nslots; ++s) v += slots[(int64_t)s * SLOT + o];
             if (fr == fc) v += reg;
             const int hi = fr > fc ? fr : fc, lo = fr > fc ? fc : fr;
-            As[hi * LD + lo] = v;
+            As[tri(hi, lo)] = v;
         }
     }
     for (int o = threadIdx.x; o < NT * 16; o += blockDim.x) {
@@ -56,8 +59,8 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
                                                     int64_t task0, const PtrT *__restrict__ ptr,
                                                     const float *__restrict__ slots, float lambda,
                                                     float *__restrict__ Xout, int *__restrict__ status) {
-    constexpr int LD = F + 1, SLOT = slot_floats(F);
-    __shared__ float As[(F + 1) * LD];
+    constexpr int SLOT = slot_floats(F);
+    __shared__ float As[(F + 1) * (F + 2) / 2];   // packed lower triangle of the bordered matrix, row F = b
     const int64_t pos = pos0 + blockIdx.x;
     const int row = perm[pos];
     const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
@@ -68,50 +71,57 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
     }
     const int first = task_off[pos] - (int)task0;
     // the slots of a split row have been summed into its first slot by k_reduce_slots
-    load_system<F, LD>(slots + (int64_t)first * SLOT, 1, lambda * (float)n_u, As, As + F * LD);
+    load_system<F>(slots + (int64_t)first * SLOT, 1, lambda * (float)n_u, As, As + tri(F, 0));
 
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     bool bad = false;
     for (int j = 0; j < F; ++j) {
         __syncthreads();
-        float d = As[j * LD + j];
+        float d = As[tri(j, j)];
         if (!(d > 0.f)) { bad = true; d = 1.f; }
         const float invd = 1.f / d;
         // rows i in (j, F] (row F is b), columns k in (j, min(i, F-1)]
         for (int i = j + 1 + ty; i <= F; i += 16) {
-            const float lij = As[i * LD + j] * invd;
+            const int ri = tri(i, 0);
+            const float lij = As[ri + j] * invd;
             const int kmax = i < F ? i : F - 1;
-            for (int k = j + 1 + tx; k <= kmax; k += 16) As[i * LD + k] -= lij * As[k * LD + j];
+            for (int k = j + 1 + tx; k <= kmax; k += 16) As[ri + k] -= lij * As[tri(k, j)];
         }
     }
     __syncthreads();
     if (bad && threadIdx.x == 0) atomicOr(status, kStatusBadPivot);
     if (threadIdx.x >= 64) return;
-    // back substitution by one wavefront: lane l owns z_l and z_{l+64}
+    // back substitution by one wavefront: lane l owns z_l, z_{l+64}, ...
+    constexpr int NZ = (F + 63) / 64;
     const int l = threadIdx.x;
-    float z0 = (l < F) ? As[F * LD + l] : 0.f;
-    float z1 = (l + 64 < F) ? As[F * LD + l + 64] : 0.f;
-    float x0 = 0.f, x1 = 0.f;
+    float z[NZ], xs[NZ];
+#pragma unroll
+    for (int q = 0; q < NZ; ++q) {
+        z[q] = (l + 64 * q < F) ? As[tri(F, l + 64 * q)] : 0.f;
+        xs[q] = 0.f;
+    }
     for (int k = F - 1; k >= 0; --k) {
-        const float zk = __shfl(k < 64 ? z0 : z1, k & 63);
-        float dk = As[k * LD + k];
+        float zsel = z[0];
+#pragma unroll
+        for (int q = 1; q < NZ; ++q) zsel = (k >> 6) == q ? z[q] : zsel;
+        const float zk = __shfl(zsel, k & 63);
+        float dk = As[tri(k, k)];
         if (!(dk > 0.f)) dk = 1.f;
         const float xk = zk / dk;
-        if (l == (k & 63)) {
-            if (k < 64) x0 = xk; else x1 = xk;
-        }
         // z_i -= (L[k][i] d_i) x_k for i < k
-        if (l < k) z0 -= As[k * LD + l] * xk;
-        if (l + 64 < k) z1 -= As[k * LD + l + 64] * xk;
+        const int rk = tri(k, 0);
+#pragma unroll
+        for (int q = 0; q < NZ; ++q) {
+            if (l + 64 * q == k) xs[q] = xk;
+            if (l + 64 * q < k) z[q] -= As[rk + l + 64 * q] * xk;
+        }
     }
-    if (l < F) {
-        x[l] = x0;
-        if (!isfinite(x0)) atomicOr(status, kStatusNonFinite);
-    }
-    if (l + 64 < F) {
-        x[l + 64] = x1;
-        if (!isfinite(x1)) atomicOr(status, kStatusNonFinite);
-    }
+#pragma unroll
+    for (int q = 0; q < NZ; ++q)
+        if (l + 64 * q < F) {
+            x[l + 64 * q] = xs[q];
+            if (!isfinite(xs[q])) atomicOr(status, kStatusNonFinite);
+        }
 }
 
 // ---- dense export (tests, breakdown runs) -----------------------------------------------------
@@ -121,19 +131,19 @@ __global__ __launch_bounds__(256) void k_export_dense(const int32_t *__restrict_
                                                       int64_t task0, const PtrT *__restrict__ ptr,
                                                       const float *__restrict__ slots, float lambda, int64_t row0,
                                                       float *__restrict__ A_out, float *__restrict__ b_out) {
-    constexpr int LD = F + 1, SLOT = slot_floats(F);
-    __shared__ float As[F * LD];
+    constexpr int SLOT = slot_floats(F);
+    __shared__ float As[F * (F + 1) / 2];
     __shared__ float bs[F];
     const int64_t pos = pos0 + blockIdx.x;
     const int row = perm[pos];
     const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
     const int first = task_off[pos] - (int)task0, nslots = task_off[pos + 1] - task_off[pos];
-    load_system<F, LD>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, bs);
+    load_system<F>(slots + (int64_t)first * SLOT, nslots, lambda * (float)n_u, As, bs);
     __syncthreads();
     float *A = A_out + (row - row0) * (int64_t)F * F;
     for (int o = threadIdx.x; o < F * F; o += blockDim.x) {
         const int r = o / F, c = o % F;
-        A[o] = (c <= r) ? As[r * LD + c] : As[c * LD + r];
+        A[o] = (c <= r) ? As[tri(r, c)] : As[tri(c, r)];
     }
     for (int o = threadIdx.x; o < F; o += blockDim.x) b_out[(row - row0) * (int64_t)F + o] = bs[o];
 }
