@@ -65,7 +65,7 @@ typedef struct als_sparse {
 } als_sparse;
 
 typedef struct als_config {
-    int32_t f;            /* number of latent features; supported: 16, 32, 64, 100, 128                 */
+    int32_t f;            /* number of latent features; supported: 16, 32, 64, 100, 128, 256            */
     int32_t solver;       /* ALS_SOLVER_*                                                                */
     int32_t cg_iters;     /* f_s of Algorithm 1 (used when solver == ALS_SOLVER_CG)                      */
     float cg_eps;         /* epsilon of Algorithm 1: stop when sqrt(r^T r) < cg_eps; 0 = fixed f_s steps */
@@ -79,7 +79,7 @@ typedef struct als_config {
     void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */
     int32_t chunk;        /* stored entries per work item, a power of two in [64, 2^20]; longer rows are
                              split (0 = default 1024)                                                    */
-    int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = default 131072)           */
+    int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = about 4 GB worth)           */
     int32_t profile;      /* 1: bracket every kernel with HIP events (see als_kernel_time)               */
 } als_config;
 

@@ -24,6 +24,8 @@ namespace als {
 constexpr int tiles_1d(int F) { return (F + 15) / 16; }
 constexpr int tiles_tri(int F) { return tiles_1d(F) * (tiles_1d(F) + 1) / 2; }
 constexpr int slot_floats(int F) { return tiles_tri(F) * 256 + tiles_1d(F) * 16; }
+// tiles of the tile rows [R0, R1): what one wavefront holds when a work item is shared by several
+constexpr int tiles_range(int R0, int R1) { return R1 * (R1 + 1) / 2 - R0 * (R0 + 1) / 2; }
 // slot with the tiles stored as packed bf16 pairs (registers 2h, 2h+1 of a tile in one 32-bit word at
 // word offset (2t+h)*64 + l), b_u still fp32: the reduced-precision storage of Section 4.2
 constexpr int slot_words16(int F) { return tiles_tri(F) * 128 + tiles_1d(F) * 16; }
@@ -73,6 +75,9 @@ hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t
 hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
+hipError_t launch_solve_cg_rows(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                float lambda, int fs, float eps, float *Xout, int *status);
 hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
                                int64_t task0, float *slots);
 
@@ -101,6 +106,8 @@ hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
 hipError_t transpose_csr(bool ptr64, hipStream_t st, int64_t nrows, int64_t ncols, int64_t nnz, const void *ptr,
                          const int32_t *idx, const float *val, void *cptr, int32_t *cidx, float *cval);
 
-inline bool supported_f(int f) { return f == 16 || f == 32 || f == 64 || f == 100 || f == 128; }
+inline bool supported_f(int f) { return f == 16 || f == 32 || f == 64 || f == 100 || f == 128 || f == 256; }
+// f whose lower triangle fits the registers of one wavefront (fused build+solve, wave-per-row CG)
+inline bool single_wave_f(int f) { return f <= 128; }
 
 }  // namespace als

@@ -179,7 +179,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const bool wide = (uint64_t)a->ncols * (uint64_t)f * esize >= (1ull << 32);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
-    const int64_t slot_rows = cg ? p->split_pos : m;
+    const bool one_wave = single_wave_f(f);   // larger f: no fusion, every row goes through a slot
+    const int64_t slot_rows = (cg && one_wave) ? p->split_pos : m;
     int64_t pos = 0;
     while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
@@ -201,7 +202,11 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             Timed t(ctx, ALS_K_SOLVE);
             if (ntasks > end - pos)   // some row of the batch has several slots
                 HIP_TRY(ctx, launch_reduce_slots(f, s16, ctx->stream, p->task_off, pos, end - pos, task0, ctx->slots));
-            if (cg)
+            if (cg && !one_wave)
+                HIP_TRY(ctx, launch_solve_cg_rows(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
+                                                  a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
+                                                  Out, ctx->status));
+            else if (cg)
                 HIP_TRY(ctx, launch_solve_cg_wave(f, p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
@@ -234,7 +239,9 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (cfg->factor_dtype != ALS_F32 && cfg->factor_dtype != ALS_BF16 && cfg->factor_dtype != ALS_F16) return ALS_EINVAL;
     // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
     // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
-    if (cfg->herm_dtype != ALS_F32 && !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG)) return ALS_EINVAL;
+    if (cfg->herm_dtype != ALS_F32 &&
+        !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG && single_wave_f(cfg->f)))
+        return ALS_EINVAL;
     if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
     if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;
     int ndev = 0;
@@ -243,7 +250,11 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (!ctx) return ALS_ENOMEM;
     ctx->cfg = *cfg;
     if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 1024;
-    if (ctx->cfg.batch_slots == 0) ctx->cfg.batch_slots = 131072;
+    if (ctx->cfg.batch_slots == 0) {   // about 4 GB of slots
+        ctx->cfg.batch_slots = 131072;
+        while (ctx->cfg.batch_slots > 1024 && (size_t)ctx->cfg.batch_slots * slot_floats(cfg->f) * 4 > (4ull << 30))
+            ctx->cfg.batch_slots /= 2;
+    }
     ctx->stream = (hipStream_t)cfg->stream;
     if (hipSetDevice(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
         hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||

@@ -87,6 +87,7 @@ hipError_t launch_sse(int f, bool ptr64, hipStream_t st, const int32_t *task_row
         case 64: return CALL(64);
         case 100: return CALL(100);
         case 128: return CALL(128);
+        case 256: return CALL(256);
         default: return hipErrorInvalidValue;
     }
 #undef CALL

@@ -168,6 +168,7 @@ static hipError_t solve_f(int solver, int cg_iters, float cg_eps, hipStream_t st
         case 64: return CALL(64);                  \
         case 100: return CALL(100);                \
         case 128: return CALL(128);                \
+        case 256: return CALL(256);                \
         default: return hipErrorInvalidValue;      \
     }
 

@@ -88,10 +88,14 @@ __device__ __forceinline__ float widen_hi(uint32_t w) {   // high 16 bits of w
     else return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16));
 }
 
-template <int F, bool IN_VGPR, int D, bool WIDE, int ET>
+// R0, R1: the wavefront accumulates the tile rows [R0, R1) only (acc[R(R+1)/2 + C - R0(R0+1)/2]); the
+// default is the whole triangle.  WANT_B: also produce b_u (one wavefront of a work item does).
+template <int F, bool IN_VGPR, int D, bool WIDE, int ET, int R0 = 0, int R1 = tiles_1d(F), bool WANT_B = true>
 __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                  const void *__restrict__ Theta, int64_t s0, int len,
-                                                 v4f (&acc)[tiles_tri(F)], float (&b)[tiles_1d(F)]) {
+                                                 v4f (&acc)[tiles_range(R0, R1)], float (&b)[tiles_1d(F)]) {
+    static_assert((R0 == 0 && R1 == tiles_1d(F)) || (F % 16) == 0, "partial tile ranges need f to be a multiple of 16");
+    constexpr int ABASE = R0 * (R0 + 1) / 2;
     constexpr int NT = TileGeom<F>::NT, NB = D + 1;
     constexpr bool RIT = TileGeom<F>::RIT;
     constexpr int RI = TileGeom<F>::RI;
@@ -234,7 +238,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         }
         if constexpr (RIT) {
             g[NT - 1] = (i == RI) ? r : g[NT - 1];
-        } else {
+        } else if constexpr (WANT_B) {
 #pragma unroll
             for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
         }
@@ -247,9 +251,9 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             for (int q = 1; q < NT; ++q) asm volatile("" : "+v"(g[q]), "+v"(g[0]));
         }
 #pragma unroll
-        for (int R = 0; R < NT; ++R)
+        for (int R = R0; R < R1; ++R)
 #pragma unroll
-            for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[R * (R + 1) / 2 + C], g[R], g[C]);
+            for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[R * (R + 1) / 2 + C - ABASE], g[R], g[C]);
     };
     auto round = [&](auto mtag, int s, int limit) {
         [&]<int... d>(std::integer_sequence<int, d...>) {
@@ -280,7 +284,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
                 const bool keep = (4 * g4 + r < RI) && (T < NT - 1 || c < RI);
                 acc[(NT - 1) * NT / 2 + T][r] = keep ? acc[(NT - 1) * NT / 2 + T][r] : 0.f;
             }
-    } else {
+    } else if constexpr (WANT_B) {
 #pragma unroll
         for (int q = 0; q < NT; ++q) b[q] = colsum4(bacc[q]);
     }

@@ -38,7 +38,7 @@ def P():
 TOL_EXACT = 1e-4
 
 
-@pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
+@pytest.mark.parametrize("f", [16, 32, 64, 100, 128, 256])
 def test_hermitian_and_bias_match_oracle_on_edge_degrees(P, f):
     n = 5000
     degrees = [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 127, 255, 256, 257, 300, 1023, 1024, 1025, 2048, 2500, 4097, 0, 1]
@@ -320,3 +320,46 @@ def test_reduced_precision_storage_of_split_rows(P):
     assert abs(r - hist[-1]["rmse"]) <= 2e-3
     als.close()
     ref.close()
+
+
+@pytest.mark.parametrize("f", [32, 64, 128, 256])
+def test_factor_width_sweep_exact_and_cg(P, f):
+    """The factor-width sweep on a reduced shape: one exact sweep per row 1e-4, CG(4/6/8) against the same
+    Algorithm 1 in double, and the 10-sweep CG(6) training RMSE against the exact oracle."""
+    w = W.Workload(f"width_{f}", 3_000, 1_200, 240_000, f, 0.05, 1.0, 1, 1_100, 1.0, 20, seed=40 + f, sweeps=10)
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=256)
+    X, T = _dev(X0), _dev(T0)
+    als.update_rows(csr, T, w.lam, X)
+    als.update_cols(csc, X, w.lam, T)
+    als.synchronize()
+    Xo = oracle.update_rows(a.ptr, a.idx, a.val, T0, w.lam)
+    To = oracle.update_rows(c.ptr, c.idx, c.val, Xo, w.lam)
+    ex, et = _row_rel_err(X.cpu().numpy(), Xo), _row_rel_err(T.cpu().numpy(), To)
+    print(f"f={f} exact sweep: X max {ex.max():.2e} Theta max {et.max():.2e}")
+    assert ex.max() <= TOL_EXACT and et.max() <= TOL_EXACT
+    als.close()
+    warm = W.random_factors(w.m, f, seed=6, scale=0.1)
+    for fs in (4, 6, 8):
+        als = P.Als(f, solver=P.SOLVER_CG, cg_iters=fs, chunk=256)
+        Xc = _dev(warm.copy())
+        als.update_rows(csr, _dev(T0), w.lam, Xc)
+        als.synchronize()
+        ref = oracle.update_rows_cg(a.ptr, a.idx, a.val, T0, w.lam, warm, fs=fs)
+        assert _row_rel_err(Xc.cpu().numpy(), ref).max() <= 2e-3
+        als.close()
+    _, _, hist = oracle.als((a.ptr, a.idx, a.val), (c.ptr, c.idx, c.val), X0, T0, w.lam, w.sweeps)
+    als = P.Als(f, solver=P.SOLVER_CG, cg_iters=6)
+    X, T = _dev(X0), _dev(T0)
+    for _ in range(w.sweeps):
+        als.update_rows(csr, T, w.lam, X)
+        als.update_cols(csc, X, w.lam, T)
+    r = als.rmse(csr, X, T)
+    als.synchronize()
+    print(f"f={f} CG(6) 10 sweeps: rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
+    assert abs(r - hist[-1]["rmse"]) <= 2e-3
+    als.close()
