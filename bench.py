@@ -59,7 +59,21 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--batch-slots", type=int, default=0)
     ap.add_argument("--cpu-stride", type=int, default=8, help="oracle baseline on every k-th row/column; 0 = skip")
+    ap.add_argument("--f", type=int, default=0, help="override the workload's factor width (factor-width sweep)")
+    ap.add_argument("--factor-dtype", default="f32", choices=["f32", "bf16", "f16"],
+                    help="element type of the gathered factor matrix (16-bit: widened in registers, fp32 accumulate)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1.0, out=dst)      # an elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "5 x (read 1 GiB, write 1 GiB), torch elementwise add kernel"}))
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
                  "path would shard). Run with --gpus 1.")
@@ -72,13 +86,17 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     w = W.CONFIGS[args.workload]
+    if args.f:
+        w = w.with_f(args.f)
     dev = "cuda:0"
     t0 = time.perf_counter()
     a = W.generate(w)
     log(f"[bench] generated {w.name}: {w.m} x {w.n}, {a.nnz} stored entries in {time.perf_counter() - t0:.1f} s")
     solver = P.SOLVER_CG if args.solver == "cg" else P.SOLVER_CHOLESKY
+    fcode = {"f32": P.F32, "bf16": P.BF16, "f16": P.F16}[args.factor_dtype]
+    ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.factor_dtype]
     als = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
-                profile=True)
+                profile=True, factor_dtype=fcode)
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, device=dev)
     csc = als.csr_to_csc(csr)
     X0, T0 = W.init_factors(w)
@@ -86,8 +104,9 @@ def main():
     del X0
 
     def sweep():
-        als.update_rows(csr, T, w.lam, X)
-        als.update_cols(csc, X, w.lam, T)
+        # 16-bit modes: the gathered factor is converted by torch inside the timed region (part of the sweep)
+        als.update_rows(csr, T if fcode == P.F32 else T.to(ftorch), w.lam, X)
+        als.update_cols(csc, X if fcode == P.F32 else X.to(ftorch), w.lam, T)
 
     for _ in range(args.warmup):
         sweep()
@@ -103,7 +122,7 @@ def main():
     fused_ms, fused_n = als.kernel_time(P.K_FUSED)
     solve_ms, solve_n = als.kernel_time(P.K_SOLVE)
     als.synchronize()
-    rmse = als.rmse(csr, X, T)
+    rmse = P.Als(w.f).rmse(csr, X, T) if fcode != P.F32 else als.rmse(csr, X, T)
     K = args.steps
     log(f"[bench] {K} sweeps in {elapsed:.3f} s; rmse {rmse:.5f}; per sweep: k_hermitian {herm_ms / K:.2f} ms "
         f"({herm_n // K} launches), k_hermitian_cg {fused_ms / K:.2f} ms ({fused_n // K}), "
@@ -131,9 +150,10 @@ def main():
                 "k_hermitian_cg": {"tflops": (2 * w.nnz - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
                                    "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * w.nnz - nnz_slot}}
     out = {
-        "metric": "seconds per ALS sweep (X+Theta) at f=100", "value": sec_per_sweep, "unit": "s/sweep",
+        "metric": f"seconds per ALS sweep (X+Theta) at f={w.f}", "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "factor_dtype": args.factor_dtype,
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={w.nnz} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
                    "chunk": chunk, "batch_slots": als.cfg.batch_slots or 131072},
