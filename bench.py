@@ -48,6 +48,22 @@ def cpu_baseline(w, a_host, stride):
                       f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries"}
 
 
+# HBM bytes moved by the get_hermitian launches of one sweep (k_hermitian x2 + k_hermitian_cg), from the
+# rocprofv3 counter runs summarised in profiles/k_hermitian_mid_f100_cg6_counters.txt: FETCH_SIZE and WRITE_SIZE
+# summed over those dispatches, scaled by what the same counters read for a copy of known size (2 KiB and
+# 1 KiB per count).  Counters cannot be read from inside this process, so the figure is only reported for
+# the configuration it was measured on.
+MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 1024): 47.5e9 + 4.9e9}
+
+
+def measured_traffic(w, args, chunk, launches):
+    key = (w.name, w.f, args.solver, args.cg_iters if args.solver == "cg" else 0, args.factor_dtype, chunk)
+    total = MEASURED_TRAFFIC_BYTES_PER_SWEEP.get(key)
+    if total is None or launches <= 0 or args.batch_slots != 0:
+        return None
+    return total / launches
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -130,18 +146,20 @@ def main():
 
     # get_hermitian roofline.  Algorithmic flops = f*(f+1) per stored entry and half-sweep (lower triangle
     # of theta theta^T, FMA = 2).  Rows with >= chunk entries are built by k_hermitian into slots, shorter
-    # rows by k_hermitian_cg (which also runs Algorithm 1: its time is charged to get_hermitian in full).
+    # rows by k_hermitian_cg (which also runs the solver: its time is charged to get_hermitian in full).
     chunk = als.cfg.chunk or 1024
     deg_r = np.diff(a.ptr)
     deg_c = np.bincount(a.idx, minlength=w.n)
-    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if args.solver == "cg" else 2 * w.nnz
+    # (the fused kernel exists for f <= 128; the exact solver uses it with fp32 factor inputs only)
+    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if fused_n > 0 else 2 * w.nnz
     per_entry = w.f * (w.f + 1)
     flops_sweep = 2.0 * w.nnz * per_entry
     herm_s = (herm_ms + fused_ms) * 1e-3 / K
     achieved = flops_sweep / herm_s / 1e12
     launches = (herm_n + fused_n) // K
     roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                "traffic": measured_traffic(w, args, chunk, launches),
                 "kernel": "k_hermitian + k_hermitian_cg (all get_hermitian work of a sweep)",
                 "launches_per_sweep": launches, "avg_launch_ms": (herm_ms + fused_ms) / max(herm_n + fused_n, 1),
                 "flops_per_launch": flops_sweep / max(launches, 1),

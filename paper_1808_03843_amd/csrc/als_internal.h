@@ -69,10 +69,11 @@ hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipS
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots);
 
-hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm,
+// solver: ALS_SOLVER_CG or ALS_SOLVER_CHOLESKY (the latter with fp32 factor inputs only)
+hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
-hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
 hipError_t launch_solve_cg_rows(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,

@@ -180,7 +180,10 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
     const bool one_wave = single_wave_f(f);   // larger f: no fusion, every row goes through a slot
-    const int64_t slot_rows = (cg && one_wave) ? p->split_pos : m;
+    // rows shorter than a chunk are built and solved by one wavefront without leaving the registers; the
+    // exact solver does that for fp32 factor inputs
+    const bool tiles_solver = one_wave && (cg || ctx->cfg.factor_dtype == ALS_F32);
+    const int64_t slot_rows = tiles_solver ? p->split_pos : m;
     int64_t pos = 0;
     while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
@@ -206,8 +209,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                 HIP_TRY(ctx, launch_solve_cg_rows(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
-            else if (cg)
-                HIP_TRY(ctx, launch_solve_cg_wave(f, p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
+            else if (tiles_solver)
+                HIP_TRY(ctx, launch_solve_cg_wave(f, p64, s16, ctx->cfg.solver, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
             else
@@ -219,7 +222,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     }
     if (slot_rows < m) {
         Timed t(ctx, ALS_K_FUSED);
-        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
+        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
                                          a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
                                          ctx->status));
     }

@@ -11,10 +11,11 @@
 //
 //   k_hermitian        work items of long rows: the partial A_u, b_u go to a slot in memory.
 //   k_hermitian_cg     whole short rows: A_u never leaves the registers; the same wavefront runs
-//                      Algorithm 1 on the accumulator tiles and writes x_u (the paper flushes A_u to
-//                      global memory and reads it back in the solver, Section 3 and Observation 4).
+//                      Algorithm 1 (or, in exact mode, an LDL^T factorisation and the triangular solves)
+//                      on the accumulator tiles and writes x_u (the paper flushes A_u to global memory
+//                      and reads it back in the solver, Section 3 and Observation 4).
 //   k_reduce_slots     sums the slots of a split row into its first slot, in slot order.
-//   k_solve_cg_wave    Algorithm 1 for rows whose A_u sits in a slot, one wavefront per row.
+//   k_solve_cg_wave    the same two solvers for rows whose A_u sits in a slot, one wavefront per row.
 #include "tiles.h"
 
 namespace als {
@@ -112,7 +113,7 @@ __device__ __forceinline__ void store_zero_vec(float *__restrict__ dst) {
     for (int q = threadIdx.x; q < F; q += 64) dst[q] = 0.f;
 }
 
-template <int F, typename PtrT, bool WIDE, int ET>
+template <int F, typename PtrT, bool WIDE, int ET, int SOLVER>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F), fused_waves(F)))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
                                                      const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                      const float *__restrict__ val, const void *__restrict__ Theta,
@@ -135,12 +136,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
     accumulate_tiles<F, true, kDepthFused, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
     add_diagonal<F>(acc, lambda * (float)len);
     float x[NT];
-    load_vec<F>(xg, x);
-    cg_tiles<F>(acc, b, x, fs, eps);
+    if constexpr (SOLVER == ALS_SOLVER_CG) {
+        load_vec<F>(xg, x);
+        cg_tiles<F>(acc, b, x, fs, eps);
+    } else {
+        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+    }
     store_vec<F>(xg, x, status);
 }
 
-template <int F, typename PtrT, bool S16>
+template <int F, typename PtrT, bool S16, int SOLVER>
 __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict__ perm,
                                                       const int32_t *__restrict__ task_off, int64_t pos0,
                                                       int64_t task0, const PtrT *__restrict__ ptr,
@@ -181,8 +186,12 @@ __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict_
     }
     add_diagonal<F>(acc, lambda * (float)n_u);
     float x[NT];
-    load_vec<F>(xg, x);
-    cg_tiles<F>(acc, b, x, fs, eps);
+    if constexpr (SOLVER == ALS_SOLVER_CG) {
+        load_vec<F>(xg, x);
+        cg_tiles<F>(acc, b, x, fs, eps);
+    } else {
+        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+    }
     store_vec<F>(xg, x, status);
 }
 
@@ -438,66 +447,75 @@ hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipS
 }
 
 template <int F, typename PtrT, bool WIDE>
-static hipError_t herm_cg_e(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
-                            const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
-                            float *Xout, int *status) {
+static hipError_t herm_cg_e(int et, int solver, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                            const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
+                            int fs, float eps, float *Xout, int *status) {
     const dim3 grid((unsigned)npos), block(64);
     const PtrT *p = (const PtrT *)ptr;
-    if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32>), grid, block, 0, st, perm, pos0, p, idx, val,
-                           Theta, lambda, fs, eps, Xout, status);
+    if (solver == ALS_SOLVER_CHOLESKY) {   // exact solve on the tiles: fp32 factor inputs only
+        if (et != ALS_F32) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CHOLESKY>), grid, block, 0, st, perm,
+                           pos0, p, idx, val, Theta, lambda, fs, eps, Xout, status);
+    } else if (et == ALS_F32)
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0, p,
+                           idx, val, Theta, lambda, fs, eps, Xout, status);
     else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16>), grid, block, 0, st, perm, pos0, p, idx, val,
-                           Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0,
+                           p, idx, val, Theta, lambda, fs, eps, Xout, status);
     else
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16>), grid, block, 0, st, perm, pos0, p, idx, val,
-                           Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0, p,
+                           idx, val, Theta, lambda, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
 template <int F, typename PtrT>
-static hipError_t herm_cg_f(bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
-                            const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
-                            int fs, float eps, float *Xout, int *status) {
+static hipError_t herm_cg_f(bool wide, int et, int solver, hipStream_t st, const int32_t *perm, int64_t pos0,
+                            int64_t npos, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                            float lambda, int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    return wide ? herm_cg_e<F, PtrT, true>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status)
-                : herm_cg_e<F, PtrT, false>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,
-                                            status);
+    return wide ? herm_cg_e<F, PtrT, true>(et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,
+                                           Xout, status)
+                : herm_cg_e<F, PtrT, false>(et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,
+                                            Xout, status);
 }
 
-hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm,
+hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
-#define CALL(FF)                                                                                                    \
-    (ptr64 ? herm_cg_f<FF, int64_t>(wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,    \
-                                    status)                                                                         \
-           : herm_cg_f<FF, int32_t>(wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,    \
-                                    status))
+#define CALL(FF)                                                                                                     \
+    (ptr64 ? herm_cg_f<FF, int64_t>(wide, et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,   \
+                                    Xout, status)                                                                    \
+           : herm_cg_f<FF, int32_t>(wide, et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,   \
+                                    Xout, status))
     ALS_FOR_F(CALL)
 #undef CALL
 }
 
 template <int F, typename PtrT>
-static hipError_t solve_wave_f(bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off, int64_t pos0,
-                               int64_t npos, int64_t task0, const void *ptr, const float *slots, float lambda, int fs,
-                               float eps, float *Xout, int *status) {
+static hipError_t solve_wave_f(bool s16, int solver, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                               int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                               float lambda, int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    if (s16)
-        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, true>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off,
-                           pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+    if (solver == ALS_SOLVER_CHOLESKY) {
+        if (s16) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CHOLESKY>), dim3((unsigned)npos), dim3(64), 0, st,
+                           perm, task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+    } else if (s16)
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, true, ALS_SOLVER_CG>), dim3((unsigned)npos), dim3(64), 0, st, perm,
+                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
     else
-        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false>), dim3((unsigned)npos), dim3(64), 0, st, perm, task_off,
-                           pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CG>), dim3((unsigned)npos), dim3(64), 0, st, perm,
+                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
-hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status) {
 #define CALL(FF)                                                                                                   \
-    (ptr64 ? solve_wave_f<FF, int64_t>(s16, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+    (ptr64 ? solve_wave_f<FF, int64_t>(s16, solver, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
                                        status)                                                                     \
-           : solve_wave_f<FF, int32_t>(s16, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
+           : solve_wave_f<FF, int32_t>(s16, solver, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, fs, eps, Xout,  \
                                        status))
     ALS_FOR_F(CALL)
 #undef CALL

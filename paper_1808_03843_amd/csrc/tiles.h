@@ -384,6 +384,87 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
     }
 }
 
+// Exact solve (Section 2 step (ii), Section 4.1 baseline) of one system held by one wavefront: LDL^T
+// without square roots, right-looking and unblocked, directly on the accumulator tiles, then the two
+// triangular solves.  Same argument layout as cg_tiles; acc is overwritten (column j ends up holding
+// L[:,j]*d_j).  Returns false if a pivot was not positive (the pivot is then replaced by 1).
+//   per column j (tile column K, lane jl): the column is fetched into the "row layout" of every tile
+//   row (4 permutes each), turned into the "column layout" and scaled by 1/d_j (one permute each);
+//   the rank-1 update of the remaining tiles and the forward substitution use both.
+template <int F>
+__device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float (&b)[tiles_1d(F)],
+                                           float (&x)[tiles_1d(F)]) {
+    constexpr int NT = tiles_1d(F);
+    constexpr int LASTCOLS = (F % 16) ? (F % 16) : 16;   // feature columns of the last tile
+    const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
+    const int addr_cl = 4 * (16 * (c >> 2) + c);
+    const int csel = c & 3;
+    float z[NT], dinv[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        z[q] = b[q];
+        dinv[q] = 0.f;
+    }
+    bool ok = true;
+    auto pick = [](const v4f &t, int r) { return r == 0 ? t[0] : r == 1 ? t[1] : r == 2 ? t[2] : t[3]; };
+#pragma unroll
+    for (int K = 0; K < NT; ++K) {
+        const int ncol = (K == NT - 1) ? LASTCOLS : 16;
+#pragma unroll 1
+        for (int jl = 0; jl < ncol; ++jl) {
+            const int jr = jl & 3, jg = jl >> 2;
+            float d = bperm(4 * (16 * jg + jl), pick(acc[K * (K + 1) / 2 + K], jr));
+            if (!(d > 0.f)) {
+                ok = false;
+                d = 1.f;
+            }
+            const float inv = 1.f / d;
+            float colv[NT][4], rowv[NT];
+            const int addr_rl = 4 * (16 * g + jl);
+#pragma unroll
+            for (int R = K; R < NT; ++R) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) colv[R][r] = bperm(addr_rl, acc[R * (R + 1) / 2 + K][r]);
+                const float sel = csel == 0 ? colv[R][0] : csel == 1 ? colv[R][1] : csel == 2 ? colv[R][2] : colv[R][3];
+                rowv[R] = bperm(addr_cl, sel) * inv;
+            }
+            rowv[K] = (c > jl) ? rowv[K] : 0.f;   // columns up to j of this tile column are final
+            const float zj = bperm(4 * jl, z[K]);
+            dinv[K] = (c == jl) ? inv : dinv[K];
+#pragma unroll
+            for (int C = K; C < NT; ++C) z[C] = fmaf(-rowv[C], zj, z[C]);
+#pragma unroll
+            for (int R = K; R < NT; ++R)
+#pragma unroll
+                for (int C = K; C <= R; ++C)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        acc[R * (R + 1) / 2 + C][r] = fmaf(-colv[R][r], rowv[C], acc[R * (R + 1) / 2 + C][r]);
+        }
+    }
+    // back substitution, columns from the last to the first: x_j = z_j/d_j, then z_i -= (L[j][i] d_i) x_j, i < j
+#pragma unroll
+    for (int q = 0; q < NT; ++q) x[q] = 0.f;
+#pragma unroll
+    for (int K = NT - 1; K >= 0; --K) {
+        const int ncol = (K == NT - 1) ? LASTCOLS : 16;
+#pragma unroll 1
+        for (int jl = ncol - 1; jl >= 0; --jl) {
+            const int jr = jl & 3, jg = jl >> 2;
+            const float xj = bperm(4 * jl, z[K] * dinv[K]);
+            x[K] = (c == jl) ? xj : x[K];
+            const int addr_row = 4 * (16 * jg + c);   // lane (c, jg) holds row j of the tiles (K, C)
+#pragma unroll
+            for (int C = 0; C <= K; ++C) {
+                float upd = bperm(addr_row, pick(acc[K * (K + 1) / 2 + C], jr)) * xj;
+                if (C == K) upd = (c < jl) ? upd : 0.f;
+                z[C] -= upd;
+            }
+        }
+    }
+    return ok;
+}
+
 // adds reg to the diagonal entries of the diagonal tiles that belong to a feature
 template <int F>
 __device__ __forceinline__ void add_diagonal(v4f (&acc)[tiles_tri(F)], float reg) {
