@@ -69,6 +69,11 @@ def _load():
         lib.oracle_regulariser.restype = d
         lib.oracle_csr_to_csc.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp]
         lib.oracle_bin_rows.argtypes = [i64, vp, ci, vp, vp]
+        lib.oracle_implicit_normal_eq.argtypes = [ci, i64, i64, vp, vp, vp, d, d, vp, vp, vp]
+        lib.oracle_implicit_update_selected.argtypes = [i64, vp, vp, vp, vp, vp, i64, ci, d, d, vp]
+        lib.oracle_implicit_update_selected.restype = i64
+        lib.oracle_implicit_objective.argtypes = [i64, i64, vp, vp, vp, vp, vp, ci, d, d]
+        lib.oracle_implicit_objective.restype = d
         lib.oracle_num_threads.restype = ci
         _lib = lib
     return _lib
@@ -211,6 +216,46 @@ def als(csr, csc, X0, Theta0, lam, sweeps, solver="cholesky", fs=6, eps=0.0):
             T = update_rows_cg(*csc, X, lam, T, fs, eps)
         hist.append({"rmse": rmse(*csr, X, T), "objective": objective(*csr, X, T, lam)})
     return X, T, hist
+
+
+def implicit_update_selected(rows, ptr, idx, val, Theta, lam, alpha):
+    """Implicit-feedback update (Section 5.6) of the listed rows (None: all), exact: len(rows) x f."""
+    ptr, idx, val, Theta = _c(ptr, _i64), _c(idx, _i32), _c(val, _f32), _c(Theta, _f64)
+    n, f = Theta.shape
+    if rows is None:
+        nsel, rp = len(ptr) - 1, None
+    else:
+        rows = _c(rows, _i64)
+        nsel, rp = len(rows), _p(rows)
+    X = np.empty((nsel, f), _f64)
+    bad = _load().oracle_implicit_update_selected(nsel, rp, _p(ptr), _p(idx), _p(val), _p(Theta), n, f,
+                                                  float(lam), float(alpha), _p(X))
+    if bad:
+        raise np.linalg.LinAlgError(f"{bad} rows with a non-positive pivot")
+    return X
+
+
+def implicit_update_rows(ptr, idx, val, Theta, lam, alpha):
+    return implicit_update_selected(None, ptr, idx, val, Theta, lam, alpha)
+
+
+def implicit_normal_eq(idx, r, Theta, lam, alpha):
+    """A_u, b_u of one row under the implicit cost, summed over all columns (the definition)."""
+    idx, r, Theta = _c(idx, _i32), _c(r, _f32), _c(Theta, _f64)
+    n, f = Theta.shape
+    A, b = np.empty((f, f), _f64), np.empty(f, _f64)
+    scratch = np.zeros(n, _f64)
+    _load().oracle_implicit_normal_eq(f, n, len(idx), _p(idx), _p(r), _p(Theta), float(lam), float(alpha),
+                                      _p(A), _p(b), _p(scratch))
+    return A, b
+
+
+def implicit_objective(ptr, idx, val, X, Theta, lam, alpha):
+    """Implicit cost over all m*n pairs plus lambda*(|X|^2 + |Theta|^2) (Section 5.6); O(m n f)."""
+    ptr, idx, val = _c(ptr, _i64), _c(idx, _i32), _c(val, _f32)
+    X, Theta = _c(X, _f64), _c(Theta, _f64)
+    return _load().oracle_implicit_objective(X.shape[0], Theta.shape[0], _p(ptr), _p(idx), _p(val), _p(X),
+                                             _p(Theta), X.shape[1], float(lam), float(alpha))
 
 
 def num_threads() -> int:

@@ -28,7 +28,10 @@
  * Parity pins (tests/test_oracle_*.py): brute-force regularised least squares
  * by QR, f = 1 closed form, identical-theta (Sherman-Morrison) closed form,
  * orthonormal closed form, normal-equation residual, monotone objective,
- * CG(f) == Cholesky, CG finite termination, CSR/CSC symmetry and invariants.
+ * CG(f) == Cholesky, CG finite termination, CSR/CSC symmetry and invariants;
+ * implicit feedback: weighted least squares by QR over all columns, f = 1 closed form,
+ * alpha = 0 ridge regression, reduction to the explicit update on a fully observed row,
+ * monotone implicit cost.
  * Parity unpinned: none of the exact-mode functions.  The CG-solver ALS sweep
  * (oracle_update_rows_cg) is pinned only through oracle_cg itself.
  *
@@ -334,6 +337,92 @@ void oracle_bin_rows(int64_t m, const int64_t *ptr, int nclass, int32_t *perm, i
         perm[count[slot]++] = (int32_t)u;
     }
     free(count);
+}
+
+/* ---- implicit feedback (Section 5.6) -------------------------------------------------------
+ * Cost: sum over ALL m*n pairs of c_uv (p_uv - x_u^T theta_v)^2 with p_uv = 1 if r_uv > 0 else 0 and
+ * confidence c_uv = 1 + alpha*r_uv; pairs that are not stored have r_uv = 0 (p = 0, c = 1).
+ * Readings: the printed cost has no regulariser, the method it follows has lambda*(|X|^2 + |Theta|^2),
+ * not weighted by n_u: that is what is added here.  A stored r_uv <= 0 counts like a missing pair
+ * (c = 1 + alpha*max(r,0)); the paper defines p and c for r >= 0 only.
+ *
+ * The row update is the ridge regression over all n columns, written out as its definition:
+ *   A_u = sum_v c_uv theta_v theta_v^T + lambda*I,   b_u = sum_v c_uv p_uv theta_v
+ * (no Theta^T Theta shortcut).  cdense is scratch of n doubles, all zero on entry and on return. */
+void oracle_implicit_normal_eq(int f, int64_t n, int64_t n_u, const int32_t *idx, const float *r,
+                               const double *Theta, double lambda, double alpha, double *A, double *b,
+                               double *cdense) {
+    for (int i = 0; i < f * f; i++) A[i] = 0.0;
+    for (int i = 0; i < f; i++) b[i] = 0.0;
+    for (int64_t q = 0; q < n_u; q++) cdense[idx[q]] = r[q] > 0.f ? (double)r[q] : 0.0;
+    for (int64_t v = 0; v < n; v++) {
+        const double *t = Theta + v * f;
+        double ruv = cdense[v];
+        double c = 1.0 + alpha * ruv, p = ruv > 0.0 ? 1.0 : 0.0;
+        for (int i = 0; i < f; i++) {
+            double cti = c * t[i];
+            double *Ai = A + (int64_t)i * f;
+            for (int j = 0; j < f; j++) Ai[j] += cti * t[j];
+            b[i] += c * p * t[i];
+        }
+    }
+    for (int i = 0; i < f; i++) A[(int64_t)i * f + i] += lambda;
+    for (int64_t q = 0; q < n_u; q++) cdense[idx[q]] = 0.0;
+}
+
+/* Implicit "Update X" for the listed rows (rows == NULL: rows 0..nsel-1), exact solver.
+ * Theta is n x f.  With the CSC of R and X it is the implicit "Update Theta".  Returns failed pivots. */
+int64_t oracle_implicit_update_selected(int64_t nsel, const int64_t *rows, const int64_t *ptr, const int32_t *idx,
+                                        const float *val, const double *Theta, int64_t n, int f, double lambda,
+                                        double alpha, double *X_sel) {
+    int64_t bad = 0;
+#pragma omp parallel reduction(+ : bad)
+    {
+        double *A = (double *)malloc(sizeof(double) * ((size_t)f * f + f));
+        double *b = A + (size_t)f * f;
+        double *cdense = (double *)calloc((size_t)n, sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t q = 0; q < nsel; q++) {
+            int64_t u = rows ? rows[q] : q;
+            int64_t s = ptr[u], n_u = ptr[u + 1] - ptr[u];
+            oracle_implicit_normal_eq(f, n, n_u, idx + s, val + s, Theta, lambda, alpha, A, b, cdense);
+            if (oracle_cholesky_solve(f, A, b) != 0) bad++;
+            for (int i = 0; i < f; i++) X_sel[q * f + i] = b[i];
+        }
+        free(A);
+        free(cdense);
+    }
+    return bad;
+}
+
+/* The implicit cost itself, over all m*n pairs, plus lambda*(|X|_F^2 + |Theta|_F^2).  O(m*n*f). */
+double oracle_implicit_objective(int64_t m, int64_t n, const int64_t *ptr, const int32_t *idx, const float *val,
+                                 const double *X, const double *Theta, int f, double lambda, double alpha) {
+    double total = 0.0;
+#pragma omp parallel reduction(+ : total)
+    {
+        double *rdense = (double *)calloc((size_t)n, sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t u = 0; u < m; u++) {
+            for (int64_t q = ptr[u]; q < ptr[u + 1]; q++) rdense[idx[q]] = val[q] > 0.f ? (double)val[q] : 0.0;
+            const double *x = X + u * f;
+            double row = 0.0;
+            for (int64_t v = 0; v < n; v++) {
+                const double *t = Theta + v * f;
+                double d = 0.0;
+                for (int i = 0; i < f; i++) d += x[i] * t[i];
+                double c = 1.0 + alpha * rdense[v], p = rdense[v] > 0.0 ? 1.0 : 0.0;
+                row += c * (p - d) * (p - d);
+            }
+            for (int64_t q = ptr[u]; q < ptr[u + 1]; q++) rdense[idx[q]] = 0.0;
+            total += row;
+        }
+        free(rdense);
+    }
+    double reg = 0.0;
+    for (int64_t q = 0; q < m * f; q++) reg += X[q] * X[q];
+    for (int64_t q = 0; q < n * f; q++) reg += Theta[q] * Theta[q];
+    return total + lambda * reg;
 }
 
 int oracle_num_threads(void) {
