@@ -110,6 +110,32 @@ int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float la
  * rmse_out: HOST double.  Blocks until the result is available. */
 int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out);
 
+/* Implicit-feedback "Update X" (Section 5.6): the cost is the sum over ALL pairs (u, v) of
+ * c_uv (p_uv - x_u^T theta_v)^2 with p_uv = 1 if r_uv > 0 else 0 and c_uv = 1 + alpha * max(r_uv, 0)
+ * (pairs that are not stored have r_uv = 0), plus lambda * (|X|_F^2 + |Theta|_F^2) (not weighted by
+ * n_u).  For every row u of csr:
+ *     A_u = Theta^T Theta + sum_{v in Omega_u} (c_uv - 1) theta_v theta_v^T + lambda I,
+ *     b_u = sum_{v in Omega_u, r_uv > 0} c_uv theta_v,     x_u = A_u^-1 b_u
+ * which equals the sum over all n columns.  Theta^T Theta is computed once per call by the same
+ * gathered kernel.  Arguments as for als_update_rows; alpha >= 0; requires f <= 128, fp32 factors
+ * and fp32 storage of A_u.  Rows with n_u = 0 get x_u = 0. */
+int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
+                             int f, float *X);
+
+/* Implicit-feedback "Update Theta": the same with the compressed columns of R and X gathered. */
+int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, float alpha,
+                             int f, float *Theta);
+
+/* The implicit cost of Section 5.6 over all nrows x ncols pairs, regulariser included, evaluated as
+ *     sum_{stored} [c (p - d)^2 - d^2] + <X^T X, Theta^T Theta> + lambda (tr X^T X + tr Theta^T Theta),
+ * d = x_u^T theta_v (fp32 dots and Gram matrices, fp64 sums).  loss_out: HOST double.  Blocks. */
+int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda,
+                      float alpha, int f, double *loss_out);
+
+/* G^T G for a factor matrix G (DEVICE, n x f float): out (DEVICE, f x f floats, row-major, full
+ * symmetric).  The dense term of the implicit update; exported for tests.  f <= 128. */
+int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out);
+
 /* get_hermitian / get_bias alone (Section 2, step (i)) for rows [row0, row0+nrows):
  * A_out (DEVICE, nrows x f x f floats, full symmetric, lambda*n_u on the diagonal
  * included) and b_out (DEVICE, nrows x f).  Meant for tests and breakdown runs. */
@@ -141,7 +167,8 @@ int als_synchronize(als_ctx *ctx);
 #define ALS_K_RMSE 2
 #define ALS_K_PLAN 3
 #define ALS_K_FUSED 4 /* get_hermitian and Algorithm 1 in one kernel (rows shorter than chunk, CG solver) */
-#define ALS_K_COUNT 5
+#define ALS_K_GRAM 5  /* Theta^T Theta of the implicit update (Section 5.6)                                   */
+#define ALS_K_COUNT 6
 
 /* With config.profile = 1: total milliseconds and number of launches of one
  * kernel class since the last als_profile_reset, measured with HIP events on

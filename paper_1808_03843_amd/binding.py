@@ -17,12 +17,12 @@ from . import build as _build
 ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
 SOLVER_CHOLESKY, SOLVER_CG = 0, 1
 F32, BF16, F16 = 0, 1, 2
-K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED = 0, 1, 2, 3, 4
+K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
-    "als_profile_reset",
+    "als_profile_reset", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
 ]
 
 
@@ -63,6 +63,10 @@ def load_library() -> ctypes.CDLL:
     lib.als_update_rows.argtypes = [vp, sp, vp, fl, ctypes.c_int, vp]
     lib.als_update_cols.argtypes = [vp, sp, vp, fl, ctypes.c_int, vp]
     lib.als_rmse.argtypes = [vp, sp, vp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    lib.als_update_rows_implicit.argtypes = [vp, sp, vp, fl, fl, ctypes.c_int, vp]
+    lib.als_update_cols_implicit.argtypes = [vp, sp, vp, fl, fl, ctypes.c_int, vp]
+    lib.als_implicit_loss.argtypes = [vp, sp, vp, vp, fl, fl, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    lib.als_gram.argtypes = [vp, vp, i64, ctypes.c_int, vp]
     lib.als_hermitian.argtypes = [vp, sp, vp, fl, ctypes.c_int, i64, i64, vp, vp]
     lib.als_bin_rows.argtypes = [vp, sp, ctypes.c_int, vp, ctypes.POINTER(i64)]
     lib.als_csr_to_csc.argtypes = [vp, sp, vp, vp, vp]
@@ -154,6 +158,29 @@ class Als:
     def update_cols(self, csc: SparseMatrix, X: torch.Tensor, lam: float, Theta: torch.Tensor):
         self._check(self._lib.als_update_cols(self._ctx, ctypes.byref(csc.desc), self._gathered(X, csc.ncols),
                                               lam, self.f, self._factor(Theta, csc.nrows, self.f)))
+
+    def update_rows_implicit(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, alpha: float, X: torch.Tensor):
+        self._check(self._lib.als_update_rows_implicit(self._ctx, ctypes.byref(csr.desc),
+                                                       self._factor(Theta, csr.ncols, self.f), lam, alpha, self.f,
+                                                       self._factor(X, csr.nrows, self.f)))
+
+    def update_cols_implicit(self, csc: SparseMatrix, X: torch.Tensor, lam: float, alpha: float, Theta: torch.Tensor):
+        self._check(self._lib.als_update_cols_implicit(self._ctx, ctypes.byref(csc.desc),
+                                                       self._factor(X, csc.ncols, self.f), lam, alpha, self.f,
+                                                       self._factor(Theta, csc.nrows, self.f)))
+
+    def implicit_loss(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor, lam: float, alpha: float) -> float:
+        out = ctypes.c_double()
+        self._check(self._lib.als_implicit_loss(self._ctx, ctypes.byref(csr.desc), self._factor(X, csr.nrows, self.f),
+                                                self._factor(Theta, csr.ncols, self.f), lam, alpha, self.f,
+                                                ctypes.byref(out)))
+        return out.value
+
+    def gram(self, G: torch.Tensor) -> torch.Tensor:
+        out = torch.empty((self.f, self.f), dtype=torch.float32, device=G.device)
+        self._check(self._lib.als_gram(self._ctx, self._factor(G, G.shape[0], self.f), G.shape[0], self.f,
+                                       out.data_ptr()))
+        return out
 
     def rmse(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor) -> float:
         out = ctypes.c_double()

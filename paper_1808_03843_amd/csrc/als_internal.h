@@ -44,6 +44,11 @@ __host__ __device__ constexpr int feature_of(int F, int t, int i) {
 
 constexpr int kWave = 64;
 
+// what the gathered accumulation computes (template parameter MODE of the kernels)
+constexpr int kExplicit = 0;   // eq. (2): sum theta theta^T, b = sum r theta
+constexpr int kImplicit = 1;   // Section 5.6: sum alpha*r theta theta^T, b = sum (1 + alpha*r) theta over r > 0
+constexpr int kGram = 2;       // rows s0..s0+len of the factor matrix itself, unit weights, no b
+
 struct Plan {                     // per sparse matrix, built once and cached
     const void *key_ptr = nullptr;
     int64_t nrows = 0, nnz = 0;
@@ -90,9 +95,28 @@ hipError_t launch_export_dense(int f, bool ptr64, hipStream_t st, const int32_t 
                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                float lambda, int64_t row0, float *A_out, float *b_out);
 
-hipError_t launch_sse(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                      int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
-                      const float *X, const float *Theta, double *partial, double *total);
+hipError_t launch_sse(int f, bool ptr64, bool implicit, float alpha, hipStream_t st, const int32_t *task_row,
+                      const int32_t *task_chunk, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
+                      const float *val, const float *X, const float *Theta, double *partial, double *total);
+
+// implicit feedback (Section 5.6), f <= 128, fp32 factors and slots
+// G^T G of the n x f matrix G: nslots work items of `per` rows each (per a multiple of 4) -> slots -> out (tile layout)
+hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
+                       float *out);
+hipError_t launch_tiles_to_dense(int f, hipStream_t st, const float *tiles, float *out);
+hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B, double *out3);
+hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+                                     const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                     const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                                     float alpha, float *slots);
+hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
+                                        int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx,
+                                        const float *val, const void *Theta, float lambda, float alpha,
+                                        const float *gram, int fs, float eps, float *Xout, int *status);
+hipError_t launch_solve_wave_implicit(int f, bool ptr64, int solver, hipStream_t st, const int32_t *perm,
+                                      const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
+                                      const void *ptr, const float *slots, float lambda, const float *gram, int fs,
+                                      float eps, float *Xout, int *status);
 
 // plan.hip
 hipError_t plan_bin_rows(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, int nclass, int32_t *perm,

@@ -31,6 +31,8 @@ struct als_ctx {
     double *sse_partial = nullptr;
     size_t sse_partial_bytes = 0;
     double *sse_total = nullptr; // DEVICE
+    float *gram[2] = {nullptr, nullptr};   // DEVICE, tile layout: G^T G of the gathered factor (implicit mode)
+    double *gram_dot = nullptr;            // DEVICE, 3 doubles
     std::vector<TimedLaunch> timed;
     std::vector<hipEvent_t> free_events;
 };
@@ -156,8 +158,40 @@ int ensure_slots(als_ctx *ctx, int64_t nslots, bool s16) {
     return ALS_OK;
 }
 
+// G^T G (n x f fp32 rows) into ctx->gram[which], tile layout.  Uses the slot workspace.
+int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
+    const int f = ctx->cfg.f;
+    if (!ctx->gram[which]) HIP_TRY(ctx, hipMalloc(&ctx->gram[which], sizeof(float) * (size_t)slot_floats(f)));
+    if (n == 0) {
+        HIP_TRY(ctx, hipMemsetAsync(ctx->gram[which], 0, sizeof(float) * (size_t)slot_floats(f), ctx->stream));
+        return ALS_OK;
+    }
+    // work items of `per` rows (a multiple of 4): enough of them to fill the chip, few enough to sum quickly
+    int64_t items = (n + 255) / 256;
+    if (items > 2048) items = 2048;
+    int64_t per = ((n + items - 1) / items + 3) & ~(int64_t)3;
+    if (per > (1 << 28)) return fail(ctx, ALS_EINVAL, "factor matrix too tall for the Gram kernel");
+    const int nslots = (int)((n + per - 1) / per);
+    int rc = ensure_slots(ctx, nslots, false);
+    if (rc != ALS_OK) return rc;
+    const bool wide = (uint64_t)n * (uint64_t)f * 4u >= (1ull << 32);
+    Timed t(ctx, ALS_K_GRAM);
+    HIP_TRY(ctx, launch_gram(f, wide, ctx->stream, G, n, (int)per, nslots, ctx->slots, ctx->gram[which]));
+    return ALS_OK;
+}
+
+int check_implicit(als_ctx *ctx, float alpha) {
+    if (!single_wave_f(ctx->cfg.f)) return fail(ctx, ALS_EINVAL, "implicit feedback needs f <= 128");
+    if (ctx->cfg.factor_dtype != ALS_F32 || ctx->cfg.herm_dtype != ALS_F32)
+        return fail(ctx, ALS_EINVAL, "implicit feedback needs fp32 factors and fp32 storage of A_u");
+    if (!(alpha >= 0.f)) return fail(ctx, ALS_EINVAL, "alpha must be >= 0");
+    return ALS_OK;
+}
+
 // One half-sweep: rows of `a` updated from the gathered factor `G` into `Out`.
-int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f, float *Out) {
+// mode kExplicit: eq. (2)/(3); kImplicit: Section 5.6 with confidence scale alpha.
+int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f, float *Out, int mode = kExplicit,
+           float alpha = 0.f) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, a);
     if (rc != ALS_OK) return rc;
@@ -166,6 +200,15 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     if (!Out || (a->nnz > 0 && !G)) return fail(ctx, ALS_EINVAL, "factor pointer is null");
     if (a->nrows == 0) return ALS_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    const bool implicit = mode == kImplicit;
+    if (implicit) {
+        rc = check_implicit(ctx, alpha);
+        if (rc != ALS_OK) return rc;
+        if (!G) return fail(ctx, ALS_EINVAL, "factor pointer is null");
+        rc = compute_gram(ctx, (const float *)G, a->ncols, 0);
+        if (rc != ALS_OK) return rc;
+    }
+    const float *gram = ctx->gram[0];
     Plan *p = nullptr;
     rc = get_plan(ctx, a, &p);
     if (rc != ALS_OK) return rc;
@@ -198,14 +241,24 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         if (rc != ALS_OK) return rc;
         {
             Timed t(ctx, ALS_K_HERMITIAN);
-            HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, s16, ctx->stream, p->task_row, p->task_chunk, task0, ntasks,
-                                          ctx->cfg.chunk, a->ptr, a->idx, a->val, G, ctx->slots));
+            if (implicit)
+                HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, task0,
+                                                       ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G, alpha,
+                                                       ctx->slots));
+            else
+                HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, s16, ctx->stream, p->task_row,
+                                              p->task_chunk, task0, ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G,
+                                              ctx->slots));
         }
         {
             Timed t(ctx, ALS_K_SOLVE);
             if (ntasks > end - pos)   // some row of the batch has several slots
                 HIP_TRY(ctx, launch_reduce_slots(f, s16, ctx->stream, p->task_off, pos, end - pos, task0, ctx->slots));
-            if (cg && !one_wave)
+            if (implicit)
+                HIP_TRY(ctx, launch_solve_wave_implicit(f, p64, ctx->cfg.solver, ctx->stream, p->perm, p->task_off, pos,
+                                                        end - pos, task0, a->ptr, ctx->slots, lambda, gram,
+                                                        ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+            else if (cg && !one_wave)
                 HIP_TRY(ctx, launch_solve_cg_rows(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
@@ -222,9 +275,14 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     }
     if (slot_rows < m) {
         Timed t(ctx, ALS_K_FUSED);
-        HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm, slot_rows, m - slot_rows, a->ptr, a->idx,
-                                         a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
-                                         ctx->status));
+        if (implicit)
+            HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, slot_rows,
+                                                      m - slot_rows, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
+                                                      ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+        else
+            HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
+                                             slot_rows, m - slot_rows, a->ptr, a->idx, a->val, G, lambda,
+                                             ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
     }
     return ALS_OK;
 }
@@ -276,7 +334,7 @@ void als_destroy(als_ctx *ctx) {
     hipStreamSynchronize(ctx->stream);
     for (auto &p : ctx->plans) free_plan(p);
     hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
-    hipFree(ctx->sse_total);
+    hipFree(ctx->sse_total); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
     for (auto &t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     for (auto e : ctx->free_events) hipEventDestroy(e);
     delete ctx;
@@ -292,6 +350,59 @@ int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float la
     return update(ctx, csc, X, lambda, f, Theta);
 }
 
+int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
+                             int f, float *X) {
+    return update(ctx, csr, Theta, lambda, f, X, kImplicit, alpha);
+}
+
+int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, float alpha, int f,
+                             float *Theta) {
+    return update(ctx, csc, X, lambda, f, Theta, kImplicit, alpha);
+}
+
+int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
+    if (!ctx) return ALS_EINVAL;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (!single_wave_f(f)) return fail(ctx, ALS_EINVAL, "als_gram needs f <= 128");
+    if (n < 0 || n > 0x7fffffff || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    int rc = compute_gram(ctx, G, n, 0);
+    if (rc != ALS_OK) return rc;
+    HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, ctx->gram[0], out));
+    return ALS_OK;
+}
+
+static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f,
+                            bool implicit, float alpha, double *sum_out);
+
+int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda,
+                      float alpha, int f, double *loss_out) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, csr);
+    if (rc != ALS_OK) return rc;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (!loss_out || !X || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
+    rc = check_implicit(ctx, alpha);
+    if (rc != ALS_OK) return rc;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    double entries = 0.0;
+    if (csr->nnz > 0) {
+        rc = sum_over_entries(ctx, csr, X, Theta, f, true, alpha, &entries);
+        if (rc != ALS_OK) return rc;
+    }
+    rc = compute_gram(ctx, X, csr->nrows, 0);
+    if (rc != ALS_OK) return rc;
+    rc = compute_gram(ctx, Theta, csr->ncols, 1);
+    if (rc != ALS_OK) return rc;
+    if (!ctx->gram_dot) HIP_TRY(ctx, hipMalloc(&ctx->gram_dot, 3 * sizeof(double)));
+    HIP_TRY(ctx, launch_gram_dot(f, ctx->stream, ctx->gram[0], ctx->gram[1], ctx->gram_dot));
+    double d3[3] = {0, 0, 0};
+    HIP_TRY(ctx, hipMemcpyAsync(d3, ctx->gram_dot, sizeof(d3), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    *loss_out = entries + d3[0] + (double)lambda * (d3[1] + d3[2]);
+    return ALS_OK;
+}
+
 int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
@@ -300,6 +411,17 @@ int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *T
     if (!rmse_out || (csr->nnz > 0 && (!X || !Theta))) return fail(ctx, ALS_EINVAL, "null pointer");
     if (csr->nnz == 0) { *rmse_out = 0.0; return ALS_OK; }
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    double sse = 0.0;
+    rc = sum_over_entries(ctx, csr, X, Theta, f, false, 0.f, &sse);
+    if (rc != ALS_OK) return rc;
+    *rmse_out = sqrt(sse / (double)csr->nnz);
+    return ALS_OK;
+}
+
+// sum over the stored entries of the squared error (explicit) or of the entry part of the implicit cost
+static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f,
+                            bool implicit, float alpha, double *sum_out) {
+    int rc;
     Plan *p = nullptr;
     rc = get_plan(ctx, csr, &p);
     if (rc != ALS_OK) return rc;
@@ -312,14 +434,14 @@ int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *T
     }
     {
         Timed t(ctx, ALS_K_RMSE);
-        HIP_TRY(ctx, launch_sse(f, csr->ptr_is_64 != 0, ctx->stream, p->task_row, p->task_chunk, p->ntasks,
-                                ctx->cfg.chunk, csr->ptr, csr->idx, csr->val, X, Theta, ctx->sse_partial,
+        HIP_TRY(ctx, launch_sse(f, csr->ptr_is_64 != 0, implicit, alpha, ctx->stream, p->task_row, p->task_chunk,
+                                p->ntasks, ctx->cfg.chunk, csr->ptr, csr->idx, csr->val, X, Theta, ctx->sse_partial,
                                 ctx->sse_total));
     }
     double sse = 0.0;
     HIP_TRY(ctx, hipMemcpyAsync(&sse, ctx->sse_total, sizeof(double), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    *rmse_out = sqrt(sse / (double)csr->nnz);
+    *sum_out = sse;
     return ALS_OK;
 }
 

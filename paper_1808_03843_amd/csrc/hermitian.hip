@@ -16,184 +16,9 @@
 //                      and reads it back in the solver, Section 3 and Observation 4).
 //   k_reduce_slots     sums the slots of a split row into its first slot, in slot order.
 //   k_solve_cg_wave    the same two solvers for rows whose A_u sits in a slot, one wavefront per row.
-#include "tiles.h"
+#include "hermitian_kernels.h"
 
 namespace als {
-
-// gather pipeline depth (register sets of theta operands in flight per wavefront)
-#ifndef ALS_DEPTH_SLOTS
-#define ALS_DEPTH_SLOTS 3
-#endif
-#ifndef ALS_DEPTH_FUSED
-#define ALS_DEPTH_FUSED 3
-#endif
-#ifndef ALS_FUSED_WAVES
-#define ALS_FUSED_WAVES 2
-#endif
-constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
-// wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
-constexpr int fused_waves(int F) { return F <= 100 ? ALS_FUSED_WAVES : 2; }
-
-// a value that is the same in every lane, moved to scalar registers
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-template <int F, typename PtrT, bool WIDE, int ET, bool S16>
-__global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
-                                                  const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
-                                                  const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                  const float *__restrict__ val, const void *__restrict__ Theta,
-                                                  float *__restrict__ slots) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
-    const int lane = threadIdx.x;
-    const int64_t t = blockIdx.x;
-    const int row = task_row[task0 + t];
-    const int ch = task_chunk[task0 + t];
-    const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
-    const int64_t s0 = rs + (int64_t)ch * chunk;
-    const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);   // >= 1: rows without entries have no work items
-
-    v4f acc[NTILES];
-#pragma unroll
-    for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
-
-    float *out = slots + t * (int64_t)SLOT;
-    if constexpr (S16) {
-        uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
-#pragma unroll
-        for (int q = 0; q < NTILES; ++q)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) out32[(q * 2 + h) * 64 + lane] = pack_bf16(acc[q][2 * h], acc[q][2 * h + 1]);
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-            if (lane < 16) out[NTILES * 128 + 16 * q + lane] = b[q];
-    } else {
-#pragma unroll
-        for (int q = 0; q < NTILES; ++q)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
-#pragma unroll
-        for (int q = 0; q < NT; ++q)
-            if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
-    }
-}
-
-// x (column layout, virtual coordinates) <-> a factor row in memory
-template <int F>
-__device__ __forceinline__ void load_vec(const float *__restrict__ src, float (&x)[tiles_1d(F)]) {
-    const int c = threadIdx.x & 15;
-#pragma unroll
-    for (int q = 0; q < tiles_1d(F); ++q) {
-        const int ft = feature_of(F, q, c);
-        x[q] = ft >= 0 ? src[ft] : 0.f;
-    }
-}
-template <int F>
-__device__ __forceinline__ void store_vec(float *__restrict__ dst, const float (&x)[tiles_1d(F)], int *status) {
-    const int lane = threadIdx.x & 63;
-    bool bad = false;
-#pragma unroll
-    for (int q = 0; q < tiles_1d(F); ++q) {
-        const int ft = feature_of(F, q, lane & 15);
-        if (lane < 16 && ft >= 0) {
-            dst[ft] = x[q];
-            bad |= !isfinite(x[q]);
-        }
-    }
-    if (bad) atomicOr(status, kStatusNonFinite);
-}
-template <int F>
-__device__ __forceinline__ void store_zero_vec(float *__restrict__ dst) {
-    for (int q = threadIdx.x; q < F; q += 64) dst[q] = 0.f;
-}
-
-template <int F, typename PtrT, bool WIDE, int ET, int SOLVER>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F), fused_waves(F)))) void k_hermitian_cg(const int32_t *__restrict__ perm, int64_t pos0,
-                                                     const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                     const float *__restrict__ val, const void *__restrict__ Theta,
-                                                     float lambda, int fs, float eps, float *__restrict__ Xout,
-                                                     int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F);
-    const int lane = threadIdx.x;
-    const int row = perm[pos0 + blockIdx.x];
-    const int64_t s0 = (int64_t)ptr[row];
-    const int len = (int)((int64_t)ptr[row + 1] - s0);
-    float *xg = Xout + (int64_t)row * F;
-    if (len == 0) {   // no observation: x_u = 0
-        store_zero_vec<F>(xg);
-        return;
-    }
-    v4f acc[NTILES];
-#pragma unroll
-    for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float b[NT];
-    accumulate_tiles<F, true, kDepthFused, WIDE, ET>(idx, val, Theta, uniform64(s0), len, acc, b);
-    add_diagonal<F>(acc, lambda * (float)len);
-    float x[NT];
-    if constexpr (SOLVER == ALS_SOLVER_CG) {
-        load_vec<F>(xg, x);
-        cg_tiles<F>(acc, b, x, fs, eps);
-    } else {
-        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
-    }
-    store_vec<F>(xg, x, status);
-}
-
-template <int F, typename PtrT, bool S16, int SOLVER>
-__global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict__ perm,
-                                                      const int32_t *__restrict__ task_off, int64_t pos0,
-                                                      int64_t task0, const PtrT *__restrict__ ptr,
-                                                      const float *__restrict__ slots, float lambda, int fs,
-                                                      float eps, float *__restrict__ Xout, int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
-    const int lane = threadIdx.x, c = lane & 15;
-    const int64_t pos = pos0 + blockIdx.x;
-    const int row = perm[pos];
-    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
-    float *xg = Xout + (int64_t)row * F;
-    if (n_u == 0) {
-        store_zero_vec<F>(xg);
-        return;
-    }
-    const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;
-    v4f acc[NTILES];
-    float b[NT];
-    if constexpr (S16) {
-        const uint32_t *slot32 = reinterpret_cast<const uint32_t *>(slot);
-#pragma unroll
-        for (int q = 0; q < NTILES; ++q)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t w = slot32[(q * 2 + h) * 64 + lane];
-                acc[q][2 * h] = bits_to_float(w << 16);
-                acc[q][2 * h + 1] = bits_to_float(w & 0xffff0000u);
-            }
-#pragma unroll
-        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 128 + 16 * q + c];
-    } else {
-#pragma unroll
-        for (int q = 0; q < NTILES; ++q)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[q][r] = slot[(q * 4 + r) * 64 + lane];
-#pragma unroll
-        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 256 + 16 * q + c];
-    }
-    add_diagonal<F>(acc, lambda * (float)n_u);
-    float x[NT];
-    if constexpr (SOLVER == ALS_SOLVER_CG) {
-        load_vec<F>(xg, x);
-        cg_tiles<F>(acc, b, x, fs, eps);
-    } else {
-        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
-    }
-    store_vec<F>(xg, x, status);
-}
 
 // slots[first] += slots[first+1] + ... (in slot order) for every row of the batch with several slots
 template <int F, bool S16>
@@ -405,14 +230,14 @@ static hipError_t herm_e(int et, hipStream_t st, const int32_t *task_row, const 
     const dim3 grid((unsigned)ntasks), block(64);
     const PtrT *p = (const PtrT *)ptr;
     if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32, S16>), grid, block, 0, st, task_row, task_chunk, task0,
-                           chunk, p, idx, val, Theta, slots);
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, 0.f, slots);
     else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16, S16>), grid, block, 0, st, task_row, task_chunk, task0,
-                           chunk, p, idx, val, Theta, slots);
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, 0.f, slots);
     else
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16, S16>), grid, block, 0, st, task_row, task_chunk, task0,
-                           chunk, p, idx, val, Theta, slots);
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+                           chunk, p, idx, val, Theta, 0.f, slots);
     return hipGetLastError();
 }
 
@@ -454,17 +279,17 @@ static hipError_t herm_cg_e(int et, int solver, hipStream_t st, const int32_t *p
     const PtrT *p = (const PtrT *)ptr;
     if (solver == ALS_SOLVER_CHOLESKY) {   // exact solve on the tiles: fp32 factor inputs only
         if (et != ALS_F32) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CHOLESKY>), grid, block, 0, st, perm,
-                           pos0, p, idx, val, Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CHOLESKY, kExplicit>), grid, block, 0, st, perm,
+                           pos0, p, idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
     } else if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0, p,
-                           idx, val, Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0, p,
+                           idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
     else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0,
-                           p, idx, val, Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0,
+                           p, idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
     else
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16, ALS_SOLVER_CG>), grid, block, 0, st, perm, pos0, p,
-                           idx, val, Theta, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0, p,
+                           idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
     return hipGetLastError();
 }
 
@@ -498,14 +323,14 @@ static hipError_t solve_wave_f(bool s16, int solver, hipStream_t st, const int32
     if (npos <= 0) return hipSuccess;
     if (solver == ALS_SOLVER_CHOLESKY) {
         if (s16) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CHOLESKY>), dim3((unsigned)npos), dim3(64), 0, st,
-                           perm, task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CHOLESKY, kExplicit>), dim3((unsigned)npos), dim3(64), 0, st,
+                           perm, task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, (const float *)nullptr, fs, eps, Xout, status);
     } else if (s16)
-        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, true, ALS_SOLVER_CG>), dim3((unsigned)npos), dim3(64), 0, st, perm,
-                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, true, ALS_SOLVER_CG, kExplicit>), dim3((unsigned)npos), dim3(64), 0, st, perm,
+                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, (const float *)nullptr, fs, eps, Xout, status);
     else
-        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CG>), dim3((unsigned)npos), dim3(64), 0, st, perm,
-                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, fs, eps, Xout, status);
+        hipLaunchKernelGGL((k_solve_cg_wave<F, PtrT, false, ALS_SOLVER_CG, kExplicit>), dim3((unsigned)npos), dim3(64), 0, st, perm,
+                           task_off, pos0, task0, (const PtrT *)ptr, slots, lambda, (const float *)nullptr, fs, eps, Xout, status);
     return hipGetLastError();
 }
 

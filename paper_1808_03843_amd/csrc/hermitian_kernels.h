@@ -1,0 +1,208 @@
+// Kernel templates of get_hermitian + get_bias and of the two solvers that run on the accumulator tiles
+// (instantiated by hermitian.hip for eq. (2)/(3) and by implicit.hip for Section 5.6).
+#pragma once
+#include "tiles.h"
+
+namespace als {
+
+// gather pipeline depth (register sets of theta operands in flight per wavefront)
+#ifndef ALS_DEPTH_SLOTS
+#define ALS_DEPTH_SLOTS 3
+#endif
+#ifndef ALS_DEPTH_FUSED
+#define ALS_DEPTH_FUSED 3
+#endif
+#ifndef ALS_FUSED_WAVES
+#define ALS_FUSED_WAVES 2
+#endif
+constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
+// wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
+constexpr int fused_waves(int F) { return F <= 100 ? ALS_FUSED_WAVES : 2; }
+
+// a value that is the same in every lane, moved to scalar registers
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// MODE: kExplicit (eq. (2)) or kImplicit (Section 5.6: every stored entry weighted by alpha * r_uv, b_u by
+// 1 + alpha * r_uv; the dense Theta^T Theta term is added by the solver kernels).
+template <int F, typename PtrT, bool WIDE, int ET, bool S16, int MODE>
+__global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
+                                                  const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
+                                                  const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                  const float *__restrict__ val, const void *__restrict__ Theta,
+                                                  float alpha, float *__restrict__ slots) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
+    const int lane = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const int row = task_row[task0 + t];
+    const int ch = task_chunk[task0 + t];
+    const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
+    const int64_t s0 = rs + (int64_t)ch * chunk;
+    const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
+    const int len = (int)(s1 - s0);   // >= 1: rows without entries have no work items
+
+    v4f acc[NTILES];
+#pragma unroll
+    for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    float b[NT];
+    accumulate_tiles<F, false, kDepthSlots, WIDE, ET, 0, tiles_1d(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                 alpha);
+
+    float *out = slots + t * (int64_t)SLOT;
+    if constexpr (S16) {
+        uint32_t *out32 = reinterpret_cast<uint32_t *>(out);
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) out32[(q * 2 + h) * 64 + lane] = pack_bf16(acc[q][2 * h], acc[q][2 * h + 1]);
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16) out[NTILES * 128 + 16 * q + lane] = b[q];
+    } else {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) out[(q * 4 + r) * 64 + lane] = acc[q][r];
+#pragma unroll
+        for (int q = 0; q < NT; ++q)
+            if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
+    }
+}
+
+// x (column layout, virtual coordinates) <-> a factor row in memory
+template <int F>
+__device__ __forceinline__ void load_vec(const float *__restrict__ src, float (&x)[tiles_1d(F)]) {
+    const int c = threadIdx.x & 15;
+#pragma unroll
+    for (int q = 0; q < tiles_1d(F); ++q) {
+        const int ft = feature_of(F, q, c);
+        x[q] = ft >= 0 ? src[ft] : 0.f;
+    }
+}
+template <int F>
+__device__ __forceinline__ void store_vec(float *__restrict__ dst, const float (&x)[tiles_1d(F)], int *status) {
+    const int lane = threadIdx.x & 63;
+    bool bad = false;
+#pragma unroll
+    for (int q = 0; q < tiles_1d(F); ++q) {
+        const int ft = feature_of(F, q, lane & 15);
+        if (lane < 16 && ft >= 0) {
+            dst[ft] = x[q];
+            bad |= !isfinite(x[q]);
+        }
+    }
+    if (bad) atomicOr(status, kStatusNonFinite);
+}
+template <int F>
+__device__ __forceinline__ void store_zero_vec(float *__restrict__ dst) {
+    for (int q = threadIdx.x; q < F; q += 64) dst[q] = 0.f;
+}
+
+// Tiles of a Gram matrix stored like a slot (tile q, register r, lane l at (4q+r)*64 + l)
+template <int F>
+__device__ __forceinline__ void load_tiles(const float *__restrict__ src, v4f (&acc)[tiles_tri(F)]) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < tiles_tri(F); ++q)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[q][r] = src[(q * 4 + r) * 64 + lane];
+}
+
+// gram (kImplicit only): tiles of Theta^T Theta, the starting value of the accumulators
+template <int F, typename PtrT, bool WIDE, int ET, int SOLVER, int MODE>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F), fused_waves(F)))) void k_hermitian_cg(
+    const int32_t *__restrict__ perm, int64_t pos0, const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+    const float *__restrict__ val, const void *__restrict__ Theta, float lambda, float alpha,
+    const float *__restrict__ gram, int fs, float eps, float *__restrict__ Xout, int *__restrict__ status) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F);
+    const int lane = threadIdx.x;
+    const int row = perm[pos0 + blockIdx.x];
+    const int64_t s0 = (int64_t)ptr[row];
+    const int len = (int)((int64_t)ptr[row + 1] - s0);
+    float *xg = Xout + (int64_t)row * F;
+    if (len == 0) {   // no observation: x_u = 0
+        store_zero_vec<F>(xg);
+        return;
+    }
+    v4f acc[NTILES];
+    if constexpr (MODE == kImplicit) {
+        load_tiles<F>(gram, acc);
+    } else {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    float b[NT];
+    accumulate_tiles<F, true, kDepthFused, WIDE, ET, 0, tiles_1d(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                alpha);
+    add_diagonal<F>(acc, MODE == kImplicit ? lambda : lambda * (float)len);
+    float x[NT];
+    if constexpr (SOLVER == ALS_SOLVER_CG) {
+        load_vec<F>(xg, x);
+        cg_tiles<F>(acc, b, x, fs, eps);
+    } else {
+        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+    }
+    store_vec<F>(xg, x, status);
+}
+
+template <int F, typename PtrT, bool S16, int SOLVER, int MODE>
+__global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict__ perm,
+                                                      const int32_t *__restrict__ task_off, int64_t pos0,
+                                                      int64_t task0, const PtrT *__restrict__ ptr,
+                                                      const float *__restrict__ slots, float lambda,
+                                                      const float *__restrict__ gram, int fs, float eps,
+                                                      float *__restrict__ Xout, int *__restrict__ status) {
+    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
+    const int lane = threadIdx.x, c = lane & 15;
+    const int64_t pos = pos0 + blockIdx.x;
+    const int row = perm[pos];
+    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
+    float *xg = Xout + (int64_t)row * F;
+    if (n_u == 0) {
+        store_zero_vec<F>(xg);
+        return;
+    }
+    const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;
+    v4f acc[NTILES];
+    float b[NT];
+    if constexpr (S16) {
+        const uint32_t *slot32 = reinterpret_cast<const uint32_t *>(slot);
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t w = slot32[(q * 2 + h) * 64 + lane];
+                acc[q][2 * h] = bits_to_float(w << 16);
+                acc[q][2 * h + 1] = bits_to_float(w & 0xffff0000u);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 128 + 16 * q + c];
+    } else {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[q][r] = slot[(q * 4 + r) * 64 + lane];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = slot[NTILES * 256 + 16 * q + c];
+    }
+    if constexpr (MODE == kImplicit) {
+#pragma unroll
+        for (int q = 0; q < NTILES; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[q][r] += gram[(q * 4 + r) * 64 + lane];
+    }
+    add_diagonal<F>(acc, MODE == kImplicit ? lambda : lambda * (float)n_u);
+    float x[NT];
+    if constexpr (SOLVER == ALS_SOLVER_CG) {
+        load_vec<F>(xg, x);
+        cg_tiles<F>(acc, b, x, fs, eps);
+    } else {
+        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+    }
+    store_vec<F>(xg, x, status);
+}
+
+}  // namespace als

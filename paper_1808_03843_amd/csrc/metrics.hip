@@ -1,4 +1,6 @@
 // Batched RMSE (Section 5.2 metric): sum over stored entries of (r_uv - x_u^T theta_v)^2.
+// In implicit mode (Section 5.6) the per-entry term is c (p - d)^2 - d^2 with d = x_u^T theta_v,
+// p = [r > 0], c = 1 + alpha max(r, 0): the part of the all-pairs cost that depends on the stored entries.
 // One wavefront per work item (the same row chunks as the update), 4 stored entries per step with
 // 16 lanes sharing one dot product; fp32 dots, fp64 accumulation of the squared errors, per-item
 // partial sums added in item order by a single block (deterministic).
@@ -6,12 +8,13 @@
 
 namespace als {
 
-template <int F, typename PtrT>
+template <int F, typename PtrT, int MODE>
 __global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row,
                                             const int32_t *__restrict__ task_chunk, int chunk,
                                             const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                             const float *__restrict__ val, const float *__restrict__ X,
-                                            const float *__restrict__ Theta, double *__restrict__ partial) {
+                                            const float *__restrict__ Theta, float alpha,
+                                            double *__restrict__ partial) {
     constexpr int NT = tiles_1d(F);
     const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
     const int64_t t = blockIdx.x;
@@ -39,8 +42,14 @@ __global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row
         }
 #pragma unroll
         for (int o = 1; o < 16; o <<= 1) d += __shfl_xor(d, o);
-        const float err = r - d;
-        if (ok && i == 0) acc += (double)err * (double)err;
+        if constexpr (MODE == kImplicit) {
+            const double rp = r > 0.f ? (double)r : 0.0, dd = (double)d;
+            const double pe = (r > 0.f ? 1.0 : 0.0) - dd;
+            if (ok && i == 0) acc += (1.0 + (double)alpha * rp) * pe * pe - dd * dd;
+        } else {
+            const float err = r - d;
+            if (ok && i == 0) acc += (double)err * (double)err;
+        }
     }
     acc += __shfl_xor(acc, 16);
     acc += __shfl_xor(acc, 32);
@@ -65,22 +74,29 @@ __global__ __launch_bounds__(1024) void k_sum_partials(const double *__restrict_
 }
 
 template <int F, typename PtrT>
-static hipError_t sse_f(hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t ntasks, int chunk,
-                        const void *ptr, const int32_t *idx, const float *val, const float *X, const float *Theta,
-                        double *partial, double *total) {
-    if (ntasks > 0)
-        hipLaunchKernelGGL((k_sse<F, PtrT>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk, chunk,
-                           (const PtrT *)ptr, idx, val, X, Theta, partial);
+static hipError_t sse_f(bool implicit, float alpha, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+                        int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
+                        const float *X, const float *Theta, double *partial, double *total) {
+    if (ntasks > 0) {
+        if (implicit)
+            hipLaunchKernelGGL((k_sse<F, PtrT, kImplicit>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk,
+                               chunk, (const PtrT *)ptr, idx, val, X, Theta, alpha, partial);
+        else
+            hipLaunchKernelGGL((k_sse<F, PtrT, kExplicit>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk,
+                               chunk, (const PtrT *)ptr, idx, val, X, Theta, alpha, partial);
+    }
     hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, partial, ntasks, total);
     return hipGetLastError();
 }
 
-hipError_t launch_sse(int f, bool ptr64, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                      int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
-                      const float *X, const float *Theta, double *partial, double *total) {
-#define CALL(FF)                                                                                               \
-    (ptr64 ? sse_f<FF, int64_t>(st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta, partial, total) \
-           : sse_f<FF, int32_t>(st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta, partial, total))
+hipError_t launch_sse(int f, bool ptr64, bool implicit, float alpha, hipStream_t st, const int32_t *task_row,
+                      const int32_t *task_chunk, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
+                      const float *val, const float *X, const float *Theta, double *partial, double *total) {
+#define CALL(FF)                                                                                                      \
+    (ptr64 ? sse_f<FF, int64_t>(implicit, alpha, st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta,    \
+                                partial, total)                                                                       \
+           : sse_f<FF, int32_t>(implicit, alpha, st, task_row, task_chunk, ntasks, chunk, ptr, idx, val, X, Theta,    \
+                                partial, total))
     switch (f) {
         case 16: return CALL(16);
         case 32: return CALL(32);

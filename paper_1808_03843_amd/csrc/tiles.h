@@ -108,11 +108,19 @@ __device__ __forceinline__ float widen_hi(uint32_t w) {   // high 16 bits of w
 
 // R0, R1: the wavefront accumulates the tile rows [R0, R1) only (acc[R(R+1)/2 + C - R0(R0+1)/2]); the
 // default is the whole triangle.  WANT_B: also produce b_u (one wavefront of a work item does).
-template <int F, bool IN_VGPR, int D, bool WIDE, int ET, int R0 = 0, int R1 = tiles_1d(F), bool WANT_B = true>
+// MODE: kExplicit as described above.  kImplicit (Section 5.6): the entry (u, v) enters A_u with weight
+// w = alpha * max(r_uv, 0) (both operands are scaled by sqrt(w)) and b_u with weight 1 + w if r_uv > 0.
+// kGram: the "entries" are the rows s0 .. s0+len-1 of Theta themselves (idx and val are not read),
+// unit weights, for Theta^T Theta.
+template <int F, bool IN_VGPR, int D, bool WIDE, int ET, int R0 = 0, int R1 = tiles_1d(F), bool WANT_B = true,
+          int MODE = kExplicit>
 __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                  const void *__restrict__ Theta, int64_t s0, int len,
-                                                 v4f (&acc)[tiles_range(R0, R1)], float (&b)[tiles_1d(F)]) {
+                                                 v4f (&acc)[tiles_range(R0, R1)], float (&b)[tiles_1d(F)],
+                                                 float alpha = 0.f) {
     static_assert((R0 == 0 && R1 == tiles_1d(F)) || (F % 16) == 0, "partial tile ranges need f to be a multiple of 16");
+    static_assert(MODE == kExplicit || !TileGeom<F>::RIT, "the rating lane carries the plain rating only");
+    static_assert(MODE != kGram || !WANT_B, "a Gram matrix has no right-hand side");
     constexpr int ABASE = R0 * (R0 + 1) / 2;
     constexpr int NT = TileGeom<F>::NT, NB = D + 1;
     constexpr bool RIT = TileGeom<F>::RIT, STRIP = TileGeom<F>::STRIP;
@@ -134,8 +142,15 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         return (uint32_t)(e < last ? e : last);
     };
     // entry -> column id / rating: scalar base + 32-bit byte offset (a work item has < 2^30 entries)
-    auto load_id = [&](uint32_t e) { return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(ib) + 4u * e); };
-    auto load_rating = [&](uint32_t e) { return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(vb) + 4u * e); };
+    const int row0 = (int)s0;   // kGram: entry e is row s0 + e
+    auto load_id = [&](uint32_t e) -> int32_t {
+        if constexpr (MODE == kGram) return row0 + (int)e;
+        else return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(ib) + 4u * e);
+    };
+    auto load_rating = [&](uint32_t e) -> float {
+        if constexpr (MODE == kGram) return 1.f;
+        else return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(vb) + 4u * e);
+    };
     // One theta row -> raw registers, with the widest loads the feature permutation allows: 4, 2 and 1
     // elements per lane.  Addresses are (scalar base) + (32-bit lane offset) + (immediate) unless WIDE.
     const uint32_t lane_a = (uint32_t)(4 * ES) * (uint32_t)i;
@@ -255,13 +270,22 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             for (int q = 0; q < NT; ++q) g[q] = ok ? g[q] : 0.f;
             r = ok ? r : 0.f;
         }
-        if constexpr (RIT) {
+        if constexpr (MODE == kImplicit) {
+            const float w = alpha * fmaxf(r, 0.f);
+            const float bw = r > 0.f ? 1.f + w : 0.f;
+            const float sw = __builtin_amdgcn_sqrtf(w);
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                if constexpr (WANT_B) bacc[q] = fmaf(bw, g[q], bacc[q]);
+                g[q] *= sw;
+            }
+        } else if constexpr (RIT) {
             g[NT - 1] = (i == RI) ? r : g[NT - 1];
         } else if constexpr (WANT_B) {
 #pragma unroll
             for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
         }
-        if constexpr (MASKED || ET != ALS_F32 || (RIT && NT < 3)) {
+        if constexpr (MASKED || ET != ALS_F32 || (RIT && NT < 3) || MODE == kImplicit) {
             // An operand written by the vector ALU must not be read by an MFMA in the next few cycles,
             // and the compiler, to which the MFMAs are opaque, does not keep that distance: wait here,
             // and tie every operand to the wait so that no MFMA can be moved in front of it.
@@ -314,7 +338,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     if constexpr (STRIP) {
         // lane (c, kq) register r holds the share of lane row kq in element (row r, column c) of the strip:
         // summed over kq this is the ordinary tile layout of lane row 0; the other lane rows are padding
-        b[NT - 1] = (c < RI) ? b[NT - 1] : 0.f;
+        if constexpr (WANT_B) b[NT - 1] = (c < RI) ? b[NT - 1] : 0.f;
 #pragma unroll
         for (int T = 0; T < NT; ++T)
 #pragma unroll
