@@ -57,6 +57,8 @@ MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 1024): 47.4e9 +
 
 
 def measured_traffic(w, args, chunk, launches):
+    if args.implicit is not None:
+        return None
     key = (w.name, w.f, args.solver, args.cg_iters if args.solver == "cg" else 0, args.factor_dtype, chunk)
     total = MEASURED_TRAFFIC_BYTES_PER_SWEEP.get(key)
     if total is None or launches <= 0 or args.batch_slots != 0:
@@ -71,6 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
+    ap.add_argument("--implicit", type=float, default=None, metavar="ALPHA",
+                    help="time implicit-feedback sweeps (Section 5.6) with this confidence scale instead")
     ap.add_argument("--cg-iters", type=int, default=6)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--batch-slots", type=int, default=0)
@@ -120,6 +124,10 @@ def main():
     del X0
 
     def sweep():
+        if args.implicit is not None:
+            als.update_rows_implicit(csr, T, w.lam, args.implicit, X)
+            als.update_cols_implicit(csc, X, w.lam, args.implicit, T)
+            return
         # 16-bit modes: the gathered factor is converted by torch inside the timed region (part of the sweep)
         als.update_rows(csr, T if fcode == P.F32 else T.to(ftorch), w.lam, X)
         als.update_cols(csc, X if fcode == P.F32 else X.to(ftorch), w.lam, T)
@@ -137,12 +145,15 @@ def main():
     herm_ms, herm_n = als.kernel_time(P.K_HERMITIAN)
     fused_ms, fused_n = als.kernel_time(P.K_FUSED)
     solve_ms, solve_n = als.kernel_time(P.K_SOLVE)
+    gram_ms, gram_n = als.kernel_time(P.K_GRAM)
     als.synchronize()
     rmse = P.Als(w.f).rmse(csr, X, T) if fcode != P.F32 else als.rmse(csr, X, T)
     K = args.steps
     log(f"[bench] {K} sweeps in {elapsed:.3f} s; rmse {rmse:.5f}; per sweep: k_hermitian {herm_ms / K:.2f} ms "
         f"({herm_n // K} launches), k_hermitian_cg {fused_ms / K:.2f} ms ({fused_n // K}), "
-        f"slot solve {solve_ms / K:.2f} ms ({solve_n // K})")
+        f"slot solve {solve_ms / K:.2f} ms ({solve_n // K})"
+        + (f", gram {gram_ms / K:.2f} ms ({gram_n // K}); implicit cost {als.implicit_loss(csr, X, T, w.lam, args.implicit):.6e}"
+           if args.implicit is not None else ""))
 
     # get_hermitian roofline.  Algorithmic flops = f*(f+1) per stored entry and half-sweep (lower triangle
     # of theta theta^T, FMA = 2).  Rows with >= chunk entries are built by k_hermitian into slots, shorter
@@ -168,12 +179,14 @@ def main():
                 "k_hermitian_cg": {"tflops": (2 * w.nnz - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
                                    "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * w.nnz - nnz_slot}}
     out = {
-        "metric": f"seconds per ALS sweep (X+Theta) at f={w.f}", "value": sec_per_sweep, "unit": "s/sweep",
+        "metric": f"seconds per {'implicit-feedback ' if args.implicit is not None else ''}ALS sweep (X+Theta) at f={w.f}",
+        "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "factor_dtype": args.factor_dtype,
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={w.nnz} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
+                   **({"implicit_alpha": args.implicit} if args.implicit is not None else {}),
                    "chunk": chunk, "batch_slots": als.cfg.batch_slots or 131072},
         "hermitian_tflops": achieved, "hermitian_ms_per_sweep": (herm_ms + fused_ms) / K,
         "solve_ms_per_sweep": solve_ms / K, "train_rmse": rmse,
