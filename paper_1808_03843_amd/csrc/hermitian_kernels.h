@@ -143,7 +143,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         load_vec<F>(xg, x);
         cg_tiles<F>(acc, b, x, fs, eps);
     } else {
-        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+        __shared__ float tbuf[16 * 17];   // one wavefront per workgroup
+        if (!ldlt_tiles<F>(acc, b, x, tbuf) && lane == 0) atomicOr(status, kStatusBadPivot);
     }
     store_vec<F>(xg, x, status);
 }
@@ -200,7 +201,8 @@ __global__ __launch_bounds__(64) void k_solve_cg_wave(const int32_t *__restrict_
         load_vec<F>(xg, x);
         cg_tiles<F>(acc, b, x, fs, eps);
     } else {
-        if (!ldlt_tiles<F>(acc, b, x) && lane == 0) atomicOr(status, kStatusBadPivot);
+        __shared__ float tbuf[16 * 17];   // one wavefront per workgroup
+        if (!ldlt_tiles<F>(acc, b, x, tbuf) && lane == 0) atomicOr(status, kStatusBadPivot);
     }
     store_vec<F>(xg, x, status);
 }

@@ -39,6 +39,31 @@ __device__ __forceinline__ void mfma_4x4x1(v4f &acc, float a, float b) {
 // The MFMAs above are opaque to the compiler's hazard recogniser: leave the matrix pipeline time to
 // retire the last accumulator writes before they are read (8 passes = 32 cycles, plus margin).
 __device__ __forceinline__ void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory"); }
+// The same wait at the end of a block of MFMAs that is followed by a control-flow edge (loop back edge or
+// exit, end of a conditional step): the register copies the compiler places on such edges read the
+// accumulators, and it cannot know that they are still being written.  16 wait states cover the 8 passes
+// of the last 16x16x4 instruction.
+// Every tile is an operand of the (otherwise empty) statements, so that none of the MFMAs, which the
+// compiler may reorder, can be placed after the wait.
+template <bool IN_VGPR, int N>
+__device__ __forceinline__ void mfma_settle(v4f (&acc)[N]) {
+    constexpr int G = 8;   // operands per statement (the limit is 30)
+#pragma unroll
+    for (int q = 0; q + G <= N; q += G) {
+        if constexpr (IN_VGPR)
+            asm volatile("" : "+v"(acc[q]), "+v"(acc[q + 1]), "+v"(acc[q + 2]), "+v"(acc[q + 3]), "+v"(acc[q + 4]),
+                         "+v"(acc[q + 5]), "+v"(acc[q + 6]), "+v"(acc[q + 7]));
+        else
+            asm volatile("" : "+a"(acc[q]), "+a"(acc[q + 1]), "+a"(acc[q + 2]), "+a"(acc[q + 3]), "+a"(acc[q + 4]),
+                         "+a"(acc[q + 5]), "+a"(acc[q + 6]), "+a"(acc[q + 7]));
+    }
+#pragma unroll
+    for (int q = N - N % G; q < N; ++q) {
+        if constexpr (IN_VGPR) asm volatile("" : "+v"(acc[q]));
+        else asm volatile("" : "+a"(acc[q]));
+    }
+    asm volatile("s_nop 15" ::: "memory");
+}
 
 // ---- cross-lane helpers -----------------------------------------------------------------------
 template <int CTRL>
@@ -61,6 +86,18 @@ __device__ __forceinline__ float colsum4(float v) {
 }
 __device__ __forceinline__ float bperm(int byte_addr, float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(byte_addr, __builtin_bit_cast(int, v)));
+}
+
+// m ? b : a per lane, m a 64-bit lane mask.  Written as the instruction: the optimiser turns chains of
+// per-lane selects on values that come back from LDS permutes into divergent branches.
+__device__ __forceinline__ float lane_select(float a, float b, uint64_t m) {
+    float d;
+    asm("v_cndmask_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "s"(m));
+    return d;
+}
+// v[k] with k = 2*[lane in m1] + [lane in m0]
+__device__ __forceinline__ float lane_select4(float v0, float v1, float v2, float v3, uint64_t m0, uint64_t m1) {
+    return lane_select(lane_select(v0, v1, m0), lane_select(v2, v3, m0), m1);
 }
 
 // A_u (lower-triangle tiles) and b_u of the stored entries [s0, s0+len) of one row (len >= 1).
@@ -91,6 +128,29 @@ struct TileGeom {
     static constexpr bool RIT = (F % 16) != 0 && !STRIP;   // rating rides in the last tile
     static constexpr int RI = F % 16;            // its lane (RIT); number of valid rows / columns of the last tile
 };
+
+// (a << SH) + b in one full-rate instruction
+template <int SH>
+__device__ __forceinline__ uint32_t lshl_add(uint32_t a, uint32_t b) {
+    uint32_t d;
+    asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "n"(SH), "v"(b));
+    return d;
+}
+// c * M + add for the row pitches that occur (a power of two, or 25 times one: f = 100), without the
+// quarter-rate 32-bit multiply
+template <uint32_t M>
+__device__ __forceinline__ uint32_t row_offset(uint32_t c, uint32_t add) {
+    constexpr int tz = __builtin_ctz(M);
+    if constexpr ((M >> tz) == 1) {
+        return lshl_add<tz>(c, add);
+    } else if constexpr ((M >> tz) == 25) {
+        const uint32_t c3 = lshl_add<1>(c, c);      // 3c
+        const uint32_t c25 = lshl_add<3>(c3, c);    // 25c
+        return lshl_add<tz>(c25, add);
+    } else {
+        return c * M + add;
+    }
+}
 
 // ET: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16).  16-bit elements are
 // fetched with loads of half the width and widened to fp32 in registers; the MFMAs stay fp32.
@@ -137,19 +197,29 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     constexpr int base1 = 64 * N4 + 32 * N2;       // first feature fetched by the single-element loads
     constexpr int ES = ET == ALS_F32 ? 4 : 2;       // bytes per element
     constexpr int RW = ET == ALS_F32 ? NT : 2 * N4 + N2 + N1;   // 32-bit registers one gathered row needs
-    auto entry = [&](int step) -> uint32_t {   // this lane's stored entry of a step, clamped into the item
-        const int e = 4 * step + kq;
-        return (uint32_t)(e < last ? e : last);
+    // Column ids and ratings are fetched through buffer resources that span exactly this work item: a fetch
+    // beyond its end (the prefetches of the last rounds, the padding of the last step) returns 0 instead of
+    // touching memory outside it, so no index needs clamping.  Lane (i, kq) reads entry 4*step + kq, i.e. byte
+    // offset 16*step + 4*kq: a lane offset plus a compile-time constant in every unrolled step.
+    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, dword elements (gfx9 family encoding)
+    __amdgpu_buffer_rsrc_t ids_rsrc, val_rsrc;
+    if constexpr (MODE != kGram) {
+        ids_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ib), 0, 4 * len, kRsrcFlags);
+        val_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vb), 0, 4 * len, kRsrcFlags);
+    }
+    const int row0 = (int)s0;   // kGram: entry e is row s0 + e of the factor matrix
+    // eoff: byte offset of this lane's entry in step `base` (base = first step of the current round)
+    auto load_id = [&](uint32_t eoff, int step_rel) -> int32_t {
+        if constexpr (MODE == kGram) {
+            const int e = (int)(eoff >> 2) + 4 * step_rel;
+            return row0 + (e < last ? e : last);
+        } else {
+            return __builtin_amdgcn_raw_buffer_load_b32(ids_rsrc, eoff + 16u * (uint32_t)step_rel, 0, 0);
+        }
     };
-    // entry -> column id / rating: scalar base + 32-bit byte offset (a work item has < 2^30 entries)
-    const int row0 = (int)s0;   // kGram: entry e is row s0 + e
-    auto load_id = [&](uint32_t e) -> int32_t {
-        if constexpr (MODE == kGram) return row0 + (int)e;
-        else return *reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(ib) + 4u * e);
-    };
-    auto load_rating = [&](uint32_t e) -> float {
+    auto load_rating = [&](uint32_t eoff, int step_rel) -> float {
         if constexpr (MODE == kGram) return 1.f;
-        else return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(vb) + 4u * e);
+        else return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(val_rsrc, eoff + 16u * (uint32_t)step_rel, 0, 0));
     };
     // One theta row -> raw registers, with the widest loads the feature permutation allows: 4, 2 and 1
     // elements per lane.  Addresses are (scalar base) + (32-bit lane offset) + (immediate) unless WIDE.
@@ -158,17 +228,19 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     const uint32_t lane_c = (uint32_t)ES * (uint32_t)(base1 + i);
     const uint32_t lane_l = STRIP ? (uint32_t)ES * (uint32_t)(base1 + 16 * (N1 - 1) + (i & 3))
                                   : (uint32_t)ES * (uint32_t)((base1 + 16 * (N1 - 1) + i < F) ? base1 + 16 * (N1 - 1) + i : F - 1);
+    const uint32_t lane_first = N4 > 0 ? lane_a : N2 > 0 ? lane_b : N1 > 1 ? lane_c : lane_l;
     auto gather = [&](int c, uint32_t (&w)[RW]) {
         const char *p;
-        uint32_t ro = 0;
+        uint32_t ro = 0;   // offset of the lane's first load: row offset + lane_first
         if constexpr (WIDE) {
             p = reinterpret_cast<const char *>(Theta) + (int64_t)c * (ES * F);
+            ro = lane_first;
         } else {
             p = reinterpret_cast<const char *>(Theta);
-            ro = (uint32_t)c * (uint32_t)(ES * F);
+            ro = row_offset<(uint32_t)(ES * F)>((uint32_t)c, lane_first);
         }
         if constexpr (N4 > 0) {
-            const uint32_t o = ro + lane_a;
+            const uint32_t o = ro + (lane_a - lane_first);
 #pragma unroll
             for (int q = 0; q < N4; ++q) {
                 if constexpr (ET == ALS_F32) {
@@ -181,7 +253,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             }
         }
         if constexpr (N2 > 0) {
-            const uint32_t o = ro + lane_b;
+            const uint32_t o = ro + (lane_b - lane_first);
             if constexpr (ET == ALS_F32) {
                 const uint2 v = *reinterpret_cast<const uint2 *>(p + o);
                 w[4 * N4] = v.x; w[4 * N4 + 1] = v.y;
@@ -191,7 +263,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         }
         constexpr int first1 = ET == ALS_F32 ? 4 * N4 + 2 * N2 : 2 * N4 + N2;
         if constexpr (N1 > 1) {
-            const uint32_t o = ro + lane_c;
+            const uint32_t o = ro + (lane_c - lane_first);
 #pragma unroll
             for (int k = 0; k < N1 - 1; ++k) {
                 if constexpr (ET == ALS_F32) w[first1 + k] = *reinterpret_cast<const uint32_t *>(p + o + 64 * k);
@@ -199,7 +271,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             }
         }
         if constexpr (N1 > 0) {
-            const uint32_t o = ro + lane_l;
+            const uint32_t o = ro + (lane_l - lane_first);
             if constexpr (ET == ALS_F32) w[first1 + N1 - 1] = *reinterpret_cast<const uint32_t *>(p + o);
             else w[first1 + N1 - 1] = *reinterpret_cast<const unsigned short *>(p + o);
         }
@@ -235,14 +307,14 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     // Prologue in the order of the loop body (far ids first, then the gathers, oldest step first): the
     // compiler's wait-count bookkeeping merges both paths at the loop head, and any other order makes
     // it drain the outstanding gathers at the top of every round.
+    uint32_t eoff = 4u * (uint32_t)kq;   // this lane's entry offset in the first step of the current round
 #pragma unroll
-    for (int j = D; j < K; ++j) cbuf[j % NB] = load_id(entry(j));
+    for (int j = D; j < K; ++j) cbuf[j % NB] = load_id(eoff, j);
     asm volatile("" ::: "memory");
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-        const uint32_t e = entry(d);
-        rbuf[d] = load_rating(e);
-        gather(load_id(e), gbuf[d]);
+        rbuf[d] = load_rating(eoff, d);
+        gather(load_id(eoff, d), gbuf[d]);
         asm volatile("" ::: "memory");
     }
 
@@ -252,13 +324,13 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         constexpr bool MASKED = decltype(mtag)::value;
         constexpr int dn = (d + D) % NB;
         // (1) column id of step t+K
-        cbuf[(d + K) % NB] = load_id(entry(t + K));
+        cbuf[(d + K) % NB] = load_id(eoff, d + K);
         // keeps the load above here: the compiler would otherwise fold the carried value into a load
         // at its use, putting a full memory latency in front of a gather
         asm volatile("" ::: "memory");
         // (2) gathers and rating of step t+D into the set that step t-1 has finished with
         gather(cbuf[dn], gbuf[dn]);
-        rbuf[dn] = load_rating(entry(t + D));
+        rbuf[dn] = load_rating(eoff, d + D);
         __builtin_amdgcn_sched_barrier(0);
         // (3) MFMAs of step t
         float g[NT];
@@ -301,6 +373,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
 #pragma unroll
             for (int C = 0; C < NT; ++C) mfma_4x4x1<IN_VGPR>(acc[(NT - 1) * NT / 2 + C], g[NT - 1], g[C]);
         }
+        if constexpr (MASKED) mfma_settle<IN_VGPR>(acc);   // masked steps are conditional
     };
     auto round = [&](auto mtag, int s, int limit) {
         [&]<int... d>(std::integer_sequence<int, d...>) {
@@ -308,10 +381,18 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         }(std::make_integer_sequence<int, NB>{});
     };
     for (int s = 0; s < nmain; s += NB) {
+        // opaque to the optimiser: it would otherwise re-base the offsets of the round on other induction
+        // variables and spend an addition per load instead of using the instruction's immediate offset
+        asm volatile("" : "+v"(eoff));
         [&]<int... d>(std::integer_sequence<int, d...>) {
             (step(std::integral_constant<int, d>{}, std::false_type{}, s + d), ...);
         }(std::make_integer_sequence<int, NB>{});
+#ifndef ALS_NO_ROUND_SETTLE
+        mfma_settle<IN_VGPR>(acc);
+#endif
+        eoff += 16u * NB;
     }
+    asm volatile("" : "+v"(eoff));
     round(std::true_type{}, nmain, nsteps);   // at most NB steps remain
     mfma_drain();
 
@@ -339,14 +420,35 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
         // lane (c, kq) register r holds the share of lane row kq in element (row r, column c) of the strip:
         // summed over kq this is the ordinary tile layout of lane row 0; the other lane rows are padding
         if constexpr (WANT_B) b[NT - 1] = (c < RI) ? b[NT - 1] : 0.f;
+        // The permutes of a stage are issued before the first result is used (LDS round trips are long).  With
+        // the tiles in accumulation registers the batches are short: the temporaries must not push the
+        // kernel over the register budget of two wavefronts per SIMD.
+        const int a16 = 4 * (lane ^ 16), a32 = 4 * (lane ^ 32);
+        constexpr int BT = IN_VGPR ? NT : 2;   // tiles per batch
 #pragma unroll
-        for (int T = 0; T < NT; ++T)
+        for (int T0 = 0; T0 < NT; T0 += BT) {
+            constexpr int LB = (NT - 1) * NT / 2;
+            float t[BT][4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float v = colsum4(acc[(NT - 1) * NT / 2 + T][r]);
-                const bool keep = (g4 == 0) && (T < NT - 1 || c < RI);
-                acc[(NT - 1) * NT / 2 + T][r] = keep ? v : 0.f;
-            }
+            for (int T = T0; T < T0 + BT && T < NT; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) t[T - T0][r] = bperm(a16, acc[LB + T][r]);
+#pragma unroll
+            for (int T = T0; T < T0 + BT && T < NT; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[LB + T][r] += t[T - T0][r];
+#pragma unroll
+            for (int T = T0; T < T0 + BT && T < NT; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) t[T - T0][r] = bperm(a32, acc[LB + T][r]);
+#pragma unroll
+            for (int T = T0; T < T0 + BT && T < NT; ++T)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool keep = (g4 == 0) && (T < NT - 1 || c < RI);
+                    acc[LB + T][r] = keep ? acc[LB + T][r] + t[T - T0][r] : 0.f;
+                }
+        }
     }
 }
 
@@ -377,17 +479,22 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
     for (int r = 0; r < 4; ++r) addr_rl[r] = 4 * (16 * g + 4 * g + r);
     // lane (c,g) fetches y[16T + c] from lane row c/4, where register c%4 holds it
     const int addr_cl = 4 * (16 * (c >> 2) + c);
-    const int csel = c & 3;
+    const uint64_t csel0 = __ballot((c & 1) != 0), csel1 = __ballot((c & 2) != 0);   // bits of c & 3 as lane masks
+    const int a16 = 4 * (lane ^ 16), a32 = 4 * (lane ^ 32);
 
+    // LDS permutes have a long latency: all permutes of a stage are issued before the first result is used
     auto matvec = [&](const float (&p)[NT], float (&ap)[NT]) {
         float lower[NT];  // tile^T * p_R contributions, per-lane partial sums over the lane rows
 #pragma unroll
         for (int q = 0; q < NT; ++q) lower[q] = 0.f;
+        float prs[NT][4];
+#pragma unroll
+        for (int R = 1; R < NT; ++R)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) prs[R][r] = bperm(addr_rl[r], p[R]);
 #pragma unroll
         for (int R = 0; R < NT; ++R) {
-            float pr[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) pr[r] = bperm(addr_rl[r], p[R]);
+            const float (&pr)[4] = prs[R];
             float row[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int C = 0; C <= R; ++C) {
@@ -403,11 +510,19 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) row[r] = rowsum16(row[r]);
-            const float sel = csel == 0 ? row[0] : csel == 1 ? row[1] : csel == 2 ? row[2] : row[3];
-            ap[R] = bperm(addr_cl, sel);
+            ap[R] = bperm(addr_cl, lane_select4(row[0], row[1], row[2], row[3], csel0, csel1));
         }
+        if constexpr (NT > 1) {
+            float t[NT - 1];
 #pragma unroll
-        for (int q = 0; q < NT - 1; ++q) ap[q] += colsum4(lower[q]);
+            for (int q = 0; q < NT - 1; ++q) t[q] = bperm(a16, lower[q]);
+#pragma unroll
+            for (int q = 0; q < NT - 1; ++q) lower[q] += t[q];
+#pragma unroll
+            for (int q = 0; q < NT - 1; ++q) t[q] = bperm(a32, lower[q]);
+#pragma unroll
+            for (int q = 0; q < NT - 1; ++q) ap[q] += lower[q] + t[q];
+        }
     };
     auto dot = [&](const float (&u)[NT], const float (&v)[NT]) {
         float s = 0.f;
@@ -445,20 +560,29 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
 }
 
 // Exact solve (Section 2 step (ii), Section 4.1 baseline) of one system held by one wavefront: LDL^T
-// without square roots, right-looking and unblocked, directly on the accumulator tiles, then the two
-// triangular solves.  Same argument layout as cg_tiles; acc is overwritten (column j ends up holding
-// L[:,j]*d_j).  Returns false if a pivot was not positive (the pivot is then replaced by 1).
-//   per column j (tile column K, lane jl): the column is fetched into the "row layout" of every tile
-//   row (4 permutes each), turned into the "column layout" and scaled by 1/d_j (one permute each);
-//   the rank-1 update of the remaining tiles and the forward substitution use both.
+// without square roots, right-looking, blocked by tile columns, directly on the accumulator tiles; then
+// the two triangular solves.  Same argument layout as cg_tiles; acc is overwritten (column j ends up
+// holding L[:,j]*d_j).  Returns false if a pivot was not positive (the pivot is then replaced by 1).
+//   Panel (tile column K), column by column: the column is fetched into the "row layout" of every tile
+//   row (4 permutes each), turned into the "column layout" and scaled by 1/d_j (one permute each); the
+//   remaining columns of the panel tiles get their rank-1 update (4 FMAs per tile) and the forward
+//   substitution rides along.
+//   Trailing update, once per panel, on the matrix cores: tile (R, C) -= (L_RK D_K) (L_CK)^T as four
+//   16x16x4 MFMAs.  The operands are the panel tiles transposed into the operand layout (lane (i, kq),
+//   register s = element (i, 4kq+s)) through `tbuf`, 272 floats of LDS private to the wavefront.
+template <bool IN_VGPR>
+__device__ __forceinline__ void mfma_16x16x4_ordered(v4f &acc, float a, float b) {
+    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
 template <int F>
 __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float (&b)[tiles_1d(F)],
-                                           float (&x)[tiles_1d(F)]) {
+                                           float (&x)[tiles_1d(F)], float *tbuf) {
     constexpr int NT = tiles_1d(F);
     constexpr int LASTCOLS = (F % 16) ? (F % 16) : 16;   // feature columns of the last tile
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     const int addr_cl = 4 * (16 * (c >> 2) + c);
-    const int csel = c & 3;
+    const uint64_t csel0 = __ballot((c & 1) != 0), csel1 = __ballot((c & 2) != 0);   // bits of c & 3 as lane masks
     float z[NT], dinv[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) {
@@ -473,33 +597,75 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
 #pragma unroll 1
         for (int jl = 0; jl < ncol; ++jl) {
             const int jr = jl & 3, jg = jl >> 2;
+            // first LDS round trip: the pivot, z_j and the column in row layout, all issued together
             float d = bperm(4 * (16 * jg + jl), pick(acc[K * (K + 1) / 2 + K], jr));
+            const float zj = bperm(4 * jl, z[K]);
+            float colv[NT][4], rowv[NT];
+            const int addr_rl = 4 * (16 * g + jl);
+#pragma unroll
+            for (int R = K; R < NT; ++R)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) colv[R][r] = bperm(addr_rl, acc[R * (R + 1) / 2 + K][r]);
+            // second round trip: the column in column layout
+#pragma unroll
+            for (int R = K; R < NT; ++R) {
+                rowv[R] = bperm(addr_cl, lane_select4(colv[R][0], colv[R][1], colv[R][2], colv[R][3], csel0, csel1));
+            }
             if (!(d > 0.f)) {
                 ok = false;
                 d = 1.f;
             }
             const float inv = 1.f / d;
-            float colv[NT][4], rowv[NT];
-            const int addr_rl = 4 * (16 * g + jl);
 #pragma unroll
-            for (int R = K; R < NT; ++R) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) colv[R][r] = bperm(addr_rl, acc[R * (R + 1) / 2 + K][r]);
-                const float sel = csel == 0 ? colv[R][0] : csel == 1 ? colv[R][1] : csel == 2 ? colv[R][2] : colv[R][3];
-                rowv[R] = bperm(addr_cl, sel) * inv;
-            }
+            for (int R = K; R < NT; ++R) rowv[R] *= inv;
             rowv[K] = (c > jl) ? rowv[K] : 0.f;   // columns up to j of this tile column are final
-            const float zj = bperm(4 * jl, z[K]);
             dinv[K] = (c == jl) ? inv : dinv[K];
 #pragma unroll
             for (int C = K; C < NT; ++C) z[C] = fmaf(-rowv[C], zj, z[C]);
 #pragma unroll
             for (int R = K; R < NT; ++R)
 #pragma unroll
-                for (int C = K; C <= R; ++C)
+                for (int r = 0; r < 4; ++r)
+                    acc[R * (R + 1) / 2 + K][r] = fmaf(-colv[R][r], rowv[K], acc[R * (R + 1) / 2 + K][r]);
+        }
+        if (K < NT - 1) {
+            // operands of the trailing update: T[R][s] = (L_RK D_K)(i, 4kq+s), V[R][s] = -T[R][s] / d_(4kq+s)
+            float T[NT][4], V[NT][4], dk[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        acc[R * (R + 1) / 2 + C][r] = fmaf(-colv[R][r], rowv[C], acc[R * (R + 1) / 2 + C][r]);
+            for (int s4 = 0; s4 < 4; ++s4) dk[s4] = -bperm(4 * (4 * g + s4), dinv[K]);
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tbuf[(4 * g + r) * 17 + c] = acc[R * (R + 1) / 2 + K][r];
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4) {
+                    T[R][s4] = tbuf[c * 17 + 4 * g + s4];
+                    V[R][s4] = T[R][s4] * dk[s4];
+                }
+            }
+            // a register written by the vector ALU must not be read by an MFMA within the next few cycles
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R)
+                asm volatile("" : "+v"(V[R][0]), "+v"(V[R][1]), "+v"(V[R][2]), "+v"(V[R][3]), "+v"(T[R][0]), "+v"(T[R][1]),
+                             "+v"(T[R][2]), "+v"(T[R][3]));
+            asm volatile("s_nop 7" ::: "memory");
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R)
+#pragma unroll
+                for (int C = K + 1; C <= R; ++C)
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) {
+                        mfma_16x16x4_ordered<true>(acc[R * (R + 1) / 2 + C], T[R][s4], V[C][s4]);
+#ifdef ALS_DEBUG_SERIAL_MFMA
+                        mfma_drain();
+#endif
+                    }
+            mfma_drain();
+            // nothing may read the updated tiles before the wait above
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R)
+#pragma unroll
+                for (int C = K + 1; C <= R; ++C) asm volatile("" : "+v"(acc[R * (R + 1) / 2 + C]));
         }
     }
     // back substitution, columns from the last to the first: x_j = z_j/d_j, then z_i -= (L[j][i] d_i) x_j, i < j
