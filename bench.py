@@ -42,7 +42,7 @@ def cpu_baseline(w, a_host, stride):
     t0 = time.perf_counter()
     oracle.update_selected(cols, c.ptr, c.idx, c.val, Xs, w.lam)
     t_cols = time.perf_counter() - t0
-    est = t_rows * (w.nnz / max(nnz_rows, 1)) + t_cols * (w.nnz / max(nnz_cols, 1))
+    est = t_rows * (a_host.nnz / max(nnz_rows, 1)) + t_cols * (a_host.nnz / max(nnz_cols, 1))
     return {"value": est, "unit": "s/sweep", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"exact fp64 oracle on every {stride}th row ({nnz_rows} entries, {t_rows:.2f} s) and every "
                       f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries"}
@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
+    ap.add_argument("--test-frac", type=float, default=0.0,
+                    help="hold out this fraction of the entries (seeded), fit on the rest and report the held-out RMSE "
+                         "per sweep and the time to come within 0.2 %% of its best value (protocol of Section 5.2)")
     ap.add_argument("--implicit", type=float, default=None, metavar="ALPHA",
                     help="time implicit-feedback sweeps (Section 5.6) with this confidence scale instead")
     ap.add_argument("--cg-iters", type=int, default=6)
@@ -112,6 +115,10 @@ def main():
     t0 = time.perf_counter()
     a = W.generate(w)
     log(f"[bench] generated {w.name}: {w.m} x {w.n}, {a.nnz} stored entries in {time.perf_counter() - t0:.1f} s")
+    held_out = None
+    if args.test_frac > 0:
+        a, held_out = W.split(a, args.test_frac, seed=w.seed)
+        log(f"[bench] held out {held_out.nnz} entries, fitting on {a.nnz}")
     solver = P.SOLVER_CG if args.solver == "cg" else P.SOLVER_CHOLESKY
     fcode = {"f32": P.F32, "bf16": P.BF16, "f16": P.F16}[args.factor_dtype]
     ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.factor_dtype]
@@ -162,9 +169,10 @@ def main():
     deg_r = np.diff(a.ptr)
     deg_c = np.bincount(a.idx, minlength=w.n)
     # (the fused kernel exists for f <= 128; the exact solver uses it with fp32 factor inputs only)
-    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if fused_n > 0 else 2 * w.nnz
+    nnz_fit = int(a.nnz)   # entries the factors are fitted on (all of them unless --test-frac)
+    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if fused_n > 0 else 2 * nnz_fit
     per_entry = w.f * (w.f + 1)
-    flops_sweep = 2.0 * w.nnz * per_entry
+    flops_sweep = 2.0 * nnz_fit * per_entry
     herm_s = (herm_ms + fused_ms) * 1e-3 / K
     achieved = flops_sweep / herm_s / 1e12
     launches = (herm_n + fused_n) // K
@@ -176,15 +184,15 @@ def main():
                 "flops_per_launch": flops_sweep / max(launches, 1),
                 "k_hermitian": {"tflops": nnz_slot * per_entry / max(herm_ms * 1e-3 / K, 1e-12) / 1e12,
                                 "ms_per_sweep": herm_ms / K, "entries_per_sweep": nnz_slot},
-                "k_hermitian_cg": {"tflops": (2 * w.nnz - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
-                                   "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * w.nnz - nnz_slot}}
+                "k_hermitian_cg": {"tflops": (2 * nnz_fit - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
+                                   "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * nnz_fit - nnz_slot}}
     out = {
         "metric": f"seconds per {'implicit-feedback ' if args.implicit is not None else ''}ALS sweep (X+Theta) at f={w.f}",
         "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "factor_dtype": args.factor_dtype,
-        "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={w.nnz} f={w.f} lambda={w.lam}",
+        "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={nnz_fit} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
                    **({"implicit_alpha": args.implicit} if args.implicit is not None else {}),
                    "chunk": chunk, "batch_slots": als.cfg.batch_slots or 131072},
@@ -192,6 +200,27 @@ def main():
         "solve_ms_per_sweep": solve_ms / K, "train_rmse": rmse,
         "roofline": roofline,
     }
+    if held_out is not None and args.implicit is None:
+        # convergence protocol, outside the timed region: restart from the initial factors, held-out RMSE after
+        # every sweep, update time accumulated without the evaluations
+        te = P.SparseMatrix.from_host(held_out.nrows, held_out.ncols, held_out.ptr, held_out.idx, held_out.val, device=dev)
+        X0, T0 = W.init_factors(w)
+        X.copy_(torch.from_numpy(X0)); T.copy_(torch.from_numpy(T0))
+        ev = P.Als(w.f)
+        rm, cum, tsum = [], [], 0.0
+        for _ in range(max(args.steps, 1)):
+            torch.cuda.synchronize(); t1 = time.perf_counter()
+            sweep()
+            torch.cuda.synchronize(); tsum += time.perf_counter() - t1
+            rm.append(ev.rmse(te, X, T)); cum.append(tsum)
+        ev.close()
+        best = min(rm)
+        hit = next(i for i, r in enumerate(rm) if r <= 1.002 * best)
+        out["held_out"] = {"test_frac": args.test_frac, "entries": int(held_out.nnz), "rmse_per_sweep": rm,
+                           "seconds_cumulative": cum, "best_rmse": best,
+                           "seconds_to_within_0.2pct_of_best": cum[hit], "sweeps_to_within_0.2pct_of_best": hit + 1}
+        log(f"[bench] held-out rmse per sweep: " + " ".join(f"{r:.5f}" for r in rm)
+            + f"; within 0.2% of the best after {hit + 1} sweeps = {cum[hit] * 1e3:.1f} ms")
     if args.cpu_stride > 0:
         log("[bench] timing the CPU oracle on a sample ...")
         out["cpu_baseline"] = cpu_baseline(w, a, args.cpu_stride)

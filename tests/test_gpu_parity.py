@@ -363,3 +363,29 @@ def test_factor_width_sweep_exact_and_cg(P, f):
     print(f"f={f} CG(6) 10 sweeps: rmse {r:.5f} vs exact oracle {hist[-1]['rmse']:.5f}")
     assert abs(r - hist[-1]["rmse"]) <= 2e-3
     als.close()
+
+
+def test_held_out_rmse_follows_the_oracle(P):
+    """Protocol of Section 5.2: fit on the training entries, RMSE on held-out entries (a second CSR into
+    als_rmse).  Exact mode must follow the oracle's held-out RMSE sweep by sweep."""
+    w = W.TINY
+    a = W.generate(w)
+    train, test = W.split(a, 0.1, seed=5)
+    ct = W.transpose(train)
+    X0, T0 = W.init_factors(w)
+    Xo, To = X0.astype(np.float64), T0.astype(np.float64)
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY)
+    tr = P.SparseMatrix.from_host(train.nrows, train.ncols, train.ptr, train.idx, train.val)
+    trc = P.SparseMatrix.from_host(ct.nrows, ct.ncols, ct.ptr, ct.idx, ct.val)
+    te = P.SparseMatrix.from_host(test.nrows, test.ncols, test.ptr, test.idx, test.val)
+    X, T = _dev(X0.copy()), _dev(T0.copy())
+    for sweep in range(4):
+        Xo = oracle.update_rows(train.ptr, train.idx, train.val, To, w.lam)
+        To = oracle.update_rows(ct.ptr, ct.idx, ct.val, Xo, w.lam)
+        als.update_rows(tr, T, w.lam, X)
+        als.update_cols(trc, X, w.lam, T)
+        r_gpu = als.rmse(te, X, T)
+        r_orc = oracle.rmse(test.ptr, test.idx, test.val, Xo, To)
+        print(f"held-out rmse sweep {sweep + 1}: gpu {r_gpu:.6f} oracle {r_orc:.6f}", flush=True)
+        assert abs(r_gpu - r_orc) <= 1e-4 * r_orc
+    als.close()

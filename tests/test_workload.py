@@ -46,3 +46,20 @@ def test_init_factors():
     x0, t0 = W.init_factors(W.TINY)
     assert x0.shape == (2000, 16) and not x0.any()
     assert t0.dtype == np.float32 and t0.min() >= 0 and t0.max() <= 0.25
+
+
+def test_split_is_a_seeded_partition_of_the_entries():
+    a = W.generate(W.TINY)
+    tr, te = W.split(a, 0.1, seed=3)
+    tr2, te2 = W.split(a, 0.1, seed=3)
+    assert tr.nnz + te.nnz == a.nnz and 0.08 * a.nnz < te.nnz < 0.12 * a.nnz
+    assert np.array_equal(te.idx, te2.idx) and np.array_equal(tr.ptr, tr2.ptr)
+    # every entry lands in exactly one part, rows keep ascending columns
+    key = lambda m: set(zip(np.repeat(np.arange(m.nrows), np.diff(m.ptr)).tolist(), m.idx.tolist()))
+    assert key(tr) | key(te) == key(a) and not (key(tr) & key(te))
+    for m in (tr, te):
+        for u in range(0, m.nrows, 97):
+            seg = m.idx[m.ptr[u]:m.ptr[u + 1]]
+            assert np.all(np.diff(seg) > 0)
+    _, te3 = W.split(a, 0.1, seed=4)
+    assert not np.array_equal(te.idx, te3.idx)

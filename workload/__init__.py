@@ -173,6 +173,27 @@ def transpose(a: CSR) -> CSR:
                t.data.astype(np.float32))
 
 
+def split(a: CSR, test_frac: float, seed: int = 0):
+    """Seeded train / held-out split of the stored entries (the protocol of Section 5.2: fit on the training
+    entries, report the RMSE on entries that were held out).  Entry (u, v) goes to the test set iff a 64-bit
+    mix of (seed, u, v) falls below test_frac: a pure function of the entry, independent of the order of work.
+    Returns (train, test), both canonical CSR of the full shape."""
+    rows = np.repeat(np.arange(a.nrows, dtype=np.uint64), np.diff(a.ptr).astype(np.int64))
+    with np.errstate(over="ignore"):
+        h = (rows * np.uint64(0x9E3779B97F4A7C15) + a.idx.astype(np.uint64) * np.uint64(0xC2B2AE3D27D4EB4F)
+             + np.uint64(seed) * np.uint64(0x165667B19E3779F9))
+        h ^= h >> np.uint64(30); h *= np.uint64(0xBF58476D1CE4E5B9)
+        h ^= h >> np.uint64(27); h *= np.uint64(0x94D049BB133111EB)
+        h ^= h >> np.uint64(31)
+    is_test = (h >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53)) < test_frac
+    out = []
+    for keep in (~is_test, is_test):
+        cnt = np.bincount(rows[keep].astype(np.int64), minlength=a.nrows)
+        ptr = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int64)
+        out.append(CSR(a.nrows, a.ncols, ptr, a.idx[keep].copy(), a.val[keep].copy()))
+    return out[0], out[1]
+
+
 def init_factors(w: Workload, seed: Optional[int] = None):
     """X0 = 0 (m x f) and Theta0 ~ U(0, 1/sqrt(f)) (n x f), float32."""
     rng = np.random.default_rng(w.seed + 1000 if seed is None else seed)
