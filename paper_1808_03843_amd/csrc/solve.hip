@@ -53,8 +53,12 @@ __device__ __forceinline__ void load_system(const float *__restrict__ slots, int
 // Right-looking LDL^T on the bordered matrix: row F of As holds b.  After eliminating column j,
 // As[i][j] (i > j) holds L[i][j]*d_j and As[F][j] holds z_j with L z = b; then x solves
 // L^T x = D^-1 z.  One barrier per column.
+// threads per workgroup: a system of f = 256 fills the LDS of a CU (one workgroup per CU), so the only way
+// to have several wavefronts per SIMD hide each other's LDS latency is a larger workgroup
+constexpr int ldlt_threads(int F) { return F > 128 ? 1024 : 256; }
+
 template <int F, typename PtrT>
-__global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ perm,
+__global__ __launch_bounds__(ldlt_threads(F)) void k_solve_ldlt(const int32_t *__restrict__ perm,
                                                     const int32_t *__restrict__ task_off, int64_t pos0,
                                                     int64_t task0, const PtrT *__restrict__ ptr,
                                                     const float *__restrict__ slots, float lambda,
@@ -73,7 +77,8 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
     // the slots of a split row have been summed into its first slot by k_reduce_slots
     load_system<F>(slots + (int64_t)first * SLOT, 1, lambda * (float)n_u, As, As + tri(F, 0));
 
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    constexpr int TX = F > 128 ? 32 : 16, TY = ldlt_threads(F) / TX;   // thread grid over (column k, row i)
+    const int tx = threadIdx.x % TX, ty = threadIdx.x / TX;
     bool bad = false;
     for (int j = 0; j < F; ++j) {
         __syncthreads();
@@ -81,11 +86,11 @@ __global__ __launch_bounds__(256) void k_solve_ldlt(const int32_t *__restrict__ 
         if (!(d > 0.f)) { bad = true; d = 1.f; }
         const float invd = 1.f / d;
         // rows i in (j, F] (row F is b), columns k in (j, min(i, F-1)]
-        for (int i = j + 1 + ty; i <= F; i += 16) {
+        for (int i = j + 1 + ty; i <= F; i += TY) {
             const int ri = tri(i, 0);
             const float lij = As[ri + j] * invd;
             const int kmax = i < F ? i : F - 1;
-            for (int k = j + 1 + tx; k <= kmax; k += 16) As[ri + k] -= lij * As[tri(k, j)];
+            for (int k = j + 1 + tx; k <= kmax; k += TX) As[ri + k] -= lij * As[tri(k, j)];
         }
     }
     __syncthreads();
@@ -156,7 +161,7 @@ static hipError_t solve_f(int solver, int cg_iters, float cg_eps, hipStream_t st
     dim3 grid((unsigned)npos);
     (void)cg_iters; (void)cg_eps;
     if (solver != ALS_SOLVER_CHOLESKY) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(256), 0, st, perm, task_off, pos0, task0,
+    hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(ldlt_threads(F)), 0, st, perm, task_off, pos0, task0,
                            (const PtrT *)ptr, slots, lambda, Xout, status);
     return hipGetLastError();
 }
