@@ -48,12 +48,12 @@ def cpu_baseline(w, a_host, stride):
                       f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries"}
 
 
-# HBM bytes moved by the get_hermitian launches of one sweep (k_hermitian x2 + k_hermitian_cg), from the
+# HBM bytes moved by the get_hermitian launches of one sweep (k_hermitian x2 + k_hermitian_cg x2), from the
 # rocprofv3 counter runs summarised in profiles/k_hermitian_mid_f100_cg6_counters.txt: FETCH_SIZE and WRITE_SIZE
 # summed over those dispatches, scaled by what the same counters read for a copy of known size (2 KiB and
 # 1 KiB per count).  Counters cannot be read from inside this process, so the figure is only reported for
 # the configuration it was measured on.
-MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 1024): 47.4e9 + 4.9e9}
+MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 4096): 42.6e9 + 1.07e9}
 
 
 def measured_traffic(w, args, chunk, launches):
@@ -165,7 +165,7 @@ def main():
     # get_hermitian roofline.  Algorithmic flops = f*(f+1) per stored entry and half-sweep (lower triangle
     # of theta theta^T, FMA = 2).  Rows with >= chunk entries are built by k_hermitian into slots, shorter
     # rows by k_hermitian_cg (which also runs the solver: its time is charged to get_hermitian in full).
-    chunk = als.cfg.chunk or 1024
+    chunk = als.cfg.chunk or 4096
     deg_r = np.diff(a.ptr)
     deg_c = np.bincount(a.idx, minlength=w.n)
     # (the fused kernel exists for f <= 128; the exact solver uses it with fp32 factor inputs only)

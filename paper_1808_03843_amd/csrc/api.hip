@@ -310,7 +310,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
     als_ctx *ctx = new (std::nothrow) als_ctx();
     if (!ctx) return ALS_ENOMEM;
     ctx->cfg = *cfg;
-    if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 1024;
+    if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 4096;
     if (ctx->cfg.batch_slots == 0) {   // about 4 GB of slots
         ctx->cfg.batch_slots = 131072;
         while (ctx->cfg.batch_slots > 1024 && (size_t)ctx->cfg.batch_slots * slot_floats(cfg->f) * 4 > (4ull << 30))

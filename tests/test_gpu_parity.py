@@ -41,7 +41,7 @@ TOL_EXACT = 1e-4
 @pytest.mark.parametrize("f", [16, 32, 64, 100, 128, 256])
 def test_hermitian_and_bias_match_oracle_on_edge_degrees(P, f):
     n = 5000
-    degrees = [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 127, 255, 256, 257, 300, 1023, 1024, 1025, 2048, 2500, 4097, 0, 1]
+    degrees = [0, 1, 2, 3, 4, 5, 7, 8, 63, 64, 65, 127, 255, 256, 257, 300, 1023, 1024, 1025, 2048, 2500, 4095, 4096, 4097, 0, 1]
     a = _edge_matrix(n, f, 7, degrees)
     Theta = W.random_factors(n, f, seed=3, scale=0.5)
     lam = 0.05
