@@ -561,15 +561,19 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
 
 // Exact solve (Section 2 step (ii), Section 4.1 baseline) of one system held by one wavefront: LDL^T
 // without square roots, right-looking, blocked by tile columns, directly on the accumulator tiles; then
-// the two triangular solves.  Same argument layout as cg_tiles; acc is overwritten (column j ends up
-// holding L[:,j]*d_j).  Returns false if a pivot was not positive (the pivot is then replaced by 1).
-//   Panel (tile column K), column by column: the column is fetched into the "row layout" of every tile
-//   row (4 permutes each), turned into the "column layout" and scaled by 1/d_j (one permute each); the
-//   remaining columns of the panel tiles get their rank-1 update (4 FMAs per tile) and the forward
-//   substitution rides along.
-//   Trailing update, once per panel, on the matrix cores: tile (R, C) -= (L_RK D_K) (L_CK)^T as four
-//   16x16x4 MFMAs.  The operands are the panel tiles transposed into the operand layout (lane (i, kq),
-//   register s = element (i, 4kq+s)) through `tbuf`, 272 floats of LDS private to the wavefront.
+// the two triangular solves, blocked the same way.  Same argument layout as cg_tiles; acc is overwritten
+// (column j ends up holding L[:,j]*d_j).  Returns false if a pivot was not positive (the pivot is then
+// replaced by 1).
+//   Panel (tile column K), column by column: the pivot, z_j and the column in the "row layout" of every
+//   tile row of the panel (4 permutes each) are fetched in one batch; the diagonal tile's part is turned
+//   into the "column layout" (one more permute) and scaled by 1/d_j; the remaining columns of the panel
+//   tiles get their rank-1 update (4 FMAs per tile); z of the panel is forward-substituted.
+//   Once per panel, on the matrix cores: tile (R, C) -= (L_RK D_K) (L_CK)^T as four 16x16x4 MFMAs.  The
+//   operands are the panel tiles transposed into the operand layout (lane (i, kq), register s = element
+//   (i, 4kq+s)) through `tbuf`, 272 floats of LDS private to the wavefront; the same transposed tiles
+//   carry the panel's z into the tile rows below (4 FMAs per tile).
+//   Back substitution: per panel, column by column inside the diagonal tile, then one tile-times-vector
+//   product per tile to its left.
 template <bool IN_VGPR>
 __device__ __forceinline__ void mfma_16x16x4_ordered(v4f &acc, float a, float b) {
     asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
@@ -583,6 +587,7 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
     const int lane = threadIdx.x & 63, c = lane & 15, g = lane >> 4;
     const int addr_cl = 4 * (16 * (c >> 2) + c);
     const uint64_t csel0 = __ballot((c & 1) != 0), csel1 = __ballot((c & 2) != 0);   // bits of c & 3 as lane masks
+    const int a16 = 4 * (lane ^ 16), a32 = 4 * (lane ^ 32);
     float z[NT], dinv[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) {
@@ -594,45 +599,45 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
 #pragma unroll
     for (int K = 0; K < NT; ++K) {
         const int ncol = (K == NT - 1) ? LASTCOLS : 16;
+        const int DK = K * (K + 1) / 2 + K;   // the diagonal tile of the panel
 #pragma unroll 1
         for (int jl = 0; jl < ncol; ++jl) {
             const int jr = jl & 3, jg = jl >> 2;
-            // first LDS round trip: the pivot, z_j and the column in row layout, all issued together
-            float d = bperm(4 * (16 * jg + jl), pick(acc[K * (K + 1) / 2 + K], jr));
+            // one LDS round trip: the pivot, z_j and the column in row layout
+            float d = bperm(4 * (16 * jg + jl), pick(acc[DK], jr));
             const float zj = bperm(4 * jl, z[K]);
-            float colv[NT][4], rowv[NT];
+            float colv[NT][4];
             const int addr_rl = 4 * (16 * g + jl);
 #pragma unroll
             for (int R = K; R < NT; ++R)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) colv[R][r] = bperm(addr_rl, acc[R * (R + 1) / 2 + K][r]);
-            // second round trip: the column in column layout
-#pragma unroll
-            for (int R = K; R < NT; ++R) {
-                rowv[R] = bperm(addr_cl, lane_select4(colv[R][0], colv[R][1], colv[R][2], colv[R][3], csel0, csel1));
-            }
+            // second round trip: the diagonal tile's part of the column in column layout
+            float rowk = bperm(addr_cl, lane_select4(colv[K][0], colv[K][1], colv[K][2], colv[K][3], csel0, csel1));
             if (!(d > 0.f)) {
                 ok = false;
                 d = 1.f;
             }
-            const float inv = 1.f / d;
-#pragma unroll
-            for (int R = K; R < NT; ++R) rowv[R] *= inv;
-            rowv[K] = (c > jl) ? rowv[K] : 0.f;   // columns up to j of this tile column are final
+            float inv = __builtin_amdgcn_rcpf(d);
+            inv = inv * fmaf(-d, inv, 2.f);        // one Newton step: relative error ~1e-7
+            rowk = (c > jl) ? rowk * inv : 0.f;    // columns up to j of this tile column are final
             dinv[K] = (c == jl) ? inv : dinv[K];
-#pragma unroll
-            for (int C = K; C < NT; ++C) z[C] = fmaf(-rowv[C], zj, z[C]);
+            z[K] = fmaf(-rowk, zj, z[K]);
 #pragma unroll
             for (int R = K; R < NT; ++R)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[R * (R + 1) / 2 + K][r] = fmaf(-colv[R][r], rowv[K], acc[R * (R + 1) / 2 + K][r]);
+                    acc[R * (R + 1) / 2 + K][r] = fmaf(-colv[R][r], rowk, acc[R * (R + 1) / 2 + K][r]);
         }
         if (K < NT - 1) {
-            // operands of the trailing update: T[R][s] = (L_RK D_K)(i, 4kq+s), V[R][s] = -T[R][s] / d_(4kq+s)
-            float T[NT][4], V[NT][4], dk[4];
+            // T[R][s] = (L_RK D_K)(i, 4kq+s); V[R][s] = -T[R][s] / d_(4kq+s); zs[s] = z_(4kq+s) / d_(4kq+s)
+            float T[NT][4], V[NT][4], dk[4], zs[4];
+            const float zd = z[K] * dinv[K];
 #pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) dk[s4] = -bperm(4 * (4 * g + s4), dinv[K]);
+            for (int s4 = 0; s4 < 4; ++s4) {
+                dk[s4] = -bperm(4 * (4 * g + s4), dinv[K]);
+                zs[s4] = bperm(4 * (4 * g + s4), zd);
+            }
 #pragma unroll
             for (int R = K + 1; R < NT; ++R) {
 #pragma unroll
@@ -660,6 +665,24 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
                         mfma_drain();
 #endif
                     }
+            // forward substitution of the tile rows below, while the MFMAs run: z_R -= (L_RK D_K) (z_K / d_K)
+            float part[NT];
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) {
+                float p4 = T[R][0] * zs[0];
+#pragma unroll
+                for (int s4 = 1; s4 < 4; ++s4) p4 = fmaf(T[R][s4], zs[s4], p4);
+                part[R] = p4;
+            }
+            float t[NT];
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) t[R] = bperm(a16, part[R]);
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) part[R] += t[R];
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) t[R] = bperm(a32, part[R]);
+#pragma unroll
+            for (int R = K + 1; R < NT; ++R) z[R] -= part[R] + t[R];
             mfma_drain();
             // nothing may read the updated tiles before the wait above
 #pragma unroll
@@ -668,24 +691,43 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
                 for (int C = K + 1; C <= R; ++C) asm volatile("" : "+v"(acc[R * (R + 1) / 2 + C]));
         }
     }
-    // back substitution, columns from the last to the first: x_j = z_j/d_j, then z_i -= (L[j][i] d_i) x_j, i < j
+    // back substitution, panels from the last to the first: x_j = z_j/d_j, then z_i -= (L[j][i] d_i) x_j, i < j
 #pragma unroll
     for (int q = 0; q < NT; ++q) x[q] = 0.f;
 #pragma unroll
     for (int K = NT - 1; K >= 0; --K) {
         const int ncol = (K == NT - 1) ? LASTCOLS : 16;
+        const int DK = K * (K + 1) / 2 + K;
 #pragma unroll 1
         for (int jl = ncol - 1; jl >= 0; --jl) {
             const int jr = jl & 3, jg = jl >> 2;
             const float xj = bperm(4 * jl, z[K] * dinv[K]);
+            // lane (c, jg) holds row j of the diagonal tile
+            const float lrow = bperm(4 * (16 * jg + c), pick(acc[DK], jr));
             x[K] = (c == jl) ? xj : x[K];
-            const int addr_row = 4 * (16 * jg + c);   // lane (c, jg) holds row j of the tiles (K, C)
+            z[K] -= (c < jl) ? lrow * xj : 0.f;
+        }
+        if (K > 0) {
+            // tiles to the left of the diagonal: z_C -= (tile (K, C))^T x_K, rows of the tile = lane rows x registers
+            float xr[4], part[NT], t[NT];
 #pragma unroll
-            for (int C = 0; C <= K; ++C) {
-                float upd = bperm(addr_row, pick(acc[K * (K + 1) / 2 + C], jr)) * xj;
-                if (C == K) upd = (c < jl) ? upd : 0.f;
-                z[C] -= upd;
+            for (int r = 0; r < 4; ++r) xr[r] = bperm(4 * (4 * g + r), x[K]);
+#pragma unroll
+            for (int C = 0; C < K; ++C) {
+                const v4f tile = acc[K * (K + 1) / 2 + C];
+                float p4 = tile[0] * xr[0];
+#pragma unroll
+                for (int r = 1; r < 4; ++r) p4 = fmaf(tile[r], xr[r], p4);
+                part[C] = p4;
             }
+#pragma unroll
+            for (int C = 0; C < K; ++C) t[C] = bperm(a16, part[C]);
+#pragma unroll
+            for (int C = 0; C < K; ++C) part[C] += t[C];
+#pragma unroll
+            for (int C = 0; C < K; ++C) t[C] = bperm(a32, part[C]);
+#pragma unroll
+            for (int C = 0; C < K; ++C) z[C] -= part[C] + t[C];
         }
     }
     return ok;
