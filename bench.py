@@ -81,7 +81,7 @@ def main():
     ap.add_argument("--cg-iters", type=int, default=6)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--batch-slots", type=int, default=0)
-    ap.add_argument("--cpu-stride", type=int, default=8, help="oracle baseline on every k-th row/column; 0 = skip")
+    ap.add_argument("--cpu-stride", type=int, default=1, help="oracle baseline on every k-th row/column (1 = one whole exact sweep, about 20 s on 16 host threads); 0 = skip")
     ap.add_argument("--f", type=int, default=0, help="override the workload's factor width (factor-width sweep)")
     ap.add_argument("--factor-dtype", default="f32", choices=["f32", "bf16", "f16"],
                     help="element type of the gathered factor matrix (16-bit: widened in registers, fp32 accumulate)")
