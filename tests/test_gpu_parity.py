@@ -217,13 +217,20 @@ def test_bad_arguments_are_errors_not_crashes(P):
     als.close()
 
 
-def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P):
-    # a 4.3 GB factor matrix of which only a few rows are referenced: exercises the wide-offset gather
-    f, n = 16, 67_200_000
+@pytest.mark.parametrize("f,n", [(16, 67_200_000), (32, 33_600_000), (64, 16_800_000), (100, 10_800_000),
+                                 (128, 8_400_000), (256, 4_200_000)])
+def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P, f, n):
+    """A gathered factor matrix of 4 GiB or more switches the gathers to 64-bit row addresses (another
+    template instantiation of every get_hermitian kernel, and of the Gram kernel in implicit mode).  The
+    matrix is zero except for the rows the test touches; the oracle sees a compact copy."""
+    assert n * f * 4 >= 2 ** 32
     rng = np.random.default_rng(5)
     degrees = [1, 3, 40, 700, 2000]
     ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
-    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees]).astype(np.int32)
+    # ids spread over the whole matrix, the last row included
+    idx = np.concatenate([np.sort(np.unique(np.concatenate([rng.choice(n, d, replace=False)[: d - 1], [n - 1]]))[:d])
+                          for d in degrees]).astype(np.int32)
+    assert len(idx) == ptr[-1]
     val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
     used = np.unique(idx)
     rows_val = W.random_factors(len(used), f, seed=8, scale=0.5)
@@ -231,13 +238,24 @@ def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P):
     Theta[torch.from_numpy(used.astype(np.int64)).cuda()] = torch.from_numpy(rows_val).cuda()
     # the oracle sees a compact copy: column ids renumbered to the used rows
     remap = np.searchsorted(used, idx).astype(np.int32)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
     for solver in (P.SOLVER_CHOLESKY, P.SOLVER_CG):
         als = P.Als(f, solver=solver, cg_iters=f, chunk=256)
-        sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
         X = torch.zeros((len(degrees), f), device="cuda:0")
-        als.update_rows(sp, Theta, 0.05, X)
+        # lambda = 0.5: the row with one entry has cond(A_u) = (|theta|^2 + lambda) / lambda, and fp32 cannot
+        # hold 1e-4 at f = 256 with a smaller lambda
+        als.update_rows(sp, Theta, 0.5, X)
         als.synchronize()
-        ref = oracle.update_rows(ptr, remap, val, rows_val, 0.05)
+        ref = oracle.update_rows(ptr, remap, val, rows_val, 0.5)
+        assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
+        als.close()
+    if f <= 128:
+        # implicit mode: the zero rows add nothing to Theta^T Theta, so the compact problem is the same problem
+        als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=256)
+        X = torch.zeros((len(degrees), f), device="cuda:0")
+        als.update_rows_implicit(sp, Theta, 0.4, 2.0, X)
+        als.synchronize()
+        ref = oracle.implicit_update_rows(ptr, remap, val, rows_val, 0.4, 2.0)
         assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
         als.close()
     del Theta
