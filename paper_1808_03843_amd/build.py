@@ -18,11 +18,34 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-tar
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
     extra = os.environ.get("ALS_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -DALS_DEPTH_SLOTS=4 for tuning runs
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    # the register / scratch / occupancy report of every kernel is kept beside the object: the MFMAs are
+    # inline asm that the compiler cannot protect, so a kernel that spills is a kernel that may be wrong
+    cmd = [HIPCC, *FLAGS, *extra, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
+    with open(obj + ".resources", "w") as fh:
+        fh.write(r.stderr)
     return obj
+
+
+def kernel_resources(obj_dir: str = None):
+    """Parses the reports written by the last build: {kernel name: {"vgpr", "agpr", "spill", "scratch", "occupancy"}}."""
+    import re
+    obj_dir = obj_dir or OBJ_DIR
+    out = {}
+    for src in SOURCES:
+        path = os.path.join(obj_dir, src.replace(".hip", ".o") + ".resources")
+        if not os.path.exists(path):
+            continue
+        with open(path) as fh:
+            text = fh.read()
+        for blk in re.split(r"remark: Function Name: ", text)[1:]:
+            name = blk.split(" ")[0]
+            num = lambda key: int(re.search(key + r": (\d+)", blk).group(1))
+            out[name] = {"vgpr": num("VGPRs"), "agpr": num("AGPRs"), "spill": num("VGPRs Spill"),
+                         "scratch": num(r"ScratchSize \[bytes/lane\]"), "occupancy": num(r"Occupancy \[waves/SIMD\]")}
+    return out
 
 
 def stale() -> bool:

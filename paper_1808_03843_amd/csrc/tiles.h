@@ -304,6 +304,10 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
     float bacc[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) bacc[q] = 0.f;
+    // The caller has just written the accumulators (zeros, or a starting matrix) with vector-ALU or memory
+    // instructions, which the compiler is free to sink to just before their first use -- the first MFMA,
+    // which must not read a register written in the previous few cycles.  Pin those writes here.
+    mfma_settle<IN_VGPR>(acc);
     // Prologue in the order of the loop body (far ids first, then the gathers, oldest step first): the
     // compiler's wait-count bookkeeping merges both paths at the loop head, and any other order makes
     // it drain the outstanding gathers at the top of every round.
@@ -596,6 +600,11 @@ __device__ __forceinline__ bool ldlt_tiles(v4f (&acc)[tiles_tri(F)], const float
     }
     bool ok = true;
     auto pick = [](const v4f &t, int r) { return r == 0 ? t[0] : r == 1 ? t[1] : r == 2 ? t[2] : t[3]; };
+    // The trailing updates below are MFMAs that accumulate into the tiles.  The caller's last vector-ALU
+    // writes to them (the regulariser on the diagonal, an added Gram matrix) may be delayed by the compiler
+    // until just before that first use, too close for the MFMA to see them: pin them here.  Afterwards a
+    // tile is written by MFMAs only until its own panel comes up.
+    mfma_settle<true>(acc);
 #pragma unroll
     for (int K = 0; K < NT; ++K) {
         const int ncol = (K == NT - 1) ? LASTCOLS : 16;

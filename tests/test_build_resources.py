@@ -1,0 +1,31 @@
+"""Static checks on what the last build produced (no GPU needed): the kernels that hold MFMA accumulator tiles
+must not spill -- the MFMAs are inline asm, invisible to the compiler's hazard handling, so a spill store
+placed right after one would save a stale register -- and the dominant kernel must keep two wavefronts per
+SIMD at f = 100."""
+import pytest
+
+from paper_1808_03843_amd import build as B
+
+
+@pytest.fixture(scope="module")
+def res():
+    r = B.kernel_resources()
+    if not r:
+        pytest.skip("no resource reports: run paper_1808_03843_amd/build.py first")
+    return r
+
+
+def test_no_kernel_spills_or_uses_scratch(res):
+    # the library's own kernels (namespace als); rocPRIM's sort kernels use a little scratch by design
+    bad = {k: v for k, v in res.items() if k.startswith("_ZN3als") and (v["spill"] or v["scratch"])}
+    assert not bad, bad
+
+
+def test_dominant_kernel_occupancy(res):
+    import re
+    # fp32 slot storage (the bf16-slot variants need 9 more registers and run one wavefront per SIMD)
+    slots = [v for k, v in res.items() if re.search(r"11k_hermitianILi100E[il]Lb[01]ELi\dELb0E", k)]
+    fused = [v for k, v in res.items() if "14k_hermitian_cgILi100E" in k]
+    assert slots and fused
+    assert all(v["occupancy"] >= 2 for v in slots), slots
+    assert all(v["occupancy"] >= 2 for v in fused), fused
