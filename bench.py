@@ -98,8 +98,8 @@ def main():
         print(json.dumps({"copy_calibration": "5 x (read 1 GiB, write 1 GiB), torch elementwise add kernel"}))
         return
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (rows are independent; see DESIGN.md for how the "
-                 "path would shard). Run with --gpus 1.")
+        sys.exit("bench.py: this build runs on one GPU only (rows are independent, so the path shards by rows; "
+                 "no collective is built). Run with --gpus 1.")
 
     import numpy as np
     import torch

@@ -1,6 +1,6 @@
 """The Very-tall configuration (50,082,603 x 39,780, 3,101,144,313 entries, int64 row pointers, 64-bit
 factor offsets on the column side).  Heavy (tens of GB of host and device memory, minutes): it runs only
-when ALS_RUN_VERY_TALL=1 is set; the result of the last run is recorded in the design doc.
+when ALS_RUN_VERY_TALL=1 is set.
 
 The matrix does not fit a full oracle sweep, so parity is sampled: rows and columns the oracle solves one
 by one, the streamed double-precision RMSE over all entries, and the CSC checked on sampled columns plus
