@@ -154,11 +154,18 @@ def main():
     solve_ms, solve_n = als.kernel_time(P.K_SOLVE)
     gram_ms, gram_n = als.kernel_time(P.K_GRAM)
     als.synchronize()
-    rmse = P.Als(w.f).rmse(csr, X, T) if fcode != P.F32 else als.rmse(csr, X, T)
+    ev = P.Als(w.f, profile=True)
+    ev.rmse(csr, X, T)                       # first call builds the plan of the matrix
+    ev.profile_reset()
+    rmse = ev.rmse(csr, X, T)
+    rmse_ms, _ = ev.kernel_time(P.K_RMSE)
+    ev.close()
+    # batched RMSE (Section 5.2): gathered bytes per entry = 4 f (theta row) + 8 (column id, rating)
+    rmse_gbps = a.nnz * (4.0 * w.f + 8.0) / max(rmse_ms * 1e-3, 1e-12) / 1e9
     K = args.steps
     log(f"[bench] {K} sweeps in {elapsed:.3f} s; rmse {rmse:.5f}; per sweep: k_hermitian {herm_ms / K:.2f} ms "
         f"({herm_n // K} launches), k_hermitian_cg {fused_ms / K:.2f} ms ({fused_n // K}), "
-        f"slot solve {solve_ms / K:.2f} ms ({solve_n // K})"
+        f"slot solve {solve_ms / K:.2f} ms ({solve_n // K}); rmse kernel {rmse_ms:.2f} ms ({rmse_gbps:.0f} GB/s gathered)"
         + (f", gram {gram_ms / K:.2f} ms ({gram_n // K}); implicit cost {als.implicit_loss(csr, X, T, w.lam, args.implicit):.6e}"
            if args.implicit is not None else ""))
 
@@ -198,6 +205,8 @@ def main():
                    "chunk": chunk, "batch_slots": als.cfg.batch_slots or 131072},
         "hermitian_tflops": achieved, "hermitian_ms_per_sweep": (herm_ms + fused_ms) / K,
         "solve_ms_per_sweep": solve_ms / K, "train_rmse": rmse,
+        "rmse_kernel": {"ms": rmse_ms, "gathered_GBps": rmse_gbps, "hbm_peak_GBps": 8000.0,
+                        "note": "gathered bytes; above the HBM rate when the gathered factor is cache-resident"},
         "roofline": roofline,
     }
     if held_out is not None and args.implicit is None:
