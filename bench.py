@@ -44,8 +44,9 @@ def cpu_baseline(w, a_host, stride):
     t_cols = time.perf_counter() - t0
     est = t_rows * (a_host.nnz / max(nnz_rows, 1)) + t_cols * (a_host.nnz / max(nnz_cols, 1))
     return {"value": est, "unit": "s/sweep", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"exact fp64 oracle on every {stride}th row ({nnz_rows} entries, {t_rows:.2f} s) and every "
-                      f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries"}
+            "sample": (f"one whole exact fp64 sweep: all rows ({t_rows:.2f} s), then all columns ({t_cols:.2f} s)" if stride == 1
+                       else f"exact fp64 oracle on every {stride}th row ({nnz_rows} entries, {t_rows:.2f} s) and every "
+                            f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries")}
 
 
 # HBM bytes moved by the get_hermitian launches of one sweep (k_hermitian x2 + k_hermitian_cg x2), from the
