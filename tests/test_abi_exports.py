@@ -23,3 +23,14 @@ def test_product_package_does_not_import_the_oracle():
             if fn.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "als_oracle" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: asking for more must end with a message, before anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
