@@ -62,7 +62,7 @@ def measured_traffic(w, args, chunk, launches):
         return None
     key = (w.name, w.f, args.solver, args.cg_iters if args.solver == "cg" else 0, args.factor_dtype, chunk)
     total = MEASURED_TRAFFIC_BYTES_PER_SWEEP.get(key)
-    if total is None or launches <= 0 or args.batch_slots != 0:
+    if total is None or launches <= 0 or args.batch_slots != 0 or args.herm_dtype != "f32":
         return None
     return total / launches
 
@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="mid")
     ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
+    ap.add_argument("--herm-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage of the partial Gram matrices that go through slots (Section 4.2); bf16 needs --solver cg")
     ap.add_argument("--test-frac", type=float, default=0.0,
                     help="hold out this fraction of the entries (seeded), fit on the rest and report the held-out RMSE "
                          "per sweep and the time to come within 0.2 %% of its best value (protocol of Section 5.2)")
@@ -124,7 +126,7 @@ def main():
     fcode = {"f32": P.F32, "bf16": P.BF16, "f16": P.F16}[args.factor_dtype]
     ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.factor_dtype]
     als = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
-                profile=True, factor_dtype=fcode)
+                profile=True, factor_dtype=fcode, herm_dtype=P.BF16 if args.herm_dtype == "bf16" else P.F32)
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, device=dev)
     csc = als.csr_to_csc(csr)
     X0, T0 = W.init_factors(w)
@@ -199,7 +201,7 @@ def main():
         "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "factor_dtype": args.factor_dtype,
+        "factor_dtype": args.factor_dtype, "herm_dtype": args.herm_dtype,
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={nnz_fit} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
                    **({"implicit_alpha": args.implicit} if args.implicit is not None else {}),

@@ -24,8 +24,26 @@ namespace als {
 constexpr int tiles_1d(int F) { return (F + 15) / 16; }
 constexpr int tiles_tri(int F) { return tiles_1d(F) * (tiles_1d(F) + 1) / 2; }
 constexpr int slot_floats(int F) { return tiles_tri(F) * 256 + tiles_1d(F) * 16; }
-// tiles of the tile rows [R0, R1): what one wavefront holds when a work item is shared by several
-constexpr int tiles_range(int R0, int R1) { return R1 * (R1 + 1) / 2 - R0 * (R0 + 1) / 2; }
+// A set of tile rows as a bit mask (bit R = tile row R): what one wavefront holds when a system is shared by
+// several.  Its tiles are numbered row by row in ascending R, C = 0..R inside a row.
+constexpr uint32_t rows_all(int F) { return (1u << tiles_1d(F)) - 1u; }
+constexpr int tiles_in(uint32_t rows) {
+    int n = 0;
+    for (int R = 0; R < 32; ++R)
+        if ((rows >> R) & 1u) n += R + 1;
+    return n;
+}
+constexpr int tiles_below(uint32_t rows, int R) { return tiles_in(rows & ((1u << R) - 1u)); }
+// NW wavefronts share the NT tile rows in pairs (k, NT-1-k) of NT+1 tiles each: equal tile counts
+constexpr uint32_t wave_rows(int NT, int NW, int w) {
+    const int NP = NT / 2;   // pairs
+    uint32_t m = 0;
+    for (int k = 0; k < NP; ++k) {
+        const bool mine = (NW == NP) ? (k == w) : (k == w || k == NP - 1 - w);   // NW == NP or NW == NP/2
+        if (mine) m |= (1u << k) | (1u << (NT - 1 - k));
+    }
+    return m;
+}
 // slot with the tiles stored as packed bf16 pairs (registers 2h, 2h+1 of a tile in one 32-bit word at
 // word offset (2t+h)*64 + l), b_u still fp32: the reduced-precision storage of Section 4.2
 constexpr int slot_words16(int F) { return tiles_tri(F) * 128 + tiles_1d(F) * 16; }
@@ -81,7 +99,15 @@ hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver,
 hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
-hipError_t launch_solve_cg_rows(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+// f = 256 (wide.hip): a system is shared by the wavefronts of one workgroup.  Same arguments as the
+// launchers above; Algorithm 1 only (the exact solver at this width works on slots in LDS, solve.hip).
+hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
+                                 const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                                 const int32_t *idx, const float *val, const void *Theta, float *slots);
+hipError_t launch_hermitian_cg_wide(bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+                                    int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                    const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
+hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
 hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,

@@ -222,10 +222,10 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const bool wide = (uint64_t)a->ncols * (uint64_t)f * esize >= (1ull << 32);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
-    const bool one_wave = single_wave_f(f);   // larger f: no fusion, every row goes through a slot
-    // rows shorter than a chunk are built and solved by one wavefront without leaving the registers; the
-    // exact solver does that for fp32 factor inputs
-    const bool tiles_solver = one_wave && (cg || ctx->cfg.factor_dtype == ALS_F32);
+    const bool one_wave = single_wave_f(f);   // larger f: the wavefronts of a workgroup share a system
+    // rows shorter than a chunk are built and solved without leaving the registers; the exact solver does
+    // that for fp32 factor inputs and systems that fit one wavefront
+    const bool tiles_solver = cg || (one_wave && ctx->cfg.factor_dtype == ALS_F32);
     const int64_t slot_rows = tiles_solver ? p->split_pos : m;
     int64_t pos = 0;
     while (pos < slot_rows) {
@@ -259,7 +259,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                                                         end - pos, task0, a->ptr, ctx->slots, lambda, gram,
                                                         ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
             else if (cg && !one_wave)
-                HIP_TRY(ctx, launch_solve_cg_rows(f, p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
+                HIP_TRY(ctx, launch_solve_cg_wide(p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
             else if (tiles_solver)
@@ -301,7 +301,8 @@ int als_create(als_ctx **out, const als_config *cfg) {
     // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
     // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
     if (cfg->herm_dtype != ALS_F32 &&
-        !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG && single_wave_f(cfg->f)))
+        !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG &&
+          (single_wave_f(cfg->f) || cfg->factor_dtype == ALS_F32)))   // f = 256: with fp32 factor inputs only
         return ALS_EINVAL;
     if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
     if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;

@@ -58,141 +58,6 @@ __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict_
     *dst = v;
 }
 
-// get_hermitian for f too large for one wavefront's registers (f = 256: 136 tiles): three wavefronts
-// share a work item, each accumulates a band of tile rows from the same gathered theta rows (the
-// second and third gather hit the L1), the last one also accumulates b_u.  Slots only (no fusion).
-template <int F, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(192) void k_hermitian_bands(const int32_t *__restrict__ task_row,
-                                                         const int32_t *__restrict__ task_chunk, int64_t task0,
-                                                         int chunk, const PtrT *__restrict__ ptr,
-                                                         const int32_t *__restrict__ idx, const float *__restrict__ val,
-                                                         const void *__restrict__ Theta, float *__restrict__ slots) {
-    constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
-    constexpr int B1 = (NT * 9 + 8) / 16, B2 = (NT * 13 + 8) / 16;   // bands [0,B1) [B1,B2) [B2,NT): equal tile counts
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t t = blockIdx.x;
-    const int row = task_row[task0 + t];
-    const int ch = task_chunk[task0 + t];
-    const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
-    const int64_t s0 = rs + (int64_t)ch * chunk;
-    const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);
-    float *out = slots + t * (int64_t)SLOT;
-    float b[NT];
-    auto band = [&](auto r0tag, auto r1tag, auto btag) {
-        constexpr int R0 = decltype(r0tag)::value, R1 = decltype(r1tag)::value;
-        constexpr bool WB = decltype(btag)::value;
-        constexpr int N = tiles_range(R0, R1), BASE = R0 * (R0 + 1) / 2;
-        v4f acc[N];
-#pragma unroll
-        for (int q = 0; q < N; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
-        accumulate_tiles<F, false, kDepthSlots, WIDE, ET, R0, R1, WB>(idx, val, Theta, uniform64(s0), len, acc, b);
-#pragma unroll
-        for (int q = 0; q < N; ++q)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) out[((BASE + q) * 4 + r) * 64 + lane] = acc[q][r];
-        if constexpr (WB) {
-#pragma unroll
-            for (int q = 0; q < NT; ++q)
-                if (lane < 16) out[NTILES * 256 + 16 * q + lane] = b[q];
-        }
-    };
-    using std::integral_constant;
-    if (wave == 0) band(integral_constant<int, 0>{}, integral_constant<int, B1>{}, std::false_type{});
-    else if (wave == 1) band(integral_constant<int, B1>{}, integral_constant<int, B2>{}, std::false_type{});
-    else band(integral_constant<int, B2>{}, integral_constant<int, NT>{}, std::true_type{});
-}
-
-// Algorithm 1 for systems too large for one wavefront: one thread per (virtual) row keeps that row of
-// the symmetric A_u in registers, p is broadcast through LDS.  A_u comes from the row's (reduced) slot.
-template <int NW>
-__device__ __forceinline__ float block_sum(float v, float *red) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float s = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
-    return s;
-}
-
-template <int F, typename PtrT>
-__global__ __launch_bounds__(F) void k_solve_cg_rows(const int32_t *__restrict__ perm,
-                                                     const int32_t *__restrict__ task_off, int64_t pos0, int64_t task0,
-                                                     const PtrT *__restrict__ ptr, const float *__restrict__ slots,
-                                                     float lambda, int fs, float eps, float *__restrict__ Xout,
-                                                     int *__restrict__ status) {
-    static_assert(F % 64 == 0, "one thread per row, whole wavefronts");
-    constexpr int NTILES = tiles_tri(F), SLOT = slot_floats(F), NW = F / 64;
-    __shared__ __attribute__((aligned(16))) float ps[F];
-    __shared__ float red[NW];
-    const int64_t pos = pos0 + blockIdx.x;
-    const int row = perm[pos];
-    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
-    float *xg = Xout + (int64_t)row * F;
-    const int vi = threadIdx.x;                       // virtual row of this thread
-    const int ft = feature_of(F, vi >> 4, vi & 15);   // its feature (every virtual index is one: F % 16 == 0)
-    if (n_u == 0) {
-        xg[ft] = 0.f;
-        return;
-    }
-    const float *slot = slots + (int64_t)(task_off[pos] - task0) * SLOT;
-    // row vi of the symmetric matrix from the lower-triangle tiles: element (hi, lo) of tile (hi/16, lo/16)
-    float a[F];
-    const int R = vi >> 4, lr = vi & 15;
-#pragma unroll
-    for (int vj = 0; vj < F; ++vj) {
-        const int C = vj >> 4, lc = vj & 15;
-        int off;
-        if (C < R || (C == R && lc <= lr))   // (vi, vj) is stored: tile (R, C), row lr, column lc
-            off = ((R * (R + 1) / 2 + C) * 4 + (lr & 3)) * 64 + (lr >> 2) * 16 + lc;
-        else                                 // mirror: tile (C, R), row lc, column lr
-            off = ((C * (C + 1) / 2 + R) * 4 + (lc & 3)) * 64 + (lc >> 2) * 16 + lr;
-        a[vj] = slot[off];
-    }
-    const float reg = lambda * (float)n_u;
-    float x = xg[ft];
-    ps[vi] = x;
-    __syncthreads();
-    auto matvec = [&]() {
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-        for (int j = 0; j < F; j += 4) {
-            const float4 p4 = *reinterpret_cast<const float4 *>(&ps[j]);
-            s0 = fmaf(a[j], p4.x, s0);
-            s1 = fmaf(a[j + 1], p4.y, s1);
-            s2 = fmaf(a[j + 2], p4.z, s2);
-            s3 = fmaf(a[j + 3], p4.w, s3);
-        }
-        return fmaf(reg, ps[vi], (s0 + s1) + (s2 + s3));   // + lambda*n_u on the diagonal
-    };
-    const float bi = slot[NTILES * 256 + vi];
-    float r = bi - matvec();
-    float p = r;
-    float rs_old = block_sum<NW>(r * r, red);
-    if (rs_old > 0.f) {
-        for (int it = 0; it < fs; ++it) {
-            __syncthreads();
-            ps[vi] = p;
-            __syncthreads();
-            const float ap = matvec();
-            const float pap = block_sum<NW>(p * ap, red);
-            if (!(pap > 0.f) || !isfinite(pap)) break;
-            const float alpha = rs_old / pap;
-            x = fmaf(alpha, p, x);
-            r = fmaf(-alpha, ap, r);
-            const float rs_new = block_sum<NW>(r * r, red);
-            if (sqrtf(rs_new) < eps) break;
-            p = fmaf(rs_new / rs_old, p, r);
-            rs_old = rs_new;
-        }
-    }
-    xg[ft] = x;
-    if (!isfinite(x)) atomicOr(status, kStatusNonFinite);
-}
-
 #define ALS_FOR_F(CALL)                       \
     switch (f) {                              \
         case 16: return CALL(16);             \
@@ -202,25 +67,6 @@ __global__ __launch_bounds__(F) void k_solve_cg_rows(const int32_t *__restrict__
         case 128: return CALL(128);           \
         default: return hipErrorInvalidValue; \
     }
-
-template <int F, typename PtrT>
-static hipError_t herm_bands_f(bool wide, int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
-                               int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
-                               const float *val, const void *Theta, float *slots) {
-    if (ntasks <= 0) return hipSuccess;
-    const dim3 grid((unsigned)ntasks), block(192);
-    const PtrT *p = (const PtrT *)ptr;
-#define LAUNCH(W, E)                                                                                             \
-    hipLaunchKernelGGL((k_hermitian_bands<F, PtrT, W, E>), grid, block, 0, st, task_row, task_chunk, task0, chunk, p, \
-                       idx, val, Theta, slots)
-    if (wide) {
-        if (et == ALS_F32) LAUNCH(true, ALS_F32); else if (et == ALS_BF16) LAUNCH(true, ALS_BF16); else LAUNCH(true, ALS_F16);
-    } else {
-        if (et == ALS_F32) LAUNCH(false, ALS_F32); else if (et == ALS_BF16) LAUNCH(false, ALS_BF16); else LAUNCH(false, ALS_F16);
-    }
-#undef LAUNCH
-    return hipGetLastError();
-}
 
 // dispatch on the run-time switches that are template parameters of the kernels
 template <int F, typename PtrT, bool WIDE, bool S16>
@@ -255,13 +101,9 @@ static hipError_t herm_f(bool wide, int et, bool s16, hipStream_t st, const int3
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots) {
-    if (f == 256) {
-        if (s16) return hipErrorInvalidValue;
-        return ptr64 ? herm_bands_f<256, int64_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx,
-                                                  val, Theta, slots)
-                     : herm_bands_f<256, int32_t>(wide, et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx,
-                                                  val, Theta, slots);
-    }
+    if (f == 256)
+        return launch_hermitian_wide(ptr64, wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val,
+                                     Theta, slots);
 #define CALL(FF)                                                                                                      \
     (ptr64 ? herm_f<FF, int64_t>(wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, \
                                  slots)                                                                               \
@@ -307,6 +149,11 @@ static hipError_t herm_cg_f(bool wide, int et, int solver, hipStream_t st, const
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
+    if (f == 256) {
+        if (solver != ALS_SOLVER_CG) return hipErrorInvalidValue;
+        return launch_hermitian_cg_wide(ptr64, wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,
+                                        status);
+    }
 #define CALL(FF)                                                                                                     \
     (ptr64 ? herm_cg_f<FF, int64_t>(wide, et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,   \
                                     Xout, status)                                                                    \
@@ -359,23 +206,9 @@ static hipError_t reduce_f(bool s16, hipStream_t st, const int32_t *task_off, in
     return hipGetLastError();
 }
 
-hipError_t launch_solve_cg_rows(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
-                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
-                                float lambda, int fs, float eps, float *Xout, int *status) {
-    if (f != 256) return hipErrorInvalidValue;
-    if (npos <= 0) return hipSuccess;
-    if (ptr64)
-        hipLaunchKernelGGL((k_solve_cg_rows<256, int64_t>), dim3((unsigned)npos), dim3(256), 0, st, perm, task_off,
-                           pos0, task0, (const int64_t *)ptr, slots, lambda, fs, eps, Xout, status);
-    else
-        hipLaunchKernelGGL((k_solve_cg_rows<256, int32_t>), dim3((unsigned)npos), dim3(256), 0, st, perm, task_off,
-                           pos0, task0, (const int32_t *)ptr, slots, lambda, fs, eps, Xout, status);
-    return hipGetLastError();
-}
-
 hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
                                int64_t task0, float *slots) {
-    if (f == 256) return s16 ? hipErrorInvalidValue : reduce_f<256>(false, st, task_off, pos0, npos, task0, slots);
+    if (f == 256) return reduce_f<256>(s16, st, task_off, pos0, npos, task0, slots);
 #define CALL(FF) reduce_f<FF>(s16, st, task_off, pos0, npos, task0, slots)
     ALS_FOR_F(CALL)
 #undef CALL

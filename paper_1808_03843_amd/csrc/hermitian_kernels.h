@@ -48,7 +48,7 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE, ET, 0, tiles_1d(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+    accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
                                                                                  alpha);
 
     float *out = slots + t * (int64_t)SLOT;
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     float b[NT];
-    accumulate_tiles<F, true, kDepthFused, WIDE, ET, 0, tiles_1d(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+    accumulate_tiles<F, true, kDepthFused, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
                                                                                 alpha);
     add_diagonal<F>(acc, MODE == kImplicit ? lambda : lambda * (float)len);
     float x[NT];

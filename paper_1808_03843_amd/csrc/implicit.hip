@@ -24,7 +24,7 @@ __global__ __launch_bounds__(64) void k_gram(const float *__restrict__ G, int64_
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE, ALS_F32, 0, NT, false, kGram>(nullptr, nullptr, G, uniform64(s0), len,
+    accumulate_tiles<F, false, kDepthSlots, WIDE, ALS_F32, rows_all(F), false, kGram>(nullptr, nullptr, G, uniform64(s0), len,
                                                                                 acc, b);
     float *out = slots + (int64_t)blockIdx.x * SLOT;
 #pragma unroll

@@ -183,22 +183,22 @@ __device__ __forceinline__ float widen_hi(uint32_t w) {   // high 16 bits of w
     else return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16));
 }
 
-// R0, R1: the wavefront accumulates the tile rows [R0, R1) only (acc[R(R+1)/2 + C - R0(R0+1)/2]); the
-// default is the whole triangle.  WANT_B: also produce b_u (one wavefront of a work item does).
+// ROWS: the wavefront accumulates the tile rows of this set only (acc[tiles_below(ROWS, R) + C]); the
+// default is the whole triangle.  WANT_B: also produce b_u, for the tile rows of the set.
 // MODE: kExplicit as described above.  kImplicit (Section 5.6): the entry (u, v) enters A_u with weight
 // w = alpha * max(r_uv, 0) (both operands are scaled by sqrt(w)) and b_u with weight 1 + w if r_uv > 0.
 // kGram: the "entries" are the rows s0 .. s0+len-1 of Theta themselves (idx and val are not read),
 // unit weights, for Theta^T Theta.
-template <int F, bool IN_VGPR, int D, bool WIDE, int ET, int R0 = 0, int R1 = tiles_1d(F), bool WANT_B = true,
+template <int F, bool IN_VGPR, int D, bool WIDE, int ET, uint32_t ROWS = rows_all(F), bool WANT_B = true,
           int MODE = kExplicit>
 __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                  const void *__restrict__ Theta, int64_t s0, int len,
-                                                 v4f (&acc)[tiles_range(R0, R1)], float (&b)[tiles_1d(F)],
+                                                 v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)],
                                                  float alpha = 0.f) {
-    static_assert((R0 == 0 && R1 == tiles_1d(F)) || (F % 16) == 0, "partial tile ranges need f to be a multiple of 16");
+    static_assert(ROWS == rows_all(F) || (F % 16) == 0, "partial sets of tile rows need f to be a multiple of 16");
+    static_assert(ROWS != 0 && (ROWS & ~rows_all(F)) == 0, "tile rows out of range");
     static_assert(MODE == kExplicit || !TileGeom<F>::RIT, "the rating lane carries the plain rating only");
     static_assert(MODE != kGram || !WANT_B, "a Gram matrix has no right-hand side");
-    constexpr int ABASE = R0 * (R0 + 1) / 2;
     constexpr int NT = TileGeom<F>::NT, NB = D + 1;
     constexpr bool RIT = TileGeom<F>::RIT, STRIP = TileGeom<F>::STRIP;
     constexpr int RI = TileGeom<F>::RI;
@@ -376,7 +376,8 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             g[NT - 1] = (i == RI) ? r : g[NT - 1];
         } else if constexpr (WANT_B) {
 #pragma unroll
-            for (int q = 0; q < NT; ++q) bacc[q] = fmaf(r, g[q], bacc[q]);
+            for (int q = 0; q < NT; ++q)
+                if ((ROWS >> q) & 1u) bacc[q] = fmaf(r, g[q], bacc[q]);
         }
         if constexpr (MASKED || ET != ALS_F32 || (RIT && NT < 3) || MODE == kImplicit) {
             // An operand written by the vector ALU must not be read by an MFMA in the next few cycles,
@@ -387,9 +388,11 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             for (int q = 1; q < NT; ++q) asm volatile("" : "+v"(g[q]), "+v"(g[0]));
         }
 #pragma unroll
-        for (int R = R0; R < (STRIP ? R1 - 1 : R1); ++R)
+        for (int R = 0; R < (STRIP ? NT - 1 : NT); ++R)
+            if ((ROWS >> R) & 1u) {
 #pragma unroll
-            for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[R * (R + 1) / 2 + C - ABASE], g[R], g[C]);
+                for (int C = 0; C <= R; ++C) mfma_16x16x4<IN_VGPR>(acc[tiles_below(ROWS, R) + C], g[R], g[C]);
+            }
         if constexpr (STRIP) {
 #pragma unroll
             for (int C = 0; C < NT; ++C) mfma_4x4x1<IN_VGPR>(acc[(NT - 1) * NT / 2 + C], g[NT - 1], g[C]);
@@ -435,7 +438,7 @@ __device__ __forceinline__ void accumulate_tiles(const int32_t *__restrict__ idx
             }
     } else if constexpr (WANT_B) {
 #pragma unroll
-        for (int q = 0; q < NT; ++q) b[q] = colsum4(bacc[q]);
+        for (int q = 0; q < NT; ++q) b[q] = ((ROWS >> q) & 1u) ? colsum4(bacc[q]) : 0.f;
     }
     if constexpr (STRIP) {
         // lane (c, kq) register r holds the share of lane row kq in element (row r, column c) of the strip:

@@ -118,7 +118,7 @@ def test_sixteen_bit_factor_inputs(P, mat, f, name, chunk):
         assert err.max() <= tol, (name, int(err.argmax()) + 1, float(err.max()))
 
 
-@pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
+@pytest.mark.parametrize("f", [16, 32, 64, 100, 128, 256])
 def test_bf16_slots_and_rmse_kernels(P, mat, f):
     degrees, ptr, idx, val = mat
     Theta = W.random_factors(N_COLS, f, seed=37 + f, scale=0.3)
