@@ -74,7 +74,8 @@ typedef struct als_config {
                              all arithmetic and the written factor stay fp32                            */
     int32_t herm_dtype;   /* storage type of A_u where it is materialised, i.e. the partial Gram matrices of
                              rows split over several work items (Section 4.2): ALS_F32, or ALS_BF16 with
-                             ALS_SOLVER_CG (fp32 accumulate, bf16 in memory)                             */
+                             ALS_SOLVER_CG (fp32 accumulate, bf16 in memory; at f = 256 only together
+                             with factor_dtype == ALS_F32)                                               */
     int32_t device;       /* HIP device ordinal                                                          */
     void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */
     int32_t chunk;        /* stored entries per work item, a power of two in [64, 2^20]; longer rows are

@@ -22,9 +22,23 @@ namespace als {
 #define ALS_WIDE_WAVES 8
 #endif
 constexpr int kWideWaves = ALS_WIDE_WAVES;   // 8: one pair of tile rows per wavefront; 4: two pairs
-// 17 tiles per wavefront fit the vector registers beside the operand ring (two wavefronts per SIMD);
-// 34 go to the accumulation registers
+// 17 tiles per wavefront fit the vector registers beside the operand ring; 34 go to the accumulation
+// registers (measured: the same speed)
 constexpr bool kWideInVgpr = kWideWaves >= 8;
+// The fused kernel is built for four wavefronts per SIMD, i.e. two workgroups per CU, so that Algorithm 1 of
+// one row (no MFMA work) overlaps the accumulation of another; that leaves registers for a gather pipeline
+// of depth 1 only (depth 3 with one workgroup per CU was 19 % slower).
+#ifndef ALS_DEPTH_WIDE
+#define ALS_DEPTH_WIDE (ALS_WIDE_WAVES >= 8 ? 1 : 3)
+#endif
+#ifndef ALS_WIDE_EU
+#define ALS_WIDE_EU (ALS_WIDE_WAVES >= 8 ? 4 : 1)
+#endif
+#ifndef ALS_DEPTH_WIDE_SLOTS
+#define ALS_DEPTH_WIDE_SLOTS 3
+#endif
+constexpr int kDepthWide = ALS_DEPTH_WIDE;   // gather pipeline depth of the fused kernel
+constexpr int kDepthWideSlots = ALS_DEPTH_WIDE_SLOTS;
 
 // fn(integral_constant<w>) for the (wavefront-uniform) w == wave
 template <int NW, typename Fn>
@@ -41,7 +55,7 @@ struct WideShared {
     float yrow[F];                              // tile * p_C sums, complete
     float ylow[NW * 4][YS];                     // tile^T * p_R sums per wavefront and lane row
     float bs[F];                                // b_u (fused kernel)
-    float red[NW];
+    float red[2][NW];                           // wavefront sums of a dot product, two buffers in turn
 };
 
 // the share of one wavefront in A*p (p in sh.ps); ROWS = its tile rows
@@ -76,16 +90,19 @@ __device__ __forceinline__ void matvec_part(const v4f (&acc)[tiles_in(ROWS)], Wi
     for (int C = 0; C < RMAX; ++C) sh.ylow[wave * 4 + g][16 * C + c] = lower[C];   // columns >= RMAX stay zero
 }
 
+// Sum over the workgroup, the same value in every thread.  One barrier: consecutive calls alternate between
+// two buffers, and a thread can only be two calls ahead of another one after a barrier in between.
 template <int NW>
-__device__ __forceinline__ float wide_sum(float v, float *red) {
+__device__ __forceinline__ float wide_sum(float v, float (&red)[2][NW], int &turn) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    float *buf = red[turn];
+    turn ^= 1;
+    if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
     __syncthreads();
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) s += red[w];
+    for (int w = 0; w < NW; ++w) s += buf[w];
     return s;
 }
 
@@ -102,8 +119,10 @@ __device__ __forceinline__ void cg_wide(const v4f (&acc)[tiles_tri(F) / NW], Wid
     const bool own = tid < F;   // owner of element tid of the vectors (virtual order)
     const int ft = feature_of(F, (tid >> 4) & (NT - 1), tid & 15);
     for (int k = tid; k < NW * 4 * WideShared<F, NW>::YS; k += 64 * NW) (&sh.ylow[0][0])[k] = 0.f;
+    int turn = 0;
+    // (no barrier in front: the last readers of ps passed the third barrier of the previous product, and the
+    // owners' reads of yrow / ylow are followed by the barrier of a dot product before the next product)
     auto matvec = [&](float v) -> float {
-        __syncthreads();   // the readers of the previous product are done
         if (own) sh.ps[tid] = v;
         __syncthreads();
         for_wave<NW>(wave, [&](auto wt) {
@@ -123,16 +142,16 @@ __device__ __forceinline__ void cg_wide(const v4f (&acc)[tiles_tri(F) / NW], Wid
     const float ax = matvec(x);
     float r = own ? bsrc[tid] - ax : 0.f;
     float p = r;
-    float rs_old = wide_sum<NW>(r * r, sh.red);
+    float rs_old = wide_sum<NW>(r * r, sh.red, turn);
     if (rs_old > 0.f) {
         for (int it = 0; it < fs; ++it) {
             const float ap = matvec(p);
-            const float pap = wide_sum<NW>(p * ap, sh.red);
+            const float pap = wide_sum<NW>(p * ap, sh.red, turn);
             if (!(pap > 0.f) || !isfinite(pap)) break;
             const float alpha = rs_old / pap;
             x = fmaf(alpha, p, x);
             r = fmaf(-alpha, ap, r);
-            const float rs_new = wide_sum<NW>(r * r, sh.red);
+            const float rs_new = wide_sum<NW>(r * r, sh.red, turn);
             if (sqrtf(rs_new) < eps) break;
             p = fmaf(rs_new / rs_old, p, r);
             rs_old = rs_new;
@@ -167,7 +186,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 #pragma unroll
         for (int q = 0; q < tiles_in(ROWS); ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
         float b[NT];
-        accumulate_tiles<F, kWideInVgpr, kDepthSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if ((ROWS >> R) & 1u) {
@@ -190,7 +209,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 }
 
 template <int F, int NW, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(64 * NW) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_WIDE_EU, ALS_WIDE_EU))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                 const PtrT *__restrict__ ptr,
                                                                 const int32_t *__restrict__ idx,
                                                                 const float *__restrict__ val,
@@ -215,7 +234,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_cg_wide(const int32_t *__
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         static_assert(tiles_in(ROWS) == NTW);
         float b[NT];
-        accumulate_tiles<F, kWideInVgpr, kDepthFused, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) sh.bs[16 * R + lane] = b[R];
