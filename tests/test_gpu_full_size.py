@@ -33,21 +33,29 @@ def _rel(g, o):
     return np.linalg.norm(g.astype(np.float64) - o, axis=1) / np.maximum(np.linalg.norm(o, axis=1), 1e-30)
 
 
-def _check_side(P, w, a, G_host, label, rng, n_random, n_heavy):
-    """One half-sweep on matrix `a` gathering G_host: CG(6) from a seeded warm start, then exact."""
+def _check_side(P, w, a, G_host, label, rng, n_random, n_heavy, fs=6, cg_dtype=None):
+    """One half-sweep on matrix `a` gathering G_host: CG(fs) from a seeded warm start, then exact.
+    cg_dtype: the CG pass gathers a 16-bit copy of the factor (the oracle gets the same rounded values)."""
     rows = _sample_rows(a, rng, n_random, n_heavy, 8)
     sptr, sidx, sval = _sub_csr(a, rows)
     sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
     G = _dev(G_host)
     warm = W.random_factors(a.nrows, w.f, seed=77, scale=0.05)
     # approximate mode: same Algorithm 1 in double on the sampled rows
-    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6)
+    if cg_dtype is None:
+        als, Gc, Gc_host = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=fs), G, G_host
+    else:
+        tdt, code = {"bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[cg_dtype]
+        Gc = G.to(tdt)
+        Gc_host = Gc.to(torch.float32).cpu().numpy()
+        als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=fs, factor_dtype=code)
     out = _dev(warm.copy())
-    als.update_rows(sp, G, w.lam, out)
+    als.update_rows(sp, Gc, w.lam, out)
     als.synchronize()
-    ref = oracle.update_rows_cg(sptr, sidx, sval, G_host, w.lam, warm[rows], fs=6)
+    ref = oracle.update_rows_cg(sptr, sidx, sval, Gc_host, w.lam, warm[rows], fs=fs)
     err_cg = _rel(out[torch.from_numpy(rows).cuda()].cpu().numpy(), ref)
     als.close()
+    del Gc
     # exact mode: per-row 1e-4
     als = P.Als(w.f, solver=P.SOLVER_CHOLESKY)
     out = torch.zeros((a.nrows, w.f), device="cuda:0")
@@ -59,7 +67,8 @@ def _check_side(P, w, a, G_host, label, rng, n_random, n_heavy):
     assert torch.isfinite(out).all().item()
     als.close()
     print(f"{w.name} {label}: {len(rows)} sampled rows (max degree {int((sptr[1:] - sptr[:-1]).max())}); "
-          f"CG(6) vs double Algorithm 1 max {err_cg.max():.2e}; exact max {err_ex.max():.2e}", flush=True)
+          f"CG({fs}{', ' + cg_dtype if cg_dtype else ''}) vs double Algorithm 1 max {err_cg.max():.2e}; "
+          f"exact max {err_ex.max():.2e}", flush=True)
     assert err_cg.max() <= 2e-3
     assert err_ex.max() <= 1e-4
 
@@ -185,3 +194,22 @@ def test_mid_full_size():
 def test_large_square_full_size():
     import paper_1808_03843_amd as P
     _full_size(P, W.LARGE_SQUARE, n_random=200, n_heavy=4)
+
+
+def test_mid_shape_factor_width_sweep_full_size():
+    """The factor-width configurations (Mid shape, f = 32, 64, 128, 256) at full size in the default launch
+    configuration: sampled rows and columns, CG(4/6/8) with 16-bit factor inputs against the double-precision
+    Algorithm 1 on the same rounded inputs, and the exact solver with fp32 inputs against the oracle."""
+    import paper_1808_03843_amd as P
+    a = W.generate(W.MID)
+    cptr, cidx, cval = oracle.csr_to_csc(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    c = W.CSR(a.ncols, a.nrows, cptr, cidx, cval)
+    for f, fs, dt in [(32, 4, "bf16"), (64, 6, "f16"), (128, 8, "bf16"), (256, 6, "bf16")]:
+        w = W.MID.with_f(f)
+        rng = np.random.default_rng(w.seed + f)
+        _, T0 = W.init_factors(w)
+        _check_side(P, w, a, T0, "rows", rng, 150, 3, fs=fs, cg_dtype=dt)
+        Xs = W.random_factors(w.m, f, seed=21, scale=0.3)
+        _check_side(P, w, c, Xs, "cols", rng, 24, 2, fs=fs, cg_dtype=dt)
+        del Xs
+        torch.cuda.empty_cache()
