@@ -104,7 +104,7 @@ hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStre
 hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                                  const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                                  const int32_t *idx, const float *val, const void *Theta, float *slots);
-hipError_t launch_hermitian_cg_wide(bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+hipError_t launch_hermitian_cg_wide(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
                                     int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                     const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
 hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,

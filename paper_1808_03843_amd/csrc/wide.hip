@@ -37,8 +37,9 @@ constexpr bool kWideInVgpr = kWideWaves >= 8;
 #ifndef ALS_DEPTH_WIDE_SLOTS
 #define ALS_DEPTH_WIDE_SLOTS 3
 #endif
-constexpr int kDepthWide = ALS_DEPTH_WIDE;   // gather pipeline depth of the fused kernel
 constexpr int kDepthWideSlots = ALS_DEPTH_WIDE_SLOTS;
+// wavefronts per SIMD the fused kernel is compiled for, and its gather pipeline depth
+constexpr int kWideEu = ALS_WIDE_EU, kDepthWide = ALS_DEPTH_WIDE;
 
 // fn(integral_constant<w>) for the (wavefront-uniform) w == wave
 template <int NW, typename Fn>
@@ -209,7 +210,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 }
 
 template <int F, int NW, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_WIDE_EU, ALS_WIDE_EU))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(kWideEu, kWideEu))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                 const PtrT *__restrict__ ptr,
                                                                 const int32_t *__restrict__ idx,
                                                                 const float *__restrict__ val,
@@ -309,7 +310,7 @@ hipError_t herm_wide_e(int et, bool s16, hipStream_t st, const int32_t *task_row
     return hipGetLastError();
 }
 
-template <typename PtrT, bool WIDE>
+template <int WF, int NW, typename PtrT, bool WIDE>
 hipError_t herm_cg_wide_e(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
                           const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
                           float *Xout, int *status) {
@@ -336,13 +337,14 @@ hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStr
 #undef ARGS
 }
 
-hipError_t launch_hermitian_cg_wide(bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+hipError_t launch_hermitian_cg_wide(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
                                     int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                     const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
 #define ARGS et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status
-    if (ptr64) return wide ? herm_cg_wide_e<int64_t, true>(ARGS) : herm_cg_wide_e<int64_t, false>(ARGS);
-    return wide ? herm_cg_wide_e<int32_t, true>(ARGS) : herm_cg_wide_e<int32_t, false>(ARGS);
+    if (f != 256) return hipErrorInvalidValue;
+    if (ptr64) return wide ? herm_cg_wide_e<WF, NW, int64_t, true>(ARGS) : herm_cg_wide_e<WF, NW, int64_t, false>(ARGS);
+    return wide ? herm_cg_wide_e<WF, NW, int32_t, true>(ARGS) : herm_cg_wide_e<WF, NW, int32_t, false>(ARGS);
 #undef ARGS
 }
 
