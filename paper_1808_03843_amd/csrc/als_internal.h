@@ -107,6 +107,13 @@ hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStr
 hipError_t launch_hermitian_cg_wide(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
                                     int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                     const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
+// exact solver at f = 256 (wide_ldlt.hip): fused with the build for short rows, from fp32 slots otherwise
+hipError_t launch_hermitian_ldlt_wide(bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+                                      int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                      const void *Theta, float lambda, float *Xout, int *status);
+hipError_t launch_solve_ldlt_wide(bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                  int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                  float lambda, float *Xout, int *status);
 hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);

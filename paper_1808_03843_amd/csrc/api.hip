@@ -225,7 +225,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const bool one_wave = single_wave_f(f);   // larger f: the wavefronts of a workgroup share a system
     // rows shorter than a chunk are built and solved without leaving the registers; the exact solver does
     // that for fp32 factor inputs and systems that fit one wavefront
-    const bool tiles_solver = cg || (one_wave && ctx->cfg.factor_dtype == ALS_F32);
+    const bool tiles_solver = cg || !one_wave || ctx->cfg.factor_dtype == ALS_F32;
     const int64_t slot_rows = tiles_solver ? p->split_pos : m;
     int64_t pos = 0;
     while (pos < slot_rows) {
@@ -258,6 +258,9 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                 HIP_TRY(ctx, launch_solve_wave_implicit(f, p64, ctx->cfg.solver, ctx->stream, p->perm, p->task_off, pos,
                                                         end - pos, task0, a->ptr, ctx->slots, lambda, gram,
                                                         ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+            else if (!cg && !one_wave)
+                HIP_TRY(ctx, launch_solve_ldlt_wide(p64, ctx->stream, p->perm, p->task_off, pos, end - pos, task0, a->ptr,
+                                                    ctx->slots, lambda, Out, ctx->status));
             else if (cg && !one_wave)
                 HIP_TRY(ctx, launch_solve_cg_wide(p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,

@@ -149,7 +149,8 @@ static hipError_t herm_cg_f(bool wide, int et, int solver, hipStream_t st, const
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
-    if (f == 256 && solver != ALS_SOLVER_CG) return hipErrorInvalidValue;
+    if (f == 256 && solver != ALS_SOLVER_CG)
+        return launch_hermitian_ldlt_wide(ptr64, wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, Xout, status);
     if (f == 256)
         return launch_hermitian_cg_wide(f, ptr64, wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps,
                                         Xout, status);

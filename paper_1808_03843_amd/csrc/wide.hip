@@ -12,42 +12,9 @@
 // LDS; every wavefront multiplies its tiles (tile * p_C summed over the 16 lanes of a row gives rows of
 // block R; tile^T * p_R gives per-lane-row partial sums of block C) and leaves the results in LDS, where
 // the owner of each element adds them up in a fixed order.  Dot products: wavefront sums, then LDS.
-#include <utility>
-
-#include "hermitian_kernels.h"
+#include "wide.h"
 
 namespace als {
-
-#ifndef ALS_WIDE_WAVES
-#define ALS_WIDE_WAVES 8
-#endif
-constexpr int kWideWaves = ALS_WIDE_WAVES;   // 8: one pair of tile rows per wavefront; 4: two pairs
-// 17 tiles per wavefront fit the vector registers beside the operand ring; 34 go to the accumulation
-// registers (measured: the same speed)
-constexpr bool kWideInVgpr = kWideWaves >= 8;
-// The fused kernel is built for four wavefronts per SIMD, i.e. two workgroups per CU, so that Algorithm 1 of
-// one row (no MFMA work) overlaps the accumulation of another; that leaves registers for a gather pipeline
-// of depth 1 only (depth 3 with one workgroup per CU was 19 % slower).
-#ifndef ALS_DEPTH_WIDE
-#define ALS_DEPTH_WIDE (ALS_WIDE_WAVES >= 8 ? 1 : 3)
-#endif
-#ifndef ALS_WIDE_EU
-#define ALS_WIDE_EU (ALS_WIDE_WAVES >= 8 ? 4 : 1)
-#endif
-#ifndef ALS_DEPTH_WIDE_SLOTS
-#define ALS_DEPTH_WIDE_SLOTS 3
-#endif
-constexpr int kDepthWideSlots = ALS_DEPTH_WIDE_SLOTS;
-// wavefronts per SIMD the fused kernel is compiled for, and its gather pipeline depth
-constexpr int kWideEu = ALS_WIDE_EU, kDepthWide = ALS_DEPTH_WIDE;
-
-// fn(integral_constant<w>) for the (wavefront-uniform) w == wave
-template <int NW, typename Fn>
-__device__ __forceinline__ void for_wave(int wave, Fn &&fn) {
-    [&]<int... w>(std::integer_sequence<int, w...>) {
-        ((wave == w ? fn(std::integral_constant<int, w>{}) : void()), ...);
-    }(std::make_integer_sequence<int, NW>{});
-}
 
 template <int F, int NW>
 struct WideShared {
