@@ -129,206 +129,6 @@ __global__ __launch_bounds__(ldlt_threads(F)) void k_solve_ldlt(const int32_t *_
         }
 }
 
-// ---- exact solve for f too large for one wavefront's registers (f = 256) ------------------------
-// Blocked LDL^T of one system per workgroup of 4 wavefronts, the matrix resident in LDS in the slot's own
-// tile layout (tile q at 256q floats, element (row lr, column lc) at (lr%4)*64 + (lr/4)*16 + lc), so that
-// loading is a straight copy and a tile is read into the MFMA accumulator layout without bank conflicts.
-// Per panel (tile column K):
-//   (a) wavefront 0, one lane per row, factors the 16x16 diagonal tile in registers (shuffles only) and
-//       forward-substitutes the panel's part of b;
-//   (b) one thread per row below the panel: x = a L_KK^-T (16-step substitution against the unit factor
-//       kept in LDS), written back as L*d and, row-major, into P; b of that row is updated;
-//   (c) the trailing tiles (R, C), K < C <= R, are shared out over the four wavefronts and updated on the
-//       matrix cores: tile -= P_R (P_C D_K^-1)^T, four 16x16x4 MFMAs per tile.
-// Back substitution panel by panel from the last: inside the diagonal tile by wavefront 0, then one thread
-// per column to the left.  Column j ends as L[:,j]*d_j; b holds z, then x.
-__device__ __forceinline__ float rdlane(float v, int l) {   // l: wave-uniform
-    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
-}
-
-template <int F>
-__device__ __forceinline__ int tile_addr(int R, int C, int lr, int lc) {
-    return (R * (R + 1) / 2 + C) * 256 + (lr & 3) * 64 + (lr >> 2) * 16 + lc;
-}
-
-template <int F, typename PtrT>
-__global__ __launch_bounds__(256) void k_solve_ldlt_blocked(const int32_t *__restrict__ perm,
-                                                            const int32_t *__restrict__ task_off, int64_t pos0,
-                                                            int64_t task0, const PtrT *__restrict__ ptr,
-                                                            const float *__restrict__ slots, float lambda,
-                                                            float *__restrict__ Xout, int *__restrict__ status) {
-    static_assert(F % 16 == 0 && F / 16 <= 16, "whole tiles, one thread per row");
-    constexpr int NT = F / 16, NTILES = tiles_tri(F), SLOT = slot_floats(F);
-    __shared__ float As[NTILES * 256];
-    __shared__ float bs[F];          // b, then z, then x (virtual coordinates)
-    __shared__ float dall[F];        // 1/d_j
-    __shared__ float P[F * 17];      // rows below the current panel: (L d)(row, 0..15 of the panel)
-    __shared__ float Lkk[16 * 17];   // unit lower factor of the current diagonal tile
-    __shared__ float zk[16];         // z_j / d_j of the current panel
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t pos = pos0 + blockIdx.x;
-    const int row = perm[pos];
-    const int64_t n_u = (int64_t)ptr[row + 1] - (int64_t)ptr[row];
-    float *xg = Xout + (int64_t)row * F;
-    if (n_u == 0) {
-        for (int q = tid; q < F; q += 256) xg[q] = 0.f;
-        return;
-    }
-    // the slots of a split row have been summed into its first slot by k_reduce_slots
-    const float *slot = slots + (int64_t)(task_off[pos] - (int)task0) * SLOT;
-    for (int o = 4 * tid; o < NTILES * 256; o += 1024)
-        *reinterpret_cast<float4 *>(As + o) = *reinterpret_cast<const float4 *>(slot + o);
-    if (tid < F) bs[tid] = slot[NTILES * 256 + tid];
-    __syncthreads();
-    if (tid < F) As[tile_addr<F>(tid >> 4, tid >> 4, tid & 15, tid & 15)] += lambda * (float)n_u;
-    bool bad = false;
-
-    for (int K = 0; K < NT; ++K) {
-        __syncthreads();
-        if (wave == 0) {   // (a): lanes 0..15 each hold a row of the diagonal tile; the other lanes idle along
-            const int i = lane & 15;
-            float a[16];
-#pragma unroll
-            for (int c = 0; c < 16; ++c) a[c] = As[tile_addr<F>(K, K, i, c)];
-            float z = bs[16 * K + i];
-            float dinv_mine = 0.f;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                // values of other rows come through scalar registers (v_readlane): no LDS round trip in the
-                // 16 dependent steps
-                float d = rdlane(a[j], j);
-                if (!(d > 0.f)) { bad = true; d = 1.f; }
-                const float inv = 1.f / d;
-                if (i == j) dinv_mine = inv;
-                const float l = a[j] * inv;            // L[i][j]
-                const float zj = rdlane(z, j);
-                if (i > j) z = fmaf(-l, zj, z);
-#pragma unroll
-                for (int c = j + 1; c < 16; ++c) {
-                    const float t = rdlane(a[j], c);   // (L d)[c][j]
-                    if (i >= c) a[c] = fmaf(-l, t, a[c]);
-                }
-                if (lane < 16) Lkk[i * 17 + j] = (i > j) ? l : (i == j ? 1.f : 0.f);
-            }
-            if (lane < 16) {
-#pragma unroll
-                for (int c = 0; c < 16; ++c)
-                    if (c <= i) As[tile_addr<F>(K, K, i, c)] = a[c];
-                bs[16 * K + i] = z;
-                dall[16 * K + i] = dinv_mine;
-                zk[i] = z * dinv_mine;
-            }
-        }
-        __syncthreads();
-        {   // (b): thread per row below the panel
-            const int v = 16 * (K + 1) + tid;
-            if (v < F) {
-                const int R = v >> 4, lr = v & 15;
-                float x[16];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) x[k] = As[tile_addr<F>(R, K, lr, k)];
-#pragma unroll
-                for (int k = 0; k < 15; ++k)      // x_k is final here; independent updates of the x_j behind it
-#pragma unroll
-                    for (int j = k + 1; j < 16; ++j) x[j] = fmaf(-x[k], Lkk[j * 17 + k], x[j]);
-                float zr = bs[v];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    As[tile_addr<F>(R, K, lr, k)] = x[k];
-                    P[v * 17 + k] = x[k];
-                    zr = fmaf(-x[k], zk[k], zr);
-                }
-                bs[v] = zr;
-            }
-        }
-        __syncthreads();
-        if (K < NT - 1) {   // (c): trailing update on the matrix cores
-            const int c16 = lane & 15, g = lane >> 4;
-            float dk[4];
-#pragma unroll
-            for (int s4 = 0; s4 < 4; ++s4) dk[s4] = -dall[16 * K + 4 * g + s4];
-            const int nrem = NT - 1 - K;               // tile rows / columns left: K+1 .. NT-1
-            const int ntr = nrem * (nrem + 1) / 2;
-            // two tiles per iteration, so that the LDS reads of one overlap the MFMAs of the other
-            for (int t0 = 2 * wave; t0 < ntr; t0 += 8) {
-                float *tile[2];
-                v4f acc[2];
-                float T[2][4], V[2][4];
-                const int nb = (t0 + 1 < ntr) ? 2 : 1;
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int t = (u < nb) ? t0 + u : t0;
-                    int rr = 0;
-                    while ((rr + 1) * (rr + 2) / 2 <= t) ++rr;
-                    const int R = K + 1 + rr, C = K + 1 + (t - rr * (rr + 1) / 2);
-                    tile[u] = As + (R * (R + 1) / 2 + C) * 256;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[u][r] = tile[u][r * 64 + lane];
-#pragma unroll
-                    for (int s4 = 0; s4 < 4; ++s4) {
-                        T[u][s4] = P[(16 * R + c16) * 17 + 4 * g + s4];
-                        V[u][s4] = P[(16 * C + c16) * 17 + 4 * g + s4] * dk[s4];
-                    }
-                }
-                // registers written by the vector ALU or by LDS reads must have landed before an MFMA reads them
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-                    asm volatile("" : "+v"(acc[u]), "+v"(T[u][0]), "+v"(T[u][1]), "+v"(T[u][2]), "+v"(T[u][3]),
-                                 "+v"(V[u][0]), "+v"(V[u][1]), "+v"(V[u][2]), "+v"(V[u][3]));
-                asm volatile("s_nop 7" ::: "memory");
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4)
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) mfma_16x16x4_ordered<true>(acc[u], T[u][s4], V[u][s4]);
-                mfma_drain();
-#pragma unroll
-                for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(acc[u]));
-#pragma unroll
-                for (int r = 0; r < 4; ++r) tile[0][r * 64 + lane] = acc[0][r];
-                if (nb > 1) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) tile[1][r * 64 + lane] = acc[1][r];
-                }
-            }
-        }
-    }
-    // back substitution: x_j = z_j / d_j, then z_i -= (L d)[j][i] x_j for i < j
-    for (int K = NT - 1; K >= 0; --K) {
-        __syncthreads();
-        if (wave == 0) {
-            const int i = lane & 15;
-            float z = bs[16 * K + i];
-            const float dinv = dall[16 * K + i];
-            float xi = 0.f;
-            float lrow[16];   // column i of the diagonal tile: (L d)[j][i]
-#pragma unroll
-            for (int j = 0; j < 16; ++j) lrow[j] = As[tile_addr<F>(K, K, j, i)];
-#pragma unroll
-            for (int j = 15; j >= 0; --j) {
-                const float xj = rdlane(z * dinv, j);
-                if (i == j) xi = xj;
-                if (i < j) z = fmaf(-lrow[j], xj, z);
-            }
-            if (lane < 16) bs[16 * K + i] = xi;
-        }
-        __syncthreads();
-        if (tid < 16 * K) {   // columns to the left of the panel
-            const int C = tid >> 4, c = tid & 15;
-            float z = bs[tid];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) z = fmaf(-As[tile_addr<F>(K, C, j, c)], bs[16 * K + j], z);
-            bs[tid] = z;
-        }
-    }
-    __syncthreads();
-    if (__syncthreads_or(bad ? 1 : 0) && tid == 0) atomicOr(status, kStatusBadPivot);
-    if (tid < F) {
-        const float xv = bs[tid];
-        xg[feature_of(F, tid >> 4, tid & 15)] = xv;
-        if (!isfinite(xv)) atomicOr(status, kStatusNonFinite);
-    }
-}
-
 // ---- dense export (tests, breakdown runs) -----------------------------------------------------
 template <int F, typename PtrT>
 __global__ __launch_bounds__(256) void k_export_dense(const int32_t *__restrict__ perm,
@@ -361,13 +161,13 @@ static hipError_t solve_f(int solver, int cg_iters, float cg_eps, hipStream_t st
     dim3 grid((unsigned)npos);
     (void)cg_iters; (void)cg_eps;
     if (solver != ALS_SOLVER_CHOLESKY) return hipErrorInvalidValue;
-    if constexpr (F > 128)
-        hipLaunchKernelGGL((k_solve_ldlt_blocked<F, PtrT>), grid, dim3(256), 0, st, perm, task_off, pos0, task0,
-                           (const PtrT *)ptr, slots, lambda, Xout, status);
-    else
+    if constexpr (F > 128) {   // wider systems are solved on the register tiles of a workgroup (wide_ldlt.hip)
+        return hipErrorInvalidValue;
+    } else {
         hipLaunchKernelGGL((k_solve_ldlt<F, PtrT>), grid, dim3(ldlt_threads(F)), 0, st, perm, task_off, pos0, task0,
                            (const PtrT *)ptr, slots, lambda, Xout, status);
-    return hipGetLastError();
+        return hipGetLastError();
+    }
 }
 
 #define ALS_DISPATCH_F(CALL)                       \

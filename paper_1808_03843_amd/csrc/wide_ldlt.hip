@@ -20,6 +20,13 @@
 
 namespace als {
 
+// wavefronts that share a system here (the slot layout does not depend on it), and where their tiles live
+#ifndef ALS_LDLT_WAVES
+#define ALS_LDLT_WAVES 8
+#endif
+constexpr int kLdltWaves = ALS_LDLT_WAVES;
+constexpr bool kLdltInVgpr = kLdltWaves >= 8;   // 17 tiles in vector registers, 34 in accumulation registers
+
 template <int N, typename Fn>
 __device__ __forceinline__ void static_for(Fn &&fn) {
     [&]<int... k>(std::integer_sequence<int, k...>) ALS_INLINE { (fn(std::integral_constant<int, k>{}), ...); }(
@@ -38,15 +45,28 @@ struct LdltShared {
     float D[TS];          // staging of the diagonal tile
     __attribute__((aligned(16))) float bs[F];   // b, then y (L y = b), then x; virtual order
     float dinv[F];        // 1 / d_j
-    float zk[16];         // y_j / d_j of the current panel
+    float zk[2][16];      // y_j / d_j of the current panel (even / odd K: the next panel's is written early)
 };
 
 // MFMA on operands that were written by LDS reads or the vector ALU a moment ago
+template <bool IN_VGPR>
 __device__ __forceinline__ void mfma4(v4f &acc, float (&a)[4], float (&b)[4]) {
-    asm volatile("s_nop 7" : "+v"(acc), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]), "+v"(b[2]),
-                 "+v"(b[3]));
+    if constexpr (IN_VGPR) {
+        asm volatile("s_nop 7" : "+v"(acc), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]),
+                     "+v"(b[2]), "+v"(b[3]));
 #pragma unroll
-    for (int s = 0; s < 4; ++s) mfma_16x16x4_ordered<true>(acc, a[s], b[s]);
+        for (int s = 0; s < 4; ++s) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a[s]), "v"(b[s]));
+    } else {
+        asm volatile("s_nop 7" : "+a"(acc), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]),
+                     "+v"(b[2]), "+v"(b[3]));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a[s]), "v"(b[s]));
+    }
+}
+template <bool IN_VGPR>
+__device__ __forceinline__ void tie(v4f &acc) {
+    if constexpr (IN_VGPR) asm volatile("" : "+v"(acc));
+    else asm volatile("" : "+a"(acc));
 }
 
 // The part of wavefront W.  acc: its tiles (regulariser already on the diagonal).  Returns false if a pivot was
@@ -60,55 +80,70 @@ __device__ __forceinline__ bool ldlt_wide_wave(v4f (&acc)[tiles_tri(F) / NW], Ld
     const int c = lane & 15, g = lane >> 4;   // accumulator layout: register r = element (4g + r, c);
                                               // operand layout: register s = element (c, 4g + s)
     bool bad = false;
-    static_for<NT>([&](auto kt) ALS_INLINE {
+    // (A) for panel K, run by the wavefront that owns the diagonal tile
+    auto factor_diagonal = [&](auto kt) ALS_INLINE {
         constexpr int K = decltype(kt)::value;
-        // ---- (A) diagonal tile
-        if constexpr ((ROWS >> K) & 1u) {
-            constexpr int q = tiles_below(ROWS, K) + K;
+        constexpr int q = tiles_below(ROWS, K) + K;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) sh.D[(4 * g + r) * 17 + c] = acc[q][r];
-            const int i = c;   // lane i (of every lane row) holds row i
-            float a[16];
+        for (int r = 0; r < 4; ++r) sh.D[(4 * g + r) * 17 + c] = acc[q][r];
+        const int i = c;   // lane i (of every lane row) holds row i
+        float a[16];
 #pragma unroll
-            for (int cc = 0; cc < 16; ++cc) a[cc] = sh.D[i * 17 + cc];
-            float z = sh.bs[16 * K + i];
-            float dinv_mine = 0.f;
-            float lcol[16];   // lcol[j] = L[i][j]
-            static_for<16>([&](auto jt) ALS_INLINE {
+        for (int cc = 0; cc < 16; ++cc) a[cc] = sh.D[i * 17 + cc];
+        float z = sh.bs[16 * K + i];
+        float dinv_mine = 0.f;
+        float lcol[16];   // lcol[j] = L[i][j] (lanes i > j; the other lanes hold values nobody reads)
+        static_for<16>([&](auto jt) ALS_INLINE {
+            constexpr int j = decltype(jt)::value;
+            float d = read_lane(a[j], j);
+            if (!(d > 0.f)) { bad = true; d = 1.f; }
+            float inv = __builtin_amdgcn_rcpf(d);
+            inv = fmaf(fmaf(-d, inv, 1.f), inv, inv);   // one Newton step: as accurate as a division here
+            if (i == j) dinv_mine = inv;
+            const float l = a[j] * inv;
+            lcol[j] = l;
+            const float zj = read_lane(z, j);
+            if (i > j) z = fmaf(-l, zj, z);
+            // rank-1 update of the columns behind j; rows above the diagonal pick up values that are never
+            // read (row i only ever uses its columns <= i), which saves a select per element
+            static_for<15 - j>([&](auto ct) ALS_INLINE {
+                constexpr int cc = j + 1 + decltype(ct)::value;
+                a[cc] = fmaf(-l, read_lane(a[j], cc), a[cc]);   // (L d)[cc][j] comes from lane cc
+            });
+            __builtin_amdgcn_sched_barrier(0);   // keeps the broadcasts of later steps out of scalar registers
+        });
+        // W = L^-1, lane i holds column i: W[r][i] = [r == i] - sum_{j < r} L[r][j] W[j][i]
+        float w[16];
+        static_for<16>([&](auto rt) ALS_INLINE {
+            constexpr int r = decltype(rt)::value;
+            float s = (r == i) ? 1.f : 0.f;
+            static_for<r>([&](auto jt) ALS_INLINE {
                 constexpr int j = decltype(jt)::value;
-                float d = read_lane(a[j], j);
-                if (!(d > 0.f)) { bad = true; d = 1.f; }
-                const float inv = 1.f / d;
-                if (i == j) dinv_mine = inv;
-                const float l = a[j] * inv;
-                lcol[j] = l;
-                const float zj = read_lane(z, j);
-                if (i > j) z = fmaf(-l, zj, z);
-                static_for<15 - j>([&](auto ct) ALS_INLINE {
-                    constexpr int cc = j + 1 + decltype(ct)::value;
-                    const float t = read_lane(a[j], cc);   // (L d)[cc][j]
-                    if (i >= cc) a[cc] = fmaf(-l, t, a[cc]);
-                });
+                s = fmaf(-read_lane(lcol[j], r), w[j], s);
             });
-            // W = L^-1, lane i holds column i: W[r][i] = [r == i] - sum_{j < r} L[r][j] W[j][i]
-            float w[16];
-            static_for<16>([&](auto rt) ALS_INLINE {
-                constexpr int r = decltype(rt)::value;
-                float s = (r == i) ? 1.f : 0.f;
-                static_for<r>([&](auto jt) ALS_INLINE {
-                    constexpr int j = decltype(jt)::value;
-                    s = fmaf(-read_lane(lcol[j], r), w[j], s);
-                });
-                w[r] = s;
-                if (lane < 16) sh.Winv[K][r * 17 + i] = s;
-            });
-            if (lane < 16) {
-                sh.bs[16 * K + i] = z;
-                sh.dinv[16 * K + i] = dinv_mine;
-                sh.zk[i] = z * dinv_mine;
-            }
+            w[r] = s;
+            if (lane < 16) sh.Winv[K][r * 17 + i] = s;
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (lane < 16) {
+            sh.bs[16 * K + i] = z;
+            sh.dinv[16 * K + i] = dinv_mine;
+            sh.zk[K & 1][i] = z * dinv_mine;
         }
-        __syncthreads();
+    };
+    // (C) for one tile: tile(R, C) -= X_RK D_K^-1 X_CK^T
+    auto update_tile = [&](auto rt, auto ct, float (&aop)[4], const float (&ndk)[4]) ALS_INLINE {
+        constexpr int R = decltype(rt)::value, C = decltype(ct)::value;
+        float bop[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) bop[s] = sh.P[C][c * 17 + 4 * g + s] * ndk[s];
+        mfma4<kLdltInVgpr>(acc[tiles_below(ROWS, R) + C], aop, bop);
+    };
+
+    if constexpr (ROWS & 1u) factor_diagonal(std::integral_constant<int, 0>{});
+    __syncthreads();
+    static_for<NT - 1>([&](auto kt) ALS_INLINE {
+        constexpr int K = decltype(kt)::value;
         // ---- (B) panel tiles of this wavefront
         static_for<NT>([&](auto rt) ALS_INLINE {
             constexpr int R = decltype(rt)::value;
@@ -124,7 +159,7 @@ __device__ __forceinline__ bool ldlt_wide_wave(v4f (&acc)[tiles_tri(F) / NW], Ld
                     wop[s] = sh.Winv[K][c * 17 + 4 * g + s];
                 }
                 v4f x = (v4f){0.f, 0.f, 0.f, 0.f};
-                mfma4(x, aop, wop);
+                mfma4<true>(x, aop, wop);
                 mfma_drain();
                 asm volatile("" : "+v"(x));
                 acc[q] = x;
@@ -133,38 +168,52 @@ __device__ __forceinline__ bool ldlt_wide_wave(v4f (&acc)[tiles_tri(F) / NW], Ld
             }
         });
         __syncthreads();
-        // ---- (C) trailing tiles of this wavefront, and b of the rows below the panel
-        if constexpr (K < NT - 1) {
-            float ndk[4];
+        // ---- (C) trailing tiles of this wavefront and b of the rows below the panel.  The owner of the next
+        // diagonal tile updates that tile first and factors it right away, while the others are still busy
+        // with their trailing tiles: the serial step (A) leaves the critical path where there is trailing work.
+        float ndk[4];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) ndk[s] = -sh.dinv[16 * K + 4 * g + s];
-            static_for<NT>([&](auto rt) ALS_INLINE {
-                constexpr int R = decltype(rt)::value;
-                if constexpr (((ROWS >> R) & 1u) && R > K) {
-                    float aop[4];
+        for (int s = 0; s < 4; ++s) ndk[s] = -sh.dinv[16 * K + 4 * g + s];
+        constexpr bool NEXT_OWNER = ((ROWS >> (K + 1)) & 1u) != 0;
+        if constexpr (NEXT_OWNER) {
+            constexpr int R = K + 1;
+            float aop[4];
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) aop[s] = sh.P[R][c * 17 + 4 * g + s];
-                    static_for<R - K>([&](auto ct) ALS_INLINE {
-                        constexpr int C = K + 1 + decltype(ct)::value;
-                        float bop[4];
-#pragma unroll
-                        for (int s = 0; s < 4; ++s) bop[s] = sh.P[C][c * 17 + 4 * g + s] * ndk[s];
-                        mfma4(acc[tiles_below(ROWS, R) + C], aop, bop);
-                    });
-                }
-            });
-            if (tid < F && tid >= 16 * (K + 1)) {
-                const float *xr = &sh.P[tid >> 4][(tid & 15) * 17];
-                float z = sh.bs[tid];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) z = fmaf(-xr[k], sh.zk[k], z);
-                sh.bs[tid] = z;
-            }
+            for (int s = 0; s < 4; ++s) aop[s] = sh.P[R][c * 17 + 4 * g + s];
+            update_tile(std::integral_constant<int, R>{}, std::integral_constant<int, R>{}, aop, ndk);
             mfma_drain();
+            tie<kLdltInVgpr>(acc[tiles_below(ROWS, R) + R]);
+            {   // b of the rows of the next panel (lane i = row i; every lane row computes the same)
+                const float *xr = &sh.P[R][c * 17];
+                float z = sh.bs[16 * R + c];
 #pragma unroll
-            for (int t = 0; t < tiles_tri(F) / NW; ++t) asm volatile("" : "+v"(acc[t]));
-            __syncthreads();
+                for (int k = 0; k < 16; ++k) z = fmaf(-xr[k], sh.zk[K & 1][k], z);
+                if (lane < 16) sh.bs[16 * R + c] = z;
+            }
+            factor_diagonal(std::integral_constant<int, R>{});
         }
+        static_for<NT>([&](auto rt) ALS_INLINE {
+            constexpr int R = decltype(rt)::value;
+            if constexpr (((ROWS >> R) & 1u) && R > K + 1) {
+                float aop[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) aop[s] = sh.P[R][c * 17 + 4 * g + s];
+                static_for<R - K>([&](auto ct) ALS_INLINE {
+                    update_tile(rt, std::integral_constant<int, K + 1 + decltype(ct)::value>{}, aop, ndk);
+                });
+            }
+        });
+        if (tid < F && tid >= 16 * (K + 2)) {
+            const float *xr = &sh.P[tid >> 4][(tid & 15) * 17];
+            float z = sh.bs[tid];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) z = fmaf(-xr[k], sh.zk[K & 1][k], z);
+            sh.bs[tid] = z;
+        }
+        mfma_drain();
+#pragma unroll
+        for (int t = 0; t < tiles_tri(F) / NW; ++t) tie<kLdltInVgpr>(acc[t]);
+        __syncthreads();
     });
     // ---- back substitution
     static_for<NT>([&](auto it) ALS_INLINE {
@@ -202,7 +251,7 @@ __device__ __forceinline__ bool ldlt_wide_wave(v4f (&acc)[tiles_tri(F) / NW], Ld
 template <int F, int NW>
 __device__ __forceinline__ void ldlt_wide(v4f (&acc)[tiles_tri(F) / NW], LdltShared<F> &sh, const float *bsrc,
                                           float reg, float *__restrict__ xg, int *status) {
-    static_assert(F % 16 == 0 && F <= 64 * NW && kWideInVgpr, "tiles in vector registers, one thread per element");
+    static_assert(F % 16 == 0 && F <= 64 * NW, "one thread per element");
     constexpr int NT = tiles_1d(F);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -232,8 +281,14 @@ __device__ __forceinline__ void ldlt_wide(v4f (&acc)[tiles_tri(F) / NW], LdltSha
 }
 
 // short rows: built and solved without leaving the registers of the workgroup
+#ifndef ALS_LDLT_WIDE_EU
+#define ALS_LDLT_WIDE_EU 2
+#endif
+#ifndef ALS_LDLT_WIDE_DEPTH
+#define ALS_LDLT_WIDE_DEPTH 3
+#endif
 template <int F, int NW, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(64 * NW) void k_hermitian_ldlt_wide(const int32_t *__restrict__ perm, int64_t pos0,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDLT_WIDE_EU, ALS_LDLT_WIDE_EU))) void k_hermitian_ldlt_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                   const PtrT *__restrict__ ptr,
                                                                   const int32_t *__restrict__ idx,
                                                                   const float *__restrict__ val,
@@ -257,7 +312,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_ldlt_wide(const int32_t *
     for_wave<NW>(wave, [&](auto wt) ALS_INLINE {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         float b[NT];
-        accumulate_tiles<F, true, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) bsrc[16 * R + lane] = b[R];
@@ -268,7 +323,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_ldlt_wide(const int32_t *
 
 // rows whose A_u sits in a (reduced) fp32 slot
 template <int F, int NW, typename PtrT>
-__global__ __launch_bounds__(64 * NW) void k_solve_ldlt_wide(const int32_t *__restrict__ perm,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDLT_WIDE_EU, ALS_LDLT_WIDE_EU))) void k_solve_ldlt_wide(const int32_t *__restrict__ perm,
                                                               const int32_t *__restrict__ task_off, int64_t pos0,
                                                               int64_t task0, const PtrT *__restrict__ ptr,
                                                               const float *__restrict__ slots, float lambda,
@@ -304,7 +359,7 @@ __global__ __launch_bounds__(64 * NW) void k_solve_ldlt_wide(const int32_t *__re
 
 // ---- launchers ---------------------------------------------------------------------------------------
 namespace {
-constexpr int WF = 256, NW = kWideWaves;
+constexpr int WF = 256, NW = kLdltWaves;
 
 template <typename PtrT, bool WIDE>
 hipError_t herm_ldlt_wide_e(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
