@@ -11,6 +11,14 @@
 using namespace als;
 
 namespace {
+
+// 32-bit byte offsets into the gathered factor matrix are enough below 4 GiB; row pitches that are not a power
+// of two are multiplied with a 24-bit instruction, which also limits the row index
+bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
+    const uint64_t pitch = (uint64_t)f * esize;
+    if ((uint64_t)rows * pitch >= (1ull << 32)) return true;
+    return (pitch & (pitch - 1)) != 0 && rows >= (1 << 24);
+}
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
 
@@ -174,7 +182,7 @@ int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
     const int nslots = (int)((n + per - 1) / per);
     int rc = ensure_slots(ctx, nslots, false);
     if (rc != ALS_OK) return rc;
-    const bool wide = (uint64_t)n * (uint64_t)f * 4u >= (1ull << 32);
+    const bool wide = needs_wide_offsets(n, f, 4);
     Timed t(ctx, ALS_K_GRAM);
     HIP_TRY(ctx, launch_gram(f, wide, ctx->stream, G, n, (int)per, nslots, ctx->slots, ctx->gram[which]));
     return ALS_OK;
@@ -219,7 +227,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
     const bool s16 = ctx->cfg.herm_dtype == ALS_BF16;
     const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
-    const bool wide = (uint64_t)a->ncols * (uint64_t)f * esize >= (1ull << 32);
+    const bool wide = needs_wide_offsets(a->ncols, f, esize);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
     const bool one_wave = single_wave_f(f);   // larger f: the wavefronts of a workgroup share a system
@@ -462,7 +470,7 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     // a throw-away plan over the row range, in natural order
     const bool p64 = csr->ptr_is_64 != 0;
     const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
-    const bool wide = (uint64_t)csr->ncols * (uint64_t)f * esize >= (1ull << 32);
+    const bool wide = needs_wide_offsets(csr->ncols, f, esize);
     int32_t *perm = nullptr, *task_off = nullptr, *task_row = nullptr, *task_chunk = nullptr;
     auto cleanup = [&]() { hipFree(perm); hipFree(task_off); hipFree(task_row); hipFree(task_chunk); };
     hipError_t e;

@@ -161,9 +161,11 @@ __device__ __forceinline__ uint32_t row_offset(uint32_t c, uint32_t add) {
     if constexpr ((M >> tz) == 1) {
         return lshl_add<tz>(c, add);
     } else if constexpr ((M >> tz) == 25) {
-        const uint32_t c3 = lshl_add<1>(c, c);      // 3c
-        const uint32_t c25 = lshl_add<3>(c3, c);    // 25c
-        return lshl_add<tz>(c25, add);
+        // one full-rate 24-bit multiply-add: the row index is below 2^24 whenever the matrix is below 4 GiB
+        // (M >= 200 bytes per row)
+        uint32_t d;
+        asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(d) : "v"(c), "v"(M), "v"(add));
+        return d;
     } else {
         return c * M + add;
     }

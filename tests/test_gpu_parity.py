@@ -262,6 +262,36 @@ def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P, f, n):
     torch.cuda.empty_cache()
 
 
+def test_f100_16_bit_factor_beyond_2_pow_24_rows(P):
+    """f = 100 with 16-bit factor inputs: the row pitch (200 bytes) is not a power of two and the 32-bit row
+    offsets are formed with a 24-bit multiply, so a matrix of 2^24 rows or more (still below 4 GiB) must take
+    the 64-bit path.  Zero matrix except for the touched rows; the oracle sees a compact copy."""
+    f, n = 100, 17_000_000
+    assert n >= 2 ** 24 and n * f * 2 < 2 ** 32
+    rng = np.random.default_rng(6)
+    degrees = [2, 50, 900]
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(np.unique(np.concatenate([rng.choice(n - 2 ** 24, d - 1, replace=False) + 2 ** 24 - 1,
+                                                            [n - 1]]))[:d]) for d in degrees]).astype(np.int32)
+    assert len(idx) == ptr[-1] and idx.max() == n - 1
+    val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+    used = np.unique(idx)
+    rows16 = torch.from_numpy(W.random_factors(len(used), f, seed=9, scale=0.5)).to(torch.bfloat16)
+    Theta = torch.zeros((n, f), device="cuda:0", dtype=torch.bfloat16)
+    Theta[torch.from_numpy(used.astype(np.int64)).cuda()] = rows16.cuda()
+    remap = np.searchsorted(used, idx).astype(np.int32)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+    als = P.Als(f, solver=P.SOLVER_CG, cg_iters=f, chunk=256, factor_dtype=P.BF16)
+    X = torch.zeros((len(degrees), f), device="cuda:0")
+    als.update_rows(sp, Theta, 0.5, X)
+    als.synchronize()
+    ref = oracle.update_rows(ptr, remap, val, rows16.to(torch.float32).numpy(), 0.5)
+    assert _row_rel_err(X.cpu().numpy(), ref).max() <= 1e-3   # f iterations of Algorithm 1: exact up to fp32 rounding
+    als.close()
+    del Theta
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name", ["bf16", "f16"])
 def test_reduced_precision_factor_inputs(P, name):
     """16-bit factor inputs, fp32 accumulate: same arithmetic as fp32 on the rounded values, and the
