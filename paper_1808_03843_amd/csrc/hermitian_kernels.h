@@ -2,6 +2,7 @@
 // (instantiated by hermitian.hip for eq. (2)/(3) and by implicit.hip for Section 5.6).
 #pragma once
 #include "tiles.h"
+#include "tiles16.h"
 
 namespace als {
 
@@ -19,6 +20,13 @@ constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
 constexpr int fused_waves(int F) { return F <= 100 ? ALS_FUSED_WAVES : 2; }
 
+// 16-bit factor inputs go to the 16-bit matrix cores where the width allows it (tiles16.h)
+constexpr bool use_tiles16(int F, int ET, int MODE) { return ET != ALS_F32 && MODE == kExplicit && has_tiles16(F); }
+
+// least number of wavefronts per SIMD k_hermitian is compiled for: with 16-bit inputs at f = 100 the allocator
+// otherwise lands just above the register budget of two and then spreads out to one
+constexpr int slot_waves(int F, int ET) { return (F == 100 && ET != ALS_F32) ? 2 : 1; }
+
 // a value that is the same in every lane, moved to scalar registers
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
@@ -29,7 +37,7 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 // MODE: kExplicit (eq. (2)) or kImplicit (Section 5.6: every stored entry weighted by alpha * r_uv, b_u by
 // 1 + alpha * r_uv; the dense Theta^T Theta term is added by the solver kernels).
 template <int F, typename PtrT, bool WIDE, int ET, bool S16, int MODE>
-__global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ task_row,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F, ET)))) void k_hermitian(const int32_t *__restrict__ task_row,
                                                   const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                   const float *__restrict__ val, const void *__restrict__ Theta,
@@ -48,8 +56,11 @@ __global__ __launch_bounds__(64) void k_hermitian(const int32_t *__restrict__ ta
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
-                                                                                 alpha);
+    if constexpr (use_tiles16(F, ET, MODE))
+        accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    else
+        accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc,
+                                                                                   b, alpha);
 
     float *out = slots + t * (int64_t)SLOT;
     if constexpr (S16) {
@@ -135,8 +146,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     float b[NT];
-    accumulate_tiles<F, true, kDepthFused, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
-                                                                                alpha);
+    if constexpr (use_tiles16(F, ET, MODE))
+        accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    else
+        accumulate_tiles<F, true, kDepthFused, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                  alpha);
     add_diagonal<F>(acc, MODE == kImplicit ? lambda : lambda * (float)len);
     float x[NT];
     if constexpr (SOLVER == ALS_SOLVER_CG) {

@@ -1,0 +1,237 @@
+// get_hermitian + get_bias (Section 2 step (i), Section 3) on the 16-bit matrix cores, for factor matrices
+// that are gathered as bf16 or fp16 (the reduced-precision route of Section 4.2 taken one step further: the
+// products of two 16-bit values are exact in fp32, so v_mfma_f32_16x16x32_{bf16,f16} with its fp32
+// accumulators computes the same sums as widening the inputs and multiplying in fp32 -- at 16 times the rate).
+//
+// One step consumes 32 stored entries: lane (i, kq) supplies, for every tile, the value of "its" feature in
+// the 8 entries 8kq .. 8kq+7 of the step, packed in pairs (4 registers per tile).  The contraction index of the
+// MFMA is the entry, and since the A and B operands of tile (R, C) are the same registers g[R], g[C], any
+// assignment of entries to (lane row, register half) is as good as any other.
+// Rows are gathered entry by entry with the widest loads the feature permutation allows (4, 2, 1 features per
+// lane, the same lane -> feature map as the fp32 path, so that everything downstream is unchanged) and
+// repacked with one byte-permute per register.
+//
+// b_u rides along: f is not a multiple of 16 here, and three spare lanes of the last tile (features f, f+1,
+// f+2 of the padded row) carry the rating split into three 16-bit parts (hi + mid + lo = the fp32 rating up to
+// 2^-24, or better), so rows f .. f+2 of the accumulated matrix add up to b_u; they and the remaining padding
+// are zeroed at the end.
+#pragma once
+#include "tiles.h"
+
+namespace als {
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+// widths for which this route exists: three spare lanes in the last tile
+constexpr bool has_tiles16(int F) { return (F % 16) >= 1 && (F % 16) <= 13; }
+
+template <int ET>
+__device__ __forceinline__ void mfma_16x16x32(v4f &acc, const v4u &a, const v4u &b) {
+    if constexpr (ET == ALS_BF16)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), acc, 0, 0, 0);
+    else
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), acc, 0, 0, 0);
+}
+
+// two fp32 values -> their leading 16-bit parts packed (first in the low half), and the remainders
+template <int ET>
+__device__ __forceinline__ uint32_t split16(float &x0, float &x1) {
+    if constexpr (ET == ALS_BF16) {   // truncation: the remainder is exact
+        const uint32_t u0 = __builtin_bit_cast(uint32_t, x0), u1 = __builtin_bit_cast(uint32_t, x1);
+        const uint32_t packed = __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+        x0 -= bits_to_float(u0 & 0xffff0000u);
+        x1 -= bits_to_float(u1 & 0xffff0000u);
+        return packed;
+    } else {
+        typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+        const v2h h = __builtin_bit_cast(v2h, __builtin_amdgcn_cvt_pkrtz(x0, x1));
+        x0 -= (float)h.x;
+        x1 -= (float)h.y;
+        return __builtin_bit_cast(uint32_t, h);
+    }
+}
+
+// Same contract as accumulate_tiles<F, ..., rows_all(F), WANT_B, kExplicit>: acc += lower-triangle tiles of
+// sum theta theta^T over the entries [s0, s0+len), b = sum r theta in column layout, padding zeroed.
+template <int F, bool WIDE, int ET, bool WANT_B>
+__device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                   const void *__restrict__ Theta, int64_t s0, int len,
+                                                   v4f (&acc)[tiles_tri(F)], float (&b)[tiles_1d(F)]) {
+    static_assert(ET == ALS_BF16 || ET == ALS_F16);
+    static_assert(has_tiles16(F));
+    constexpr int NT = tiles_1d(F), RI = F % 16;
+    constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
+    constexpr int base1 = 64 * N4 + 32 * N2;
+    constexpr int RWE = 2 * N4 + N2 + N1;   // raw registers per gathered row
+    constexpr int LB = (NT - 1) * NT / 2;
+    const int lane = threadIdx.x & 63, i = lane & 15, kq = lane >> 4;
+    const int32_t *__restrict__ ib = idx + s0;
+    const float *__restrict__ vb = val + s0;
+    constexpr int kRsrcFlags = 0x00020000;
+    const __amdgpu_buffer_rsrc_t ids_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ib), 0, 4 * len, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vb), 0, 4 * len, kRsrcFlags);
+    const int nsteps = (len + 31) >> 5;
+    // lane offsets of the three kinds of loads inside a row (bytes)
+    const uint32_t lane_a = 8u * (uint32_t)i;
+    const uint32_t lane_b = 128u * N4 + 4u * (uint32_t)i;
+    const uint32_t lane_c = 2u * (uint32_t)(base1 + i);
+    const uint32_t lane_l = 2u * (uint32_t)((base1 + 16 * (N1 - 1) + i < F) ? base1 + 16 * (N1 - 1) + i : F - 1);
+    const uint32_t eoff0 = 32u * (uint32_t)kq;   // this lane's 8 entries inside a step (bytes into idx / val)
+
+    struct Ids { v4u lo, hi; };
+    auto load_ids = [&](int t) -> Ids {
+        const uint32_t o = eoff0 + 128u * (uint32_t)t;
+        Ids r;
+        r.lo = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(ids_rsrc, o, 0, 0));
+        r.hi = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(ids_rsrc, o + 16u, 0, 0));
+        return r;
+    };
+    auto load_ratings = [&](int t, float (&r)[8]) {
+        const uint32_t o = eoff0 + 128u * (uint32_t)t;
+        const v4u a = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o, 0, 0));
+        const v4u c = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o + 16u, 0, 0));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            r[j] = bits_to_float(a[j]);
+            r[4 + j] = bits_to_float(c[j]);
+        }
+    };
+    // one gathered row -> raw registers (entries beyond the work item read row 0 and are masked later)
+    const uint32_t d_ab = lane_b - lane_a, d_ac = lane_c - lane_a, d_al = lane_l - lane_a;
+    auto gather = [&](uint32_t c, uint32_t (&w)[RWE]) {
+        const char *p;
+        uint32_t oa;
+        if constexpr (WIDE) {
+            p = reinterpret_cast<const char *>(Theta) + (int64_t)c * (2 * F);
+            oa = lane_a;
+        } else {
+            p = reinterpret_cast<const char *>(Theta);
+            oa = row_offset<(uint32_t)(2 * F)>(c, lane_a);
+        }
+#pragma unroll
+        for (int q = 0; q < N4; ++q) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(p + oa + 128 * q);
+            w[2 * q] = v.x;
+            w[2 * q + 1] = v.y;
+        }
+        if constexpr (N2 > 0) w[2 * N4] = *reinterpret_cast<const uint32_t *>(p + (oa + d_ab));
+        if constexpr (N1 > 1) {
+            const uint32_t oc = oa + d_ac;
+#pragma unroll
+            for (int k = 0; k < N1 - 1; ++k) w[2 * N4 + N2 + k] = *reinterpret_cast<const unsigned short *>(p + oc + 32 * k);
+        }
+        if constexpr (N1 > 0) w[2 * N4 + N2 + N1 - 1] = *reinterpret_cast<const unsigned short *>(p + (oa + d_al));
+    };
+    auto gather8 = [&](const Ids &ids, uint32_t (&raw)[8][RWE]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            gather(ids.lo[j], raw[j]);
+            gather(ids.hi[j], raw[4 + j]);
+        }
+    };
+    // operands of one step: g[T] = 4 registers, pair m holds (entry 2m in the low half, entry 2m+1 in the high half)
+    constexpr uint32_t kLoLo = 0x05040100u, kHiHi = 0x07060302u;
+    auto pack = [&](const uint32_t (&raw)[8][RWE], v4u (&g)[NT]) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t (&e0)[RWE] = raw[2 * m];
+            const uint32_t (&e1)[RWE] = raw[2 * m + 1];
+#pragma unroll
+            for (int q = 0; q < N4; ++q) {
+                g[4 * q][m] = __builtin_amdgcn_perm(e1[2 * q], e0[2 * q], kLoLo);
+                g[4 * q + 1][m] = __builtin_amdgcn_perm(e1[2 * q], e0[2 * q], kHiHi);
+                g[4 * q + 2][m] = __builtin_amdgcn_perm(e1[2 * q + 1], e0[2 * q + 1], kLoLo);
+                g[4 * q + 3][m] = __builtin_amdgcn_perm(e1[2 * q + 1], e0[2 * q + 1], kHiHi);
+            }
+            if constexpr (N2 > 0) {
+                g[4 * N4][m] = __builtin_amdgcn_perm(e1[2 * N4], e0[2 * N4], kLoLo);
+                g[4 * N4 + 1][m] = __builtin_amdgcn_perm(e1[2 * N4], e0[2 * N4], kHiHi);
+            }
+#pragma unroll
+            for (int k = 0; k < N1; ++k)
+                g[4 * N4 + 2 * N2 + k][m] = __builtin_amdgcn_perm(e1[2 * N4 + N2 + k], e0[2 * N4 + N2 + k], kLoLo);
+        }
+    };
+
+    const bool is_r0 = i == RI, is_r1 = i == RI + 1, is_r2 = i == RI + 2, is_feat = i < RI;
+    auto compute = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t) {
+        v4u g[NT];
+        pack(raw, g);
+        // the rating lanes of the last tile
+        if constexpr (WANT_B) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t p0 = split16<ET>(r[2 * m], r[2 * m + 1]);
+                const uint32_t p1 = split16<ET>(r[2 * m], r[2 * m + 1]);
+                const uint32_t p2 = split16<ET>(r[2 * m], r[2 * m + 1]);
+                const uint32_t rp = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
+                g[NT - 1][m] = is_feat ? g[NT - 1][m] : rp;
+            }
+        } else {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) g[NT - 1][m] = is_feat ? g[NT - 1][m] : 0u;
+        }
+        if (t == nsteps - 1) {   // the last step may hold fewer than 32 entries: zero the others
+            const int e0 = 32 * t + 8 * kq;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t mask = ((e0 + 2 * m < len) ? 0x0000ffffu : 0u) | ((e0 + 2 * m + 1 < len) ? 0xffff0000u : 0u);
+#pragma unroll
+                for (int T = 0; T < NT; ++T) g[T][m] &= mask;
+            }
+        }
+#pragma unroll
+        for (int R = 0; R < NT; ++R)
+#pragma unroll
+            for (int C = 0; C <= R; ++C) mfma_16x16x32<ET>(acc[R * (R + 1) / 2 + C], g[R], g[C]);
+    };
+
+    // two register sets in turn: the gathers of step t+1 are in flight during the MFMAs of step t, the column
+    // ids run one step further ahead
+    uint32_t raw[2][8][RWE];
+    float rat[2][8];
+    Ids ids = load_ids(0);
+    gather8(ids, raw[0]);
+    load_ratings(0, rat[0]);
+    ids = load_ids(1);
+    for (int t = 0; t < nsteps; t += 2) {
+        [&]<int... P>(std::integer_sequence<int, P...>) {
+            ((t + P < nsteps ? ([&] {
+                  if (t + P + 1 < nsteps) {
+                      gather8(ids, raw[P ^ 1]);            // step t+P+1
+                      load_ratings(t + P + 1, rat[P ^ 1]);
+                      ids = load_ids(t + P + 2);           // (beyond the end: zeros, never used)
+                  }
+                  compute(raw[P], rat[P], t + P);
+              }())
+                             : void()),
+             ...);
+        }(std::make_integer_sequence<int, 2>{});
+    }
+
+    // b_u = rows RI .. RI+2 of the last tile row (lane row RI/4 .. ), then zero the padding
+    const int c = i, g4 = kq;
+    if constexpr (WANT_B) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < 3; ++k) {
+                const int row = RI + k;   // row of the tile (compile-time after unrolling): lane row row/4, register row%4
+                s += bperm(4 * (16 * (row / 4) + c), acc[LB + T][row % 4]);
+            }
+            b[T] = (T < NT - 1 || c < RI) ? s : 0.f;
+        }
+    }
+#pragma unroll
+    for (int T = 0; T < NT; ++T)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool keep = (4 * g4 + r < RI) && (T < NT - 1 || c < RI);
+            acc[LB + T][r] = keep ? acc[LB + T][r] : 0.f;
+        }
+}
+
+}  // namespace als
