@@ -120,10 +120,6 @@ hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int3
 hipError_t launch_reduce_slots(int f, bool s16, hipStream_t st, const int32_t *task_off, int64_t pos0, int64_t npos,
                                int64_t task0, float *slots);
 
-hipError_t launch_solve(int f, int solver, int cg_iters, float cg_eps, bool ptr64, hipStream_t st,
-                        const int32_t *perm, const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
-                        const void *ptr, const float *slots, float lambda, float *Xout, int *status);
-
 hipError_t launch_export_dense(int f, bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                float lambda, int64_t row0, float *A_out, float *b_out);

@@ -231,10 +231,9 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
     const bool one_wave = single_wave_f(f);   // larger f: the wavefronts of a workgroup share a system
-    // rows shorter than a chunk are built and solved without leaving the registers; the exact solver does
-    // that for fp32 factor inputs and systems that fit one wavefront
-    const bool tiles_solver = cg || !one_wave || ctx->cfg.factor_dtype == ALS_F32;
-    const int64_t slot_rows = tiles_solver ? p->split_pos : m;
+    // rows shorter than a chunk are built and solved without leaving the registers (both solvers); longer
+    // rows go through slots
+    const int64_t slot_rows = p->split_pos;
     int64_t pos = 0;
     while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
@@ -273,14 +272,10 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                 HIP_TRY(ctx, launch_solve_cg_wide(p64, s16, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
-            else if (tiles_solver)
+            else
                 HIP_TRY(ctx, launch_solve_cg_wave(f, p64, s16, ctx->cfg.solver, ctx->stream, p->perm, p->task_off, pos, end - pos, task0,
                                                   a->ptr, ctx->slots, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps,
                                                   Out, ctx->status));
-            else
-                HIP_TRY(ctx, launch_solve(f, ctx->cfg.solver, ctx->cfg.cg_iters, ctx->cfg.cg_eps, p64, ctx->stream,
-                                          p->perm, p->task_off, pos, end - pos, task0, a->ptr, ctx->slots, lambda,
-                                          Out, ctx->status));
         }
         pos = end;
     }

@@ -119,19 +119,19 @@ static hipError_t herm_cg_e(int et, int solver, hipStream_t st, const int32_t *p
                             int fs, float eps, float *Xout, int *status) {
     const dim3 grid((unsigned)npos), block(64);
     const PtrT *p = (const PtrT *)ptr;
-    if (solver == ALS_SOLVER_CHOLESKY) {   // exact solve on the tiles: fp32 factor inputs only
-        if (et != ALS_F32) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CHOLESKY, kExplicit>), grid, block, 0, st, perm,
-                           pos0, p, idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
-    } else if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F32, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0, p,
-                           idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
-    else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_BF16, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0,
-                           p, idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
-    else
-        hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, ALS_F16, ALS_SOLVER_CG, kExplicit>), grid, block, 0, st, perm, pos0, p,
-                           idx, val, Theta, lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status);
+#define LAUNCH(E, S)                                                                                                 \
+    hipLaunchKernelGGL((k_hermitian_cg<F, PtrT, WIDE, E, S, kExplicit>), grid, block, 0, st, perm, pos0, p, idx, val, Theta, \
+                       lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status)
+    if (solver == ALS_SOLVER_CHOLESKY) {
+        if (et == ALS_F32) LAUNCH(ALS_F32, ALS_SOLVER_CHOLESKY);
+        else if (et == ALS_BF16) LAUNCH(ALS_BF16, ALS_SOLVER_CHOLESKY);
+        else LAUNCH(ALS_F16, ALS_SOLVER_CHOLESKY);
+    } else {
+        if (et == ALS_F32) LAUNCH(ALS_F32, ALS_SOLVER_CG);
+        else if (et == ALS_BF16) LAUNCH(ALS_BF16, ALS_SOLVER_CG);
+        else LAUNCH(ALS_F16, ALS_SOLVER_CG);
+    }
+#undef LAUNCH
     return hipGetLastError();
 }
 

@@ -18,7 +18,8 @@ namespace als {
 #endif
 constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
-constexpr int fused_waves(int F) { return F <= 100 ? ALS_FUSED_WAVES : 2; }
+// (f = 128 with 16-bit inputs: the operand sets of 32 entries and the extra b_u tiles need the whole file)
+constexpr int fused_waves(int F, int ET = ALS_F32) { return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2); }
 
 // 16-bit factor inputs go to the 16-bit matrix cores where the width allows it (tiles16.h)
 constexpr bool use_tiles16(int F, int ET, int MODE) { return ET != ALS_F32 && MODE == kExplicit && has_tiles16(F); }
@@ -124,7 +125,7 @@ __device__ __forceinline__ void load_tiles(const float *__restrict__ src, v4f (&
 
 // gram (kImplicit only): tiles of Theta^T Theta, the starting value of the accumulators
 template <int F, typename PtrT, bool WIDE, int ET, int SOLVER, int MODE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F), fused_waves(F)))) void k_hermitian_cg(
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F, ET), fused_waves(F, ET)))) void k_hermitian_cg(
     const int32_t *__restrict__ perm, int64_t pos0, const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
     const float *__restrict__ val, const void *__restrict__ Theta, float lambda, float alpha,
     const float *__restrict__ gram, int fs, float eps, float *__restrict__ Xout, int *__restrict__ status) {

@@ -11,10 +11,12 @@
 // lane, the same lane -> feature map as the fp32 path, so that everything downstream is unchanged) and
 // repacked with one byte-permute per register.
 //
-// b_u rides along: f is not a multiple of 16 here, and three spare lanes of the last tile (features f, f+1,
-// f+2 of the padded row) carry the rating split into three 16-bit parts (hi + mid + lo = the fp32 rating up to
-// 2^-24, or better), so rows f .. f+2 of the accumulated matrix add up to b_u; they and the remaining padding
-// are zeroed at the end.
+// b_u rides along: the rating is split into three 16-bit parts (hi + mid + lo = the fp32 rating up to 2^-24, or
+// better).  When f is not a multiple of 16, three spare lanes of the last tile (features f, f+1, f+2 of the
+// padded row) carry them, so rows f .. f+2 of the accumulated matrix add up to b_u; they and the remaining
+// padding are zeroed at the end.  When f is a multiple of 16 there is no spare lane: the parts form an operand of
+// their own (lanes 0..2, the others zero) and one more row of NT tiles is accumulated, whose rows 0..2 add up to
+// b_u (NT more MFMAs per step).
 #pragma once
 #include "tiles.h"
 
@@ -24,8 +26,8 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
-// widths for which this route exists: three spare lanes in the last tile
-constexpr bool has_tiles16(int F) { return (F % 16) >= 1 && (F % 16) <= 13; }
+// widths for which this route exists (one wavefront per system; up to 13 features in a partial last tile)
+constexpr bool has_tiles16(int F) { return F <= 128 && (F % 16) <= 13; }
 
 template <int ET>
 __device__ __forceinline__ void mfma_16x16x32(v4f &acc, const v4u &a, const v4u &b) {
@@ -62,6 +64,7 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
     static_assert(ET == ALS_BF16 || ET == ALS_F16);
     static_assert(has_tiles16(F));
     constexpr int NT = tiles_1d(F), RI = F % 16;
+    constexpr bool BX = RI == 0;   // the rating parts are an operand of their own
     constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
     constexpr int base1 = 64 * N4 + 32 * N2;
     constexpr int RWE = 2 * N4 + N2 + N1;   // raw registers per gathered row
@@ -156,10 +159,14 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
     };
 
     const bool is_r0 = i == RI, is_r1 = i == RI + 1, is_r2 = i == RI + 2, is_feat = i < RI;
+    v4f bt[BX ? NT : 1];   // BX: rows 0..2 of these tiles are the three parts of b_u
+#pragma unroll
+    for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
     auto compute = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t) {
         v4u g[NT];
         pack(raw, g);
-        // the rating lanes of the last tile
+        // the rating lanes: of the last tile, or of the extra operand
+        v4u gr = (v4u){0u, 0u, 0u, 0u};
         if constexpr (WANT_B) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
@@ -167,9 +174,10 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
                 const uint32_t p1 = split16<ET>(r[2 * m], r[2 * m + 1]);
                 const uint32_t p2 = split16<ET>(r[2 * m], r[2 * m + 1]);
                 const uint32_t rp = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
-                g[NT - 1][m] = is_feat ? g[NT - 1][m] : rp;
+                if constexpr (BX) gr[m] = rp;
+                else g[NT - 1][m] = is_feat ? g[NT - 1][m] : rp;
             }
-        } else {
+        } else if constexpr (!BX) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) g[NT - 1][m] = is_feat ? g[NT - 1][m] : 0u;
         }
@@ -181,6 +189,10 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
 #pragma unroll
                 for (int T = 0; T < NT; ++T) g[T][m] &= mask;
             }
+        }
+        if constexpr (BX && WANT_B) {
+#pragma unroll
+            for (int C = 0; C < NT; ++C) mfma_16x16x32<ET>(bt[C], gr, g[C]);
         }
 #pragma unroll
         for (int R = 0; R < NT; ++R)
@@ -211,7 +223,7 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
         }(std::make_integer_sequence<int, 2>{});
     }
 
-    // b_u = rows RI .. RI+2 of the last tile row (lane row RI/4 .. ), then zero the padding
+    // b_u = rows RI .. RI+2 of the last tile row (or rows 0 .. 2 of the extra tiles), then zero the padding
     const int c = i, g4 = kq;
     if constexpr (WANT_B) {
 #pragma unroll
@@ -220,18 +232,20 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
 #pragma unroll
             for (int k = 0; k < 3; ++k) {
                 const int row = RI + k;   // row of the tile (compile-time after unrolling): lane row row/4, register row%4
-                s += bperm(4 * (16 * (row / 4) + c), acc[LB + T][row % 4]);
+                s += bperm(4 * (16 * (row / 4) + c), BX ? bt[T][row % 4] : acc[LB + T][row % 4]);
             }
-            b[T] = (T < NT - 1 || c < RI) ? s : 0.f;
+            b[T] = (BX || T < NT - 1 || c < RI) ? s : 0.f;
         }
     }
+    if constexpr (!BX) {
 #pragma unroll
-    for (int T = 0; T < NT; ++T)
+        for (int T = 0; T < NT; ++T)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const bool keep = (4 * g4 + r < RI) && (T < NT - 1 || c < RI);
-            acc[LB + T][r] = keep ? acc[LB + T][r] : 0.f;
-        }
+            for (int r = 0; r < 4; ++r) {
+                const bool keep = (4 * g4 + r < RI) && (T < NT - 1 || c < RI);
+                acc[LB + T][r] = keep ? acc[LB + T][r] : 0.f;
+            }
+    }
 }
 
 }  // namespace als

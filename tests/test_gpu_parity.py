@@ -59,6 +59,34 @@ def test_hermitian_and_bias_match_oracle_on_edge_degrees(P, f):
     als.close()
 
 
+@pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_hermitian_and_bias_on_the_16_bit_matrix_cores(P, f, name):
+    """16-bit factor inputs at f <= 128 run on the 16-bit MFMAs, 32 entries per step, with b_u carried as a
+    three-part split of the rating: A_u and b_u against the oracle on the same rounded factors, with ratings
+    that no 16-bit format holds, and degrees around the step size and the chunk size."""
+    n = 5000
+    degrees = [0, 1, 2, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 95, 96, 97, 255, 256, 257, 300, 1000, 1024, 1025, 2500]
+    rng = np.random.default_rng(11)
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, int)]).astype(np.int32)
+    val = (rng.standard_normal(int(ptr[-1])) * 37.123).astype(np.float32)
+    tdt, code = (torch.bfloat16, P.BF16) if name == "bf16" else (torch.float16, P.F16)
+    T16 = torch.from_numpy(W.random_factors(n, f, seed=4, scale=0.5)).cuda().to(tdt)
+    T_rounded = T16.to(torch.float32).cpu().numpy()
+    als = P.Als(f, chunk=256, factor_dtype=code)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+    A, b = als.hermitian(sp, T16, 0.05, 0, len(degrees))
+    A, b = A.cpu().numpy(), b.cpu().numpy()
+    for u, d in enumerate(degrees):
+        s, e = ptr[u], ptr[u + 1]
+        Ao, bo = oracle.normal_eq(idx[s:e], val[s:e], T_rounded, 0.05)
+        assert np.abs(A[u] - Ao).max() <= 2e-6 * max(np.abs(Ao).max(), 1e-30) * max(1, np.sqrt(d)), (u, d)
+        assert np.abs(b[u] - bo).max() <= 2e-6 * max(np.abs(bo).max(), 1e-30) * max(1, np.sqrt(d)) + 1e-30, (u, d)
+        assert np.array_equal(A[u], A[u].T)
+    als.close()
+
+
 @pytest.mark.parametrize("chunk", [64, 1024])
 def test_one_exact_sweep_on_tiny(P, chunk):
     w = W.TINY
