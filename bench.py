@@ -16,6 +16,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+PEAK_16BIT_MFMA_TFLOPS = 2500.0   # dense bf16 / fp16 MFMA
 PEAK_FP32_MFMA_TFLOPS = 157.3   # MI355X dense fp32 matrix peak
 
 
@@ -76,6 +77,7 @@ def main():
     ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
     ap.add_argument("--herm-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage of the partial Gram matrices that go through slots (Section 4.2); bf16 needs --solver cg")
+    ap.add_argument("--no-reduced", action="store_true", help="skip the extra timing with bf16 factor inputs")
     ap.add_argument("--test-frac", type=float, default=0.0,
                     help="hold out this fraction of the entries (seeded), fit on the rest and report the held-out RMSE "
                          "per sweep and the time to come within 0.2 %% of its best value (protocol of Section 5.2)")
@@ -196,11 +198,21 @@ def main():
                                 "ms_per_sweep": herm_ms / K, "entries_per_sweep": nnz_slot},
                 "k_hermitian_cg": {"tflops": (2 * nnz_fit - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
                                    "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * nnz_fit - nnz_slot}}
+    if args.factor_dtype != "f32":
+        # 16-bit factor inputs run on the 16-bit matrix cores (16x the fp32 rate): the gathers bound the kernel.
+        # Algorithmic bytes per stored entry and half-sweep: one 16-bit factor row + column id + rating.
+        bytes_sweep = 2.0 * nnz_fit * (2.0 * w.f + 8.0)
+        gbps = bytes_sweep / herm_s / 1e9
+        roofline.update({"bound": "hbm", "achieved": gbps, "peak": 8000.0, "unit": "GB/s", "frac": gbps / 8000.0,
+                         "traffic": None, "bytes_per_launch": bytes_sweep / max(launches, 1),
+                         "mfma": {"achieved_tflops": achieved, "peak_tflops": PEAK_16BIT_MFMA_TFLOPS,
+                                  "frac": achieved / PEAK_16BIT_MFMA_TFLOPS}})
+        roofline.pop("flops_per_launch", None)
     out = {
         "metric": f"seconds per {'implicit-feedback ' if args.implicit is not None else ''}ALS sweep (X+Theta) at f={w.f}",
         "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.factor_dtype, "data": "synthetic",
         "factor_dtype": args.factor_dtype, "herm_dtype": args.herm_dtype,
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={nnz_fit} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
@@ -212,6 +224,32 @@ def main():
                         "note": "gathered bytes; above the HBM rate when the gathered factor is cache-resident"},
         "roofline": roofline,
     }
+    if args.factor_dtype == "f32" and args.implicit is None and not args.no_reduced:
+        # the same sweeps with bf16 factor inputs (Section 4.2 taken to the matrix cores), continuing from the
+        # factors reached above; reported beside the fp32 figure, never as `value`
+        a16 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
+                    factor_dtype=P.BF16)
+        X16, T16 = X.clone(), T.clone()
+
+        def sweep16():
+            a16.update_rows(csr, T16.to(torch.bfloat16), w.lam, X16)
+            a16.update_cols(csc, X16.to(torch.bfloat16), w.lam, T16)
+        sweep16()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            sweep16()
+        torch.cuda.synchronize()
+        ms16 = (time.perf_counter() - t1) / args.steps * 1e3
+        ev = P.Als(w.f)
+        rmse16 = ev.rmse(csr, X16, T16)
+        ev.close()
+        a16.close()
+        del X16, T16
+        out["bf16_factor_inputs"] = {"ms_per_step": ms16, "train_rmse": rmse16, "sweeps_after_fp32": args.steps + 1,
+                                     "note": "gathered factor rounded to bf16 each half-sweep (conversion timed), "
+                                             "v_mfma_f32_16x16x32_bf16 with fp32 accumulate, fp32 solver and output"}
+        log(f"[bench] bf16 factor inputs: {ms16:.2f} ms per sweep, rmse {rmse16:.5f}")
     if held_out is not None and args.implicit is None:
         # convergence protocol, outside the timed region: restart from the initial factors, held-out RMSE after
         # every sweep, update time accumulated without the evaluations

@@ -27,7 +27,7 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 // widths for which this route exists (one wavefront per system; up to 13 features in a partial last tile)
-constexpr bool has_tiles16(int F) { return F <= 128 && (F % 16) <= 13; }
+constexpr bool has_tiles16(int F) { return (F % 16) <= 13; }
 
 template <int ET>
 __device__ __forceinline__ void mfma_16x16x32(v4f &acc, const v4u &a, const v4u &b) {
@@ -55,14 +55,16 @@ __device__ __forceinline__ uint32_t split16(float &x0, float &x1) {
     }
 }
 
-// Same contract as accumulate_tiles<F, ..., rows_all(F), WANT_B, kExplicit>: acc += lower-triangle tiles of
-// sum theta theta^T over the entries [s0, s0+len), b = sum r theta in column layout, padding zeroed.
-template <int F, bool WIDE, int ET, bool WANT_B>
+// Same contract as accumulate_tiles<F, ..., ROWS, WANT_B, kExplicit>: acc += the tiles of the tile rows ROWS of
+// sum theta theta^T over the entries [s0, s0+len), b = sum r theta in column layout (tile rows of ROWS; zero
+// elsewhere), padding zeroed.
+template <int F, bool WIDE, int ET, bool WANT_B, uint32_t ROWS = rows_all(F)>
 __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                    const void *__restrict__ Theta, int64_t s0, int len,
-                                                   v4f (&acc)[tiles_tri(F)], float (&b)[tiles_1d(F)]) {
+                                                   v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)]) {
     static_assert(ET == ALS_BF16 || ET == ALS_F16);
     static_assert(has_tiles16(F));
+    static_assert(ROWS == rows_all(F) || (F % 16) == 0, "partial sets of tile rows need f to be a multiple of 16");
     constexpr int NT = tiles_1d(F), RI = F % 16;
     constexpr bool BX = RI == 0;   // the rating parts are an operand of their own
     constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
@@ -162,11 +164,11 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
     v4f bt[BX ? NT : 1];   // BX: rows 0..2 of these tiles are the three parts of b_u
 #pragma unroll
     for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
-    auto compute = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t) {
-        v4u g[NT];
+    // operands of step t from the gathered rows and ratings
+    auto operands = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t, v4u (&g)[NT], v4u &gr) {
         pack(raw, g);
         // the rating lanes: of the last tile, or of the extra operand
-        v4u gr = (v4u){0u, 0u, 0u, 0u};
+        gr = (v4u){0u, 0u, 0u, 0u};
         if constexpr (WANT_B) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
@@ -190,37 +192,39 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
                 for (int T = 0; T < NT; ++T) g[T][m] &= mask;
             }
         }
+    };
+    auto multiply = [&](const v4u (&g)[NT], const v4u &gr) {
         if constexpr (BX && WANT_B) {
 #pragma unroll
-            for (int C = 0; C < NT; ++C) mfma_16x16x32<ET>(bt[C], gr, g[C]);
+            for (int C = 0; C < NT; ++C)
+                if ((ROWS >> C) & 1u) mfma_16x16x32<ET>(bt[C], gr, g[C]);
         }
 #pragma unroll
         for (int R = 0; R < NT; ++R)
+            if ((ROWS >> R) & 1u) {
 #pragma unroll
-            for (int C = 0; C <= R; ++C) mfma_16x16x32<ET>(acc[R * (R + 1) / 2 + C], g[R], g[C]);
+                for (int C = 0; C <= R; ++C) mfma_16x16x32<ET>(acc[tiles_below(ROWS, R) + C], g[R], g[C]);
+            }
     };
 
-    // two register sets in turn: the gathers of step t+1 are in flight during the MFMAs of step t, the column
-    // ids run one step further ahead
-    uint32_t raw[2][8][RWE];
-    float rat[2][8];
+    // One set of row registers: the rows of step t are repacked into operands as soon as they have arrived,
+    // the gathers of step t+1 are issued into the same registers and are in flight during the MFMAs of step t;
+    // the column ids run one step further ahead.
+    uint32_t raw[8][RWE];
+    float rat[8];
     Ids ids = load_ids(0);
-    gather8(ids, raw[0]);
-    load_ratings(0, rat[0]);
+    gather8(ids, raw);
+    load_ratings(0, rat);
     ids = load_ids(1);
-    for (int t = 0; t < nsteps; t += 2) {
-        [&]<int... P>(std::integer_sequence<int, P...>) {
-            ((t + P < nsteps ? ([&] {
-                  if (t + P + 1 < nsteps) {
-                      gather8(ids, raw[P ^ 1]);            // step t+P+1
-                      load_ratings(t + P + 1, rat[P ^ 1]);
-                      ids = load_ids(t + P + 2);           // (beyond the end: zeros, never used)
-                  }
-                  compute(raw[P], rat[P], t + P);
-              }())
-                             : void()),
-             ...);
-        }(std::make_integer_sequence<int, 2>{});
+    for (int t = 0; t < nsteps; ++t) {
+        v4u g[NT], gr;
+        operands(raw, rat, t, g, gr);
+        if (t + 1 < nsteps) {
+            gather8(ids, raw);
+            load_ratings(t + 1, rat);
+            ids = load_ids(t + 2);   // (beyond the end: zeros, never used)
+        }
+        multiply(g, gr);
     }
 
     // b_u = rows RI .. RI+2 of the last tile row (or rows 0 .. 2 of the extra tiles), then zero the padding
@@ -234,7 +238,7 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
                 const int row = RI + k;   // row of the tile (compile-time after unrolling): lane row row/4, register row%4
                 s += bperm(4 * (16 * (row / 4) + c), BX ? bt[T][row % 4] : acc[LB + T][row % 4]);
             }
-            b[T] = (BX || T < NT - 1 || c < RI) ? s : 0.f;
+            b[T] = (((ROWS >> T) & 1u) && (BX || T < NT - 1 || c < RI)) ? s : 0.f;
         }
     }
     if constexpr (!BX) {

@@ -154,7 +154,12 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 #pragma unroll
         for (int q = 0; q < tiles_in(ROWS); ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
         float b[NT];
-        accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
+        // the registers of two wavefronts per SIMD do not suffice
+        if constexpr (ET != ALS_F32 && !WIDE)
+            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        else
+            accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if ((ROWS >> R) & 1u) {
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 }
 
 template <int F, int NW, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(kWideEu, kWideEu))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu(ET), wide_eu(ET)))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                 const PtrT *__restrict__ ptr,
                                                                 const int32_t *__restrict__ idx,
                                                                 const float *__restrict__ val,
@@ -202,7 +207,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(kWideEu
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         static_assert(tiles_in(ROWS) == NTW);
         float b[NT];
-        accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
+        // the registers of two wavefronts per SIMD do not suffice
+        if constexpr (ET != ALS_F32 && !WIDE)
+            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        else
+            accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) sh.bs[16 * R + lane] = b[R];

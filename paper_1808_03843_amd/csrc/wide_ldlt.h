@@ -315,7 +315,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDL
     for_wave<NW>(wave, [&](auto wt) ALS_INLINE {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         float b[NT];
-        accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
+        // the registers of two wavefronts per SIMD do not suffice
+        if constexpr (ET != ALS_F32 && !WIDE)
+            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        else
+            accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) bsrc[16 * R + lane] = b[R];
