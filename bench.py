@@ -180,7 +180,6 @@ def main():
     chunk = als.cfg.chunk or 4096
     deg_r = np.diff(a.ptr)
     deg_c = np.bincount(a.idx, minlength=w.n)
-    # (the fused kernel exists for f <= 128; the exact solver uses it with fp32 factor inputs only)
     nnz_fit = int(a.nnz)   # entries the factors are fitted on (all of them unless --test-frac)
     nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if fused_n > 0 else 2 * nnz_fit
     per_entry = w.f * (w.f + 1)

@@ -70,8 +70,9 @@ typedef struct als_config {
     int32_t cg_iters;     /* f_s of Algorithm 1 (used when solver == ALS_SOLVER_CG)                      */
     float cg_eps;         /* epsilon of Algorithm 1: stop when sqrt(r^T r) < cg_eps; 0 = fixed f_s steps */
     int32_t factor_dtype; /* ALS_F32 / ALS_BF16 / ALS_F16: element type of the factor matrix that is GATHERED
-                             (Theta in als_update_rows, X in als_update_cols); widened to fp32 in registers,
-                             all arithmetic and the written factor stay fp32                            */
+                             (Theta in als_update_rows, X in als_update_cols).  16-bit elements are multiplied
+                             on the 16-bit matrix cores with fp32 accumulation (exact products, so the sums
+                             are those of the widened values); solvers and the written factor stay fp32  */
     int32_t herm_dtype;   /* storage type of A_u where it is materialised, i.e. the partial Gram matrices of
                              rows split over several work items (Section 4.2): ALS_F32, or ALS_BF16 with
                              ALS_SOLVER_CG (fp32 accumulate, bf16 in memory; at f = 256 only together
