@@ -104,4 +104,29 @@ def test_very_tall():
         print(f"very_tall sweep {s + 1}: {dt:.3f} s{' (column half only)' if s == 0 else ''}, training rmse {hist[-1][1]:.5f}", flush=True)
     assert hist[2][1] < hist[0][1]
     als.synchronize()
+    # the reduced-precision mode of this configuration: bf16 factor inputs on the 16-bit matrix cores.  Sampled
+    # rows against double-precision Algorithm 1 on the same rounded factor, then two timed sweeps.
+    a16 = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.BF16)
+    T16 = T.to(torch.bfloat16)
+    sel = torch.from_numpy(rows).to(dev)
+    warm_rows = X[sel].cpu().numpy()
+    Xb = X.clone()
+    a16.update_rows(csr, T16, w.lam, Xb)
+    a16.synchronize()
+    ref = oracle.update_rows_cg(sptr, sidx, sval, T16.to(torch.float32).cpu().numpy(), w.lam, warm_rows, fs=6)
+    err = _rel(Xb[sel].cpu().numpy(), ref)
+    print(f"very_tall rows, bf16 inputs: {len(rows)} sampled, CG(6) vs double Algorithm 1 max {err.max():.2e}", flush=True)
+    assert err.max() <= 2e-3
+    del Xb
+    for s in range(2):
+        torch.cuda.synchronize()
+        t0 = time.time()
+        a16.update_rows(csr, T.to(torch.bfloat16), w.lam, X)
+        a16.update_cols(csc, X.to(torch.bfloat16), w.lam, T)
+        torch.cuda.synchronize()
+        dt = time.time() - t0
+        r16 = als.rmse(csr, X, T)
+        print(f"very_tall sweep {s + 4} (bf16 inputs): {dt:.3f} s, training rmse {r16:.5f}", flush=True)
+        assert r16 < hist[2][1] + 2e-3
+    a16.close()
     als.close()
