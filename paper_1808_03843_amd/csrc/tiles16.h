@@ -253,3 +253,166 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
 }
 
 }  // namespace als
+
+namespace als {
+
+// The same for a system shared by the NW wavefronts of a workgroup (f = 256, tile rows ROWS per wavefront):
+// instead of every wavefront gathering every row, the rows of a step are gathered once -- wavefront w fetches
+// entries 4w .. 4w+3 of the 32 -- repacked, and put into LDS in the operand layout, from where every wavefront
+// reads the operand registers of the tiles it needs (16 bytes per lane and tile, conflict-free).  Two staging
+// buffers in turn, one barrier per step.  Every wavefront of the workgroup must call, with the same s0 and len.
+//   stage: 2 * tiles_1d(F) * 256 words of LDS.
+// Producer lane (i, kq): entry pair p = kq % 2 of the wavefront's four entries, feature half kq / 2 (tiles
+// 8*(kq/2) .. +7, the usual lane -> feature map), so that both entries of an operand word are in one lane.
+template <int F, int NW, bool WIDE, int ET, bool WANT_B, uint32_t ROWS>
+__device__ __forceinline__ void accumulate_tiles16_shared(const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                                          const void *__restrict__ Theta, int64_t s0, int len,
+                                                          v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)],
+                                                          uint32_t *stage, int wave) {
+    static_assert(ET == ALS_BF16 || ET == ALS_F16);
+    static_assert(F == 256 && NW == 8, "16 tiles, four 8-byte loads per row and lane pair, 8 wavefronts x 4 entries");
+    constexpr int NT = tiles_1d(F);
+    constexpr int RMAX = 31 - __builtin_clz(ROWS);
+    constexpr int STAGE = NT * 256;   // words per staging buffer
+    const int lane = threadIdx.x & 63, i = lane & 15, kq = lane >> 4;
+    const int p = kq & 1, hf = kq >> 1;
+    const int32_t *__restrict__ ib = idx + s0;
+    const float *__restrict__ vb = val + s0;
+    constexpr int kRsrcFlags = 0x00020000;
+    const __amdgpu_buffer_rsrc_t ids_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ib), 0, 4 * len, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vb), 0, 4 * len, kRsrcFlags);
+    const int nsteps = (len + 31) >> 5;
+    const int e_in_step = 4 * wave + 2 * p;                 // first of this lane's two entries inside a step
+    const uint32_t id_off = 4u * (uint32_t)e_in_step;
+    const uint32_t lane_a = 8u * (uint32_t)i + 256u * (uint32_t)hf;   // bytes into the row: tiles 8hf .. 8hf+7
+    // word of (tile T, this lane's pair) in a staging buffer: lane (i, kq') of the consumers, register m
+    const int P = 2 * wave + p;
+    const int w_base = (16 * (P >> 2) + i) * 4 + (P & 3);
+
+    struct Pair { uint32_t a, b; };
+    auto load_pair_ids = [&](int t) -> Pair {
+        Pair r;
+        r.a = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(ids_rsrc, id_off + 128u * (uint32_t)t, 0, 0);
+        r.b = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(ids_rsrc, id_off + 4u + 128u * (uint32_t)t, 0, 0);
+        return r;
+    };
+    auto gather = [&](uint32_t c, uint32_t (&w)[4]) {   // 8 features of one row: two 8-byte loads
+        const char *q;
+        uint32_t o;
+        if constexpr (WIDE) {
+            q = reinterpret_cast<const char *>(Theta) + (int64_t)c * (2 * F);
+            o = lane_a;
+        } else {
+            q = reinterpret_cast<const char *>(Theta);
+            o = row_offset<(uint32_t)(2 * F)>(c, lane_a);
+        }
+        const uint2 v0 = *reinterpret_cast<const uint2 *>(q + o);
+        const uint2 v1 = *reinterpret_cast<const uint2 *>(q + o + 128);
+        w[0] = v0.x; w[1] = v0.y; w[2] = v1.x; w[3] = v1.y;
+    };
+    constexpr uint32_t kLoLo = 0x05040100u, kHiHi = 0x07060302u;
+    // rows of step t (raw registers e0, e1) -> staging buffer; entries beyond the work item become zeros
+    auto stage_rows = [&](const uint32_t (&e0)[4], const uint32_t (&e1)[4], int t, uint32_t *buf) {
+        const int e = 32 * t + e_in_step;
+        const uint32_t mask = ((e < len) ? 0x0000ffffu : 0u) | ((e + 1 < len) ? 0xffff0000u : 0u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {   // register k holds the features of tiles 8hf + 2k (low half) and 8hf + 2k + 1 (high)
+            const uint32_t lo = __builtin_amdgcn_perm(e1[k], e0[k], kLoLo) & mask;
+            const uint32_t hi = __builtin_amdgcn_perm(e1[k], e0[k], kHiHi) & mask;
+            buf[(8 * hf + 2 * k) * 256 + w_base] = lo;
+            buf[(8 * hf + 2 * k + 1) * 256 + w_base] = hi;
+        }
+    };
+    auto load_ratings = [&](int t, float (&r)[8]) {
+        const uint32_t o = 32u * (uint32_t)kq + 128u * (uint32_t)t;
+        const v4u a = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o, 0, 0));
+        const v4u c = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o + 16u, 0, 0));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            r[j] = bits_to_float(a[j]);
+            r[4 + j] = bits_to_float(c[j]);
+        }
+    };
+
+    v4f bt[NT];   // rows 0..2 of these tiles are the three parts of b_u (tile rows of ROWS only)
+#pragma unroll
+    for (int T = 0; T < NT; ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
+    const bool is_r0 = i == 0, is_r1 = i == 1, is_r2 = i == 2;
+
+    // Gathers run PD steps ahead of their use (a step's rows are 8 registers per lane here, and with one workgroup
+    // per CU nothing else hides the memory latency); the column ids one step further.
+    constexpr int PD = 4;
+    uint32_t raw[PD][2][4];
+    float rat[8];
+    Pair ids;
+    auto fetch = [&](auto slot, int step) {   // ids must hold the column ids of `step`
+        gather(ids.a, raw[decltype(slot)::value][0]);
+        gather(ids.b, raw[decltype(slot)::value][1]);
+        (void)step;
+    };
+    [&]<int... u>(std::integer_sequence<int, u...>) {
+        ((u < nsteps ? (ids = load_pair_ids(u), fetch(std::integral_constant<int, u>{}, u)) : void()), ...);
+    }(std::make_integer_sequence<int, PD>{});
+    stage_rows(raw[0][0], raw[0][1], 0, stage);
+    if (PD < nsteps) {
+        ids = load_pair_ids(PD);
+        fetch(std::integral_constant<int, 0>{}, PD);
+    }
+    ids = load_pair_ids(PD + 1);   // (beyond the end: zeros, never used)
+    if constexpr (WANT_B) load_ratings(0, rat);
+    __syncthreads();
+    auto step = [&](auto utag, int t) {
+        constexpr int U = decltype(utag)::value;     // t % PD
+        constexpr int S = (U + 1) % PD;              // register set of step t+1, reused for step t+1+PD
+        const uint32_t *cur = stage + (t & 1) * STAGE;
+        v4u g[RMAX + 1];
+#pragma unroll
+        for (int T = 0; T <= RMAX; ++T) g[T] = *reinterpret_cast<const v4u *>(cur + T * 256 + 4 * lane);
+        v4u gr = (v4u){0u, 0u, 0u, 0u};
+        if constexpr (WANT_B) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t p0 = split16<ET>(rat[2 * m], rat[2 * m + 1]);
+                const uint32_t p1 = split16<ET>(rat[2 * m], rat[2 * m + 1]);
+                const uint32_t p2 = split16<ET>(rat[2 * m], rat[2 * m + 1]);
+                gr[m] = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
+            }
+        }
+        if (t + 1 < nsteps) {   // rows of the next step into the other buffer, then its registers take new gathers
+            stage_rows(raw[S][0], raw[S][1], t + 1, stage + ((t + 1) & 1) * STAGE);
+            if constexpr (WANT_B) load_ratings(t + 1, rat);
+            if (t + 1 + PD < nsteps) fetch(std::integral_constant<int, S>{}, t + 1 + PD);
+            ids = load_pair_ids(t + 2 + PD);
+        }
+        if constexpr (WANT_B) {
+#pragma unroll
+            for (int C = 0; C < NT; ++C)
+                if ((ROWS >> C) & 1u) mfma_16x16x32<ET>(bt[C], gr, g[C]);
+        }
+#pragma unroll
+        for (int R = 0; R < NT; ++R)
+            if ((ROWS >> R) & 1u) {
+#pragma unroll
+                for (int C = 0; C <= R; ++C) mfma_16x16x32<ET>(acc[tiles_below(ROWS, R) + C], g[R], g[C]);
+            }
+        __syncthreads();   // the next buffer is complete; everybody is done reading this one
+    };
+    for (int t0 = 0; t0 < nsteps; t0 += PD) {
+        [&]<int... u>(std::integer_sequence<int, u...>) {
+            ((t0 + u < nsteps ? step(std::integral_constant<int, u>{}, t0 + u) : void()), ...);
+        }(std::make_integer_sequence<int, PD>{});
+    }
+    if constexpr (WANT_B) {
+#pragma unroll
+        for (int T = 0; T < NT; ++T) {
+            float s = 0.f;
+            if ((ROWS >> T) & 1u) {
+#pragma unroll
+                for (int k = 0; k < 3; ++k) s += bperm(4 * i, bt[T][k]);   // rows 0..2: lane row 0, registers 0..2
+            }
+            b[T] = s;
+        }
+    }
+}
+
+}  // namespace als

@@ -28,8 +28,7 @@ constexpr bool kWideInVgpr = kWideWaves >= 8;
 constexpr int kDepthWideSlots = ALS_DEPTH_WIDE_SLOTS;
 // wavefronts per SIMD the fused kernel is compiled for, and its gather pipeline depth
 constexpr int kWideEu = ALS_WIDE_EU, kDepthWide = ALS_DEPTH_WIDE;
-// (16-bit inputs: the operand set of a 32-entry step needs the register budget of two wavefronts per SIMD)
-constexpr int wide_eu(int ET) { return ET == ALS_F32 ? kWideEu : (kWideEu > 2 ? 2 : kWideEu); }
+constexpr int wide_eu(int ET) { return ET == ALS_F32 ? kWideEu : (kWideEu > 2 ? 2 : kWideEu); }   // 16-bit inputs: two
 
 // fn(integral_constant<w>) for the (wavefront-uniform) w == wave
 template <int NW, typename Fn>

@@ -139,6 +139,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
                                                              const float *__restrict__ val,
                                                              const void *__restrict__ Theta, float *__restrict__ slots) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
+    __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t t = blockIdx.x;
     const int row = task_row[task0 + t];
@@ -154,10 +155,9 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
 #pragma unroll
         for (int q = 0; q < tiles_in(ROWS); ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
         float b[NT];
-        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
-        // the registers of two wavefronts per SIMD do not suffice
-        if constexpr (ET != ALS_F32 && !WIDE)
-            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores, the rows gathered once per workgroup (tiles16.h)
+        if constexpr (ET != ALS_F32)
+            accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
             accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
@@ -191,6 +191,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu
                                                                 int *__restrict__ status) {
     constexpr int NT = tiles_1d(F), NTW = tiles_tri(F) / NW;
     __shared__ WideShared<F, NW> sh;
+    __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = perm[pos0 + blockIdx.x];
     const int64_t s0 = (int64_t)ptr[row];
@@ -207,10 +208,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         static_assert(tiles_in(ROWS) == NTW);
         float b[NT];
-        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
-        // the registers of two wavefronts per SIMD do not suffice
-        if constexpr (ET != ALS_F32 && !WIDE)
-            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores, the rows gathered once per workgroup (tiles16.h)
+        if constexpr (ET != ALS_F32)
+            accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
             accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll

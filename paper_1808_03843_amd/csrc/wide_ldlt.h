@@ -300,6 +300,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDL
     constexpr int NT = tiles_1d(F), NTW = tiles_tri(F) / NW;
     __shared__ LdltShared<F> sh;
     __shared__ float bsrc[F];
+    __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = perm[pos0 + blockIdx.x];
     const int64_t s0 = (int64_t)ptr[row];
@@ -315,10 +316,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDL
     for_wave<NW>(wave, [&](auto wt) ALS_INLINE {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         float b[NT];
-        // 16-bit inputs: on the 16-bit matrix cores (tiles16.h), unless the rows need 64-bit addresses, for which
-        // the registers of two wavefronts per SIMD do not suffice
-        if constexpr (ET != ALS_F32 && !WIDE)
-            accumulate_tiles16<F, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b);
+        // 16-bit inputs: on the 16-bit matrix cores, the rows gathered once per workgroup (tiles16.h)
+        if constexpr (ET != ALS_F32)
+            accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
             accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
 #pragma unroll
