@@ -290,16 +290,18 @@ def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P, f, n):
     torch.cuda.empty_cache()
 
 
-def test_f100_16_bit_factor_beyond_2_pow_24_rows(P):
-    """f = 100 with 16-bit factor inputs: the row pitch (200 bytes) is not a power of two and the 32-bit row
-    offsets are formed with a 24-bit multiply, so a matrix of 2^24 rows or more (still below 4 GiB) must take
-    the 64-bit path.  Zero matrix except for the touched rows; the oracle sees a compact copy."""
-    f, n = 100, 17_000_000
-    assert n >= 2 ** 24 and n * f * 2 < 2 ** 32
+@pytest.mark.parametrize("f,n", [(100, 17_000_000), (128, 16_800_000), (256, 8_400_000)])
+def test_16_bit_factor_with_64_bit_row_addresses(P, f, n):
+    """16-bit factor inputs whose rows need 64-bit addresses.  f = 100: the row pitch (200 bytes) is not a power
+    of two and the 32-bit row offsets are formed with a 24-bit multiply, so a matrix of 2^24 rows or more (still
+    below 4 GiB) must take the 64-bit path; f = 128, 256: 4 GiB or more.  Zero matrix except for the touched rows;
+    the oracle sees a compact copy."""
+    assert n >= 2 ** 24 or n * f * 2 >= 2 ** 32
     rng = np.random.default_rng(6)
     degrees = [2, 50, 900]
     ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
-    idx = np.concatenate([np.sort(np.unique(np.concatenate([rng.choice(n - 2 ** 24, d - 1, replace=False) + 2 ** 24 - 1,
+    lo = n - 300_000   # every touched row lies beyond the 32-bit / 24-bit limit
+    idx = np.concatenate([np.sort(np.unique(np.concatenate([rng.choice(n - lo - 1, d - 1, replace=False) + lo,
                                                             [n - 1]]))[:d]) for d in degrees]).astype(np.int32)
     assert len(idx) == ptr[-1] and idx.max() == n - 1
     val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
@@ -309,13 +311,15 @@ def test_f100_16_bit_factor_beyond_2_pow_24_rows(P):
     Theta[torch.from_numpy(used.astype(np.int64)).cuda()] = rows16.cuda()
     remap = np.searchsorted(used, idx).astype(np.int32)
     sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
-    als = P.Als(f, solver=P.SOLVER_CG, cg_iters=f, chunk=256, factor_dtype=P.BF16)
-    X = torch.zeros((len(degrees), f), device="cuda:0")
-    als.update_rows(sp, Theta, 0.5, X)
-    als.synchronize()
     ref = oracle.update_rows(ptr, remap, val, rows16.to(torch.float32).numpy(), 0.5)
-    assert _row_rel_err(X.cpu().numpy(), ref).max() <= 1e-3   # f iterations of Algorithm 1: exact up to fp32 rounding
-    als.close()
+    # (f iterations of Algorithm 1: exact up to fp32 rounding)
+    for solver, tol in ((P.SOLVER_CG, 1e-3), (P.SOLVER_CHOLESKY, TOL_EXACT)):
+        als = P.Als(f, solver=solver, cg_iters=f, chunk=256, factor_dtype=P.BF16)
+        X = torch.zeros((len(degrees), f), device="cuda:0")
+        als.update_rows(sp, Theta, 0.5, X)
+        als.synchronize()
+        assert _row_rel_err(X.cpu().numpy(), ref).max() <= tol, solver
+        als.close()
     del Theta
     torch.cuda.empty_cache()
 
