@@ -119,8 +119,8 @@ int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *T
  *     A_u = Theta^T Theta + sum_{v in Omega_u} (c_uv - 1) theta_v theta_v^T + lambda I,
  *     b_u = sum_{v in Omega_u, r_uv > 0} c_uv theta_v,     x_u = A_u^-1 b_u
  * which equals the sum over all n columns.  Theta^T Theta is computed once per call by the same
- * gathered kernel.  Arguments as for als_update_rows; alpha >= 0; requires f <= 128, fp32 factors
- * and fp32 storage of A_u.  Rows with n_u = 0 get x_u = 0. */
+ * gathered kernel.  Arguments as for als_update_rows; alpha >= 0; requires fp32 factors and fp32
+ * storage of A_u.  Rows with n_u = 0 get x_u = 0. */
 int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
                              int f, float *X);
 
@@ -135,7 +135,7 @@ int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const
                       float alpha, int f, double *loss_out);
 
 /* G^T G for a factor matrix G (DEVICE, n x f float): out (DEVICE, f x f floats, row-major, full
- * symmetric).  The dense term of the implicit update; exported for tests.  f <= 128. */
+ * symmetric).  The dense term of the implicit update; exported for tests. */
 int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out);
 
 /* get_hermitian / get_bias alone (Section 2, step (i)) for rows [row0, row0+nrows):

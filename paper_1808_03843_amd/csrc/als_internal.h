@@ -114,6 +114,28 @@ hipError_t launch_hermitian_ldlt_wide(bool ptr64, bool wide, int et, hipStream_t
 hipError_t launch_solve_ldlt_wide(bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                   int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                   float lambda, float *Xout, int *status);
+// implicit feedback at f = 256 (wide.hip, wide_ldlt_implicit.hip): the f = 256 counterparts of launch_gram's
+// first stage and of the three implicit launchers below
+hipError_t launch_gram_wide(bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots);
+hipError_t launch_hermitian_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+                                          const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                          const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                                          float alpha, float *slots);
+hipError_t launch_hermitian_cg_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
+                                             int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                             const void *Theta, float lambda, float alpha, const float *gram, int fs,
+                                             float eps, float *Xout, int *status);
+hipError_t launch_solve_cg_wide_implicit(bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                         int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                         float lambda, const float *gram, int fs, float eps, float *Xout, int *status);
+hipError_t launch_hermitian_ldlt_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
+                                               int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                               const void *Theta, float lambda, float alpha, const float *gram,
+                                               float *Xout, int *status);
+hipError_t launch_solve_ldlt_wide_implicit(bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                           int64_t pos0, int64_t npos, int64_t task0, const void *ptr,
+                                           const float *slots, float lambda, const float *gram, float *Xout,
+                                           int *status);
 hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);

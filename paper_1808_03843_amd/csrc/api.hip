@@ -189,7 +189,6 @@ int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
 }
 
 int check_implicit(als_ctx *ctx, float alpha) {
-    if (!single_wave_f(ctx->cfg.f)) return fail(ctx, ALS_EINVAL, "implicit feedback needs f <= 128");
     if (ctx->cfg.factor_dtype != ALS_F32 || ctx->cfg.herm_dtype != ALS_F32)
         return fail(ctx, ALS_EINVAL, "implicit feedback needs fp32 factors and fp32 storage of A_u");
     if (!(alpha >= 0.f)) return fail(ctx, ALS_EINVAL, "alpha must be >= 0");
@@ -370,7 +369,6 @@ int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X,
 int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
     if (!ctx) return ALS_EINVAL;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
-    if (!single_wave_f(f)) return fail(ctx, ALS_EINVAL, "als_gram needs f <= 128");
     if (n < 0 || n > 0x7fffffff || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     int rc = compute_gram(ctx, G, n, 0);

@@ -120,6 +120,12 @@ static hipError_t gram_f(bool wide, hipStream_t st, const float *G, int64_t n, i
 
 hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
                        float *out) {
+    if (f == 256) {   // the wavefronts of a workgroup share the matrix (wide.hip); the sum of the slots is the same
+        const hipError_t e = launch_gram_wide(wide, st, G, n, per, nslots, slots);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_sum_slots<256>), dim3((tiles_tri(256) * 64 + 255) / 256), dim3(256), 0, st, slots, nslots, out);
+        return hipGetLastError();
+    }
 #define CALL(FF) gram_f<FF>(wide, st, G, n, per, nslots, slots, out)
     ALS_FOR_F(CALL)
 #undef CALL
@@ -131,6 +137,7 @@ static hipError_t dense_f(hipStream_t st, const float *tiles, float *out) {
     return hipGetLastError();
 }
 hipError_t launch_tiles_to_dense(int f, hipStream_t st, const float *tiles, float *out) {
+    if (f == 256) return dense_f<256>(st, tiles, out);
 #define CALL(FF) dense_f<FF>(st, tiles, out)
     ALS_FOR_F(CALL)
 #undef CALL
@@ -142,6 +149,7 @@ static hipError_t dot_f(hipStream_t st, const float *A, const float *B, double *
     return hipGetLastError();
 }
 hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B, double *out) {
+    if (f == 256) return dot_f<256>(st, A, B, out);
 #define CALL(FF) dot_f<FF>(st, A, B, out)
     ALS_FOR_F(CALL)
 #undef CALL
@@ -168,6 +176,9 @@ hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t s
                                      const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
                                      const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                      float alpha, float *slots) {
+    if (f == 256)
+        return launch_hermitian_wide_implicit(ptr64, wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val,
+                                              Theta, alpha, slots);
 #define CALL(FF)                                                                                                   \
     (ptr64 ? herm_imp_f<FF, int64_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,   \
                                      alpha, slots)                                                                 \
@@ -207,6 +218,12 @@ hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int solver
                                         int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx,
                                         const float *val, const void *Theta, float lambda, float alpha,
                                         const float *gram, int fs, float eps, float *Xout, int *status) {
+    if (f == 256)
+        return solver == ALS_SOLVER_CG
+                   ? launch_hermitian_cg_wide_implicit(ptr64, wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, alpha,
+                                                       gram, fs, eps, Xout, status)
+                   : launch_hermitian_ldlt_wide_implicit(ptr64, wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda,
+                                                         alpha, gram, Xout, status);
 #define CALL(FF)                                                                                                     \
     (ptr64 ? fused_imp_f<FF, int64_t>(wide, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, alpha, gram, \
                                       fs, eps, Xout, status)                                                         \
@@ -235,6 +252,12 @@ hipError_t launch_solve_wave_implicit(int f, bool ptr64, int solver, hipStream_t
                                       const int32_t *task_off, int64_t pos0, int64_t npos, int64_t task0,
                                       const void *ptr, const float *slots, float lambda, const float *gram, int fs,
                                       float eps, float *Xout, int *status) {
+    if (f == 256)
+        return solver == ALS_SOLVER_CG
+                   ? launch_solve_cg_wide_implicit(ptr64, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, gram, fs,
+                                                   eps, Xout, status)
+                   : launch_solve_ldlt_wide_implicit(ptr64, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, gram,
+                                                     Xout, status);
 #define CALL(FF)                                                                                                      \
     (ptr64 ? solve_imp_f<FF, int64_t>(solver, st, perm, task_off, pos0, npos, task0, ptr, slots, lambda, gram, fs,    \
                                       eps, Xout, status)                                                              \

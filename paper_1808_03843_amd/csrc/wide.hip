@@ -131,13 +131,17 @@ __device__ __forceinline__ void cg_wide(const v4f (&acc)[tiles_tri(F) / NW], Wid
     }
 }
 
-template <int F, int NW, typename PtrT, bool WIDE, int ET, bool S16>
+// MODE: kExplicit, or kImplicit (Section 5.6: entries weighted by alpha * r_uv; the dense Theta^T Theta term is
+// added by the solver kernels, as for f <= 128)
+template <int F, int NW, typename PtrT, bool WIDE, int ET, bool S16, int MODE = kExplicit>
 __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__restrict__ task_row,
                                                              const int32_t *__restrict__ task_chunk, int64_t task0,
                                                              int chunk, const PtrT *__restrict__ ptr,
                                                              const int32_t *__restrict__ idx,
                                                              const float *__restrict__ val,
-                                                             const void *__restrict__ Theta, float *__restrict__ slots) {
+                                                             const void *__restrict__ Theta, float alpha,
+                                                             float *__restrict__ slots) {
+    static_assert(MODE == kExplicit || ET == ALS_F32, "implicit feedback: fp32 factors");
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -159,7 +163,8 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
         if constexpr (ET != ALS_F32)
             accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
-            accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+            accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ET, ROWS, true, MODE>(idx, val, Theta, uniform64(s0), len,
+                                                                                          acc, b, alpha);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if ((ROWS >> R) & 1u) {
@@ -181,14 +186,17 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
     });
 }
 
-template <int F, int NW, typename PtrT, bool WIDE, int ET>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu(ET), wide_eu(ET)))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
+// gram (kImplicit only): tiles of Theta^T Theta in the slot layout, the starting value of the accumulators
+template <int F, int NW, typename PtrT, bool WIDE, int ET, int MODE = kExplicit>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu(ET, MODE), wide_eu(ET, MODE)))) void k_hermitian_cg_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                 const PtrT *__restrict__ ptr,
                                                                 const int32_t *__restrict__ idx,
                                                                 const float *__restrict__ val,
-                                                                const void *__restrict__ Theta, float lambda, int fs,
+                                                                const void *__restrict__ Theta, float lambda,
+                                                                float alpha, const float *__restrict__ gram, int fs,
                                                                 float eps, float *__restrict__ Xout,
                                                                 int *__restrict__ status) {
+    static_assert(MODE == kExplicit || ET == ALS_F32, "implicit feedback: fp32 factors");
     constexpr int NT = tiles_1d(F), NTW = tiles_tri(F) / NW;
     __shared__ WideShared<F, NW> sh;
     __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
@@ -207,24 +215,27 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(wide_eu
     for_wave<NW>(wave, [&](auto wt) {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
         static_assert(tiles_in(ROWS) == NTW);
+        if constexpr (MODE == kImplicit) load_tiles_rows<F, ROWS>(gram, acc);
         float b[NT];
         // 16-bit inputs: on the 16-bit matrix cores, the rows gathered once per workgroup (tiles16.h)
         if constexpr (ET != ALS_F32)
             accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
-            accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+            accumulate_tiles<F, kWideInVgpr, kDepthWide, WIDE, ET, ROWS, true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                     alpha);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) sh.bs[16 * R + lane] = b[R];
     });
-    cg_wide<F, NW>(acc, sh, sh.bs, lambda * (float)len, fs, eps, xg, status);
+    cg_wide<F, NW>(acc, sh, sh.bs, MODE == kImplicit ? lambda : lambda * (float)len, fs, eps, xg, status);
 }
 
-template <int F, int NW, typename PtrT, bool S16>
+template <int F, int NW, typename PtrT, bool S16, int MODE = kExplicit>
 __global__ __launch_bounds__(64 * NW) void k_solve_cg_wide(const int32_t *__restrict__ perm,
                                                             const int32_t *__restrict__ task_off, int64_t pos0,
                                                             int64_t task0, const PtrT *__restrict__ ptr,
-                                                            const float *__restrict__ slots, float lambda, int fs,
+                                                            const float *__restrict__ slots, float lambda,
+                                                            const float *__restrict__ gram, int fs,
                                                             float eps, float *__restrict__ Xout,
                                                             int *__restrict__ status) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), NTW = NTILES / NW;
@@ -258,10 +269,15 @@ __global__ __launch_bounds__(64 * NW) void k_solve_cg_wide(const int32_t *__rest
 #pragma unroll
                         for (int r = 0; r < 4; ++r) acc[q][r] = slot[(T * 4 + r) * 64 + lane];
                     }
+                    if constexpr (MODE == kImplicit) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[q][r] += gram[(T * 4 + r) * 64 + lane];
+                    }
                 }
             }
     });
-    cg_wide<F, NW>(acc, sh, slot + NTILES * (S16 ? 128 : 256), lambda * (float)n_u, fs, eps, xg, status);
+    cg_wide<F, NW>(acc, sh, slot + NTILES * (S16 ? 128 : 256), MODE == kImplicit ? lambda : lambda * (float)n_u, fs, eps,
+                   xg, status);
 }
 
 // ---- launchers ---------------------------------------------------------------------------------------
@@ -276,7 +292,7 @@ hipError_t herm_wide_e(int et, bool s16, hipStream_t st, const int32_t *task_row
     const PtrT *p = (const PtrT *)ptr;
 #define LAUNCH(E, S)                                                                                                \
     hipLaunchKernelGGL((k_hermitian_wide<WF, NW, PtrT, WIDE, E, S>), grid, block, 0, st, task_row, task_chunk, task0, \
-                       chunk, p, idx, val, Theta, slots)
+                       chunk, p, idx, val, Theta, 0.f, slots)
     if (s16) {   // bf16 slots: fp32 factor inputs only
         if (et != ALS_F32) return hipErrorInvalidValue;
         LAUNCH(ALS_F32, true);
@@ -295,7 +311,7 @@ hipError_t herm_cg_wide_e(int et, hipStream_t st, const int32_t *perm, int64_t p
     const PtrT *p = (const PtrT *)ptr;
 #define LAUNCH(E)                                                                                                   \
     hipLaunchKernelGGL((k_hermitian_cg_wide<WF, NW, PtrT, WIDE, E>), grid, block, 0, st, perm, pos0, p, idx, val, Theta, \
-                       lambda, fs, eps, Xout, status)
+                       lambda, 0.f, (const float *)nullptr, fs, eps, Xout, status)
     if (et == ALS_F32) LAUNCH(ALS_F32);
     else if (et == ALS_BF16) LAUNCH(ALS_BF16);
     else LAUNCH(ALS_F16);
@@ -332,10 +348,93 @@ hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int3
     const dim3 grid((unsigned)npos), block(64 * NW);
 #define LAUNCH(P, S)                                                                                               \
     hipLaunchKernelGGL((k_solve_cg_wide<WF, NW, P, S>), grid, block, 0, st, perm, task_off, pos0, task0, (const P *)ptr, \
-                       slots, lambda, fs, eps, Xout, status)
+                       slots, lambda, (const float *)nullptr, fs, eps, Xout, status)
     if (ptr64) { if (s16) LAUNCH(int64_t, true); else LAUNCH(int64_t, false); }
     else       { if (s16) LAUNCH(int32_t, true); else LAUNCH(int32_t, false); }
 #undef LAUNCH
+    return hipGetLastError();
+}
+
+// ---- implicit feedback at f = 256 (Section 5.6): Theta^T Theta and the launchers in kImplicit mode ----
+// the rows [blockIdx.x * per, ...) of G as the "entries" of one work item (kGram mode), tiles to a slot
+template <int F, int NW, bool WIDE>
+__global__ __launch_bounds__(64 * NW) void k_gram_wide(const float *__restrict__ G, int64_t n, int per,
+                                                        float *__restrict__ slots) {
+    constexpr int NT = tiles_1d(F), SLOT = slot_floats(F);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t s0 = (int64_t)blockIdx.x * per;
+    const int len = (int)((s0 + per < n) ? per : n - s0);   // >= 1 by the choice of the grid
+    float *out = slots + (int64_t)blockIdx.x * SLOT;
+    for_wave<NW>(wave, [&](auto wt) {
+        constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
+        v4f acc[tiles_in(ROWS)];
+#pragma unroll
+        for (int q = 0; q < tiles_in(ROWS); ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
+        float b[NT];
+        accumulate_tiles<F, kWideInVgpr, kDepthWideSlots, WIDE, ALS_F32, ROWS, false, kGram>(nullptr, nullptr, G, uniform64(s0),
+                                                                                              len, acc, b);
+#pragma unroll
+        for (int R = 0; R < NT; ++R)
+            if ((ROWS >> R) & 1u) {
+#pragma unroll
+                for (int C = 0; C <= R; ++C) {
+                    const v4f a = acc[tiles_below(ROWS, R) + C];
+                    const int T = R * (R + 1) / 2 + C;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) out[(T * 4 + r) * 64 + lane] = a[r];
+                }
+            }
+    });
+}
+
+hipError_t launch_gram_wide(bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots) {
+    if (nslots <= 0) return hipSuccess;
+    if (wide) hipLaunchKernelGGL((k_gram_wide<WF, NW, true>), dim3(nslots), dim3(64 * NW), 0, st, G, n, per, slots);
+    else hipLaunchKernelGGL((k_gram_wide<WF, NW, false>), dim3(nslots), dim3(64 * NW), 0, st, G, n, per, slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_hermitian_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+                                          const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                          const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                                          float alpha, float *slots) {
+    if (ntasks <= 0) return hipSuccess;
+    const dim3 grid((unsigned)ntasks), block(64 * NW);
+#define LAUNCH(P, W)                                                                                               \
+    hipLaunchKernelGGL((k_hermitian_wide<WF, NW, P, W, ALS_F32, false, kImplicit>), grid, block, 0, st, task_row,   \
+                       task_chunk, task0, chunk, (const P *)ptr, idx, val, Theta, alpha, slots)
+    if (ptr64) { if (wide) LAUNCH(int64_t, true); else LAUNCH(int64_t, false); }
+    else       { if (wide) LAUNCH(int32_t, true); else LAUNCH(int32_t, false); }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_hermitian_cg_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
+                                             int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                             const void *Theta, float lambda, float alpha, const float *gram, int fs,
+                                             float eps, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    const dim3 grid((unsigned)npos), block(64 * NW);
+#define LAUNCH(P, W)                                                                                              \
+    hipLaunchKernelGGL((k_hermitian_cg_wide<WF, NW, P, W, ALS_F32, kImplicit>), grid, block, 0, st, perm, pos0,    \
+                       (const P *)ptr, idx, val, Theta, lambda, alpha, gram, fs, eps, Xout, status)
+    if (ptr64) { if (wide) LAUNCH(int64_t, true); else LAUNCH(int64_t, false); }
+    else       { if (wide) LAUNCH(int32_t, true); else LAUNCH(int32_t, false); }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_solve_cg_wide_implicit(bool ptr64, hipStream_t st, const int32_t *perm, const int32_t *task_off,
+                                         int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
+                                         float lambda, const float *gram, int fs, float eps, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    const dim3 grid((unsigned)npos), block(64 * NW);
+    if (ptr64)
+        hipLaunchKernelGGL((k_solve_cg_wide<WF, NW, int64_t, false, kImplicit>), grid, block, 0, st, perm, task_off, pos0,
+                           task0, (const int64_t *)ptr, slots, lambda, gram, fs, eps, Xout, status);
+    else
+        hipLaunchKernelGGL((k_solve_cg_wide<WF, NW, int32_t, false, kImplicit>), grid, block, 0, st, perm, task_off, pos0,
+                           task0, (const int32_t *)ptr, slots, lambda, gram, fs, eps, Xout, status);
     return hipGetLastError();
 }
 

@@ -290,13 +290,17 @@ __device__ __forceinline__ void ldlt_wide(v4f (&acc)[tiles_tri(F) / NW], LdltSha
 #ifndef ALS_LDLT_WIDE_DEPTH
 #define ALS_LDLT_WIDE_DEPTH 3
 #endif
-template <int F, int NW, typename PtrT, bool WIDE, int ET>
+// MODE kImplicit (Section 5.6): weighted entries, the accumulators start from the tiles of Theta^T Theta (gram),
+// regulariser lambda instead of lambda * n_u
+template <int F, int NW, typename PtrT, bool WIDE, int ET, int MODE = kExplicit>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDLT_WIDE_EU, ALS_LDLT_WIDE_EU))) void k_hermitian_ldlt_wide(const int32_t *__restrict__ perm, int64_t pos0,
                                                                   const PtrT *__restrict__ ptr,
                                                                   const int32_t *__restrict__ idx,
                                                                   const float *__restrict__ val,
                                                                   const void *__restrict__ Theta, float lambda,
+                                                                  float alpha, const float *__restrict__ gram,
                                                                   float *__restrict__ Xout, int *__restrict__ status) {
+    static_assert(MODE == kExplicit || ET == ALS_F32, "implicit feedback: fp32 factors");
     constexpr int NT = tiles_1d(F), NTW = tiles_tri(F) / NW;
     __shared__ LdltShared<F> sh;
     __shared__ float bsrc[F];
@@ -315,26 +319,29 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDL
     for (int q = 0; q < NTW; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     for_wave<NW>(wave, [&](auto wt) ALS_INLINE {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);
+        if constexpr (MODE == kImplicit) load_tiles_rows<F, ROWS>(gram, acc);
         float b[NT];
         // 16-bit inputs: on the 16-bit matrix cores, the rows gathered once per workgroup (tiles16.h)
         if constexpr (ET != ALS_F32)
             accumulate_tiles16_shared<F, NW, WIDE, ET, true, ROWS>(idx, val, Theta, uniform64(s0), len, acc, b, stage16, wave);
         else
-            accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+            accumulate_tiles<F, kLdltInVgpr, ALS_LDLT_WIDE_DEPTH, WIDE, ET, ROWS, true, MODE>(idx, val, Theta, uniform64(s0),
+                                                                                              len, acc, b, alpha);
 #pragma unroll
         for (int R = 0; R < NT; ++R)
             if (((ROWS >> R) & 1u) && lane < 16) bsrc[16 * R + lane] = b[R];
     });
     __syncthreads();
-    ldlt_wide<F, NW>(acc, sh, bsrc, lambda * (float)len, xg, status);
+    ldlt_wide<F, NW>(acc, sh, bsrc, MODE == kImplicit ? lambda : lambda * (float)len, xg, status);
 }
 
 // rows whose A_u sits in a (reduced) fp32 slot
-template <int F, int NW, typename PtrT>
+template <int F, int NW, typename PtrT, int MODE = kExplicit>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDLT_WIDE_EU, ALS_LDLT_WIDE_EU))) void k_solve_ldlt_wide(const int32_t *__restrict__ perm,
                                                               const int32_t *__restrict__ task_off, int64_t pos0,
                                                               int64_t task0, const PtrT *__restrict__ ptr,
                                                               const float *__restrict__ slots, float lambda,
+                                                              const float *__restrict__ gram,
                                                               float *__restrict__ Xout, int *__restrict__ status) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), NTW = NTILES / NW, SLOT = slot_floats(F);
     __shared__ LdltShared<F> sh;
@@ -359,10 +366,14 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(ALS_LDL
                     const int T = R * (R + 1) / 2 + C, q = tiles_below(ROWS, R) + C;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) acc[q][r] = slot[(T * 4 + r) * 64 + lane];
+                    if constexpr (MODE == kImplicit) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[q][r] += gram[(T * 4 + r) * 64 + lane];
+                    }
                 }
             }
     });
-    ldlt_wide<F, NW>(acc, sh, slot + NTILES * 256, lambda * (float)n_u, xg, status);
+    ldlt_wide<F, NW>(acc, sh, slot + NTILES * 256, MODE == kImplicit ? lambda : lambda * (float)n_u, xg, status);
 }
 
 // launch of the fused kernel for one element type of the gathered factor (one translation unit each: the
@@ -375,7 +386,7 @@ hipError_t launch_hermitian_ldlt_wide_et(bool ptr64, bool wide, hipStream_t st, 
     const dim3 grid((unsigned)npos), block(64 * NW);
 #define LAUNCH(P, W)                                                                                              \
     hipLaunchKernelGGL((k_hermitian_ldlt_wide<WF, NW, P, W, ET>), grid, block, 0, st, perm, pos0, (const P *)ptr, idx, \
-                       val, Theta, lambda, Xout, status)
+                       val, Theta, lambda, 0.f, (const float *)nullptr, Xout, status)
     if (ptr64) { if (wide) LAUNCH(int64_t, true); else LAUNCH(int64_t, false); }
     else       { if (wide) LAUNCH(int32_t, true); else LAUNCH(int32_t, false); }
 #undef LAUNCH

@@ -23,10 +23,10 @@ hipError_t launch_solve_ldlt_wide(bool ptr64, hipStream_t st, const int32_t *per
     const dim3 grid((unsigned)npos), block(64 * NW);
     if (ptr64)
         hipLaunchKernelGGL((k_solve_ldlt_wide<WF, NW, int64_t>), grid, block, 0, st, perm, task_off, pos0, task0,
-                           (const int64_t *)ptr, slots, lambda, Xout, status);
+                           (const int64_t *)ptr, slots, lambda, (const float *)nullptr, Xout, status);
     else
         hipLaunchKernelGGL((k_solve_ldlt_wide<WF, NW, int32_t>), grid, block, 0, st, perm, task_off, pos0, task0,
-                           (const int32_t *)ptr, slots, lambda, Xout, status);
+                           (const int32_t *)ptr, slots, lambda, (const float *)nullptr, Xout, status);
     return hipGetLastError();
 }
 

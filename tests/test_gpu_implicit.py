@@ -34,7 +34,7 @@ def P():
     return pkg
 
 
-@pytest.mark.parametrize("f,n", [(16, 1), (16, 777), (32, 5001), (64, 300), (100, 4099), (128, 2500)])
+@pytest.mark.parametrize("f,n", [(16, 1), (16, 777), (32, 5001), (64, 300), (100, 4099), (128, 2500), (256, 1), (256, 3001)])
 def test_gram_matches_double_precision(P, f, n):
     G = W.random_factors(n, f, seed=100 + f, scale=0.4) + 0.1
     als = P.Als(f)
@@ -184,9 +184,7 @@ def test_implicit_argument_errors(P):
         als._check(als._lib.als_update_rows_implicit(als._ctx, __import__("ctypes").byref(csr.desc), T.data_ptr(), LAM,
                                                      ALPHA, w.f, X.data_ptr()))
     als.close()
-    als = P.Als(256)
-    T256 = torch.zeros((w.n, 256), device="cuda:0")
-    X256 = torch.zeros((w.m, 256), device="cuda:0")
+    als = P.Als(w.f, solver=P.SOLVER_CG, herm_dtype=P.BF16)   # reduced-precision storage of A_u: explicit mode only
     with pytest.raises(P.AlsError):
-        als.update_rows_implicit(csr, T256, LAM, ALPHA, X256)
+        als.update_rows_implicit(csr, T, LAM, ALPHA, X)
     als.close()

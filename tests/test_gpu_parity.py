@@ -277,15 +277,14 @@ def test_factor_matrix_beyond_4_gib_uses_64_bit_offsets(P, f, n):
         ref = oracle.update_rows(ptr, remap, val, rows_val, 0.5)
         assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
         als.close()
-    if f <= 128:
-        # implicit mode: the zero rows add nothing to Theta^T Theta, so the compact problem is the same problem
-        als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=256)
-        X = torch.zeros((len(degrees), f), device="cuda:0")
-        als.update_rows_implicit(sp, Theta, 0.4, 2.0, X)
-        als.synchronize()
-        ref = oracle.implicit_update_rows(ptr, remap, val, rows_val, 0.4, 2.0)
-        assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
-        als.close()
+    # implicit mode: the zero rows add nothing to Theta^T Theta, so the compact problem is the same problem
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=256)
+    X = torch.zeros((len(degrees), f), device="cuda:0")
+    als.update_rows_implicit(sp, Theta, 0.4, 2.0, X)
+    als.synchronize()
+    ref = oracle.implicit_update_rows(ptr, remap, val, rows_val, 0.4, 2.0)
+    assert _row_rel_err(X.cpu().numpy(), ref).max() <= TOL_EXACT
+    als.close()
     del Theta
     torch.cuda.empty_cache()
 

@@ -76,7 +76,7 @@ def test_explicit_half_sweep(P, mat, f, solver, chunk, p64):
     assert err[1:].max() <= tol, (int(err[1:].argmax()) + 1, float(err.max()))
 
 
-@pytest.mark.parametrize("f,solver,chunk", [(f, s, c) for f in (16, 32, 64, 100, 128) for s in ("cholesky", "cg")
+@pytest.mark.parametrize("f,solver,chunk", [(f, s, c) for f in (16, 32, 64, 100, 128, 256) for s in ("cholesky", "cg")
                                            for c in (0, 128)])
 def test_implicit_half_sweep(P, mat, f, solver, chunk):
     degrees, ptr, idx, val = mat
