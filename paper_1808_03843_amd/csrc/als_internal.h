@@ -75,6 +75,8 @@ struct Plan {                     // per sparse matrix, built once and cached
     int32_t *task_off = nullptr;  // DEVICE [nrows+1] first work item of the row at each perm position
     int32_t *task_row = nullptr;  // DEVICE [ntasks]
     int32_t *task_chunk = nullptr;// DEVICE [ntasks]
+    int32_t *task_order = nullptr;// DEVICE [work items of the slot path]: launch order inside every batch (see ensure_order)
+    int64_t order_cap = -1;       // the batch capacity task_order was built for
     int32_t *task_off_host = nullptr; // HOST copy of task_off
     int64_t ntasks = 0;
     int64_t split_pos = 0;        // perm positions [0, split_pos): rows with >= chunk entries (slot path)
@@ -89,7 +91,7 @@ constexpr int kStatusNonFinite = 2;
 // et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16)
 // s16: slots hold bf16 tiles (slot_words16) instead of fp32 tiles (slot_floats)
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
-                            const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                            const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots);
 
 // solver: ALS_SOLVER_CG or ALS_SOLVER_CHOLESKY (the latter with fp32 factor inputs only)
@@ -102,7 +104,7 @@ hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStre
 // f = 256 (wide.hip): a system is shared by the wavefronts of one workgroup.  Same arguments as the
 // launchers above; Algorithm 1 only (the exact solver at this width works on slots in LDS, solve.hip).
 hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
-                                 const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                                 const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                                  const int32_t *idx, const float *val, const void *Theta, float *slots);
 hipError_t launch_hermitian_cg_wide(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
                                     int64_t npos, const void *ptr, const int32_t *idx, const float *val,
@@ -118,7 +120,7 @@ hipError_t launch_solve_ldlt_wide(bool ptr64, hipStream_t st, const int32_t *per
 // first stage and of the three implicit launchers below
 hipError_t launch_gram_wide(bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots);
 hipError_t launch_hermitian_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
-                                          const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                          const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                           const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                           float alpha, float *slots);
 hipError_t launch_hermitian_cg_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *perm, int64_t pos0,
@@ -157,7 +159,7 @@ hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t
 hipError_t launch_tiles_to_dense(int f, hipStream_t st, const float *tiles, float *out);
 hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B, double *out3);
 hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
-                                     const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                     const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                      const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                      float alpha, float *slots);
 hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
@@ -177,6 +179,9 @@ hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr
 hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
+// key[t] = index of the first stored entry of work item t, t < ntasks (DEVICE arrays)
+hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
+                          const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key);
 
 // transpose.hip
 hipError_t transpose_csr(bool ptr64, hipStream_t st, int64_t nrows, int64_t ncols, int64_t nnz, const void *ptr,

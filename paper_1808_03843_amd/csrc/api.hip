@@ -21,6 +21,10 @@ bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
 }
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
+#ifndef ALS_TASK_ORDER
+#define ALS_TASK_ORDER 1
+#endif
+constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work items of a batch (ensure_order)
 
 struct TimedLaunch { hipEvent_t a, b; int kernel; };
 }  // namespace
@@ -62,7 +66,7 @@ int fail_hip(als_ctx *ctx, hipError_t e, const char *what) {
     } while (0)
 
 void free_plan(Plan &p) {
-    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk);
+    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk); hipFree(p.task_order);
     delete[] p.task_off_host;
     p = Plan();
 }
@@ -153,6 +157,49 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     return ALS_OK;
 }
 
+// largest end with off[end] - off[pos] <= cap (at least pos + 1): the rows of one batch of the slot path
+int64_t batch_end(const int32_t *off, int64_t pos, int64_t slot_rows, int64_t cap) {
+    int64_t lo = pos + 1, hi = slot_rows;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Launch order of the work items inside every batch of the slot path.  The entries of a row are sorted by
+// index, so a work item (a chunk of a long row) gathers from a band of the factor matrix that starts at its first
+// index; workgroups are dispatched in launch order, and ordering the work items of a batch by that first index
+// (instead of row by row, which puts disjoint bands side by side) makes the work items in flight gather from the
+// same band, which then stays in the L2.  The slot of a work item is still its index in the batch.
+int ensure_order(als_ctx *ctx, Plan *p, const als_sparse *a, int64_t cap) {
+    if (p->order_cap == cap) return ALS_OK;
+    const int32_t *off = p->task_off_host;
+    const int64_t slot_rows = p->split_pos, n = slot_rows > 0 ? off[slot_rows] : 0;
+    if (p->task_order) {
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+        HIP_TRY(ctx, hipFree(p->task_order));
+        p->task_order = nullptr;
+    }
+    p->order_cap = cap;
+    if (n == 0) return ALS_OK;
+    HIP_TRY(ctx, hipMalloc(&p->task_order, sizeof(int32_t) * (size_t)n));
+    HIP_TRY(ctx, plan_task_keys(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->idx, p->task_row, p->task_chunk, n, p->chunk,
+                                p->task_order));
+    std::vector<int32_t> key((size_t)n), order((size_t)n);
+    HIP_TRY(ctx, hipMemcpyAsync(key.data(), p->task_order, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (int64_t pos = 0; pos < slot_rows;) {
+        const int64_t end = batch_end(off, pos, slot_rows, cap);
+        int32_t *first = order.data() + off[pos], *last = order.data() + off[end];
+        for (int32_t t = off[pos]; t < off[end]; ++t) order[(size_t)t] = t;
+        std::stable_sort(first, last, [&](int32_t x, int32_t y) { return key[(size_t)x] < key[(size_t)y]; });
+        pos = end;
+    }
+    HIP_TRY(ctx, hipMemcpy(p->task_order, order.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+    return ALS_OK;
+}
+
 int ensure_slots(als_ctx *ctx, int64_t nslots, bool s16) {
     const size_t need = (size_t)nslots * (s16 ? slot_words16(ctx->cfg.f) : slot_floats(ctx->cfg.f)) * sizeof(float);
     if (ctx->slots_bytes >= need) return ALS_OK;
@@ -233,27 +280,25 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // rows shorter than a chunk are built and solved without leaving the registers (both solvers); longer
     // rows go through slots
     const int64_t slot_rows = p->split_pos;
+    rc = ensure_order(ctx, p, a, cap);
+    if (rc != ALS_OK) return rc;
+    const int32_t *order = kTaskOrder ? p->task_order : nullptr;
     int64_t pos = 0;
     while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
-        int64_t lo = pos + 1, hi = slot_rows;   // largest end with off[end]-off[pos] <= cap
-        while (lo < hi) {
-            const int64_t mid = (lo + hi + 1) >> 1;
-            if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
-        }
-        const int64_t end = lo;
+        const int64_t end = batch_end(off, pos, slot_rows, cap);
         const int64_t task0 = off[pos], ntasks = (int64_t)off[end] - off[pos];
         rc = ensure_slots(ctx, ntasks > 0 ? ntasks : 1, s16);
         if (rc != ALS_OK) return rc;
         {
             Timed t(ctx, ALS_K_HERMITIAN);
             if (implicit)
-                HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, task0,
+                HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, order, task0,
                                                        ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G, alpha,
                                                        ctx->slots));
             else
                 HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, s16, ctx->stream, p->task_row,
-                                              p->task_chunk, task0, ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G,
+                                              p->task_chunk, order, task0, ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G,
                                               ctx->slots));
         }
         {
@@ -494,7 +539,7 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     if (rc != ALS_OK) { cleanup(); return rc; }
     {
         Timed t(ctx, ALS_K_HERMITIAN);
-        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, false, ctx->stream, task_row, task_chunk, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
+        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, false, ctx->stream, task_row, task_chunk, nullptr, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
                              csr->val, Theta, ctx->slots);
     }
     if (e == hipSuccess)

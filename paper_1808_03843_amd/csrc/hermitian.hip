@@ -70,44 +70,44 @@ __global__ __launch_bounds__(256) void k_reduce_slots(const int32_t *__restrict_
 
 // dispatch on the run-time switches that are template parameters of the kernels
 template <int F, typename PtrT, bool WIDE, bool S16>
-static hipError_t herm_e(int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, int64_t task0,
+static hipError_t herm_e(int et, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, const int32_t *task_order, int64_t task0,
                          int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
                          const void *Theta, float *slots) {
     const dim3 grid((unsigned)ntasks), block(64);
     const PtrT *p = (const PtrT *)ptr;
     if (et == ALS_F32)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F32, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task_order, task0,
                            chunk, p, idx, val, Theta, 0.f, slots);
     else if (et == ALS_BF16)
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_BF16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task_order, task0,
                            chunk, p, idx, val, Theta, 0.f, slots);
     else
-        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task0,
+        hipLaunchKernelGGL((k_hermitian<F, PtrT, WIDE, ALS_F16, S16, kExplicit>), grid, block, 0, st, task_row, task_chunk, task_order, task0,
                            chunk, p, idx, val, Theta, 0.f, slots);
     return hipGetLastError();
 }
 
 template <int F, typename PtrT>
 static hipError_t herm_f(bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
-                         const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                         const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                          const int32_t *idx, const float *val, const void *Theta, float *slots) {
     if (ntasks <= 0) return hipSuccess;
-#define ARGS et, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots
+#define ARGS et, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta, slots
     if (s16) return wide ? herm_e<F, PtrT, true, true>(ARGS) : herm_e<F, PtrT, false, true>(ARGS);
     return wide ? herm_e<F, PtrT, true, false>(ARGS) : herm_e<F, PtrT, false, false>(ARGS);
 #undef ARGS
 }
 
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
-                            const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                            const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots) {
     if (f == 256)
-        return launch_hermitian_wide(ptr64, wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val,
+        return launch_hermitian_wide(ptr64, wide, et, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val,
                                      Theta, slots);
 #define CALL(FF)                                                                                                      \
-    (ptr64 ? herm_f<FF, int64_t>(wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, \
+    (ptr64 ? herm_f<FF, int64_t>(wide, et, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta, \
                                  slots)                                                                               \
-           : herm_f<FF, int32_t>(wide, et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, \
+           : herm_f<FF, int32_t>(wide, et, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta, \
                                  slots))
     ALS_FOR_F(CALL)
 #undef CALL

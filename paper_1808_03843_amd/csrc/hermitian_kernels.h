@@ -39,13 +39,14 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 // 1 + alpha * r_uv; the dense Theta^T Theta term is added by the solver kernels).
 template <int F, typename PtrT, bool WIDE, int ET, bool S16, int MODE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F, ET)))) void k_hermitian(const int32_t *__restrict__ task_row,
-                                                  const int32_t *__restrict__ task_chunk, int64_t task0, int chunk,
+                                                  const int32_t *__restrict__ task_chunk, const int32_t *__restrict__ task_order, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                   const float *__restrict__ val, const void *__restrict__ Theta,
                                                   float alpha, float *__restrict__ slots) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     const int lane = threadIdx.x;
-    const int64_t t = blockIdx.x;
+    // task_order (optional): the work item each workgroup of the launch takes (a permutation of the batch)
+    const int64_t t = task_order ? (int64_t)task_order[task0 + blockIdx.x] - task0 : (int64_t)blockIdx.x;
     const int row = task_row[task0 + t];
     const int ch = task_chunk[task0 + t];
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];

@@ -157,7 +157,7 @@ hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B
 
 // ---- the gathered kernels in implicit mode (fp32 factors, fp32 slots) ----------------------------
 template <int F, typename PtrT>
-static hipError_t herm_imp_f(bool wide, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+static hipError_t herm_imp_f(bool wide, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, const int32_t *task_order,
                              int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
                              const float *val, const void *Theta, float alpha, float *slots) {
     if (ntasks <= 0) return hipSuccess;
@@ -165,24 +165,24 @@ static hipError_t herm_imp_f(bool wide, hipStream_t st, const int32_t *task_row,
     const PtrT *p = (const PtrT *)ptr;
     if (wide)
         hipLaunchKernelGGL((k_hermitian<F, PtrT, true, ALS_F32, false, kImplicit>), grid, block, 0, st, task_row,
-                           task_chunk, task0, chunk, p, idx, val, Theta, alpha, slots);
+                           task_chunk, task_order, task0, chunk, p, idx, val, Theta, alpha, slots);
     else
         hipLaunchKernelGGL((k_hermitian<F, PtrT, false, ALS_F32, false, kImplicit>), grid, block, 0, st, task_row,
-                           task_chunk, task0, chunk, p, idx, val, Theta, alpha, slots);
+                           task_chunk, task_order, task0, chunk, p, idx, val, Theta, alpha, slots);
     return hipGetLastError();
 }
 
 hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
-                                     const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                     const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                      const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                      float alpha, float *slots) {
     if (f == 256)
-        return launch_hermitian_wide_implicit(ptr64, wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val,
+        return launch_hermitian_wide_implicit(ptr64, wide, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val,
                                               Theta, alpha, slots);
 #define CALL(FF)                                                                                                   \
-    (ptr64 ? herm_imp_f<FF, int64_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,   \
+    (ptr64 ? herm_imp_f<FF, int64_t>(wide, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta,   \
                                      alpha, slots)                                                                 \
-           : herm_imp_f<FF, int32_t>(wide, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta,   \
+           : herm_imp_f<FF, int32_t>(wide, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta,   \
                                      alpha, slots))
     ALS_FOR_F(CALL)
 #undef CALL

@@ -227,6 +227,30 @@ hipError_t plan_emit(bool, hipStream_t st, int64_t nrows, const void *, const in
     return hipGetLastError();
 }
 
+// key[t] = index of the first stored entry of work item t (its position in the gathered factor matrix)
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_task_keys(const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                   const int32_t *__restrict__ task_row,
+                                                   const int32_t *__restrict__ task_chunk, int64_t ntasks, int chunk,
+                                                   int32_t *__restrict__ key) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntasks) return;
+    key[t] = idx[(int64_t)ptr[task_row[t]] + (int64_t)task_chunk[t] * chunk];
+}
+
+hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
+                          const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key) {
+    if (ntasks <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((ntasks + 255) / 256)), block(256);
+    if (ptr64)
+        hipLaunchKernelGGL(k_task_keys<int64_t>, grid, block, 0, st, (const int64_t *)ptr, idx, task_row, task_chunk, ntasks,
+                           chunk, key);
+    else
+        hipLaunchKernelGGL(k_task_keys<int32_t>, grid, block, 0, st, (const int32_t *)ptr, idx, task_row, task_chunk, ntasks,
+                           chunk, key);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_iota(int32_t *__restrict__ p, int64_t n, int32_t first) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = first + (int32_t)i;

@@ -135,7 +135,7 @@ __device__ __forceinline__ void cg_wide(const v4f (&acc)[tiles_tri(F) / NW], Wid
 // added by the solver kernels, as for f <= 128)
 template <int F, int NW, typename PtrT, bool WIDE, int ET, bool S16, int MODE = kExplicit>
 __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__restrict__ task_row,
-                                                             const int32_t *__restrict__ task_chunk, int64_t task0,
+                                                             const int32_t *__restrict__ task_chunk, const int32_t *__restrict__ task_order, int64_t task0,
                                                              int chunk, const PtrT *__restrict__ ptr,
                                                              const int32_t *__restrict__ idx,
                                                              const float *__restrict__ val,
@@ -145,7 +145,8 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     __shared__ __attribute__((aligned(16))) uint32_t stage16[ET != ALS_F32 ? 2 * tiles_1d(F) * 256 : 4];   // operand staging, 16-bit inputs
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t t = blockIdx.x;
+    // task_order (optional): the work item each workgroup of the launch takes (a permutation of the batch)
+    const int64_t t = task_order ? (int64_t)task_order[task0 + blockIdx.x] - task0 : (int64_t)blockIdx.x;
     const int row = task_row[task0 + t];
     const int ch = task_chunk[task0 + t];
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
@@ -285,13 +286,13 @@ namespace {
 constexpr int WF = 256, NW = kWideWaves;
 
 template <typename PtrT, bool WIDE>
-hipError_t herm_wide_e(int et, bool s16, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
+hipError_t herm_wide_e(int et, bool s16, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk, const int32_t *task_order,
                        int64_t task0, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
                        const void *Theta, float *slots) {
     const dim3 grid((unsigned)ntasks), block(64 * NW);
     const PtrT *p = (const PtrT *)ptr;
 #define LAUNCH(E, S)                                                                                                \
-    hipLaunchKernelGGL((k_hermitian_wide<WF, NW, PtrT, WIDE, E, S>), grid, block, 0, st, task_row, task_chunk, task0, \
+    hipLaunchKernelGGL((k_hermitian_wide<WF, NW, PtrT, WIDE, E, S>), grid, block, 0, st, task_row, task_chunk, task_order, task0, \
                        chunk, p, idx, val, Theta, 0.f, slots)
     if (s16) {   // bf16 slots: fp32 factor inputs only
         if (et != ALS_F32) return hipErrorInvalidValue;
@@ -321,10 +322,10 @@ hipError_t herm_cg_wide_e(int et, hipStream_t st, const int32_t *perm, int64_t p
 }  // namespace
 
 hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
-                                 const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
+                                 const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                                  const int32_t *idx, const float *val, const void *Theta, float *slots) {
     if (ntasks <= 0) return hipSuccess;
-#define ARGS et, s16, st, task_row, task_chunk, task0, ntasks, chunk, ptr, idx, val, Theta, slots
+#define ARGS et, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val, Theta, slots
     if (ptr64) return wide ? herm_wide_e<int64_t, true>(ARGS) : herm_wide_e<int64_t, false>(ARGS);
     return wide ? herm_wide_e<int32_t, true>(ARGS) : herm_wide_e<int32_t, false>(ARGS);
 #undef ARGS
@@ -395,14 +396,14 @@ hipError_t launch_gram_wide(bool wide, hipStream_t st, const float *G, int64_t n
 }
 
 hipError_t launch_hermitian_wide_implicit(bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
-                                          const int32_t *task_chunk, int64_t task0, int64_t ntasks, int chunk,
+                                          const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                           const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                           float alpha, float *slots) {
     if (ntasks <= 0) return hipSuccess;
     const dim3 grid((unsigned)ntasks), block(64 * NW);
 #define LAUNCH(P, W)                                                                                               \
     hipLaunchKernelGGL((k_hermitian_wide<WF, NW, P, W, ALS_F32, false, kImplicit>), grid, block, 0, st, task_row,   \
-                       task_chunk, task0, chunk, (const P *)ptr, idx, val, Theta, alpha, slots)
+                       task_chunk, task_order, task0, chunk, (const P *)ptr, idx, val, Theta, alpha, slots)
     if (ptr64) { if (wide) LAUNCH(int64_t, true); else LAUNCH(int64_t, false); }
     else       { if (wide) LAUNCH(int32_t, true); else LAUNCH(int32_t, false); }
 #undef LAUNCH
