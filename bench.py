@@ -55,7 +55,7 @@ def cpu_baseline(w, a_host, stride):
 # summed over those dispatches, scaled by what the same counters read for a copy of known size (2 KiB and
 # 1 KiB per count).  Counters cannot be read from inside this process, so the figure is only reported for
 # the configuration it was measured on.
-MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 4096): 42.6e9 + 1.07e9}
+MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 4096): 35.1e9 + 1.07e9}
 
 
 def measured_traffic(w, args, chunk, launches):
