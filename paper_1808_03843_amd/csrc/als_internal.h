@@ -80,6 +80,7 @@ struct Plan {                     // per sparse matrix, built once and cached
     int32_t *task_off_host = nullptr; // HOST copy of task_off
     int64_t ntasks = 0;
     int64_t split_pos = 0;        // perm positions [0, split_pos): rows with >= chunk entries (slot path)
+    int64_t rows_ge[33] = {};     // rows_ge[c]: rows with at least 2^(c-1) entries (class >= c) = perm positions [0, rows_ge[c]); rows_ge[0] = nrows
 };
 
 // status word bits set by kernels
@@ -138,6 +139,11 @@ hipError_t launch_solve_ldlt_wide_implicit(bool ptr64, hipStream_t st, const int
                                            int64_t pos0, int64_t npos, int64_t task0, const void *ptr,
                                            const float *slots, float lambda, const float *gram, float *Xout,
                                            int *status);
+// exact update in the dual form for rows with fewer than 16 * ntd entries (dual.hip); fp32 factors
+bool has_dual_exact(int f, int ntd);
+hipError_t launch_dual_exact(int f, int ntd, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0,
+                             int64_t npos, const void *ptr, const int32_t *idx, const float *val, const float *Theta,
+                             float lambda, float *Xout, int *status);
 hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);

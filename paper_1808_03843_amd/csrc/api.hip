@@ -24,7 +24,11 @@ constexpr int kMaxPlans = 4;
 #ifndef ALS_TASK_ORDER
 #define ALS_TASK_ORDER 1
 #endif
-constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work items of a batch (ensure_order)
+constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;
+#ifndef ALS_DUAL_EXACT
+#define ALS_DUAL_EXACT 1
+#endif
+constexpr bool kDualExact = ALS_DUAL_EXACT != 0;   // dual-form exact solve of rows with n_u < f (dual.hip)   // band order of the work items of a batch (ensure_order)
 
 struct TimedLaunch { hipEvent_t a, b; int kernel; };
 }  // namespace
@@ -141,6 +145,8 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
         while ((1 << j) < ctx->cfg.chunk) ++j;
         p.split_pos = class_start[kPlanClasses - 1 - j];
     }
+    for (int c = 0; c <= 32; ++c)   // class c = 1 + floor(log2 n_u) (0 for empty rows), heaviest class first in perm
+        p.rows_ge[c] = c == 0 ? m : (c < kPlanClasses ? class_start[kPlanClasses - c] : 0);
     HIP_TRY(ctx, plan_tasks(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, &ctx->scratch,
                             &ctx->scratch_bytes));
     p.task_off_host = new (std::nothrow) int32_t[(size_t)m + 1];
@@ -323,15 +329,30 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         }
         pos = end;
     }
-    if (slot_rows < m) {
+    // Exact solver, fp32 factors: rows with fewer entries than features are solved in the dual form, an
+    // n_u x n_u system (dual.hip).  They are the tail of perm: fewer than 2^(c-1) entries from rows_ge[c] on.
+    int64_t fused_end = m;
+    if (kDualExact && !implicit && !cg && ctx->cfg.factor_dtype == ALS_F32) {
+        Timed t(ctx, ALS_K_FUSED);
+        for (int c = 6; c <= 8; ++c) {   // fewer than 32, 64, 128 entries: 2, 4, 8 tiles of 16 entries
+            const int ntd = 1 << (c - 5);
+            if (16 * ntd > f || !has_dual_exact(f, ntd)) break;
+            const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
+            if (lo < fused_end)
+                HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->stream, p->perm, lo, fused_end - lo, a->ptr, a->idx, a->val,
+                                               (const float *)G, lambda, Out, ctx->status));
+            if (lo < fused_end) fused_end = lo;
+        }
+    }
+    if (slot_rows < fused_end) {
         Timed t(ctx, ALS_K_FUSED);
         if (implicit)
             HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, slot_rows,
-                                                      m - slot_rows, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
+                                                      fused_end - slot_rows, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
                                                       ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
         else
             HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
-                                             slot_rows, m - slot_rows, a->ptr, a->idx, a->val, G, lambda,
+                                             slot_rows, fused_end - slot_rows, a->ptr, a->idx, a->val, G, lambda,
                                              ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
     }
     return ALS_OK;

@@ -87,6 +87,32 @@ def test_hermitian_and_bias_on_the_16_bit_matrix_cores(P, f, name):
     als.close()
 
 
+@pytest.mark.parametrize("f", [100, 128, 256])
+@pytest.mark.parametrize("p64", [False, True])
+def test_exact_rows_with_fewer_entries_than_features(P, f, p64):
+    """The exact solver handles rows with fewer than 32 / 64 / 128 entries in the dual form (an n_u x n_u system).
+    Every degree from 0 to 140, so that both sides of every switch and the padding of every size are hit,
+    non-integer ratings, against the oracle's f x f solve."""
+    n = 3000
+    degrees = list(range(0, 141)) + [200, 500]
+    rng = np.random.default_rng(21)
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, int)]).astype(np.int32)
+    val = (rng.standard_normal(int(ptr[-1])) * 2.5 + 3.0).astype(np.float32)
+    Theta = W.random_factors(n, f, seed=31 + f, scale=0.4)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val, ptr64=p64)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY)
+    X = torch.full((len(degrees), f), 7.0, device="cuda:0")
+    als.update_rows(sp, _dev(Theta), 0.3, X)
+    als.synchronize()
+    got = X.cpu().numpy()
+    ref = oracle.update_rows(ptr, idx, val, Theta, 0.3)
+    assert np.all(got[0] == 0.0)
+    err = _row_rel_err(got[1:], ref[1:])
+    assert err.max() <= TOL_EXACT, (int(err.argmax()) + 1, float(err.max()))
+    als.close()
+
+
 @pytest.mark.parametrize("chunk", [64, 1024])
 def test_one_exact_sweep_on_tiny(P, chunk):
     w = W.TINY

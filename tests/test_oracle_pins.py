@@ -301,3 +301,21 @@ def test_rmse_f32_variant_equals_the_double_one_on_float_inputs():
     X = W.random_factors(w.m, w.f, seed=1, scale=0.3)
     T = W.random_factors(w.n, w.f, seed=2, scale=0.3)
     assert oracle.rmse_f32(a.ptr, a.idx, a.val, X, T) == oracle.rmse(a.ptr, a.idx, a.val, X, T)
+
+
+@pytest.mark.parametrize("f,d", [(8, 1), (8, 5), (16, 15), (40, 31), (100, 63)])
+def test_row_update_equals_the_dual_form(f, d):
+    """For a row with fewer entries than features the minimiser of eq. (2) is also x = G^T y with
+    (G G^T + lambda n I_n) y = r (push-through identity), the form the library solves for such rows.  The oracle
+    forms the f x f system; the dual one is solved here with a library routine."""
+    rng = np.random.default_rng(40 + f + d)
+    n = 200
+    Theta = W.random_factors(n, f, seed=3 * f + d, scale=0.4)
+    cols = np.sort(rng.choice(n, d, replace=False)).astype(np.int32)
+    r = rng.standard_normal(d).astype(np.float32) * 3
+    lam = 0.07
+    ptr = np.array([0, d], np.int64)
+    x = oracle.update_rows(ptr, cols, r, Theta, lam)[0]
+    G = Theta[cols].astype(np.float64)
+    y = np.linalg.solve(G @ G.T + lam * d * np.eye(d), r.astype(np.float64))
+    assert np.abs(x - G.T @ y).max() <= 1e-10 * max(np.abs(x).max(), 1e-30)
