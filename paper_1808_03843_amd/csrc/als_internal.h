@@ -139,10 +139,10 @@ hipError_t launch_solve_ldlt_wide_implicit(bool ptr64, hipStream_t st, const int
                                            int64_t pos0, int64_t npos, int64_t task0, const void *ptr,
                                            const float *slots, float lambda, const float *gram, float *Xout,
                                            int *status);
-// exact update in the dual form for rows with fewer than 16 * ntd entries (dual.hip); fp32 factors
+// exact update in the dual form for rows with fewer than 16 * ntd entries (dual.hip)
 bool has_dual_exact(int f, int ntd);
-hipError_t launch_dual_exact(int f, int ntd, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0,
-                             int64_t npos, const void *ptr, const int32_t *idx, const float *val, const float *Theta,
+hipError_t launch_dual_exact(int f, int ntd, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+                             int64_t npos, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                              float lambda, float *Xout, int *status);
 hipError_t launch_solve_cg_wide(bool ptr64, bool s16, hipStream_t st, const int32_t *perm, const int32_t *task_off,
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,

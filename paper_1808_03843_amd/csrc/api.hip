@@ -329,18 +329,18 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         }
         pos = end;
     }
-    // Exact solver, fp32 factors: rows with fewer entries than features are solved in the dual form, an
+    // Exact solver: rows with fewer entries than features are solved in the dual form, an
     // n_u x n_u system (dual.hip).  They are the tail of perm: fewer than 2^(c-1) entries from rows_ge[c] on.
     int64_t fused_end = m;
-    if (kDualExact && !implicit && !cg && ctx->cfg.factor_dtype == ALS_F32) {
+    if (kDualExact && !implicit && !cg) {
         Timed t(ctx, ALS_K_FUSED);
         for (int c = 6; c <= 8; ++c) {   // fewer than 32, 64, 128 entries: 2, 4, 8 tiles of 16 entries
             const int ntd = 1 << (c - 5);
             if (16 * ntd > f || !has_dual_exact(f, ntd)) break;
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
             if (lo < fused_end)
-                HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->stream, p->perm, lo, fused_end - lo, a->ptr, a->idx, a->val,
-                                               (const float *)G, lambda, Out, ctx->status));
+                HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype, ctx->stream, p->perm, lo, fused_end - lo, a->ptr,
+                                               a->idx, a->val, G, lambda, Out, ctx->status));
             if (lo < fused_end) fused_end = lo;
         }
     }

@@ -17,10 +17,11 @@
 
 namespace als {
 
-template <int F, int NTD, typename PtrT>
+// ET: element type of the gathered factor (16-bit rows are widened on load: the products are those of the fp32 path)
+template <int F, int NTD, typename PtrT, int ET>
 __global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ perm, int64_t pos0,
                                                    const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                   const float *__restrict__ val, const float *__restrict__ Theta,
+                                                   const float *__restrict__ val, const void *__restrict__ Theta,
                                                    float lambda, float *__restrict__ Xout, int *__restrict__ status) {
     constexpr int N = 16 * NTD, NTILES = tiles_tri(N), NS = (F + 15) / 16;   // NS blocks of 16 features
     __shared__ float tbuf[16 * 17];
@@ -34,7 +35,8 @@ __global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ p
         return;
     }
     // entry 16T + i of the row: its theta row (entries beyond n_u: row 0, masked) and its rating
-    const float *grow[NTD];
+    constexpr int ES = ET == ALS_F32 ? 4 : 2;
+    const char *grow[NTD];
     bool live[NTD];
     float rhs[NTD];
 #pragma unroll
@@ -44,12 +46,19 @@ __global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ p
         const int64_t at = s0 + (live[T] ? e : 0);
         const int c = idx[at];
         rhs[T] = live[T] ? val[at] : 0.f;
-        grow[T] = Theta + (int64_t)c * F;
+        grow[T] = reinterpret_cast<const char *>(Theta) + (int64_t)c * (F * ES);
     }
     auto features = [&](int T, int s) -> v4f {   // features 16s + 4kq .. + 3 of entry 16T + i, zero where there is none
         const int ft = 16 * s + 4 * kq;
         v4f g = (v4f){0.f, 0.f, 0.f, 0.f};
-        if (live[T] && ft < F) g = *reinterpret_cast<const v4f *>(grow[T] + ft);   // F % 4 == 0: whole or nothing
+        if (live[T] && ft < F) {   // F % 4 == 0: whole or nothing
+            if constexpr (ET == ALS_F32) {
+                g = *reinterpret_cast<const v4f *>(grow[T] + 4 * ft);
+            } else {
+                const uint2 w = *reinterpret_cast<const uint2 *>(grow[T] + 2 * ft);
+                g = (v4f){widen_lo<ET>(w.x), widen_hi<ET>(w.x), widen_lo<ET>(w.y), widen_hi<ET>(w.y)};
+            }
+        }
         return g;
     };
     static_assert(F % 4 == 0);
@@ -104,16 +113,19 @@ __global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ p
 }
 
 template <int F, int NTD>
-static hipError_t dual_n(bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
-                         const void *ptr, const int32_t *idx, const float *val, const float *Theta, float lambda,
+static hipError_t dual_n(bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                         const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
                          float *Xout, int *status) {
     const dim3 grid((unsigned)npos), block(64);
-    if (ptr64)
-        hipLaunchKernelGGL((k_dual_exact<F, NTD, int64_t>), grid, block, 0, st, perm, pos0, (const int64_t *)ptr, idx, val,
-                           Theta, lambda, Xout, status);
-    else
-        hipLaunchKernelGGL((k_dual_exact<F, NTD, int32_t>), grid, block, 0, st, perm, pos0, (const int32_t *)ptr, idx, val,
-                           Theta, lambda, Xout, status);
+#define LAUNCH(P, E)                                                                                            \
+    hipLaunchKernelGGL((k_dual_exact<F, NTD, P, E>), grid, block, 0, st, perm, pos0, (const P *)ptr, idx, val, Theta, \
+                       lambda, Xout, status)
+    if (ptr64) {
+        if (et == ALS_F32) LAUNCH(int64_t, ALS_F32); else if (et == ALS_BF16) LAUNCH(int64_t, ALS_BF16); else LAUNCH(int64_t, ALS_F16);
+    } else {
+        if (et == ALS_F32) LAUNCH(int32_t, ALS_F32); else if (et == ALS_BF16) LAUNCH(int32_t, ALS_BF16); else LAUNCH(int32_t, ALS_F16);
+    }
+#undef LAUNCH
     return hipGetLastError();
 }
 
@@ -121,12 +133,12 @@ bool has_dual_exact(int f, int ntd) {
     return (f == 100 || f == 128) ? (ntd == 2 || ntd == 4) : f == 256 ? (ntd == 2 || ntd == 4 || ntd == 8) : false;
 }
 
-hipError_t launch_dual_exact(int f, int ntd, bool ptr64, hipStream_t st, const int32_t *perm, int64_t pos0,
-                             int64_t npos, const void *ptr, const int32_t *idx, const float *val, const float *Theta,
+hipError_t launch_dual_exact(int f, int ntd, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+                             int64_t npos, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                              float lambda, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
     if (!has_dual_exact(f, ntd)) return hipErrorInvalidValue;
-#define ARGS ptr64, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, Xout, status
+#define ARGS ptr64, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, Xout, status
     if (f == 100) return ntd == 2 ? dual_n<100, 2>(ARGS) : dual_n<100, 4>(ARGS);
     if (f == 128) return ntd == 2 ? dual_n<128, 2>(ARGS) : dual_n<128, 4>(ARGS);
     return ntd == 2 ? dual_n<256, 2>(ARGS) : ntd == 4 ? dual_n<256, 4>(ARGS) : dual_n<256, 8>(ARGS);

@@ -88,11 +88,11 @@ def test_hermitian_and_bias_on_the_16_bit_matrix_cores(P, f, name):
 
 
 @pytest.mark.parametrize("f", [100, 128, 256])
-@pytest.mark.parametrize("p64", [False, True])
-def test_exact_rows_with_fewer_entries_than_features(P, f, p64):
+@pytest.mark.parametrize("p64,name", [(False, "f32"), (True, "f32"), (False, "bf16"), (True, "f16")])
+def test_exact_rows_with_fewer_entries_than_features(P, f, p64, name):
     """The exact solver handles rows with fewer than 32 / 64 / 128 entries in the dual form (an n_u x n_u system).
     Every degree from 0 to 140, so that both sides of every switch and the padding of every size are hit,
-    non-integer ratings, against the oracle's f x f solve."""
+    non-integer ratings, against the oracle's f x f solve (on the rounded factors when the input is 16-bit)."""
     n = 3000
     degrees = list(range(0, 141)) + [200, 500]
     rng = np.random.default_rng(21)
@@ -100,10 +100,13 @@ def test_exact_rows_with_fewer_entries_than_features(P, f, p64):
     idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, int)]).astype(np.int32)
     val = (rng.standard_normal(int(ptr[-1])) * 2.5 + 3.0).astype(np.float32)
     Theta = W.random_factors(n, f, seed=31 + f, scale=0.4)
+    tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[name]
+    Td = _dev(Theta).to(tdt)
+    Theta = Td.to(torch.float32).cpu().numpy()
     sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val, ptr64=p64)
-    als = P.Als(f, solver=P.SOLVER_CHOLESKY)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY, factor_dtype=code)
     X = torch.full((len(degrees), f), 7.0, device="cuda:0")
-    als.update_rows(sp, _dev(Theta), 0.3, X)
+    als.update_rows(sp, Td, 0.3, X)
     als.synchronize()
     got = X.cpu().numpy()
     ref = oracle.update_rows(ptr, idx, val, Theta, 0.3)
