@@ -5,7 +5,7 @@
 // an n_u x n_u system instead of an f x f one (Section 2's "solve" step on the smaller of the two Gram
 // matrices; the paper always forms the f x f one).  On Netflix-shaped data most rows have n_u < f = 100.
 //
-// One wavefront per row, n_u <= 16 NTD - 1:
+// One wavefront per row, n_u <= 16 NTD - 1 (NTD = 1, 2, 3, 4, 6 or 8):
 //   K = G G^T on the matrix cores: tile (R, C) of K is a 16 x 16 x f product of the theta rows of entries
 //   16R.. and 16C..; lane (i, kq) supplies features 16s + 4kq .. + 3 of entry 16T + i (one 16-byte load per tile
 //   and block s of 16 features), i.e. the contraction runs over the features;
@@ -18,22 +18,13 @@
 namespace als {
 
 // ET: element type of the gathered factor (16-bit rows are widened on load: the products are those of the fp32 path)
-template <int F, int NTD, typename PtrT, int ET>
-__global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ perm, int64_t pos0,
-                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                   const float *__restrict__ val, const void *__restrict__ Theta,
-                                                   float lambda, float *__restrict__ Xout, int *__restrict__ status) {
+// One row of n <= 16 NTD - 1 entries starting at s0, by the calling wavefront.
+template <int F, int NTD, int ET>
+__device__ __forceinline__ void dual_row(int n, int64_t s0, const int32_t *__restrict__ idx, const float *__restrict__ val,
+                                         const void *__restrict__ Theta, float lambda, float *__restrict__ xg,
+                                         int *__restrict__ status, float *tbuf) {
     constexpr int N = 16 * NTD, NTILES = tiles_tri(N), NS = (F + 15) / 16;   // NS blocks of 16 features
-    __shared__ float tbuf[16 * 17];
     const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
-    const int row = perm[pos0 + blockIdx.x];
-    const int64_t s0 = (int64_t)ptr[row];
-    const int n = (int)((int64_t)ptr[row + 1] - s0);   // <= N - 1 by the caller's choice of rows
-    float *xg = Xout + (int64_t)row * F;
-    if (n == 0) {
-        for (int q = lane; q < F; q += 64) xg[q] = 0.f;
-        return;
-    }
     // entry 16T + i of the row: its theta row (entries beyond n_u: row 0, masked) and its rating
     constexpr int ES = ET == ALS_F32 ? 4 : 2;
     const char *grow[NTD];
@@ -110,6 +101,29 @@ __global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ p
         }
     }
     if (bad) atomicOr(status, kStatusNonFinite);
+}
+
+// One wavefront per row; the rows of a launch have fewer than 16 NTD entries, and those in the lower part of that
+// range take a system of 3/4 (NTD >= 4) or 1/2 (NTD == 2) the size: the choice is uniform over the wavefront.
+template <int F, int NTD, typename PtrT, int ET>
+__global__ __launch_bounds__(64) void k_dual_exact(const int32_t *__restrict__ perm, int64_t pos0,
+                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                   const float *__restrict__ val, const void *__restrict__ Theta,
+                                                   float lambda, float *__restrict__ Xout, int *__restrict__ status) {
+    __shared__ float tbuf[16 * 17];
+    const int row = perm[pos0 + blockIdx.x];
+    const int64_t s0 = (int64_t)ptr[row];
+    const int n = (int)((int64_t)ptr[row + 1] - s0);   // <= 16 NTD - 1 by the caller's choice of rows
+    float *xg = Xout + (int64_t)row * F;
+    if (n == 0) {
+        for (int q = threadIdx.x; q < F; q += 64) xg[q] = 0.f;
+        return;
+    }
+    constexpr int SMALL = NTD >= 4 ? 3 * NTD / 4 : NTD / 2;
+    if (n < 16 * SMALL)
+        dual_row<F, SMALL, ET>(n, s0, idx, val, Theta, lambda, xg, status, tbuf);
+    else
+        dual_row<F, NTD, ET>(n, s0, idx, val, Theta, lambda, xg, status, tbuf);
 }
 
 template <int F, int NTD>
