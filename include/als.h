@@ -81,7 +81,8 @@ typedef struct als_config {
     void *stream;         /* hipStream_t to enqueue on (NULL = the default stream)                       */
     int32_t chunk;        /* stored entries per work item, a power of two in [64, 2^20]; longer rows are
                              split (0 = default 4096)                                                    */
-    int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = about 4 GB worth)           */
+    int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = about 4 GB worth;
+                             larger values than 4,194,303 are taken as that)                                      */
     int32_t profile;      /* 1: bracket every kernel with HIP events (see als_kernel_time)               */
 } als_config;
 

@@ -83,6 +83,8 @@ struct Plan {                     // per sparse matrix, built once and cached
     int64_t rows_ge[33] = {};     // rows_ge[c]: rows with at least 2^(c-1) entries (class >= c) = perm positions [0, rows_ge[c]); rows_ge[0] = nrows
 };
 
+constexpr int kWideThreads = 512;   // threads of the largest workgroup any kernel here uses (f = 256: 8 wavefronts)
+
 // status word bits set by kernels
 constexpr int kStatusBadPivot = 1;
 constexpr int kStatusNonFinite = 2;

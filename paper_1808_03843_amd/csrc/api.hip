@@ -24,11 +24,11 @@ constexpr int kMaxPlans = 4;
 #ifndef ALS_TASK_ORDER
 #define ALS_TASK_ORDER 1
 #endif
-constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;
+constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work items of a batch (ensure_order)
 #ifndef ALS_DUAL_EXACT
 #define ALS_DUAL_EXACT 1
 #endif
-constexpr bool kDualExact = ALS_DUAL_EXACT != 0;   // dual-form exact solve of rows with n_u < f (dual.hip)   // band order of the work items of a batch (ensure_order)
+constexpr bool kDualExact = ALS_DUAL_EXACT != 0;   // dual-form exact solve of rows with n_u < f (dual.hip)
 
 struct TimedLaunch { hipEvent_t a, b; int kernel; };
 }  // namespace
@@ -112,6 +112,8 @@ struct Timed {   // brackets one launch with events when profiling is on
     }
 };
 
+int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p);
+
 // Finds or builds the plan of a matrix: degree-class permutation, work items.
 int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     for (auto &p : ctx->plans)
@@ -125,6 +127,17 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
         free_plan(p);
     }
+    const int rc = build_plan(ctx, a, p);
+    if (rc != ALS_OK) {   // nothing of a half-built plan stays behind
+        (void)hipStreamSynchronize(ctx->stream);
+        free_plan(p);
+        return rc;
+    }
+    *out = &p;
+    return ALS_OK;
+}
+
+int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
     Timed timed(ctx, ALS_K_PLAN);
     const int64_t m = a->nrows;
     const bool p64 = a->ptr_is_64 != 0;
@@ -150,7 +163,7 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     HIP_TRY(ctx, plan_tasks(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, &ctx->scratch,
                             &ctx->scratch_bytes));
     p.task_off_host = new (std::nothrow) int32_t[(size_t)m + 1];
-    if (!p.task_off_host) { free_plan(p); return fail(ctx, ALS_ENOMEM, "host allocation of the work-item offsets failed"); }
+    if (!p.task_off_host) return fail(ctx, ALS_ENOMEM, "host allocation of the work-item offsets failed");
     HIP_TRY(ctx, hipMemcpyAsync(p.task_off_host, p.task_off, sizeof(int32_t) * (size_t)(m + 1), hipMemcpyDeviceToHost,
                                 ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -159,7 +172,19 @@ int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     HIP_TRY(ctx, hipMalloc(&p.task_chunk, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
     HIP_TRY(ctx, plan_emit(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, p.task_row, p.task_chunk));
     p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz; p.chunk = ctx->cfg.chunk;
-    *out = &p;
+    return ALS_OK;
+}
+
+// A launch holds fewer than 2^32 threads.  The kernels that take one workgroup per row (or per work item) are
+// launched over pieces of at most this many workgroups.
+int64_t max_workgroups(int threads) { return (int64_t)0x7fffffff / threads; }
+
+template <typename L>
+int in_pieces(int64_t pos0, int64_t n, int64_t piece, L launch) {   // launch(first position, count) -> status
+    for (int64_t done = 0; done < n; done += piece) {
+        const int rc = launch(pos0 + done, n - done < piece ? n - done : piece);
+        if (rc != ALS_OK) return rc;
+    }
     return ALS_OK;
 }
 
@@ -332,28 +357,38 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // Exact solver: rows with fewer entries than features are solved in the dual form, an
     // n_u x n_u system (dual.hip).  They are the tail of perm: fewer than 2^(c-1) entries from rows_ge[c] on.
     int64_t fused_end = m;
+    const int64_t piece = max_workgroups(one_wave ? 64 : kWideThreads);
     if (kDualExact && !implicit && !cg) {
         Timed t(ctx, ALS_K_FUSED);
         for (int c = 6; c <= 8; ++c) {   // fewer than 32, 64, 128 entries: 2, 4, 8 tiles of 16 entries
             const int ntd = 1 << (c - 5);
             if (16 * ntd > f || !has_dual_exact(f, ntd)) break;
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
-            if (lo < fused_end)
-                HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype, ctx->stream, p->perm, lo, fused_end - lo, a->ptr,
-                                               a->idx, a->val, G, lambda, Out, ctx->status));
-            if (lo < fused_end) fused_end = lo;
+            if (lo < fused_end) {
+                rc = in_pieces(lo, fused_end - lo, max_workgroups(64), [&](int64_t pos0, int64_t npos) {
+                    HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype, ctx->stream, p->perm, pos0, npos, a->ptr,
+                                                   a->idx, a->val, G, lambda, Out, ctx->status));
+                    return (int)ALS_OK;
+                });
+                if (rc != ALS_OK) return rc;
+                fused_end = lo;
+            }
         }
     }
     if (slot_rows < fused_end) {
         Timed t(ctx, ALS_K_FUSED);
-        if (implicit)
-            HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, slot_rows,
-                                                      fused_end - slot_rows, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
-                                                      ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
-        else
-            HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
-                                             slot_rows, fused_end - slot_rows, a->ptr, a->idx, a->val, G, lambda,
-                                             ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+        rc = in_pieces(slot_rows, fused_end - slot_rows, piece, [&](int64_t pos0, int64_t npos) {
+            if (implicit)
+                HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos,
+                                                          a->ptr, a->idx, a->val, G, lambda, alpha, gram, ctx->cfg.cg_iters,
+                                                          ctx->cfg.cg_eps, Out, ctx->status));
+            else
+                HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
+                                                 pos0, npos, a->ptr, a->idx, a->val, G, lambda, ctx->cfg.cg_iters,
+                                                 ctx->cfg.cg_eps, Out, ctx->status));
+            return (int)ALS_OK;
+        });
+        if (rc != ALS_OK) return rc;
     }
     return ALS_OK;
 }
@@ -383,6 +418,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
     if (!ctx) return ALS_ENOMEM;
     ctx->cfg = *cfg;
     if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 4096;
+    if (ctx->cfg.batch_slots > max_workgroups(kWideThreads)) ctx->cfg.batch_slots = max_workgroups(kWideThreads);
     if (ctx->cfg.batch_slots == 0) {   // about 4 GB of slots
         ctx->cfg.batch_slots = 131072;
         while (ctx->cfg.batch_slots > 1024 && (size_t)ctx->cfg.batch_slots * slot_floats(cfg->f) * 4 > (4ull << 30))

@@ -77,13 +77,15 @@ template <int F, typename PtrT>
 static hipError_t sse_f(bool implicit, float alpha, hipStream_t st, const int32_t *task_row, const int32_t *task_chunk,
                         int64_t ntasks, int chunk, const void *ptr, const int32_t *idx, const float *val,
                         const float *X, const float *Theta, double *partial, double *total) {
-    if (ntasks > 0) {
+    constexpr int64_t kPiece = 0x7fffffff / 64;   // a launch holds fewer than 2^32 threads
+    for (int64_t t0 = 0; t0 < ntasks; t0 += kPiece) {
+        const dim3 grid((unsigned)(ntasks - t0 < kPiece ? ntasks - t0 : kPiece));
         if (implicit)
-            hipLaunchKernelGGL((k_sse<F, PtrT, kImplicit>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk,
-                               chunk, (const PtrT *)ptr, idx, val, X, Theta, alpha, partial);
+            hipLaunchKernelGGL((k_sse<F, PtrT, kImplicit>), grid, dim3(64), 0, st, task_row + t0, task_chunk + t0, chunk,
+                               (const PtrT *)ptr, idx, val, X, Theta, alpha, partial + t0);
         else
-            hipLaunchKernelGGL((k_sse<F, PtrT, kExplicit>), dim3((unsigned)ntasks), dim3(64), 0, st, task_row, task_chunk,
-                               chunk, (const PtrT *)ptr, idx, val, X, Theta, alpha, partial);
+            hipLaunchKernelGGL((k_sse<F, PtrT, kExplicit>), grid, dim3(64), 0, st, task_row + t0, task_chunk + t0, chunk,
+                               (const PtrT *)ptr, idx, val, X, Theta, alpha, partial + t0);
     }
     hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(1024), 0, st, partial, ntasks, total);
     return hipGetLastError();

@@ -13,6 +13,7 @@ constexpr int kWideWaves = ALS_WIDE_WAVES;   // 8: one pair of tile rows per wav
 // 17 tiles per wavefront fit the vector registers beside the operand ring; 34 go to the accumulation
 // registers (measured: the same speed)
 constexpr bool kWideInVgpr = kWideWaves >= 8;
+static_assert(64 * kWideWaves <= kWideThreads, "the host sizes its launches by kWideThreads");
 // The fused kernel is built for four wavefronts per SIMD, i.e. two workgroups per CU, so that Algorithm 1 of
 // one row (no MFMA work) overlaps the accumulation of another; that leaves registers for a gather pipeline
 // of depth 1 only (depth 3 with one workgroup per CU was 19 % slower).

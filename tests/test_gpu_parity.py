@@ -497,3 +497,36 @@ def test_held_out_rmse_follows_the_oracle(P):
         print(f"held-out rmse sweep {sweep + 1}: gpu {r_gpu:.6f} oracle {r_orc:.6f}", flush=True)
         assert abs(r_gpu - r_orc) <= 1e-4 * r_orc
     als.close()
+
+
+@pytest.mark.parametrize("f,m", [(16, (1 << 25) + 777), (256, (1 << 22) + 300)])
+def test_more_rows_than_one_launch_holds(P, f, m):
+    """A launch holds fewer than 2^32 threads, so more than 2^31 / 64 rows (2^31 / 512 at f = 256) go out in
+    several launches: one entry per row, sampled rows from both ends and the middle against the oracle, and the
+    RMSE over all work items against the closed form of the same factors."""
+    n = 1000
+    rng = np.random.default_rng(77)
+    ptr = np.arange(m + 1, dtype=np.int32)
+    idx = rng.integers(0, n, size=m, dtype=np.int32)
+    val = rng.integers(1, 6, size=m).astype(np.float32)
+    Theta = W.random_factors(n, f, seed=5, scale=0.5)
+    sp = P.SparseMatrix.from_host(m, n, ptr, idx, val)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY)
+    X = torch.full((m, f), 7.0, device="cuda:0")
+    Td = _dev(Theta)
+    als.update_rows(sp, Td, 0.1, X)
+    als.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(m - 300, m), rng.integers(0, m, 2000)]))
+    got = X[torch.from_numpy(rows).cuda()].cpu().numpy()
+    sub_ptr = np.arange(len(rows) + 1, dtype=np.int64)
+    ref = oracle.update_rows(sub_ptr, idx[rows], val[rows], Theta, 0.1)
+    err = _row_rel_err(got, ref)
+    assert err.max() <= TOL_EXACT, (int(rows[err.argmax()]), float(err.max()))
+    assert bool((X != 7.0).any(dim=1).all())          # every row was written
+    # with one entry per row the residual is r * lam / (|theta|^2 + lam): the RMSE in closed form, in double
+    t2 = (Theta.astype(np.float64) ** 2).sum(axis=1)[idx]
+    want = np.sqrt(np.mean((val.astype(np.float64) * 0.1 / (t2 + 0.1)) ** 2))
+    r = als.rmse(sp, X, Td)
+    als.close()
+    print(f"f={f} m={m}: max row err {err.max():.2e}; rmse {r:.8f} closed form {want:.8f}", flush=True)
+    assert abs(r - want) <= 1e-4 * want
