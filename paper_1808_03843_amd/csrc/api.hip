@@ -107,7 +107,12 @@ struct Timed {   // brackets one launch with events when profiling is on
     ~Timed() {
         if (a && b) {
             hipEventRecord(b, ctx->stream);
-            ctx->timed.push_back({a, b, kernel});
+            try {
+                ctx->timed.push_back({a, b, kernel});
+            } catch (...) {   // a destructor must not throw: this launch goes untimed
+                hipEventDestroy(a);
+                hipEventDestroy(b);
+            }
         }
     }
 };
@@ -393,6 +398,20 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     return ALS_OK;
 }
 
+// Runs the body of an entry point; a C++ exception (host containers running out of memory) becomes a status.
+template <typename L>
+int guarded(als_ctx *ctx, L body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        try { if (ctx) ctx->err = "host allocation failed"; } catch (...) {}
+        return ALS_ENOMEM;
+    } catch (...) {
+        try { if (ctx) ctx->err = "unexpected C++ exception"; } catch (...) {}
+        return ALS_EHIP;
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -450,25 +469,25 @@ void als_destroy(als_ctx *ctx) {
 
 const char *als_last_error(const als_ctx *ctx) { return ctx ? ctx->err.c_str() : "context is null"; }
 
-int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X) {
+static int als_update_rows_impl(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X) {
     return update(ctx, csr, Theta, lambda, f, X);
 }
 
-int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, int f, float *Theta) {
+static int als_update_cols_impl(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, int f, float *Theta) {
     return update(ctx, csc, X, lambda, f, Theta);
 }
 
-int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
+static int als_update_rows_implicit_impl(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
                              int f, float *X) {
     return update(ctx, csr, Theta, lambda, f, X, kImplicit, alpha);
 }
 
-int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, float alpha, int f,
+static int als_update_cols_implicit_impl(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, float alpha, int f,
                              float *Theta) {
     return update(ctx, csc, X, lambda, f, Theta, kImplicit, alpha);
 }
 
-int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
+static int als_gram_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
     if (!ctx) return ALS_EINVAL;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (n < 0 || n > 0x7fffffff || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
@@ -482,7 +501,7 @@ int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
 static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f,
                             bool implicit, float alpha, double *sum_out);
 
-int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda,
+static int als_implicit_loss_impl(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda,
                       float alpha, int f, double *loss_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
@@ -510,7 +529,7 @@ int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const
     return ALS_OK;
 }
 
-int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out) {
+static int als_rmse_impl(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
     if (rc != ALS_OK) return rc;
@@ -552,7 +571,7 @@ static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X,
     return ALS_OK;
 }
 
-int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, int64_t row0,
+static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, int64_t row0,
                   int64_t nrows, float *A_out, float *b_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
@@ -609,7 +628,7 @@ int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float 
     return ALS_OK;
 }
 
-int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_out, int64_t *class_start_out) {
+static int als_bin_rows_impl(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_out, int64_t *class_start_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
     if (rc != ALS_OK) return rc;
@@ -630,7 +649,7 @@ int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_
     return ALS_OK;
 }
 
-int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out) {
+static int als_csr_to_csc_impl(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, csr);
     if (rc != ALS_OK) return rc;
@@ -643,7 +662,7 @@ int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t 
     return ALS_OK;
 }
 
-int als_synchronize(als_ctx *ctx) {
+static int als_synchronize_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     int st = 0;
@@ -659,7 +678,7 @@ int als_synchronize(als_ctx *ctx) {
     return ALS_OK;
 }
 
-int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launches_out) {
+static int als_kernel_time_impl(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launches_out) {
     if (!ctx || !ms_out || !launches_out) return ALS_EINVAL;
     if (kernel_id < 0 || kernel_id >= ALS_K_COUNT) return fail(ctx, ALS_EINVAL, "unknown kernel id");
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -677,12 +696,65 @@ int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launch
     return ALS_OK;
 }
 
-int als_profile_reset(als_ctx *ctx) {
+static int als_profile_reset_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     for (auto &t : ctx->timed) { ctx->free_events.push_back(t.a); ctx->free_events.push_back(t.b); }
     ctx->timed.clear();
     return ALS_OK;
+}
+
+// The entry points proper: nothing is thrown across the C boundary.
+int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X) {
+    return guarded(ctx, [&] { return als_update_rows_impl(ctx, csr, Theta, lambda, f, X); });
+}
+
+int als_update_cols(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, int f, float *Theta) {
+    return guarded(ctx, [&] { return als_update_cols_impl(ctx, csc, X, lambda, f, Theta); });
+}
+
+int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha, int f, float *X) {
+    return guarded(ctx, [&] { return als_update_rows_implicit_impl(ctx, csr, Theta, lambda, alpha, f, X); });
+}
+
+int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X, float lambda, float alpha, int f, float *Theta) {
+    return guarded(ctx, [&] { return als_update_cols_implicit_impl(ctx, csc, X, lambda, alpha, f, Theta); });
+}
+
+int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
+    return guarded(ctx, [&] { return als_gram_impl(ctx, G, n, f, out); });
+}
+
+int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda, float alpha, int f, double *loss_out) {
+    return guarded(ctx, [&] { return als_implicit_loss_impl(ctx, csr, X, Theta, lambda, alpha, f, loss_out); });
+}
+
+int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, int f, double *rmse_out) {
+    return guarded(ctx, [&] { return als_rmse_impl(ctx, csr, X, Theta, f, rmse_out); });
+}
+
+int als_hermitian(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, int64_t row0, int64_t nrows, float *A_out, float *b_out) {
+    return guarded(ctx, [&] { return als_hermitian_impl(ctx, csr, Theta, lambda, f, row0, nrows, A_out, b_out); });
+}
+
+int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_out, int64_t *class_start_out) {
+    return guarded(ctx, [&] { return als_bin_rows_impl(ctx, csr, nclass, perm_out, class_start_out); });
+}
+
+int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out) {
+    return guarded(ctx, [&] { return als_csr_to_csc_impl(ctx, csr, cptr_out, cidx_out, cval_out); });
+}
+
+int als_synchronize(als_ctx *ctx) {
+    return guarded(ctx, [&] { return als_synchronize_impl(ctx); });
+}
+
+int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launches_out) {
+    return guarded(ctx, [&] { return als_kernel_time_impl(ctx, kernel_id, ms_out, launches_out); });
+}
+
+int als_profile_reset(als_ctx *ctx) {
+    return guarded(ctx, [&] { return als_profile_reset_impl(ctx); });
 }
 
 }  // extern "C"
