@@ -100,7 +100,12 @@ const char *als_last_error(const als_ctx *ctx);
  * (DEVICE, ncols x f, config's factor_dtype) and writes x_u into X (DEVICE,
  * nrows x f float).  With ALS_SOLVER_CG, X is also an input: row u of X is the
  * warm start of Algorithm 1.  Rows with n_u = 0 get x_u = 0.  f must equal the
- * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD). */
+ * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD).
+ * The first call on a matrix (identified by its ptr, nrows, nnz) builds its work plan and sizes the work
+ * buffers: it allocates and waits for the stream.  Later calls on the same matrix only enqueue kernels on the
+ * context's stream (no allocation, no wait, no memset), so they may be captured in a HIP graph; the same holds
+ * for als_update_cols and the implicit variants.  Errors found by the kernels (a non-positive pivot, a
+ * non-finite solution) are reported by the next als_synchronize. */
 int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X);
 
 /* "Update Theta" (eq. (3)): the same computation with csc = compressed columns

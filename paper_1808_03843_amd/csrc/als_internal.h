@@ -187,6 +187,7 @@ hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr
 hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
+hipError_t fill_zero(hipStream_t st, void *p, int64_t n);   // n 32-bit words, by a kernel
 // key[t] = index of the first stored entry of work item t, t < ntasks (DEVICE arrays)
 hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
                           const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key);

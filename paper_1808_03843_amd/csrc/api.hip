@@ -254,7 +254,7 @@ int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
     const int f = ctx->cfg.f;
     if (!ctx->gram[which]) HIP_TRY(ctx, hipMalloc(&ctx->gram[which], sizeof(float) * (size_t)slot_floats(f)));
     if (n == 0) {
-        HIP_TRY(ctx, hipMemsetAsync(ctx->gram[which], 0, sizeof(float) * (size_t)slot_floats(f), ctx->stream));
+        HIP_TRY(ctx, fill_zero(ctx->stream, ctx->gram[which], slot_floats(f)));
         return ALS_OK;
     }
     // work items of `per` rows (a multiple of 4): enough of them to fill the chip, few enough to sum quickly
@@ -669,7 +669,7 @@ static int als_synchronize_impl(als_ctx *ctx) {
     HIP_TRY(ctx, hipMemcpyAsync(&st, ctx->status, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     if (st != 0) {
-        HIP_TRY(ctx, hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream));
+        HIP_TRY(ctx, fill_zero(ctx->stream, ctx->status, 1));
         std::string msg;
         if (st & kStatusBadPivot) msg += "non-positive pivot in the exact solver; ";
         if (st & kStatusNonFinite) msg += "non-finite value in a solution; ";

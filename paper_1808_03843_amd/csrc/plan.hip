@@ -262,4 +262,16 @@ hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first) {
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void k_fill_zero(uint32_t *__restrict__ p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+// n 32-bit words set to zero by a kernel (a memset node in a captured graph is avoided on purpose)
+hipError_t fill_zero(hipStream_t st, void *p, int64_t n) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (uint32_t *)p, n);
+    return hipGetLastError();
+}
+
 }  // namespace als
