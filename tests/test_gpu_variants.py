@@ -133,8 +133,8 @@ def test_bf16_slots_and_rmse_kernels(P, mat, f):
         als.update_rows(sp, T, LAM, X)
         als.synchronize()
         outs.append(X.cpu().numpy())
-        r = als.rmse(sp, X, T)
-        ro = oracle.rmse(ptr, idx, val, outs[-1], Theta)
+        r = als.rmse(sp, torch.from_numpy(warm).cuda(), T)   # seeded factors: the oracle sees nothing the GPU computed
+        ro = oracle.rmse(ptr, idx, val, warm, Theta)
         assert abs(r - ro) <= 1e-5 * ro
         als.close()
     dev = _rel(outs[1][1:], outs[0][1:].astype(np.float64))

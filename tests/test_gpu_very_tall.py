@@ -58,7 +58,7 @@ def test_very_tall():
     del X0
     # sweep 1, rows: sampled rows against double-precision Algorithm 1
     deg = np.diff(a.ptr)
-    rows = np.unique(np.concatenate([rng.choice(w.m, 400, replace=False), np.argsort(deg)[-4:], np.argsort(deg)[:4]]))
+    rows = np.unique(np.concatenate([rng.choice(w.m, 100_000, replace=False), np.argsort(deg)[-4:], np.argsort(deg)[:4]]))
     sptr, sidx, sval = _sub_csr(a, rows)
     als.update_rows(csr, T, w.lam, X)
     als.synchronize()
@@ -73,7 +73,7 @@ def test_very_tall():
     Tw = torch.from_numpy(warm.copy()).to(dev)
     als.update_cols(csc, Xs, w.lam, Tw)
     als.synchronize()
-    ccols = np.unique(np.concatenate([rng.choice(w.n, 12, replace=False), np.argsort(col_deg)[:4]]))
+    ccols = np.unique(np.concatenate([rng.choice(w.n, 60, replace=False), np.argsort(col_deg)[:4]]))
     for v in ccols:
         s, e = int(cptr[v]), int(cptr[v + 1])
         ridx, rval = csc.idx[s:e].cpu().numpy(), csc.val[s:e].cpu().numpy()
@@ -105,12 +105,13 @@ def test_very_tall():
     assert hist[2][1] < hist[0][1]
     als.synchronize()
     # the reduced-precision mode of this configuration: bf16 factor inputs on the 16-bit matrix cores.  Sampled
-    # rows against double-precision Algorithm 1 on the same rounded factor, then two timed sweeps.
+    # rows against double-precision Algorithm 1 on a seeded, rounded factor and a seeded warm start, then two timed sweeps.
     a16 = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.BF16)
-    T16 = T.to(torch.bfloat16)
+    T16 = torch.from_numpy(Ts_host).to(dev).to(torch.bfloat16)   # seeded factor, rounded by torch
     sel = torch.from_numpy(rows).to(dev)
-    warm_rows = X[sel].cpu().numpy()
+    warm_rows = W.random_factors(len(rows), w.f, seed=24, scale=0.05)
     Xb = X.clone()
+    Xb[sel] = torch.from_numpy(warm_rows).to(dev)                # seeded warm start on the sampled rows
     a16.update_rows(csr, T16, w.lam, Xb)
     a16.synchronize()
     ref = oracle.update_rows_cg(sptr, sidx, sval, T16.to(torch.float32).cpu().numpy(), w.lam, warm_rows, fs=6)
