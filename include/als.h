@@ -169,6 +169,13 @@ int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t 
  * call flagged a non-positive pivot or a non-finite value. */
 int als_synchronize(als_ctx *ctx);
 
+/* Forgets the cached work plans (waits for the stream first).  A plan is keyed on a matrix's ptr address, nrows
+ * and nnz and holds its degree classes and work items, so the arrays of a matrix must stay unchanged between
+ * calls; call this after changing them in place, or when a different matrix with the same nrows and nnz may have
+ * been allocated at the address of an earlier one (the kernels stay inside the arrays with a stale plan, but
+ * the results are wrong).  The next call on any matrix rebuilds its plan. */
+int als_drop_plans(als_ctx *ctx);
+
 /* Kernel ids for als_kernel_time */
 #define ALS_K_HERMITIAN 0
 #define ALS_K_SOLVE 1

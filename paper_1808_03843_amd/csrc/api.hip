@@ -704,6 +704,15 @@ static int als_profile_reset_impl(als_ctx *ctx) {
     return ALS_OK;
 }
 
+static int als_drop_plans_impl(als_ctx *ctx) {
+    if (!ctx) return ALS_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto &p : ctx->plans) free_plan(p);
+    ctx->next_plan = 0;
+    return ALS_OK;
+}
+
 // The entry points proper: nothing is thrown across the C boundary.
 int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X) {
     return guarded(ctx, [&] { return als_update_rows_impl(ctx, csr, Theta, lambda, f, X); });
@@ -755,6 +764,10 @@ int als_kernel_time(als_ctx *ctx, int kernel_id, double *ms_out, int64_t *launch
 
 int als_profile_reset(als_ctx *ctx) {
     return guarded(ctx, [&] { return als_profile_reset_impl(ctx); });
+}
+
+int als_drop_plans(als_ctx *ctx) {
+    return guarded(ctx, [&] { return als_drop_plans_impl(ctx); });
 }
 
 }  // extern "C"

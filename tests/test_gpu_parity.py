@@ -530,3 +530,44 @@ def test_more_rows_than_one_launch_holds(P, f, m):
     als.close()
     print(f"f={f} m={m}: max row err {err.max():.2e}; rmse {r:.8f} closed form {want:.8f}", flush=True)
     assert abs(r - want) <= 1e-4 * want
+
+
+def test_plans_are_dropped_when_a_matrix_changes_in_place(P):
+    """The plan of a matrix is keyed on its address and sizes: after its arrays are overwritten by another matrix
+    of the same nrows and nnz (other degrees: short rows become long and the other way round), als_drop_plans
+    makes the next call build a new plan, and the result is that of the new matrix."""
+    f, n, m = 100, 3000, 600
+    rng = np.random.default_rng(8)
+    Theta = W.random_factors(n, f, seed=3, scale=0.4)
+
+    def matrix(degrees, seed):
+        r = np.random.default_rng(seed)
+        ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int32)
+        idx = np.concatenate([np.sort(r.choice(n, d, replace=False)) for d in degrees]).astype(np.int32)
+        val = r.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+        return ptr, idx, val
+
+    deg_a = rng.integers(1, 200, size=m)
+    deg_a[:5] = 2500                                  # rows that go through slots with chunk 256
+    deg_b = deg_a[::-1].copy()                        # same sum, other rows are the long ones
+    pa, ia, va = matrix(deg_a, 1)
+    pb, ib, vb = matrix(deg_b, 2)
+    assert pa[-1] == pb[-1]
+    for solver, tol in ((P.SOLVER_CG, 2e-3), (P.SOLVER_CHOLESKY, TOL_EXACT)):
+        als = P.Als(f, solver=solver, cg_iters=f, chunk=256)   # f iterations from zero: the exact solution up to fp32 rounding
+        sp = P.SparseMatrix.from_host(m, n, pa, ia, va)
+        X = torch.zeros((m, f), device="cuda:0")
+        Td = _dev(Theta)
+        als.update_rows(sp, Td, 0.2, X)
+        als.synchronize()
+        assert _row_rel_err(X.cpu().numpy(), oracle.update_rows(pa.astype(np.int64), ia, va, Theta, 0.2)).max() <= tol
+        sp.ptr.copy_(torch.from_numpy(pb))            # the same device arrays now hold matrix b
+        sp.idx.copy_(torch.from_numpy(ib))
+        sp.val.copy_(torch.from_numpy(vb))
+        als.drop_plans()
+        X.zero_()
+        als.update_rows(sp, Td, 0.2, X)
+        als.synchronize()
+        err = _row_rel_err(X.cpu().numpy(), oracle.update_rows(pb.astype(np.int64), ib, vb, Theta, 0.2))
+        als.close()
+        assert err.max() <= tol, float(err.max())
