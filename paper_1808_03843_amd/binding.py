@@ -86,6 +86,7 @@ class AlsError(RuntimeError):
 
 class SparseMatrix:
     """Device-resident compressed rows (torch tensors own the memory)."""
+    _serials = 0
 
     def __init__(self, nrows: int, ncols: int, ptr: torch.Tensor, idx: torch.Tensor, val: torch.Tensor):
         assert ptr.is_cuda and idx.is_cuda and val.is_cuda
@@ -96,6 +97,8 @@ class SparseMatrix:
         self.nnz = int(idx.numel())
         self.desc = AlsSparse(self.nrows, self.ncols, self.nnz, self.ptr.data_ptr(),
                               1 if ptr.dtype == torch.int64 else 0, self.idx.data_ptr(), self.val.data_ptr())
+        SparseMatrix._serials += 1
+        self.serial = SparseMatrix._serials   # tells two matrices apart that torch put at the same address
 
     @staticmethod
     def from_host(nrows, ncols, ptr, idx, val, device="cuda:0", ptr64: Optional[bool] = None) -> "SparseMatrix":
@@ -126,6 +129,7 @@ class Als:
             self._ctx = ctypes.c_void_p()
             raise AlsError(rc, "als_create failed (unsupported f / solver / dtype, or no such device)")
         self.f = f
+        self._plan_owner = {}
         self.factor_torch_dtype = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[factor_dtype]
 
     def close(self):
@@ -138,6 +142,16 @@ class Als:
             self.close()
         except Exception:
             pass
+
+    def _matrix(self, sp: "SparseMatrix"):
+        """Descriptor of a matrix for a call that uses its cached plan.  The library keys plans on the address of
+        ptr; when torch has handed the address of a freed matrix to a new one, the plans are dropped first."""
+        key = sp.desc.ptr
+        if self._plan_owner.get(key, sp.serial) != sp.serial:
+            self.drop_plans()
+            self._plan_owner.clear()
+        self._plan_owner[key] = sp.serial
+        return ctypes.byref(sp.desc)
 
     def _check(self, rc: int):
         if rc != ALS_OK:
@@ -153,26 +167,26 @@ class Als:
         return self._factor(t, rows, self.f, self.factor_torch_dtype)
 
     def update_rows(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, X: torch.Tensor):
-        self._check(self._lib.als_update_rows(self._ctx, ctypes.byref(csr.desc), self._gathered(Theta, csr.ncols),
+        self._check(self._lib.als_update_rows(self._ctx, self._matrix(csr), self._gathered(Theta, csr.ncols),
                                               lam, self.f, self._factor(X, csr.nrows, self.f)))
 
     def update_cols(self, csc: SparseMatrix, X: torch.Tensor, lam: float, Theta: torch.Tensor):
-        self._check(self._lib.als_update_cols(self._ctx, ctypes.byref(csc.desc), self._gathered(X, csc.ncols),
+        self._check(self._lib.als_update_cols(self._ctx, self._matrix(csc), self._gathered(X, csc.ncols),
                                               lam, self.f, self._factor(Theta, csc.nrows, self.f)))
 
     def update_rows_implicit(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, alpha: float, X: torch.Tensor):
-        self._check(self._lib.als_update_rows_implicit(self._ctx, ctypes.byref(csr.desc),
+        self._check(self._lib.als_update_rows_implicit(self._ctx, self._matrix(csr),
                                                        self._factor(Theta, csr.ncols, self.f), lam, alpha, self.f,
                                                        self._factor(X, csr.nrows, self.f)))
 
     def update_cols_implicit(self, csc: SparseMatrix, X: torch.Tensor, lam: float, alpha: float, Theta: torch.Tensor):
-        self._check(self._lib.als_update_cols_implicit(self._ctx, ctypes.byref(csc.desc),
+        self._check(self._lib.als_update_cols_implicit(self._ctx, self._matrix(csc),
                                                        self._factor(X, csc.ncols, self.f), lam, alpha, self.f,
                                                        self._factor(Theta, csc.nrows, self.f)))
 
     def implicit_loss(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor, lam: float, alpha: float) -> float:
         out = ctypes.c_double()
-        self._check(self._lib.als_implicit_loss(self._ctx, ctypes.byref(csr.desc), self._factor(X, csr.nrows, self.f),
+        self._check(self._lib.als_implicit_loss(self._ctx, self._matrix(csr), self._factor(X, csr.nrows, self.f),
                                                 self._factor(Theta, csr.ncols, self.f), lam, alpha, self.f,
                                                 ctypes.byref(out)))
         return out.value
@@ -185,14 +199,14 @@ class Als:
 
     def rmse(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor) -> float:
         out = ctypes.c_double()
-        self._check(self._lib.als_rmse(self._ctx, ctypes.byref(csr.desc), self._factor(X, csr.nrows, self.f),
+        self._check(self._lib.als_rmse(self._ctx, self._matrix(csr), self._factor(X, csr.nrows, self.f),
                                        self._factor(Theta, csr.ncols, self.f), self.f, ctypes.byref(out)))
         return out.value
 
     def hermitian(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, row0: int, nrows: int):
         A = torch.empty((nrows, self.f, self.f), dtype=torch.float32, device=Theta.device)
         b = torch.empty((nrows, self.f), dtype=torch.float32, device=Theta.device)
-        self._check(self._lib.als_hermitian(self._ctx, ctypes.byref(csr.desc), self._gathered(Theta, csr.ncols),
+        self._check(self._lib.als_hermitian(self._ctx, self._matrix(csr), self._gathered(Theta, csr.ncols),
                                             lam, self.f, row0, nrows, A.data_ptr(), b.data_ptr()))
         return A, b
 

@@ -571,3 +571,29 @@ def test_plans_are_dropped_when_a_matrix_changes_in_place(P):
         err = _row_rel_err(X.cpu().numpy(), oracle.update_rows(pb.astype(np.int64), ib, vb, Theta, 0.2))
         als.close()
         assert err.max() <= tol, float(err.max())
+
+
+def test_binding_tells_apart_matrices_at_a_reused_address(P):
+    """torch's allocator hands the memory of a freed matrix to the next one of the same size; the binding notices
+    (every SparseMatrix has a serial number) and drops the plans, so the second matrix gets its own."""
+    f, n, m = 32, 500, 400
+    Theta = W.random_factors(n, f, seed=3, scale=0.4)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=64)
+    Td = _dev(Theta)
+    X = torch.zeros((m, f), device="cuda:0")
+    addresses = set()
+    for seed in (1, 2, 3):
+        r = np.random.default_rng(seed)
+        deg = r.permutation(np.concatenate([np.full(10, 300), np.full(m - 10, 5)]))   # same sizes, other long rows
+        ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+        idx = np.concatenate([np.sort(r.choice(n, d, replace=False)) for d in deg]).astype(np.int32)
+        val = r.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+        sp = P.SparseMatrix.from_host(m, n, ptr, idx, val)
+        addresses.add(sp.ptr.data_ptr())
+        als.update_rows(sp, Td, 0.2, X)
+        als.synchronize()
+        err = _row_rel_err(X.cpu().numpy(), oracle.update_rows(ptr.astype(np.int64), idx, val, Theta, 0.2))
+        assert err.max() <= TOL_EXACT, (seed, float(err.max()))
+        del sp
+    als.close()
+    print(f"distinct ptr addresses over three matrices: {len(addresses)}", flush=True)
