@@ -166,14 +166,16 @@ int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_
 int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out);
 
 /* Waits for the stream and reports ALS_ENUMERIC if any kernel since the last
- * call flagged a non-positive pivot or a non-finite value. */
+ * call flagged a non-positive pivot or a non-finite value, ALS_EINVAL if the row
+ * offsets of a matrix no longer matched its cached plan (every call that uses a
+ * plan compares a fingerprint of ptr on the device; see als_drop_plans). */
 int als_synchronize(als_ctx *ctx);
 
 /* Forgets the cached work plans (waits for the stream first).  A plan is keyed on a matrix's ptr address, nrows
  * and nnz and holds its degree classes and work items, so the arrays of a matrix must stay unchanged between
  * calls; call this after changing them in place, or when a different matrix with the same nrows and nnz may have
  * been allocated at the address of an earlier one (the kernels stay inside the arrays with a stale plan, but
- * the results are wrong).  The next call on any matrix rebuilds its plan. */
+ * the results are wrong; als_synchronize reports it).  The next call on any matrix rebuilds its plan. */
 int als_drop_plans(als_ctx *ctx);
 
 /* Kernel ids for als_kernel_time */

@@ -75,6 +75,7 @@ struct Plan {                     // per sparse matrix, built once and cached
     int32_t *task_off = nullptr;  // DEVICE [nrows+1] first work item of the row at each perm position
     int32_t *task_row = nullptr;  // DEVICE [ntasks]
     int32_t *task_chunk = nullptr;// DEVICE [ntasks]
+    unsigned long long *fingerprint = nullptr;   // DEVICE: fingerprint of the row offsets the plan was built from
     int32_t *task_order = nullptr;// DEVICE [work items of the slot path]: launch order inside every batch (see ensure_order)
     int64_t order_cap = -1;       // the batch capacity task_order was built for
     int32_t *task_off_host = nullptr; // HOST copy of task_off
@@ -88,6 +89,7 @@ constexpr int kWideThreads = 512;   // threads of the largest workgroup any kern
 // status word bits set by kernels
 constexpr int kStatusBadPivot = 1;
 constexpr int kStatusNonFinite = 2;
+constexpr int kStatusStalePlan = 4;   // the row offsets of a matrix differ from those its cached plan was built from
 
 // ---- launchers (each defined next to its kernels) --------------------------------------------
 // wide: the gathered factor matrix is 4 GiB or larger (64-bit lane addresses)
@@ -188,6 +190,11 @@ hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
 hipError_t fill_zero(hipStream_t st, void *p, int64_t n);   // n 32-bit words, by a kernel
+// *sum (DEVICE) += fingerprint of the n row offsets: a sum of mixed (position, offset) pairs, so the order of the
+// additions does not matter
+hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum);
+// sets kStatusStalePlan in *status if *now != *want, then clears *now (all DEVICE)
+hipError_t plan_fingerprint_check(hipStream_t st, unsigned long long *now, const unsigned long long *want, int *status);
 // key[t] = index of the first stored entry of work item t, t < ntasks (DEVICE arrays)
 hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
                           const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key);

@@ -44,6 +44,7 @@ struct als_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     int *status = nullptr;       // DEVICE status word
+    unsigned long long *fp_now = nullptr;   // DEVICE: fingerprint of the row offsets of the current call (zero between calls)
     double *sse_partial = nullptr;
     size_t sse_partial_bytes = 0;
     double *sse_total = nullptr; // DEVICE
@@ -70,7 +71,7 @@ int fail_hip(als_ctx *ctx, hipError_t e, const char *what) {
     } while (0)
 
 void free_plan(Plan &p) {
-    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk); hipFree(p.task_order);
+    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk); hipFree(p.task_order); hipFree(p.fingerprint);
     delete[] p.task_off_host;
     p = Plan();
 }
@@ -176,7 +177,19 @@ int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
     HIP_TRY(ctx, hipMalloc(&p.task_row, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
     HIP_TRY(ctx, hipMalloc(&p.task_chunk, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
     HIP_TRY(ctx, plan_emit(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, p.task_row, p.task_chunk));
+    HIP_TRY(ctx, hipMalloc(&p.fingerprint, sizeof(unsigned long long)));
+    HIP_TRY(ctx, fill_zero(ctx->stream, p.fingerprint, 2));
+    HIP_TRY(ctx, plan_fingerprint(p64, ctx->stream, a->ptr, m + 1, p.fingerprint));
     p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz; p.chunk = ctx->cfg.chunk;
+    return ALS_OK;
+}
+
+// The plan of a matrix is found by address and sizes.  Every call that uses it recomputes the fingerprint of the row
+// offsets on the device and compares it with the plan's: a matrix that changed under its plan sets
+// kStatusStalePlan, which the next als_synchronize reports (kernels only: nothing here waits or allocates).
+int check_plan(als_ctx *ctx, const als_sparse *a, const Plan *p) {
+    HIP_TRY(ctx, plan_fingerprint(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->nrows + 1, ctx->fp_now));
+    HIP_TRY(ctx, plan_fingerprint_check(ctx->stream, ctx->fp_now, p->fingerprint, ctx->status));
     return ALS_OK;
 }
 
@@ -301,6 +314,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const float *gram = ctx->gram[0];
     Plan *p = nullptr;
     rc = get_plan(ctx, a, &p);
+    if (rc != ALS_OK) return rc;
+    rc = check_plan(ctx, a, p);
     if (rc != ALS_OK) return rc;
     const int64_t cap = ctx->cfg.batch_slots;
     const bool p64 = a->ptr_is_64 != 0;
@@ -446,8 +461,10 @@ int als_create(als_ctx **out, const als_config *cfg) {
     ctx->stream = (hipStream_t)cfg->stream;
     if (hipSetDevice(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
         hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
-        hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess) {
-        hipFree(ctx->status); hipFree(ctx->sse_total);
+        hipMalloc(&ctx->fp_now, sizeof(unsigned long long)) != hipSuccess ||
+        hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess ||
+        hipMemsetAsync(ctx->fp_now, 0, sizeof(unsigned long long), ctx->stream) != hipSuccess) {
+        hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now);
         delete ctx;
         return ALS_EHIP;
     }
@@ -461,7 +478,7 @@ void als_destroy(als_ctx *ctx) {
     hipStreamSynchronize(ctx->stream);
     for (auto &p : ctx->plans) free_plan(p);
     hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
-    hipFree(ctx->sse_total); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
+    hipFree(ctx->sse_total); hipFree(ctx->fp_now); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
     for (auto &t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     for (auto e : ctx->free_events) hipEventDestroy(e);
     delete ctx;
@@ -550,6 +567,8 @@ static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X,
     int rc;
     Plan *p = nullptr;
     rc = get_plan(ctx, csr, &p);
+    if (rc != ALS_OK) return rc;
+    rc = check_plan(ctx, csr, p);
     if (rc != ALS_OK) return rc;
     const size_t need = sizeof(double) * (size_t)(p->ntasks > 0 ? p->ntasks : 1);
     if (ctx->sse_partial_bytes < need) {
@@ -673,7 +692,9 @@ static int als_synchronize_impl(als_ctx *ctx) {
         std::string msg;
         if (st & kStatusBadPivot) msg += "non-positive pivot in the exact solver; ";
         if (st & kStatusNonFinite) msg += "non-finite value in a solution; ";
-        return fail(ctx, ALS_ENUMERIC, msg);
+        if (st & kStatusStalePlan)
+            msg += "the row offsets of a matrix changed after its work plan was built: results are invalid, call als_drop_plans; ";
+        return fail(ctx, (st & kStatusStalePlan) ? ALS_EINVAL : ALS_ENUMERIC, msg);
     }
     return ALS_OK;
 }

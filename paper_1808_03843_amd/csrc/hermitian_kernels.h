@@ -52,7 +52,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
     const int64_t s0 = rs + (int64_t)ch * chunk;
     const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);   // >= 1: rows without entries have no work items
+    // >= 1 with the plan of this matrix (rows without entries have no work items); a plan built from other row
+    // offsets can name a chunk beyond the end of the row: then nothing is read
+    const int len = s1 > s0 ? (int)(s1 - s0) : 0;
 
     v4f acc[NTILES];
 #pragma unroll

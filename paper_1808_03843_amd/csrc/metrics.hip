@@ -23,7 +23,7 @@ __global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
     const int64_t s0 = rs + (int64_t)ch * chunk;
     const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);
+    const int len = s1 > s0 ? (int)(s1 - s0) : 0;   // >= 1 with the plan of this matrix; 0 reads nothing
     float xr[NT];
 #pragma unroll
     for (int q = 0; q < NT; ++q) xr[q] = (16 * q + i < F) ? X[(int64_t)row * F + 16 * q + i] : 0.f;

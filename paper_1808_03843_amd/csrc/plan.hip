@@ -262,6 +262,48 @@ hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first) {
     return hipGetLastError();
 }
 
+// finaliser of a 64-bit hash (xor-shift and odd multipliers): spreads every input bit over the word
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 33;
+    x *= 0xff51afd7ed558ccdull;
+    x ^= x >> 33;
+    x *= 0xc4ceb9fe1a85ec53ull;
+    x ^= x >> 33;
+    return x;
+}
+
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_fingerprint(const PtrT *__restrict__ ptr, int64_t n,
+                                                     unsigned long long *__restrict__ sum) {
+    uint64_t h = 0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        h += mix64((uint64_t)ptr[i] + 0x9e3779b97f4a7c15ull * (uint64_t)(i + 1));
+    for (int o = 32; o > 0; o >>= 1) h += (uint64_t)__shfl_down((unsigned long long)h, o);
+    if ((threadIdx.x & 63) == 0) atomicAdd(sum, (unsigned long long)h);   // integer sum: any order gives the same word
+}
+
+__global__ void k_fingerprint_check(unsigned long long *__restrict__ now, const unsigned long long *__restrict__ want,
+                                    int *__restrict__ status) {
+    if (*now != *want) atomicOr(status, kStatusStalePlan);
+    *now = 0ull;
+}
+
+hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum) {
+    if (n <= 0) return hipSuccess;
+    int64_t nb = (n + 255) / 256;
+    if (nb > 2048) nb = 2048;
+    if (ptr64)
+        hipLaunchKernelGGL(k_fingerprint<int64_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int64_t *)ptr, n, sum);
+    else
+        hipLaunchKernelGGL(k_fingerprint<int32_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int32_t *)ptr, n, sum);
+    return hipGetLastError();
+}
+
+hipError_t plan_fingerprint_check(hipStream_t st, unsigned long long *now, const unsigned long long *want, int *status) {
+    hipLaunchKernelGGL(k_fingerprint_check, dim3(1), dim3(1), 0, st, now, want, status);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(uint32_t *__restrict__ p, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(64 * NW) void k_hermitian_wide(const int32_t *__res
     const int64_t rs = (int64_t)ptr[row], re = (int64_t)ptr[row + 1];
     const int64_t s0 = rs + (int64_t)ch * chunk;
     const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
-    const int len = (int)(s1 - s0);   // >= 1
+    const int len = s1 > s0 ? (int)(s1 - s0) : 0;   // >= 1 with the plan of this matrix; 0 reads nothing
     float *out = slots + t * (int64_t)SLOT;
     for_wave<NW>(wave, [&](auto wt) {
         constexpr uint32_t ROWS = wave_rows(NT, NW, decltype(wt)::value);

@@ -535,7 +535,7 @@ def test_more_rows_than_one_launch_holds(P, f, m):
 def test_plans_are_dropped_when_a_matrix_changes_in_place(P):
     """The plan of a matrix is keyed on its address and sizes: after its arrays are overwritten by another matrix
     of the same nrows and nnz (other degrees: short rows become long and the other way round), als_drop_plans
-    makes the next call build a new plan, and the result is that of the new matrix."""
+    makes the next call build a new plan, and the result is that of the new matrix.  Without it the call is flagged."""
     f, n, m = 100, 3000, 600
     rng = np.random.default_rng(8)
     Theta = W.random_factors(n, f, seed=3, scale=0.4)
@@ -564,6 +564,9 @@ def test_plans_are_dropped_when_a_matrix_changes_in_place(P):
         sp.ptr.copy_(torch.from_numpy(pb))            # the same device arrays now hold matrix b
         sp.idx.copy_(torch.from_numpy(ib))
         sp.val.copy_(torch.from_numpy(vb))
+        als.update_rows(sp, Td, 0.2, X)               # stale plan: the fingerprint of ptr no longer matches
+        with pytest.raises(P.AlsError, match="als_drop_plans"):
+            als.synchronize()
         als.drop_plans()
         X.zero_()
         als.update_rows(sp, Td, 0.2, X)
