@@ -300,8 +300,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     if (rc != ALS_OK) return rc;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (!(lambda >= 0.f)) return fail(ctx, ALS_EINVAL, "lambda must be >= 0");
+    if (a->nrows == 0) return ALS_OK;   // nothing to write
     if (!Out || (a->nnz > 0 && !G)) return fail(ctx, ALS_EINVAL, "factor pointer is null");
-    if (a->nrows == 0) return ALS_OK;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     const bool implicit = mode == kImplicit;
     if (implicit) {

@@ -600,3 +600,27 @@ def test_binding_tells_apart_matrices_at_a_reused_address(P):
         del sp
     als.close()
     print(f"distinct ptr addresses over three matrices: {len(addresses)}", flush=True)
+
+
+@pytest.mark.parametrize("f", [16, 100, 256])
+def test_matrix_without_entries_and_without_rows(P, f):
+    """Degenerate inputs: no stored entry at all (every x_u = 0, RMSE 0 by convention), and no rows."""
+    n, m = 50, 7
+    Theta = W.random_factors(n, f, seed=4, scale=0.4)
+    Td = _dev(Theta)
+    for solver in (P.SOLVER_CG, P.SOLVER_CHOLESKY):
+        als = P.Als(f, solver=solver)
+        sp = P.SparseMatrix.from_host(m, n, np.zeros(m + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+        X = torch.full((m, f), 7.0, device="cuda:0")
+        als.update_rows(sp, Td, 0.1, X)
+        als.synchronize()
+        assert not X.cpu().numpy().any()
+        X.fill_(7.0)
+        als.update_rows_implicit(sp, Td, 0.1, 2.0, X)     # b_u = 0: x_u = 0 as well
+        als.synchronize()
+        assert not X.cpu().numpy().any()
+        assert als.rmse(sp, X, Td) == 0.0
+        none = P.SparseMatrix.from_host(0, n, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+        als.update_rows(none, Td, 0.1, torch.zeros((0, f), device="cuda:0"))
+        als.synchronize()
+        als.close()
