@@ -171,6 +171,12 @@ int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t 
  * plan compares a fingerprint of ptr on the device; see als_drop_plans). */
 int als_synchronize(als_ctx *ctx);
 
+/* Checks a matrix against what the other calls assume and never check themselves: ptr ascending from 0 to nnz,
+ * every column id in [0, ncols), the column ids of every row strictly ascending (no duplicates).  An id out of
+ * range would make an update read outside the factor matrix.  Returns ALS_EINVAL with the findings in
+ * als_last_error; reads the whole matrix once and waits for the result (about the time of one RMSE). */
+int als_check_matrix(als_ctx *ctx, const als_sparse *a);
+
 /* Forgets the cached work plans (waits for the stream first).  A plan is keyed on a matrix's ptr address, nrows
  * and nnz and holds its degree classes and work items, so the arrays of a matrix must stay unchanged between
  * calls; call this after changing them in place, or when a different matrix with the same nrows and nnz may have

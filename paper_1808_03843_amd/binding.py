@@ -22,7 +22,7 @@ K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM = 0, 1, 2, 3, 4, 5
 EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
-    "als_profile_reset", "als_drop_plans", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
+    "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
 ]
 
 
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.als_kernel_time.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     lib.als_profile_reset.argtypes = [vp]
     lib.als_drop_plans.argtypes = [vp]
+    lib.als_check_matrix.argtypes = [vp, sp]
     _lib = lib
     return lib
 
@@ -235,6 +236,10 @@ class Als:
 
     def profile_reset(self):
         self._check(self._lib.als_profile_reset(self._ctx))
+
+    def check_matrix(self, sp: "SparseMatrix"):
+        """Raise AlsError unless ptr, the range of the column ids and their order inside every row are sound."""
+        self._check(self._lib.als_check_matrix(self._ctx, ctypes.byref(sp.desc)))
 
     def drop_plans(self):
         """Forget the cached work plans: needed after a matrix's arrays changed in place or were reallocated."""

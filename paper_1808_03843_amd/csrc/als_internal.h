@@ -190,6 +190,11 @@ hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
 hipError_t fill_zero(hipStream_t st, void *p, int64_t n);   // n 32-bit words, by a kernel
+// validation of a matrix: bits ORed into *flags (DEVICE): 1 row offsets not 0 .. nnz ascending, 2 column id out of
+// range, 4 column ids of a row not strictly ascending.  check_idx needs offsets that passed check_ptr.
+hipError_t check_ptr(bool ptr64, hipStream_t st, const void *ptr, int64_t nrows, int64_t nnz, int *flags);
+hipError_t check_idx(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, int64_t nrows, int64_t ncols,
+                     int64_t nnz, int *flags);
 // *sum (DEVICE) += fingerprint of the n row offsets: a sum of mixed (position, offset) pairs, so the order of the
 // additions does not matter
 hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum);

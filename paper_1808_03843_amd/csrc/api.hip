@@ -44,6 +44,7 @@ struct als_ctx {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
     int *status = nullptr;       // DEVICE status word
+    int *check_flags = nullptr;  // DEVICE: result word of als_check_matrix
     unsigned long long *fp_now = nullptr;   // DEVICE: fingerprint of the row offsets of the current call (zero between calls)
     double *sse_partial = nullptr;
     size_t sse_partial_bytes = 0;
@@ -478,7 +479,7 @@ void als_destroy(als_ctx *ctx) {
     hipStreamSynchronize(ctx->stream);
     for (auto &p : ctx->plans) free_plan(p);
     hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
-    hipFree(ctx->sse_total); hipFree(ctx->fp_now); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
+    hipFree(ctx->sse_total); hipFree(ctx->fp_now); hipFree(ctx->check_flags); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
     for (auto &t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     for (auto e : ctx->free_events) hipEventDestroy(e);
     delete ctx;
@@ -725,6 +726,31 @@ static int als_profile_reset_impl(als_ctx *ctx) {
     return ALS_OK;
 }
 
+static int als_check_matrix_impl(als_ctx *ctx, const als_sparse *a) {
+    if (!ctx) return ALS_EINVAL;
+    int rc = check_sparse(ctx, a);
+    if (rc != ALS_OK) return rc;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    if (!ctx->check_flags) HIP_TRY(ctx, hipMalloc(&ctx->check_flags, sizeof(int)));
+    const bool p64 = a->ptr_is_64 != 0;
+    int flags = 0;
+    HIP_TRY(ctx, fill_zero(ctx->stream, ctx->check_flags, 1));
+    HIP_TRY(ctx, check_ptr(p64, ctx->stream, a->ptr, a->nrows, a->nnz, ctx->check_flags));
+    HIP_TRY(ctx, hipMemcpyAsync(&flags, ctx->check_flags, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (flags == 0) {   // the index check walks ptr: only with sound offsets
+        HIP_TRY(ctx, check_idx(p64, ctx->stream, a->ptr, a->idx, a->nrows, a->ncols, a->nnz, ctx->check_flags));
+        HIP_TRY(ctx, hipMemcpyAsync(&flags, ctx->check_flags, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    if (flags == 0) return ALS_OK;
+    std::string msg;
+    if (flags & 1) msg += "row offsets are not an ascending sequence from 0 to nnz; ";
+    if (flags & 2) msg += "a column id lies outside [0, ncols); ";
+    if (flags & 4) msg += "the column ids of a row are not strictly ascending; ";
+    return fail(ctx, ALS_EINVAL, msg);
+}
+
 static int als_drop_plans_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
@@ -789,6 +815,10 @@ int als_profile_reset(als_ctx *ctx) {
 
 int als_drop_plans(als_ctx *ctx) {
     return guarded(ctx, [&] { return als_drop_plans_impl(ctx); });
+}
+
+int als_check_matrix(als_ctx *ctx, const als_sparse *a) {
+    return guarded(ctx, [&] { return als_check_matrix_impl(ctx, a); });
 }
 
 }  // extern "C"

@@ -262,6 +262,60 @@ hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first) {
     return hipGetLastError();
 }
 
+// ---- validation of a caller's matrix (als_check_matrix) ----
+constexpr int kBadPtr = 1, kBadIndex = 2, kBadOrder = 4;
+
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_check_ptr(const PtrT *__restrict__ ptr, int64_t nrows, int64_t nnz,
+                                                   int *__restrict__ flags) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    bool bad = false;
+    if (i < nrows) bad = (int64_t)ptr[i] > (int64_t)ptr[i + 1] || (int64_t)ptr[i] < 0;
+    if (i == 0) bad = bad || (int64_t)ptr[0] != 0 || (int64_t)ptr[nrows] != nnz;
+    if (bad) atomicOr(flags, kBadPtr);
+}
+
+// ptr has passed k_check_ptr.  Every column id in range; ids ascending inside a row: where idx[e+1] <= idx[e],
+// entry e+1 must be the first of a row, i.e. some ptr[i] == e+1 (binary search, needed about once per row).
+template <typename PtrT>
+__global__ __launch_bounds__(256) void k_check_idx(const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                   int64_t nrows, int64_t ncols, int64_t nnz, int *__restrict__ flags) {
+    int bad = 0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * 256) {
+        const int32_t c = idx[e];
+        if (c < 0 || c >= ncols) bad |= kBadIndex;
+        if (e + 1 < nnz && idx[e + 1] <= c) {
+            int64_t lo = 0, hi = nrows;   // first i with ptr[i] >= e + 1
+            while (lo < hi) {
+                const int64_t mid = (lo + hi) >> 1;
+                if ((int64_t)ptr[mid] < e + 1) lo = mid + 1; else hi = mid;
+            }
+            if ((int64_t)ptr[lo] != e + 1) bad |= kBadOrder;
+        }
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
+hipError_t check_ptr(bool ptr64, hipStream_t st, const void *ptr, int64_t nrows, int64_t nnz, int *flags) {
+    const dim3 grid((unsigned)((nrows + 256) / 256)), block(256);   // at least one workgroup: thread 0 checks the ends
+    if (ptr64) hipLaunchKernelGGL(k_check_ptr<int64_t>, grid, block, 0, st, (const int64_t *)ptr, nrows, nnz, flags);
+    else hipLaunchKernelGGL(k_check_ptr<int32_t>, grid, block, 0, st, (const int32_t *)ptr, nrows, nnz, flags);
+    return hipGetLastError();
+}
+
+hipError_t check_idx(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, int64_t nrows, int64_t ncols,
+                     int64_t nnz, int *flags) {
+    if (nnz <= 0) return hipSuccess;
+    int64_t nb = (nnz + 255) / 256;
+    if (nb > 65536) nb = 65536;
+    const dim3 grid((unsigned)nb), block(256);
+    if (ptr64)
+        hipLaunchKernelGGL(k_check_idx<int64_t>, grid, block, 0, st, (const int64_t *)ptr, idx, nrows, ncols, nnz, flags);
+    else
+        hipLaunchKernelGGL(k_check_idx<int32_t>, grid, block, 0, st, (const int32_t *)ptr, idx, nrows, ncols, nnz, flags);
+    return hipGetLastError();
+}
+
 // finaliser of a 64-bit hash (xor-shift and odd multipliers): spreads every input bit over the word
 __device__ __forceinline__ uint64_t mix64(uint64_t x) {
     x ^= x >> 33;

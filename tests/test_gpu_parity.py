@@ -624,3 +624,31 @@ def test_matrix_without_entries_and_without_rows(P, f):
         als.update_rows(none, Td, 0.1, torch.zeros((0, f), device="cuda:0"))
         als.synchronize()
         als.close()
+
+
+def test_check_matrix_finds_what_the_updates_assume(P):
+    """als_check_matrix: a generated matrix passes (int32 and int64 offsets, empty rows); an id out of range, ids out
+    of order or repeated inside a row, and broken offsets are named."""
+    w = W.TINY
+    a = W.generate(w)
+    als = P.Als(w.f)
+    for p64 in (False, True):
+        als.check_matrix(P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, ptr64=p64))
+    ptr = np.array([0, 0, 3, 3, 5, 5], np.int32)             # empty rows at both ends and in the middle
+    idx = np.array([1, 4, 9, 0, 9], np.int32)                # a descent only across the row boundary
+    val = np.ones(5, np.float32)
+    als.check_matrix(P.SparseMatrix.from_host(5, 10, ptr, idx, val))
+    cases = [
+        (ptr, np.array([1, 4, 10, 0, 9], np.int32), "outside"),
+        (ptr, np.array([1, 4, -1, 0, 9], np.int32), "outside"),
+        (ptr, np.array([4, 1, 9, 0, 9], np.int32), "ascending"),
+        (ptr, np.array([1, 4, 4, 0, 9], np.int32), "ascending"),
+        (np.array([0, 0, 3, 2, 5, 5], np.int32), idx, "offsets"),
+        (np.array([0, 0, 3, 3, 4, 4], np.int32), idx, "offsets"),
+        (np.array([1, 1, 3, 3, 5, 5], np.int32), idx, "offsets"),
+    ]
+    for bad_ptr, bad_idx, word in cases:
+        sp = P.SparseMatrix(5, 10, _dev(bad_ptr), _dev(bad_idx), _dev(val))
+        with pytest.raises(P.AlsError, match=word):
+            als.check_matrix(sp)
+    als.close()
