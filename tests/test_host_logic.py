@@ -1,0 +1,81 @@
+"""Host-side behaviour of the C ABI that needs no GPU: argument checks happen before any device is touched,
+null handles are errors, and without a device the library says so instead of falling back to anything."""
+import ctypes
+
+import pytest
+
+import paper_1808_03843_amd as P
+from paper_1808_03843_amd.binding import AlsConfig
+
+EINVAL, EHIP = -1, -2
+
+
+def _cfg(f=100, solver=None, cg_iters=6, factor_dtype=None, herm_dtype=None, device=0, chunk=0, batch_slots=0):
+    return AlsConfig(f, P.SOLVER_CG if solver is None else solver, cg_iters, 0.0,
+                     P.F32 if factor_dtype is None else factor_dtype, P.F32 if herm_dtype is None else herm_dtype,
+                     device, None, chunk, batch_slots, 0)
+
+
+def _create(cfg):
+    lib = P.load_library()
+    ctx = ctypes.c_void_p()
+    rc = lib.als_create(ctypes.byref(ctx), ctypes.byref(cfg))
+    if rc == 0:
+        lib.als_destroy(ctx)
+    return rc
+
+
+def test_error_codes_are_the_documented_ones():
+    import os
+    import re
+    header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "als.h")).read()
+    codes = dict(re.findall(r"#define (ALS_E[A-Z]+) \(?(-\d+)\)?", header))
+    assert int(codes["ALS_EINVAL"]) == EINVAL and int(codes["ALS_EHIP"]) == EHIP
+
+
+@pytest.mark.parametrize("cfg", [
+    _cfg(f=17), _cfg(f=0), _cfg(f=512),                                   # unsupported widths
+    _cfg(solver=7), _cfg(cg_iters=-1),
+    _cfg(factor_dtype=9), _cfg(herm_dtype=P.F16),                         # fp16 cannot store A_u
+    _cfg(solver=P.SOLVER_CHOLESKY, herm_dtype=P.BF16),                    # reduced storage goes with the approximate solver
+    _cfg(f=256, factor_dtype=P.BF16, herm_dtype=P.BF16),
+    _cfg(chunk=100), _cfg(chunk=32), _cfg(chunk=1 << 21), _cfg(chunk=-64), _cfg(batch_slots=-1),
+])
+def test_als_create_rejects_bad_configurations_before_touching_a_device(cfg):
+    assert _create(cfg) == EINVAL
+
+
+def test_als_create_null_arguments():
+    lib = P.load_library()
+    ctx = ctypes.c_void_p()
+    assert lib.als_create(None, ctypes.byref(_cfg())) == EINVAL
+    assert lib.als_create(ctypes.byref(ctx), None) == EINVAL
+
+
+def test_device_that_does_not_exist_is_an_error_not_a_fallback():
+    """A device ordinal beyond the last one (on a box without a GPU: any ordinal) gives ALS_EHIP and no context."""
+    assert _create(_cfg(device=4096)) == EHIP
+    assert _create(_cfg(device=-1)) == EHIP
+
+
+def test_null_context_is_rejected_by_every_entry_point():
+    lib = P.load_library()
+    lib.als_destroy(None)   # allowed
+    assert lib.als_last_error(None) == b"context is null"
+    d = ctypes.c_double()
+    n = ctypes.c_int64()
+    assert lib.als_update_rows(None, None, None, 0.1, 100, None) == EINVAL
+    assert lib.als_update_cols(None, None, None, 0.1, 100, None) == EINVAL
+    assert lib.als_update_rows_implicit(None, None, None, 0.1, 1.0, 100, None) == EINVAL
+    assert lib.als_update_cols_implicit(None, None, None, 0.1, 1.0, 100, None) == EINVAL
+    assert lib.als_rmse(None, None, None, None, 100, ctypes.byref(d)) == EINVAL
+    assert lib.als_implicit_loss(None, None, None, None, 0.1, 1.0, 100, ctypes.byref(d)) == EINVAL
+    assert lib.als_gram(None, None, 0, 100, None) == EINVAL
+    assert lib.als_hermitian(None, None, None, 0.1, 100, 0, 0, None, None) == EINVAL
+    assert lib.als_bin_rows(None, None, 8, None, None) == EINVAL
+    assert lib.als_csr_to_csc(None, None, None, None, None) == EINVAL
+    assert lib.als_synchronize(None) == EINVAL
+    assert lib.als_kernel_time(None, 0, ctypes.byref(d), ctypes.byref(n)) == EINVAL
+    assert lib.als_profile_reset(None) == EINVAL
+    assert lib.als_drop_plans(None) == EINVAL
+    assert lib.als_check_matrix(None, None) == EINVAL
