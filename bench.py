@@ -256,6 +256,19 @@ def main():
                                      "note": "gathered factor rounded to bf16 each half-sweep (conversion timed), "
                                              "v_mfma_f32_16x16x32_bf16 with fp32 accumulate, fp32 solver and output"}
         log(f"[bench] bf16 factor inputs: {ms16:.2f} ms per sweep, rmse {rmse16:.5f}")
+    # what the machine sustains on the simplest kernels (back-to-back MFMAs, a streaming copy): the reachable
+    # counterparts of the published peaks the roofline is quoted against
+    pk = P.Als(w.f)
+    mf32, mbf16, cp = (pk.measure_peak(k) for k in (P.PEAK_MFMA_F32, P.PEAK_MFMA_BF16, P.PEAK_COPY))
+    pk.close()
+    out["measured_peaks"] = {"mfma_f32_TFLOPs": mf32 / 1e12, "mfma_bf16_TFLOPs": mbf16 / 1e12, "copy_GBps": cp / 1e9,
+                             "note": "8 wavefronts per SIMD issuing independent MFMAs; copy of 1 GiB, bytes read + written"}
+    if roofline["bound"] == "mfma":
+        roofline["frac_of_measured_peak"] = roofline["achieved"] / (mf32 / 1e12)
+    else:
+        roofline["frac_of_measured_copy"] = roofline["achieved"] / (cp / 1e9)
+    log(f"[bench] sustained on this box: fp32 MFMA {mf32 / 1e12:.1f} TFLOP/s, bf16 MFMA {mbf16 / 1e12:.0f} TFLOP/s, "
+        f"copy {cp / 1e9:.0f} GB/s")
     if held_out is not None and args.implicit is None:
         # convergence protocol, outside the timed region: restart from the initial factors, held-out RMSE after
         # every sweep, update time accumulated without the evaluations

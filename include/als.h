@@ -177,6 +177,16 @@ int als_synchronize(als_ctx *ctx);
  * als_last_error; reads the whole matrix once and waits for the result (about the time of one RMSE). */
 int als_check_matrix(als_ctx *ctx, const als_sparse *a);
 
+/* Measurement aid (no part of the method): the rate this device sustains on the simplest kernel that can reach a
+ * peak -- back-to-back independent MFMAs (flop/s) or a streaming copy of 1 GiB (bytes read + written per second).
+ * The roofline fractions of the benchmark are quoted against the published peaks; these are the reachable ones.
+ * Allocates its own buffers (2 GiB for the copy), waits for the result.  rate_out: HOST. */
+#define ALS_PEAK_MFMA_F32 0  /* v_mfma_f32_16x16x4_f32   */
+#define ALS_PEAK_MFMA_BF16 1 /* v_mfma_f32_16x16x32_bf16 */
+#define ALS_PEAK_MFMA_F16 2  /* v_mfma_f32_16x16x32_f16  */
+#define ALS_PEAK_COPY 3
+int als_measure_peak(als_ctx *ctx, int what, double *rate_out);
+
 /* Forgets the cached work plans (waits for the stream first).  A plan is keyed on a matrix's ptr address, nrows
  * and nnz and holds its degree classes and work items, so the arrays of a matrix must stay unchanged between
  * calls; call this after changing them in place, or when a different matrix with the same nrows and nnz may have

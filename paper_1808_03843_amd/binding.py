@@ -17,12 +17,13 @@ from . import build as _build
 ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
 SOLVER_CHOLESKY, SOLVER_CG = 0, 1
 F32, BF16, F16 = 0, 1, 2
+PEAK_MFMA_F32, PEAK_MFMA_BF16, PEAK_MFMA_F16, PEAK_COPY = 0, 1, 2, 3   # ids of als_measure_peak
 K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM = 0, 1, 2, 3, 4, 5
 
 EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
-    "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
+    "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_measure_peak", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
 ]
 
 
@@ -75,6 +76,7 @@ def load_library() -> ctypes.CDLL:
     lib.als_profile_reset.argtypes = [vp]
     lib.als_drop_plans.argtypes = [vp]
     lib.als_check_matrix.argtypes = [vp, sp]
+    lib.als_measure_peak.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     _lib = lib
     return lib
 
@@ -240,6 +242,12 @@ class Als:
     def check_matrix(self, sp: "SparseMatrix"):
         """Raise AlsError unless ptr, the range of the column ids and their order inside every row are sound."""
         self._check(self._lib.als_check_matrix(self._ctx, ctypes.byref(sp.desc)))
+
+    def measure_peak(self, what: int) -> float:
+        """Sustained rate of the device: what = 0 / 1 / 2 MFMA fp32 / bf16 / fp16 (flop/s), 3 streaming copy (B/s)."""
+        out = ctypes.c_double()
+        self._check(self._lib.als_measure_peak(self._ctx, what, ctypes.byref(out)))
+        return out.value
 
     def drop_plans(self):
         """Forget the cached work plans: needed after a matrix's arrays changed in place or were reallocated."""

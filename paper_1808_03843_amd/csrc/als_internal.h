@@ -204,6 +204,10 @@ hipError_t plan_fingerprint_check(hipStream_t st, unsigned long long *now, const
 hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
                           const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key);
 
+// peaks.hip: the rates this machine sustains (see als_measure_peak)
+hipError_t launch_mfma_peak(int et, hipStream_t st, int workgroups, int iters, float *sink, double *flops);
+hipError_t launch_copy(hipStream_t st, int workgroups, const void *src, void *dst, int64_t bytes);
+
 // transpose.hip
 hipError_t transpose_csr(bool ptr64, hipStream_t st, int64_t nrows, int64_t ncols, int64_t nnz, const void *ptr,
                          const int32_t *idx, const float *val, void *cptr, int32_t *cidx, float *cval);

@@ -751,6 +751,44 @@ static int als_check_matrix_impl(als_ctx *ctx, const als_sparse *a) {
     return fail(ctx, ALS_EINVAL, msg);
 }
 
+static int als_measure_peak_impl(als_ctx *ctx, int what, double *rate_out) {
+    if (!ctx) return ALS_EINVAL;
+    if (!rate_out) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (what < ALS_PEAK_MFMA_F32 || what > ALS_PEAK_COPY) return fail(ctx, ALS_EINVAL, "unknown peak id");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    int cus = 0;
+    HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->cfg.device));
+    const int workgroups = 8 * cus;   // 8 wavefronts per SIMD
+    const int64_t bytes = 1ll << 30;
+    char *buf = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    double work = 0.0;
+    hipError_t e = hipMalloc(&buf, what == ALS_PEAK_COPY ? (size_t)(2 * bytes) : (size_t)4096);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    float ms = 0.f;
+    for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {   // the first pass warms up (clocks, code, pages)
+        e = hipEventRecord(e0, ctx->stream);
+        if (e != hipSuccess) break;
+        if (what == ALS_PEAK_COPY) {
+            for (int k = 0; k < 10 && e == hipSuccess; ++k) e = launch_copy(ctx->stream, 32 * cus, buf, buf + bytes, bytes);
+            work = 10.0 * 2.0 * (double)bytes;   // read + written
+        } else {
+            const int et = what == ALS_PEAK_MFMA_F32 ? ALS_F32 : what == ALS_PEAK_MFMA_BF16 ? ALS_BF16 : ALS_F16;
+            e = launch_mfma_peak(et, ctx->stream, workgroups, 20000, (float *)buf, &work);
+        }
+        if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) hipEventDestroy(e0);
+    if (e1) hipEventDestroy(e1);
+    hipFree(buf);
+    if (e != hipSuccess) return fail_hip(ctx, e, "als_measure_peak");
+    *rate_out = work / ((double)ms * 1e-3);
+    return ALS_OK;
+}
+
 static int als_drop_plans_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
@@ -819,6 +857,10 @@ int als_drop_plans(als_ctx *ctx) {
 
 int als_check_matrix(als_ctx *ctx, const als_sparse *a) {
     return guarded(ctx, [&] { return als_check_matrix_impl(ctx, a); });
+}
+
+int als_measure_peak(als_ctx *ctx, int what, double *rate_out) {
+    return guarded(ctx, [&] { return als_measure_peak_impl(ctx, what, rate_out); });
 }
 
 }  // extern "C"

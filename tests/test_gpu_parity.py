@@ -652,3 +652,21 @@ def test_check_matrix_finds_what_the_updates_assume(P):
         with pytest.raises(P.AlsError, match=word):
             als.check_matrix(sp)
     als.close()
+
+
+def test_measured_peaks_are_plausible(P):
+    """als_measure_peak: what the box sustains lies below the published peaks and within a factor of them."""
+    als = P.Als(16)
+    f32, bf16, f16, cp = (als.measure_peak(k) for k in (P.PEAK_MFMA_F32, P.PEAK_MFMA_BF16, P.PEAK_MFMA_F16, P.PEAK_COPY))
+    als.close()
+    print(f"sustained: fp32 MFMA {f32 / 1e12:.1f}, bf16 {bf16 / 1e12:.0f}, fp16 {f16 / 1e12:.0f} TFLOP/s; copy {cp / 1e9:.0f} GB/s",
+          flush=True)
+    assert 0.3 * 157.3e12 < f32 <= 1.02 * 157.3e12
+    assert 0.2 * 2.5e15 < bf16 <= 1.02 * 2.5e15 and 0.2 * 2.5e15 < f16 <= 1.02 * 2.5e15
+    assert 0.2 * 8e12 < cp <= 1.02 * 8e12
+    with pytest.raises(P.AlsError):
+        als2 = P.Als(16)
+        try:
+            als2.measure_peak(7)
+        finally:
+            als2.close()

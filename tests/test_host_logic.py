@@ -79,3 +79,4 @@ def test_null_context_is_rejected_by_every_entry_point():
     assert lib.als_profile_reset(None) == EINVAL
     assert lib.als_drop_plans(None) == EINVAL
     assert lib.als_check_matrix(None, None) == EINVAL
+    assert lib.als_measure_peak(None, 0, ctypes.byref(d)) == EINVAL
