@@ -52,6 +52,7 @@ extern "C" {
 #define ALS_F16 2
 
 typedef struct als_ctx als_ctx; /* opaque; one per (device, stream); not thread-safe */
+/* Every call makes the context's device current while it runs and restores the caller's current device on return. */
 
 /* A sparse matrix in compressed-row form, all arrays DEVICE memory.
  * For als_update_cols pass the CSC of R as the compressed rows of R^T

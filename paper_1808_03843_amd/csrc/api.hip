@@ -57,6 +57,21 @@ struct als_ctx {
 
 namespace {
 
+// Makes the context's device current for the duration of a call and puts the caller's device back afterwards.
+struct DeviceGuard {
+    int prev = -1;
+    hipError_t enter(int device) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess || cur == device) return e;
+        prev = cur;
+        return hipSetDevice(device);
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
 int fail(als_ctx *ctx, int code, const std::string &msg) {
     if (ctx) ctx->err = msg;
     return code;
@@ -303,7 +318,8 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     if (!(lambda >= 0.f)) return fail(ctx, ALS_EINVAL, "lambda must be >= 0");
     if (a->nrows == 0) return ALS_OK;   // nothing to write
     if (!Out || (a->nnz > 0 && !G)) return fail(ctx, ALS_EINVAL, "factor pointer is null");
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     const bool implicit = mode == kImplicit;
     if (implicit) {
         rc = check_implicit(ctx, alpha);
@@ -460,7 +476,8 @@ int als_create(als_ctx **out, const als_config *cfg) {
             ctx->cfg.batch_slots /= 2;
     }
     ctx->stream = (hipStream_t)cfg->stream;
-    if (hipSetDevice(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
+    DeviceGuard on_device;
+    if (on_device.enter(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
         hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
         hipMalloc(&ctx->fp_now, sizeof(unsigned long long)) != hipSuccess ||
         hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess ||
@@ -475,7 +492,8 @@ int als_create(als_ctx **out, const als_config *cfg) {
 
 void als_destroy(als_ctx *ctx) {
     if (!ctx) return;
-    hipSetDevice(ctx->cfg.device);
+    DeviceGuard on_device;
+    (void)on_device.enter(ctx->cfg.device);
     hipStreamSynchronize(ctx->stream);
     for (auto &p : ctx->plans) free_plan(p);
     hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
@@ -509,7 +527,8 @@ static int als_gram_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *
     if (!ctx) return ALS_EINVAL;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (n < 0 || n > 0x7fffffff || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int rc = compute_gram(ctx, G, n, 0);
     if (rc != ALS_OK) return rc;
     HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, ctx->gram[0], out));
@@ -528,7 +547,8 @@ static int als_implicit_loss_impl(als_ctx *ctx, const als_sparse *csr, const flo
     if (!loss_out || !X || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
     rc = check_implicit(ctx, alpha);
     if (rc != ALS_OK) return rc;
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     double entries = 0.0;
     if (csr->nnz > 0) {
         rc = sum_over_entries(ctx, csr, X, Theta, f, true, alpha, &entries);
@@ -554,7 +574,8 @@ static int als_rmse_impl(als_ctx *ctx, const als_sparse *csr, const float *X, co
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (!rmse_out || (csr->nnz > 0 && (!X || !Theta))) return fail(ctx, ALS_EINVAL, "null pointer");
     if (csr->nnz == 0) { *rmse_out = 0.0; return ALS_OK; }
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     double sse = 0.0;
     rc = sum_over_entries(ctx, csr, X, Theta, f, false, 0.f, &sse);
     if (rc != ALS_OK) return rc;
@@ -600,7 +621,8 @@ static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *T
     if (row0 < 0 || nrows < 0 || row0 + nrows > csr->nrows) return fail(ctx, ALS_EINVAL, "row range outside the matrix");
     if (!A_out || !b_out || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
     if (nrows == 0) return ALS_OK;
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     // a throw-away plan over the row range, in natural order
     const bool p64 = csr->ptr_is_64 != 0;
     const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
@@ -654,7 +676,8 @@ static int als_bin_rows_impl(als_ctx *ctx, const als_sparse *csr, int nclass, in
     if (rc != ALS_OK) return rc;
     if (nclass < 2 || nclass > 64) return fail(ctx, ALS_EINVAL, "nclass must be in [2, 64]");
     if (!perm_out || !class_start_out) return fail(ctx, ALS_EINVAL, "null pointer");
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int32_t *cs_dev = nullptr;
     HIP_TRY(ctx, hipMalloc(&cs_dev, sizeof(int32_t) * 65));
     hipError_t e = plan_bin_rows(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ptr, nclass, perm_out, cs_dev,
@@ -675,7 +698,8 @@ static int als_csr_to_csc_impl(als_ctx *ctx, const als_sparse *csr, void *cptr_o
     if (rc != ALS_OK) return rc;
     if (csr->nnz > 0xffffffffll) return fail(ctx, ALS_EINVAL, "als_csr_to_csc needs nnz < 2^32");
     if (!cptr_out || (csr->nnz > 0 && (!cidx_out || !cval_out))) return fail(ctx, ALS_EINVAL, "null pointer");
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     hipError_t e = transpose_csr(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ncols, csr->nnz, csr->ptr,
                                  csr->idx, csr->val, cptr_out, cidx_out, cval_out);
     if (e != hipSuccess) return fail_hip(ctx, e, "als_csr_to_csc");
@@ -684,7 +708,8 @@ static int als_csr_to_csc_impl(als_ctx *ctx, const als_sparse *csr, void *cptr_o
 
 static int als_synchronize_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int st = 0;
     HIP_TRY(ctx, hipMemcpyAsync(&st, ctx->status, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
@@ -730,7 +755,8 @@ static int als_check_matrix_impl(als_ctx *ctx, const als_sparse *a) {
     if (!ctx) return ALS_EINVAL;
     int rc = check_sparse(ctx, a);
     if (rc != ALS_OK) return rc;
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     if (!ctx->check_flags) HIP_TRY(ctx, hipMalloc(&ctx->check_flags, sizeof(int)));
     const bool p64 = a->ptr_is_64 != 0;
     int flags = 0;
@@ -755,7 +781,8 @@ static int als_measure_peak_impl(als_ctx *ctx, int what, double *rate_out) {
     if (!ctx) return ALS_EINVAL;
     if (!rate_out) return fail(ctx, ALS_EINVAL, "null pointer");
     if (what < ALS_PEAK_MFMA_F32 || what > ALS_PEAK_COPY) return fail(ctx, ALS_EINVAL, "unknown peak id");
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int cus = 0;
     HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->cfg.device));
     const int workgroups = 8 * cus;   // 8 wavefronts per SIMD
@@ -791,7 +818,8 @@ static int als_measure_peak_impl(als_ctx *ctx, int what, double *rate_out) {
 
 static int als_drop_plans_impl(als_ctx *ctx) {
     if (!ctx) return ALS_EINVAL;
-    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     for (auto &p : ctx->plans) free_plan(p);
     ctx->next_plan = 0;
