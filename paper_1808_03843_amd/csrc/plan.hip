@@ -329,11 +329,15 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
 template <typename PtrT>
 __global__ __launch_bounds__(256) void k_fingerprint(const PtrT *__restrict__ ptr, int64_t n,
                                                      unsigned long long *__restrict__ sum) {
+    __shared__ unsigned long long part[4];
     uint64_t h = 0;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
         h += mix64((uint64_t)ptr[i] + 0x9e3779b97f4a7c15ull * (uint64_t)(i + 1));
     for (int o = 32; o > 0; o >>= 1) h += (uint64_t)__shfl_down((unsigned long long)h, o);
-    if ((threadIdx.x & 63) == 0) atomicAdd(sum, (unsigned long long)h);   // integer sum: any order gives the same word
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
+    __syncthreads();
+    // one atomic per workgroup (many on one address would queue up); an integer sum: any order gives the same word
+    if (threadIdx.x == 0) atomicAdd(sum, part[0] + part[1] + part[2] + part[3]);
 }
 
 __global__ void k_fingerprint_check(unsigned long long *__restrict__ now, const unsigned long long *__restrict__ want,
@@ -344,8 +348,8 @@ __global__ void k_fingerprint_check(unsigned long long *__restrict__ now, const 
 
 hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum) {
     if (n <= 0) return hipSuccess;
-    int64_t nb = (n + 255) / 256;
-    if (nb > 2048) nb = 2048;
+    int64_t nb = (n + 1023) / 1024;   // at least four offsets per thread; few workgroups, since each ends in an atomic
+    if (nb > 1024) nb = 1024;
     if (ptr64)
         hipLaunchKernelGGL(k_fingerprint<int64_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int64_t *)ptr, n, sum);
     else
