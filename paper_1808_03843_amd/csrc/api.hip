@@ -1,5 +1,6 @@
 // C ABI of libals_gfx950 (see include/als.h): argument checks, the cached per-matrix plan, the
 // batch loop of an update half-sweep, error bookkeeping.  No arithmetic of the method lives here.
+#include <cstdint>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -71,6 +72,8 @@ struct DeviceGuard {
         if (prev >= 0) (void)hipSetDevice(prev);
     }
 };
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int fail(als_ctx *ctx, int code, const std::string &msg) {
     if (ctx) ctx->err = msg;
@@ -318,6 +321,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     if (!(lambda >= 0.f)) return fail(ctx, ALS_EINVAL, "lambda must be >= 0");
     if (a->nrows == 0) return ALS_OK;   // nothing to write
     if (!Out || (a->nnz > 0 && !G)) return fail(ctx, ALS_EINVAL, "factor pointer is null");
+    if (!aligned16(Out) || !aligned16(G)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     const bool implicit = mode == kImplicit;
@@ -527,6 +531,7 @@ static int als_gram_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *
     if (!ctx) return ALS_EINVAL;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (n < 0 || n > 0x7fffffff || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
+    if (!aligned16(G)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int rc = compute_gram(ctx, G, n, 0);
@@ -545,6 +550,7 @@ static int als_implicit_loss_impl(als_ctx *ctx, const als_sparse *csr, const flo
     if (rc != ALS_OK) return rc;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (!loss_out || !X || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(Theta)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     rc = check_implicit(ctx, alpha);
     if (rc != ALS_OK) return rc;
     DeviceGuard on_device;
@@ -573,6 +579,7 @@ static int als_rmse_impl(als_ctx *ctx, const als_sparse *csr, const float *X, co
     if (rc != ALS_OK) return rc;
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (!rmse_out || (csr->nnz > 0 && (!X || !Theta))) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(Theta)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     if (csr->nnz == 0) { *rmse_out = 0.0; return ALS_OK; }
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
@@ -620,6 +627,7 @@ static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *T
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (row0 < 0 || nrows < 0 || row0 + nrows > csr->nrows) return fail(ctx, ALS_EINVAL, "row range outside the matrix");
     if (!A_out || !b_out || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
+    if (!aligned16(Theta)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     if (nrows == 0) return ALS_OK;
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));

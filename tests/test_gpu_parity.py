@@ -266,6 +266,10 @@ def test_bad_arguments_are_errors_not_crashes(P):
     X = torch.zeros((a.nrows, 16), device="cuda:0")
     with pytest.raises(P.AlsError):
         als.update_rows(sp, T, -1.0, X)
+    with pytest.raises(P.AlsError, match="aligned"):   # a view that starts 4 bytes into an allocation
+        buf = torch.zeros(a.ncols * 16 + 1, device="cuda:0")
+        als._check(als._lib.als_update_rows(als._ctx, __import__("ctypes").byref(sp.desc), buf.data_ptr() + 4, 0.1, 16,
+                                            X.data_ptr()))
     # lambda = 0 and a rank-deficient row: the exact solver must flag it, not hang or crash
     als.update_rows(sp, T, 0.0, X)
     with pytest.raises(P.AlsError) as ei:
