@@ -1,0 +1,127 @@
+"""Seeded random sweep over the configuration space: factor width, solver, input type, chunk, batch size, offset
+width, explicit / implicit, bf16 slot storage, and degree patterns drawn around every boundary the kernels have
+(steps of 4, 16 and 32 entries, the dual-form sizes, the chunk size and its multiples, full rows, empty rows).
+Every case is one half-sweep through the C ABI against the oracle on the same seeded inputs; the side entry points
+(A_u and b_u, RMSE, binning, CSR -> CSC) get a sweep of their own."""
+import numpy as np
+import pytest
+
+import oracle
+import workload as W
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _rel(g, o):
+    # rows whose exact solution is 0 (all ratings 0 in implicit mode) are compared absolutely
+    return np.linalg.norm(g.astype(np.float64) - o, axis=1) / np.maximum(np.linalg.norm(o, axis=1), 1e-3)
+
+
+def _matrix(rng, n, m, chunk, implicit):
+    special = [0, 1, 2, 3, 4, 5, 15, 16, 17, 31, 32, 33, 47, 48, 63, 64, 65, 95, 96, 127, 128, 129, chunk - 1, chunk,
+               chunk + 1, 2 * chunk, 2 * chunk + 3, n]
+    deg = np.where(rng.random(m) < 0.5, rng.choice(special, m), rng.integers(0, min(n, 3 * chunk) + 1, m))
+    deg = np.minimum(deg, n).astype(np.int64)
+    ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = (rng.integers(0, 6, int(ptr[-1])) if implicit else rng.standard_normal(int(ptr[-1])) * 2 + 3).astype(np.float32)
+    return deg, ptr, idx, val
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_half_sweeps(seed):
+    import paper_1808_03843_amd as P
+    rng = np.random.default_rng(seed)
+    for case in range(60):
+        f = int(rng.choice([16, 32, 64, 100, 128, 256]))
+        solver = int(rng.choice([P.SOLVER_CG, P.SOLVER_CHOLESKY]))
+        dt = str(rng.choice(["f32", "f32", "bf16", "f16"]))
+        chunk = int(rng.choice([64, 128, 256, 1024, 4096]))
+        implicit = dt == "f32" and rng.random() < 0.3
+        herm16 = (not implicit) and solver == P.SOLVER_CG and rng.random() < 0.2 and (f != 256 or dt == "f32")
+        p64 = bool(rng.random() < 0.3)
+        n, m = int(rng.integers(300, 6000)), int(rng.integers(20, 300))
+        lam = float(rng.choice([0.05, 0.3, 1.0]))
+        # Algorithm 1 is compared row by row while it is still converging; on the well-conditioned implicit systems
+        # 40 iterations reach the exact solution, which is what the oracle has there
+        fs = 40 if implicit else int(rng.choice([3, 6]))
+        batch = int(rng.choice([0, 8, 64]))
+        deg, ptr, idx, val = _matrix(rng, n, m, chunk, implicit)
+        tag = (f"seed {seed} case {case}: f={f} solver={solver} {dt} chunk={chunk} implicit={implicit} bf16 slots={herm16} "
+               f"ptr64={p64} n={n} m={m} lambda={lam} f_s={fs} batch_slots={batch} max degree {deg.max()}")
+        print(tag, flush=True)
+        Theta = W.random_factors(n, f, seed=1000 * seed + case, scale=0.3)
+        warm = W.random_factors(m, f, seed=1000 * seed + case + 500, scale=0.05)
+        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[dt]
+        Td = torch.from_numpy(Theta).cuda().to(tdt)
+        Th = Td.to(torch.float32).cpu().numpy()
+        als = P.Als(f, solver=solver, cg_iters=fs, chunk=chunk, batch_slots=batch, factor_dtype=code,
+                    herm_dtype=P.BF16 if herm16 else P.F32)
+        sp = P.SparseMatrix.from_host(m, n, ptr, idx, val, ptr64=p64)
+        als.check_matrix(sp)
+        X = torch.from_numpy(warm.copy()).cuda()
+        if implicit:
+            als.update_rows_implicit(sp, Td, lam, 2.0, X)
+            ref, tol = oracle.implicit_update_rows(ptr, idx, val, Th, lam, 2.0), (1e-4 if solver == P.SOLVER_CHOLESKY else 5e-3)
+        else:
+            als.update_rows(sp, Td, lam, X)
+            if solver == P.SOLVER_CHOLESKY:
+                ref, tol = oracle.update_rows(ptr, idx, val, Th, lam), 1e-4
+            else:   # bf16 storage of the split rows' A_u: its rounding is the difference
+                ref, tol = oracle.update_rows_cg(ptr, idx, val, Th, lam, warm, fs=fs), (5e-2 if herm16 else 2e-3)
+        als.synchronize()
+        got = X.cpu().numpy()
+        als.close()
+        live = deg > 0
+        assert not got[~live].any(), tag
+        err = _rel(got[live], ref[live])
+        assert err.max() <= tol, (tag, float(err.max()), int(deg[live][err.argmax()]))
+
+
+def test_random_side_entry_points():
+    import paper_1808_03843_amd as P
+    rng = np.random.default_rng(5)
+    for case in range(60):
+        f = int(rng.choice([16, 32, 64, 100, 128, 256]))
+        dt = str(rng.choice(["f32", "bf16", "f16"]))
+        chunk = int(rng.choice([64, 128, 1024, 4096]))
+        p64 = bool(rng.random() < 0.3)
+        n, m = int(rng.integers(50, 3000)), int(rng.integers(1, 200))
+        deg, ptr, idx, val = _matrix(rng, n, m, chunk, False)
+        val = (val * 10).astype(np.float32)
+        tag = f"case {case}: f={f} {dt} chunk={chunk} ptr64={p64} n={n} m={m} max degree {deg.max()}"
+        print(tag, flush=True)
+        Theta = W.random_factors(n, f, seed=case + 1, scale=0.3)
+        Xf = W.random_factors(m, f, seed=case + 77, scale=0.3)
+        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[dt]
+        Td = torch.from_numpy(Theta).cuda().to(tdt)
+        Th = Td.to(torch.float32).cpu().numpy()
+        als = P.Als(f, chunk=chunk, factor_dtype=code)
+        sp = P.SparseMatrix.from_host(m, n, ptr, idx, val, ptr64=p64)
+        r0 = int(rng.integers(0, m))
+        nr = int(rng.integers(1, min(m - r0, 40) + 1))
+        A, b = als.hermitian(sp, Td, 0.07, r0, nr)
+        A, b = A.cpu().numpy(), b.cpu().numpy()
+        for k in range(nr):
+            s, e = ptr[r0 + k], ptr[r0 + k + 1]
+            Ao, bo = oracle.normal_eq(idx[s:e], val[s:e], Th, 0.07)
+            d = np.sqrt(max(1, e - s))
+            assert np.abs(A[k] - Ao).max() <= 2e-6 * max(np.abs(Ao).max(), 1e-30) * d, (tag, r0 + k)
+            assert np.abs(b[k] - bo).max() <= 2e-6 * max(np.abs(bo).max(), 1e-30) * d + 1e-30, (tag, r0 + k)
+            assert np.array_equal(A[k], A[k].T), (tag, r0 + k)
+        perm, start = als.bin_rows(sp, 12)
+        po, so = oracle.bin_rows(ptr, 12)
+        assert np.array_equal(perm.cpu().numpy(), po) and list(start) == list(so), tag
+        if ptr[-1] > 0:
+            ev = P.Als(f, chunk=chunk)
+            rg = ev.rmse(sp, torch.from_numpy(Xf).cuda(), torch.from_numpy(Theta).cuda())
+            ev.close()
+            ro = oracle.rmse(ptr, idx, val, Xf, Theta)
+            assert abs(rg - ro) <= 1e-5 * ro, tag
+            csc = als.csr_to_csc(sp)
+            cptr, cidx, cval = oracle.csr_to_csc(m, n, ptr, idx, val)
+            assert np.array_equal(csc.ptr.cpu().numpy(), cptr) and np.array_equal(csc.idx.cpu().numpy(), cidx), tag
+            assert np.array_equal(csc.val.cpu().numpy(), cval), tag
+        als.synchronize()
+        als.close()
