@@ -674,3 +674,35 @@ def test_measured_peaks_are_plausible(P):
             als2.measure_peak(7)
         finally:
             als2.close()
+
+
+def test_more_matrices_than_cached_plans(P):
+    """One context keeps four plans: seven matrices taken in turn force plans to be dropped and rebuilt, between
+    updates and RMSE calls, and every result is still that of its own matrix."""
+    rng = np.random.default_rng(3)
+    f, n = 100, 2000
+    Theta = W.random_factors(n, f, seed=1, scale=0.3)
+    Td = _dev(Theta)
+    als = P.Als(f, solver=P.SOLVER_CHOLESKY, chunk=128, batch_slots=16)
+    mats = []
+    for k in range(7):
+        m = int(rng.integers(50, 300))
+        deg = np.minimum(rng.choice([0, 1, 5, 40, 63, 64, 127, 128, 129, 300, 700, 2000], m), n)
+        ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+        idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+        val = (rng.standard_normal(int(ptr[-1])) * 2 + 3).astype(np.float32)
+        Xs = W.random_factors(m, f, seed=k + 10, scale=0.3)
+        mats.append((P.SparseMatrix.from_host(m, n, ptr, idx, val), oracle.update_rows(ptr, idx, val, Theta, 0.1), deg, Xs,
+                     oracle.rmse(ptr, idx, val, Xs, Theta)))
+    for rnd in range(3):
+        for k in rng.permutation(7):
+            sp, ref, deg, Xs, ro = mats[k]
+            X = torch.zeros((sp.nrows, f), device="cuda:0")
+            als.update_rows(sp, Td, 0.1, X)
+            if rnd == 1:
+                assert abs(als.rmse(sp, _dev(Xs), Td) - ro) <= 1e-5 * ro
+            als.synchronize()
+            got, live = X.cpu().numpy(), deg > 0
+            assert not got[~live].any()
+            assert _row_rel_err(got[live], ref[live]).max() <= TOL_EXACT, (rnd, int(k))
+    als.close()
