@@ -130,4 +130,20 @@ def test_very_tall():
         print(f"very_tall sweep {s + 4} (bf16 inputs): {dt:.3f} s, training rmse {r16:.5f}", flush=True)
         assert r16 < hist[2][1] + 2e-3
     a16.close()
+    # reduced-precision storage of A_u (Section 4.2: the partial Gram matrices of split rows are kept as bf16): on this
+    # shape that is every column; fp32 inputs, two more sweeps, the training RMSE keeps to the fp32 path's course
+    ah = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, herm_dtype=P.BF16)
+    for s in range(2):
+        torch.cuda.synchronize()
+        t0 = time.time()
+        ah.update_rows(csr, T, w.lam, X)
+        ah.update_cols(csc, X, w.lam, T)
+        torch.cuda.synchronize()
+        dt = time.time() - t0
+        rh = als.rmse(csr, X, T)
+        print(f"very_tall sweep {s + 6} (bf16 storage of A_u): {dt:.3f} s, training rmse {rh:.5f}", flush=True)
+        assert rh < r16 + 2e-3
+        r16 = rh
+    ah.synchronize()
+    ah.close()
     als.close()
