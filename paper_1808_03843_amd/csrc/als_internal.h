@@ -196,10 +196,10 @@ hipError_t check_ptr(bool ptr64, hipStream_t st, const void *ptr, int64_t nrows,
 hipError_t check_idx(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, int64_t nrows, int64_t ncols,
                      int64_t nnz, int *flags);
 // *sum (DEVICE) += fingerprint of the n row offsets: a sum of mixed (position, offset) pairs, so the order of the
-// additions does not matter
-hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum);
-// sets kStatusStalePlan in *status if *now != *want, then clears *now (all DEVICE)
-hipError_t plan_fingerprint_check(hipStream_t st, unsigned long long *now, const unsigned long long *want, int *status);
+// additions does not matter.  *done (DEVICE, zero between launches) counts the finished workgroups.  With `want`
+// (DEVICE): the last workgroup sets kStatusStalePlan in *status if the sum differs from *want, and clears *sum.
+hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum,
+                            unsigned int *done, const unsigned long long *want, int *status);
 // key[t] = index of the first stored entry of work item t, t < ntasks (DEVICE arrays)
 hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int32_t *idx, const int32_t *task_row,
                           const int32_t *task_chunk, int64_t ntasks, int chunk, int32_t *key);

@@ -46,7 +46,9 @@ struct als_ctx {
     size_t scratch_bytes = 0;
     int *status = nullptr;       // DEVICE status word
     int *check_flags = nullptr;  // DEVICE: result word of als_check_matrix
-    unsigned long long *fp_now = nullptr;   // DEVICE: fingerprint of the row offsets of the current call (zero between calls)
+    unsigned long long *fp_now = nullptr;   // DEVICE: fingerprint of the row offsets of the current call (zero between calls),
+                                            // followed by the 32-bit count of finished workgroups (fp_done)
+    unsigned int *fp_done = nullptr;
     double *sse_partial = nullptr;
     size_t sse_partial_bytes = 0;
     double *sse_total = nullptr; // DEVICE
@@ -198,7 +200,7 @@ int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
     HIP_TRY(ctx, plan_emit(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, p.task_row, p.task_chunk));
     HIP_TRY(ctx, hipMalloc(&p.fingerprint, sizeof(unsigned long long)));
     HIP_TRY(ctx, fill_zero(ctx->stream, p.fingerprint, 2));
-    HIP_TRY(ctx, plan_fingerprint(p64, ctx->stream, a->ptr, m + 1, p.fingerprint));
+    HIP_TRY(ctx, plan_fingerprint(p64, ctx->stream, a->ptr, m + 1, p.fingerprint, ctx->fp_done, nullptr, ctx->status));
     p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz; p.chunk = ctx->cfg.chunk;
     return ALS_OK;
 }
@@ -207,8 +209,8 @@ int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
 // offsets on the device and compares it with the plan's: a matrix that changed under its plan sets
 // kStatusStalePlan, which the next als_synchronize reports (kernels only: nothing here waits or allocates).
 int check_plan(als_ctx *ctx, const als_sparse *a, const Plan *p) {
-    HIP_TRY(ctx, plan_fingerprint(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->nrows + 1, ctx->fp_now));
-    HIP_TRY(ctx, plan_fingerprint_check(ctx->stream, ctx->fp_now, p->fingerprint, ctx->status));
+    HIP_TRY(ctx, plan_fingerprint(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->nrows + 1, ctx->fp_now, ctx->fp_done,
+                                  p->fingerprint, ctx->status));
     return ALS_OK;
 }
 
@@ -483,13 +485,14 @@ int als_create(als_ctx **out, const als_config *cfg) {
     DeviceGuard on_device;
     if (on_device.enter(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
         hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
-        hipMalloc(&ctx->fp_now, sizeof(unsigned long long)) != hipSuccess ||
+        hipMalloc(&ctx->fp_now, 2 * sizeof(unsigned long long)) != hipSuccess ||
         hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess ||
-        hipMemsetAsync(ctx->fp_now, 0, sizeof(unsigned long long), ctx->stream) != hipSuccess) {
+        hipMemsetAsync(ctx->fp_now, 0, 2 * sizeof(unsigned long long), ctx->stream) != hipSuccess) {
         hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now);
         delete ctx;
         return ALS_EHIP;
     }
+    ctx->fp_done = reinterpret_cast<unsigned int *>(ctx->fp_now + 1);
     *out = ctx;
     return ALS_OK;
 }

@@ -326,9 +326,14 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
     return x;
 }
 
+// *sum += fingerprint of ptr[0 .. n).  The workgroup that finishes last (a ticket counter, *done, which it puts back
+// to zero) sees the complete sum: with `want` given it compares, flags a mismatch in *status and clears *sum for the
+// next call; without, the sum stays where it is (the fingerprint a plan is built with).
 template <typename PtrT>
 __global__ __launch_bounds__(256) void k_fingerprint(const PtrT *__restrict__ ptr, int64_t n,
-                                                     unsigned long long *__restrict__ sum) {
+                                                     unsigned long long *__restrict__ sum, unsigned int *__restrict__ done,
+                                                     const unsigned long long *__restrict__ want,
+                                                     int *__restrict__ status) {
     __shared__ unsigned long long part[4];
     uint64_t h = 0;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
@@ -336,29 +341,30 @@ __global__ __launch_bounds__(256) void k_fingerprint(const PtrT *__restrict__ pt
     for (int o = 32; o > 0; o >>= 1) h += (uint64_t)__shfl_down((unsigned long long)h, o);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = h;
     __syncthreads();
+    if (threadIdx.x != 0) return;
     // one atomic per workgroup (many on one address would queue up); an integer sum: any order gives the same word
-    if (threadIdx.x == 0) atomicAdd(sum, part[0] + part[1] + part[2] + part[3]);
+    atomicAdd(sum, part[0] + part[1] + part[2] + part[3]);
+    __threadfence();
+    if (atomicAdd(done, 1u) != gridDim.x - 1) return;
+    __threadfence();
+    *done = 0u;
+    if (want) {
+        const unsigned long long total = atomicExch(sum, 0ull);
+        if (total != *want) atomicOr(status, kStatusStalePlan);
+    }
 }
 
-__global__ void k_fingerprint_check(unsigned long long *__restrict__ now, const unsigned long long *__restrict__ want,
-                                    int *__restrict__ status) {
-    if (*now != *want) atomicOr(status, kStatusStalePlan);
-    *now = 0ull;
-}
-
-hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum) {
+hipError_t plan_fingerprint(bool ptr64, hipStream_t st, const void *ptr, int64_t n, unsigned long long *sum,
+                            unsigned int *done, const unsigned long long *want, int *status) {
     if (n <= 0) return hipSuccess;
     int64_t nb = (n + 1023) / 1024;   // at least four offsets per thread; few workgroups, since each ends in an atomic
     if (nb > 1024) nb = 1024;
     if (ptr64)
-        hipLaunchKernelGGL(k_fingerprint<int64_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int64_t *)ptr, n, sum);
+        hipLaunchKernelGGL(k_fingerprint<int64_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int64_t *)ptr, n, sum, done,
+                           want, status);
     else
-        hipLaunchKernelGGL(k_fingerprint<int32_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int32_t *)ptr, n, sum);
-    return hipGetLastError();
-}
-
-hipError_t plan_fingerprint_check(hipStream_t st, unsigned long long *now, const unsigned long long *want, int *status) {
-    hipLaunchKernelGGL(k_fingerprint_check, dim3(1), dim3(1), 0, st, now, want, status);
+        hipLaunchKernelGGL(k_fingerprint<int32_t>, dim3((unsigned)nb), dim3(256), 0, st, (const int32_t *)ptr, n, sum, done,
+                           want, status);
     return hipGetLastError();
 }
 
