@@ -706,3 +706,47 @@ def test_more_matrices_than_cached_plans(P):
             assert not got[~live].any()
             assert _row_rel_err(got[live], ref[live]).max() <= TOL_EXACT, (rnd, int(k))
     als.close()
+
+
+@pytest.mark.parametrize("f,chunk", [(32, 64), (100, 256), (256, 128)])
+def test_epsilon_stopping_rule_of_algorithm_1(P, f, chunk):
+    """Algorithm 1 stops when sqrt(r^T r) < epsilon.  With f_s = 30 and an epsilon large enough to leave a visible
+    distance to the converged solution, rows of different degree stop after different numbers of iterations (the
+    oracle's counts are checked to spread).  The result follows the double-precision Algorithm 1 with the same
+    epsilon, and where stopping early changes a row by more than 3e-4 it is the early-stopped row that the GPU has.
+    A row whose residual passes within rounding of epsilon may stop one iteration apart in fp32 and fp64: two such
+    rows are allowed."""
+    n, fs, lam, eps = 1500, 30, 0.1, 0.1
+    rng = np.random.default_rng(17)
+    degrees = np.concatenate([[0, 1, 2, 3, 5, 8, 16, 33, 64, 100, 257, 600, 1500], rng.integers(1, 3 * chunk, 80)])
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = (rng.standard_normal(int(ptr[-1])) + 3).astype(np.float32)
+    Theta = W.random_factors(n, f, seed=f, scale=0.3)
+    warm = W.random_factors(len(degrees), f, seed=f + 1, scale=0.05)
+    counts = []
+    for u in (1, 4, 8, 10, 12):   # iterations the oracle takes on a few rows: the rule must bite, and not at once
+        s, e = ptr[u], ptr[u + 1]
+        A, b = oracle.normal_eq(idx[s:e], val[s:e], Theta, lam)
+        counts.append(oracle.cg(A, warm[u], b, fs=fs, eps=eps)[1])
+    assert max(counts) < fs and len(set(counts)) >= 3, counts
+    ref = oracle.update_rows_cg(ptr, idx, val, Theta, lam, warm, fs=fs, eps=eps)[1:]
+    full = oracle.update_rows_cg(ptr, idx, val, Theta, lam, warm, fs=fs, eps=0.0)[1:]
+    als = P.Als(f, solver=P.SOLVER_CG, cg_iters=fs, cg_eps=eps, chunk=chunk)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+    X = _dev(warm.copy())
+    als.update_rows(sp, _dev(Theta), lam, X)
+    als.synchronize()
+    got = X.cpu().numpy()
+    als.close()
+    assert not got[0].any()
+    err = _row_rel_err(got[1:], ref)
+    to_full = _row_rel_err(got[1:], full)
+    moved = _row_rel_err(ref, full) > 3e-4          # rows on which the rule makes a visible difference
+    print(f"f={f}: oracle iteration counts {counts}; rows moved by the rule {int(moved.sum())}; "
+          f"rows off the epsilon oracle by more than 2e-3: {int((err > 2e-3).sum())}, median {np.median(err):.2e}", flush=True)
+    assert moved.sum() >= 10
+    assert (err > 2e-3).sum() <= 2
+    assert (err[moved] < to_full[moved]).mean() >= 0.9
+
+
