@@ -750,3 +750,46 @@ def test_epsilon_stopping_rule_of_algorithm_1(P, f, chunk):
     assert (err[moved] < to_full[moved]).mean() >= 0.9
 
 
+@pytest.mark.parametrize("f", [100, 256])
+def test_zero_iterations_leave_the_warm_start(P, f):
+    """f_s = 0: Algorithm 1 computes the residual and returns x unchanged (rows without entries still become 0)."""
+    n = 400
+    rng = np.random.default_rng(2)
+    degrees = np.array([0, 1, 7, 64, 300, 400, 130, 0, 33])
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees] + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = rng.integers(1, 6, int(ptr[-1])).astype(np.float32)
+    warm = W.random_factors(len(degrees), f, seed=3, scale=0.2)
+    als = P.Als(f, solver=P.SOLVER_CG, cg_iters=0, chunk=128)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+    X = _dev(warm.copy())
+    als.update_rows(sp, _dev(W.random_factors(n, f, seed=4, scale=0.3)), 0.1, X)
+    als.synchronize()
+    got = X.cpu().numpy()
+    als.close()
+    live = degrees > 0
+    assert np.array_equal(got[live], warm[live]) and not got[~live].any()
+
+
+def test_kernel_times_are_recorded_when_profiling_is_on(P):
+    w = W.TINY
+    a = W.generate(w)
+    _, T0 = W.init_factors(w)
+    als = P.Als(w.f, solver=P.SOLVER_CG, chunk=64, profile=True)
+    sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    X = torch.zeros((w.m, w.f), device="cuda:0")
+    als.update_rows(sp, _dev(T0), w.lam, X)
+    als.rmse(sp, X, _dev(T0))
+    for kid in (P.K_HERMITIAN, P.K_SOLVE, P.K_FUSED, P.K_RMSE, P.K_PLAN):
+        ms, launches = als.kernel_time(kid)
+        assert launches >= 1 and ms > 0.0, kid
+    assert als.kernel_time(P.K_GRAM) == (0.0, 0)
+    als.profile_reset()
+    assert als.kernel_time(P.K_HERMITIAN) == (0.0, 0)
+    with pytest.raises(P.AlsError):
+        als.kernel_time(99)
+    als.close()
+    quiet = P.Als(w.f, solver=P.SOLVER_CG, chunk=64)        # profiling off: nothing is recorded
+    quiet.update_rows(sp, _dev(T0), w.lam, X)
+    assert quiet.kernel_time(P.K_HERMITIAN) == (0.0, 0)
+    quiet.close()
