@@ -793,3 +793,29 @@ def test_kernel_times_are_recorded_when_profiling_is_on(P):
     quiet.update_rows(sp, _dev(T0), w.lam, X)
     assert quiet.kernel_time(P.K_HERMITIAN) == (0.0, 0)
     quiet.close()
+
+
+def test_row_ranges_and_empty_gram(P):
+    """als_hermitian takes any row range inside the matrix, also the last rows and an empty one, and rejects a range
+    outside it; the Gram matrix of a factor without rows is zero."""
+    f, n = 32, 200
+    a = _edge_matrix(n, f, 5, [3, 0, 40, 17, 1])
+    Theta = W.random_factors(n, f, seed=6, scale=0.4)
+    als = P.Als(f)
+    sp = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    A, b = als.hermitian(sp, _dev(Theta), 0.2, 3, 2)          # the last two rows
+    for k, u in enumerate((3, 4)):
+        s, e = a.ptr[u], a.ptr[u + 1]
+        Ao, bo = oracle.normal_eq(a.idx[s:e], a.val[s:e], Theta, 0.2)
+        assert np.abs(A[k].cpu().numpy() - Ao).max() <= 1e-5 * np.abs(Ao).max()
+        assert np.abs(b[k].cpu().numpy() - bo).max() <= 1e-5 * max(np.abs(bo).max(), 1e-30)
+    import ctypes
+    dummy = torch.zeros(f * f, device="cuda:0")
+    desc = ctypes.byref(sp.desc)
+    assert als._lib.als_hermitian(als._ctx, desc, _dev(Theta).data_ptr(), 0.2, f, 5, 0, dummy.data_ptr(), dummy.data_ptr()) == 0
+    for row0, nrows in ((4, 2), (-1, 1), (0, 6)):
+        assert als._lib.als_hermitian(als._ctx, desc, _dev(Theta).data_ptr(), 0.2, f, row0, nrows, dummy.data_ptr(),
+                                      dummy.data_ptr()) == -1
+    G = als.gram(torch.zeros((0, f), device="cuda:0"))
+    assert tuple(G.shape) == (f, f) and not G.cpu().numpy().any()
+    als.close()
