@@ -624,6 +624,9 @@ def test_matrix_without_entries_and_without_rows(P, f):
         als.synchronize()
         assert not X.cpu().numpy().any()
         assert als.rmse(sp, X, Td) == 0.0
+        csc = als.csr_to_csc(sp)                          # its transpose: n empty rows
+        assert csc.nrows == n and csc.nnz == 0 and not csc.ptr.cpu().numpy().any()
+        als.check_matrix(sp)
         none = P.SparseMatrix.from_host(0, n, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
         als.update_rows(none, Td, 0.1, torch.zeros((0, f), device="cuda:0"))
         als.synchronize()
