@@ -24,6 +24,29 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def cpu_baseline_implicit(w, a_host, alpha):
+    """The implicit-feedback oracle (the sum over all m*n pairs, as the cost is defined) on a sample of rows and
+    columns; every row costs the same there (n f^2), so the sample is scaled by the number of rows."""
+    import numpy as np
+    import oracle
+    import workload as W
+    _, T0 = W.init_factors(w)
+    rows = np.linspace(0, w.m - 1, num=min(w.m, 6000), dtype=np.int64)
+    t0 = time.perf_counter()
+    oracle.implicit_update_selected(rows, a_host.ptr, a_host.idx, a_host.val, T0, w.lam, alpha)
+    t_rows = time.perf_counter() - t0
+    c = W.transpose(a_host)
+    cols = np.linspace(0, w.n - 1, num=min(w.n, 200), dtype=np.int64)
+    Xs = W.random_factors(w.m, w.f, seed=9, scale=0.5)
+    t0 = time.perf_counter()
+    oracle.implicit_update_selected(cols, c.ptr, c.idx, c.val, Xs, w.lam, alpha)
+    t_cols = time.perf_counter() - t0
+    est = t_rows * (w.m / len(rows)) + t_cols * (w.n / len(cols))
+    return {"value": est, "unit": "s/sweep", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": (f"exact fp64 all-pairs oracle on {len(rows)} evenly spaced rows ({t_rows:.2f} s) and {len(cols)} columns "
+                       f"({t_cols:.2f} s), scaled by the numbers of rows and columns")}
+
+
 def cpu_baseline(w, a_host, stride):
     """The oracle's exact sweep timed on every `stride`-th row and column, scaled by stored entries."""
     import numpy as np
@@ -292,7 +315,8 @@ def main():
             + f"; within 0.2% of the best after {hit + 1} sweeps = {cum[hit] * 1e3:.1f} ms")
     if args.cpu_stride > 0:
         log("[bench] timing the CPU oracle on a sample ...")
-        out["cpu_baseline"] = cpu_baseline(w, a, args.cpu_stride)
+        out["cpu_baseline"] = (cpu_baseline_implicit(w, a, args.implicit) if args.implicit is not None
+                               else cpu_baseline(w, a, args.cpu_stride))
     else:
         out["cpu_baseline"] = None
     als.close()
