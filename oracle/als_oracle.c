@@ -32,8 +32,10 @@
  * implicit feedback: weighted least squares by QR over all columns, f = 1 closed form,
  * alpha = 0 ridge regression, reduction to the explicit update on a fully observed row,
  * monotone implicit cost.
- * Parity unpinned: none of the exact-mode functions.  The CG-solver ALS sweep
- * (oracle_update_rows_cg) is pinned only through oracle_cg itself.
+ * The CG-solver ALS sweep (oracle_update_rows_cg): every row against Algorithm 1 run alone on
+ * that row's system and against the Krylov-space minimiser from that row's warm start,
+ * f_s = 0 leaves x alone, the exact solution is a fixed point, rows without entries become 0.
+ * Parity unpinned: none.
  *
  * Build: gcc -O3 -march=native -fopenmp -shared -fPIC (no -ffast-math).
  */

@@ -237,6 +237,63 @@ def test_cg_sweep_approaches_exact_sweep():
     assert np.linalg.norm(rough - exact) / np.linalg.norm(exact) < 0.2
 
 
+def _krylov_minimiser(A, x0, b, k):
+    """Iterate k of CG by its defining property, with no recurrence: the point of x0 + span{r0, A r0, ..., A^(k-1) r0}
+    that minimises the A-norm of the error (equivalently solves the projected system)."""
+    r0 = b - A @ x0
+    if k == 0:
+        return x0.copy()
+    K = np.empty((len(b), k))
+    v = r0.copy()
+    for j in range(k):
+        K[:, j] = v / np.linalg.norm(v)
+        v = A @ K[:, j]
+    Q, _ = np.linalg.qr(K)          # orthonormal basis: the projected system stays well conditioned
+    y = np.linalg.solve(Q.T @ A @ Q, Q.T @ r0)
+    return x0 + Q @ y
+
+
+@pytest.mark.parametrize("fs", [0, 1, 3])
+def test_cg_sweep_uses_each_rows_warm_start(fs):
+    # Algorithm 1 takes x as an input: the sweep must start row u from row u of the matrix handed in
+    # (not from 0, not from another row), must leave it alone for f_s = 0 and must zero rows without entries.
+    rng = np.random.default_rng(70 + fs)
+    m, n, f, lam = 9, 40, 6, 0.05
+    deg = [12, 0, 7, 25, 1, 0, 9, 30, 14]
+    ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, size=d, replace=False)) for d in deg]).astype(np.int32)
+    val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+    Theta = rng.standard_normal((n, f)) * 0.7
+    warm = rng.standard_normal((m, f))
+    got = oracle.update_rows_cg(ptr, idx, val, Theta, lam, warm, fs=fs)
+    for u in range(m):
+        s, e = ptr[u], ptr[u + 1]
+        if e == s:
+            assert np.all(got[u] == 0.0)          # no entries: x_u = 0 whatever the warm start
+            continue
+        A, b = oracle.normal_eq(idx[s:e], val[s:e], Theta, lam)
+        via_cg, _ = oracle.cg(A, warm[u], b, fs=fs)
+        assert np.array_equal(got[u], via_cg)      # the same routine on the same row: bit for bit
+        # and by an independent route: the Krylov-space minimiser started from THIS row's warm start
+        assert np.allclose(got[u], _krylov_minimiser(A, warm[u], b, fs), rtol=1e-8, atol=1e-10)
+        if fs == 0:
+            assert np.array_equal(got[u], warm[u])
+        elif e - s >= f:   # (a row with few entries has few distinct eigenvalues: CG is exact from any start)
+            other = _krylov_minimiser(A, warm[(u + 2) % m], b, fs)
+            cold = _krylov_minimiser(A, np.zeros(f), b, fs)
+            assert not np.allclose(got[u], other, rtol=1e-3) and not np.allclose(got[u], cold, rtol=1e-3)
+
+
+def test_cg_sweep_stays_at_the_exact_solution():
+    # a warm start that already solves every row's system is a fixed point (r0 = 0 guard), to rounding
+    w = W.TINY
+    a = W.generate(w)
+    _, T0 = W.init_factors(w)
+    exact = oracle.update_rows(a.ptr, a.idx, a.val, T0, w.lam)
+    again = oracle.update_rows_cg(a.ptr, a.idx, a.val, T0, w.lam, exact, fs=4)
+    assert np.allclose(again, exact, rtol=1e-9, atol=1e-12)
+
+
 # ---- P9 / P10: index work -------------------------------------------------------------------
 def test_csr_to_csc_invariants_and_scipy_crosscheck():
     for w in (W.TINY, W.SQUARE_SMALL):
