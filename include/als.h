@@ -145,6 +145,19 @@ int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const
  * symmetric).  The dense term of the implicit update; exported for tests. */
 int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out);
 
+/* als_gram for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels and the same result layout, but the partial Gram matrices
+ * and their sum live in a file-scope device array of 16 MiB that every GPU the library runs on holds until the
+ * process ends, so the call runs no hipMalloc, hipFree or other allocating routine and only enqueues kernels on
+ * the context's stream.  At most ALS_GRAM_STATIC_MAX_ROWS rows (ALS_EINVAL beyond).  The array holds room for
+ * min(512, 16 MiB / slot size) partial matrices (118 at f = 256), so a tall matrix is split into fewer, longer
+ * work items than als_gram uses and the fp32 partial sums may differ from its in the last bits; up to
+ * 256 * that many rows the two calls split the rows identically and agree bit for bit.  All calls on one GPU share
+ * the array: two calls that overlap on one GPU (different streams or contexts) race; calls on one stream are
+ * ordered.  Nothing in it needs clearing between calls: every word a call reads it has written before. */
+#define ALS_GRAM_STATIC_MAX_ROWS (1ll << 30)
+int als_gram_static(als_ctx *ctx, const float *G, int64_t n, int f, float *out);
+
 /* get_hermitian / get_bias alone (Section 2, step (i)) for rows [row0, row0+nrows):
  * A_out (DEVICE, nrows x f x f floats, full symmetric, lambda*n_u on the diagonal
  * included) and b_out (DEVICE, nrows x f).  Meant for tests and breakdown runs. */

@@ -24,6 +24,7 @@ EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
     "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_measure_peak", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
+    "als_gram_static",
 ]
 
 
@@ -68,6 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.als_update_cols_implicit.argtypes = [vp, sp, vp, fl, fl, ctypes.c_int, vp]
     lib.als_implicit_loss.argtypes = [vp, sp, vp, vp, fl, fl, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     lib.als_gram.argtypes = [vp, vp, i64, ctypes.c_int, vp]
+    lib.als_gram_static.argtypes = [vp, vp, i64, ctypes.c_int, vp]
     lib.als_hermitian.argtypes = [vp, sp, vp, fl, ctypes.c_int, i64, i64, vp, vp]
     lib.als_bin_rows.argtypes = [vp, sp, ctypes.c_int, vp, ctypes.POINTER(i64)]
     lib.als_csr_to_csc.argtypes = [vp, sp, vp, vp, vp]
@@ -199,6 +201,12 @@ class Als:
         self._check(self._lib.als_gram(self._ctx, self._factor(G, G.shape[0], self.f), G.shape[0], self.f,
                                        out.data_ptr()))
         return out
+
+    def gram_static(self, G: torch.Tensor, out: torch.Tensor) -> None:
+        """als_gram without allocation: the caller passes the output too (f x f float)."""
+        assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and tuple(out.shape) == (self.f, self.f)
+        self._check(self._lib.als_gram_static(self._ctx, self._factor(G, G.shape[0], self.f), G.shape[0], self.f,
+                                              out.data_ptr()))
 
     def rmse(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor) -> float:
         out = ctypes.c_double()

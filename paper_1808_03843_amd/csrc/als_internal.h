@@ -167,6 +167,11 @@ hipError_t launch_sse(int f, bool ptr64, bool implicit, float alpha, hipStream_t
 hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
                        float *out);
 hipError_t launch_tiles_to_dense(int f, hipStream_t st, const float *tiles, float *out);
+// als_gram_static: a file-scope device array of kGramStaticFloats floats (16 MiB) holds the slots and, after
+// them, the summed tiles.  gram_static_scratch returns its address on the CURRENT device.
+constexpr size_t kGramStaticFloats = (size_t)4 << 20;
+constexpr int kGramStaticMaxSlots = 512;
+hipError_t gram_static_scratch(float **ptr);
 hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B, double *out3);
 hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
                                      const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,

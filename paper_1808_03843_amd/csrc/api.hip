@@ -54,6 +54,7 @@ struct als_ctx {
     double *sse_total = nullptr; // DEVICE
     float *gram[2] = {nullptr, nullptr};   // DEVICE, tile layout: G^T G of the gathered factor (implicit mode)
     double *gram_dot = nullptr;            // DEVICE, 3 doubles
+    float *gram_static = nullptr;          // DEVICE: this device's copy of the file-scope scratch of als_gram_static
     std::vector<TimedLaunch> timed;
     std::vector<hipEvent_t> free_events;
 };
@@ -493,6 +494,11 @@ int als_create(als_ctx **out, const als_config *cfg) {
         return ALS_EHIP;
     }
     ctx->fp_done = reinterpret_cast<unsigned int *>(ctx->fp_now + 1);
+    if (gram_static_scratch(&ctx->gram_static) != hipSuccess) {   // the context's device is current here
+        hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now);
+        delete ctx;
+        return ALS_EHIP;
+    }
     *out = ctx;
     return ALS_OK;
 }
@@ -540,6 +546,34 @@ static int als_gram_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *
     int rc = compute_gram(ctx, G, n, 0);
     if (rc != ALS_OK) return rc;
     HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, ctx->gram[0], out));
+    return ALS_OK;
+}
+
+// als_gram without any allocation: slots and summed tiles live in the file-scope device array (implicit.hip).
+static int als_gram_static_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
+    if (!ctx) return ALS_EINVAL;
+    if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
+    if (n < 0 || !out || (n > 0 && !G)) return fail(ctx, ALS_EINVAL, "bad argument");
+    if (n > ALS_GRAM_STATIC_MAX_ROWS)
+        return fail(ctx, ALS_EINVAL, "als_gram_static takes at most ALS_GRAM_STATIC_MAX_ROWS (2^30) rows");
+    if (!aligned16(G)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
+    DeviceGuard on_device;
+    HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
+    const size_t tile_part = (size_t)tiles_tri(f) * 256;
+    float *slots = ctx->gram_static, *tiles = ctx->gram_static + (kGramStaticFloats - tile_part);
+    if (n == 0) {
+        HIP_TRY(ctx, fill_zero(ctx->stream, tiles, (int64_t)tile_part));
+    } else {
+        // as many work items as the array holds slots for (at most kGramStaticMaxSlots), each of `per` rows
+        int64_t cap = (int64_t)((kGramStaticFloats - tile_part) / (size_t)slot_floats(f));
+        if (cap > kGramStaticMaxSlots) cap = kGramStaticMaxSlots;
+        int64_t items = (n + 255) / 256;
+        if (items > cap) items = cap;
+        const int64_t per = ((n + items - 1) / items + 3) & ~(int64_t)3;   // <= 2^30 / 116 + 3 rows
+        const int nslots = (int)((n + per - 1) / per);
+        HIP_TRY(ctx, launch_gram(f, needs_wide_offsets(n, f, 4), ctx->stream, G, n, (int)per, nslots, slots, tiles));
+    }
+    HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, tiles, out));
     return ALS_OK;
 }
 
@@ -856,6 +890,10 @@ int als_update_cols_implicit(als_ctx *ctx, const als_sparse *csc, const void *X,
 
 int als_gram(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
     return guarded(ctx, [&] { return als_gram_impl(ctx, G, n, f, out); });
+}
+
+int als_gram_static(als_ctx *ctx, const float *G, int64_t n, int f, float *out) {
+    return guarded(ctx, [&] { return als_gram_static_impl(ctx, G, n, f, out); });
 }
 
 int als_implicit_loss(als_ctx *ctx, const als_sparse *csr, const float *X, const float *Theta, float lambda, float alpha, int f, double *loss_out) {

@@ -131,6 +131,19 @@ hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t
 #undef CALL
 }
 
+// Scratch of als_gram_static: the partial Gram matrices (slots) followed by the summed tiles, for callers
+// that cannot allocate.  Every GPU the library runs on holds its own copy until the process ends.  The name is
+// a host-side stand-in: host code uses the address that hipGetSymbolAddress returns on the current device.
+static __device__ __align__(256) float g_gram_scratch[kGramStaticFloats];
+
+hipError_t gram_static_scratch(float **ptr) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_gram_scratch));
+    if (e != hipSuccess) return e;
+    *ptr = static_cast<float *>(p);
+    return hipSuccess;
+}
+
 template <int F>
 static hipError_t dense_f(hipStream_t st, const float *tiles, float *out) {
     hipLaunchKernelGGL((k_tiles_to_dense<F>), dim3(tiles_tri(F)), dim3(256), 0, st, tiles, out);
