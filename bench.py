@@ -73,22 +73,29 @@ def cpu_baseline(w, a_host, stride):
                             f"{stride}th column ({nnz_cols} entries, {t_cols:.2f} s), scaled by stored entries")}
 
 
-# HBM bytes moved by the get_hermitian launches of one sweep (k_hermitian x2 + k_hermitian_cg x2), from the
-# rocprofv3 counter runs summarised in profiles/k_hermitian_mid_f100_cg6_counters.txt: FETCH_SIZE and WRITE_SIZE
-# summed over those dispatches, scaled by what the same counters read for a copy of known size (2 KiB and
-# 1 KiB per count).  Counters cannot be read from inside this process, so the figure is only reported for
-# the configuration it was measured on.
-MEASURED_TRAFFIC_BYTES_PER_SWEEP = {("mid", 100, "cg", 6, "f32", 4096): 35.1e9 + 1.07e9}
+# HBM bytes moved per launch by each get_hermitian kernel, from the rocprofv3 counter runs summarised in the file
+# named here: FETCH_SIZE and WRITE_SIZE summed over the kernel's dispatches of one sweep, scaled by what the same
+# counters read for a copy of known size (2 KiB and 1 KiB per count), divided by its launches.  Counters cannot be
+# read from inside this process, so the figure is only reported for the configuration it was measured on;
+# tests/test_host_logic.py checks the numbers against the file.
+TRAFFIC_SOURCE = "profiles/k_hermitian_mid_f100_cg6_counters.txt"
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
+    ("mid", 100, "cg", 6, "f32", 4096): {
+        "k_hermitian": ((3.282e5 + 1.043e7) * 2048 + (2.86e5 + 5.569e5) * 1024) / 2,
+        "k_hermitian_cg": ((2.849e6 + 3.543e6) * 2048 + (1.938e5 + 5012) * 1024) / 2,
+    },
+}
 
 
-def measured_traffic(w, args, chunk, launches):
-    if args.implicit is not None:
-        return None
+def measured_traffic(w, args, chunk, kernel):
+    """(HBM bytes per launch of `kernel`, where the figure comes from), or (None, None)."""
+    if args.implicit is not None or args.batch_slots != 0 or args.herm_dtype != "f32":
+        return None, None
     key = (w.name, w.f, args.solver, args.cg_iters if args.solver == "cg" else 0, args.factor_dtype, chunk)
-    total = MEASURED_TRAFFIC_BYTES_PER_SWEEP.get(key)
-    if total is None or launches <= 0 or args.batch_slots != 0 or args.herm_dtype != "f32":
-        return None
-    return total / launches
+    per_kernel = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(key)
+    if per_kernel is None or kernel not in per_kernel:
+        return None, None
+    return per_kernel[kernel], TRAFFIC_SOURCE
 
 
 def main():
@@ -112,7 +119,7 @@ def main():
     ap.add_argument("--cpu-stride", type=int, default=1, help="oracle baseline on every k-th row/column (1 = one whole exact sweep, about 20 s on 16 host threads); 0 = skip")
     ap.add_argument("--f", type=int, default=0, help="override the workload's factor width (factor-width sweep)")
     ap.add_argument("--factor-dtype", default="f32", choices=["f32", "bf16", "f16"],
-                    help="element type of the gathered factor matrix (16-bit: widened in registers, fp32 accumulate)")
+                    help="element type of the gathered factor matrix (16-bit: multiplied on the 16-bit matrix cores, fp32 accumulate)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -208,25 +215,54 @@ def main():
     per_entry = w.f * (w.f + 1)
     flops_sweep = 2.0 * nnz_fit * per_entry
     herm_s = (herm_ms + fused_ms) * 1e-3 / K
-    achieved = flops_sweep / herm_s / 1e12
+    achieved = flops_sweep / herm_s / 1e12          # all get_hermitian launches of a sweep together
     launches = (herm_n + fused_n) // K
-    roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                "traffic": measured_traffic(w, args, chunk, launches),
-                "kernel": "k_hermitian + k_hermitian_cg (all get_hermitian work of a sweep)",
-                "launches_per_sweep": launches, "avg_launch_ms": (herm_ms + fused_ms) / max(herm_n + fused_n, 1),
-                "flops_per_launch": flops_sweep / max(launches, 1),
-                "k_hermitian": {"tflops": nnz_slot * per_entry / max(herm_ms * 1e-3 / K, 1e-12) / 1e12,
-                                "ms_per_sweep": herm_ms / K, "entries_per_sweep": nnz_slot},
-                "k_hermitian_cg": {"tflops": (2 * nnz_fit - nnz_slot) * per_entry / max(fused_ms * 1e-3 / K, 1e-12) / 1e12,
-                                   "ms_per_sweep": fused_ms / K, "entries_per_sweep": 2 * nnz_fit - nnz_slot}}
+    # The two get_hermitian kernels, each with its own launches: entries (the unit of work), flops and time per launch.
+    kernels = {}
+    for name, what, ms, n, entries in (
+            ("k_hermitian", "get_hermitian of the work items of rows with >= chunk entries, into slots", herm_ms, herm_n, nnz_slot),
+            ("k_hermitian_cg", "get_hermitian fused with the solver (rows shorter than a chunk); its whole time is charged "
+                               "to get_hermitian", fused_ms, fused_n, 2 * nnz_fit - nnz_slot)):
+        if n <= 0:
+            continue
+        per_launch = entries / (n / K)
+        avg_ms = ms / n
+        tf = per_launch * per_entry / (avg_ms * 1e-3) / 1e12
+        kernels[name] = {"what": what, "tflops": tf, "frac": tf / PEAK_FP32_MFMA_TFLOPS, "ms_per_sweep": ms / K,
+                         "launches_per_sweep": n // K, "avg_launch_ms": avg_ms, "entries_per_launch": per_launch,
+                         "entries_per_sweep": entries}
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_sweep"])   # the kernel that takes most of the sweep
+    d = kernels[dom]
+    traffic, traffic_source = measured_traffic(w, args, chunk, dom)
+    roofline = {"bound": "mfma", "achieved": d["tflops"], "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": d["frac"], "traffic": traffic, "traffic_source": traffic_source,
+                "kernel": dom, "avg_launch_ms": d["avg_launch_ms"], "units_per_launch": d["entries_per_launch"],
+                "unit_of_work": f"stored entry: f(f+1) = {per_entry} flops (lower triangle of theta theta^T, FMA = 2), "
+                                f"{4 * w.f + 8} gathered bytes",
+                "flops_per_launch": d["entries_per_launch"] * per_entry,
+                "dominant_kernel": {"name": dom, "avg_launch_ms": d["avg_launch_ms"],
+                                    "units_per_launch": d["entries_per_launch"], "frac": d["frac"]},
+                "all_get_hermitian": {"achieved": achieved, "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                                      "ms_per_sweep": (herm_ms + fused_ms) / K, "launches_per_sweep": launches,
+                                      "flops_per_sweep": flops_sweep},
+                **kernels}
     if args.factor_dtype != "f32":
         # 16-bit factor inputs run on the 16-bit matrix cores (16x the fp32 rate): the gathers bound the kernel.
         # Algorithmic bytes per stored entry and half-sweep: one 16-bit factor row + column id + rating.
-        bytes_sweep = 2.0 * nnz_fit * (2.0 * w.f + 8.0)
-        gbps = bytes_sweep / herm_s / 1e9
-        roofline.update({"bound": "hbm", "achieved": gbps, "peak": 8000.0, "unit": "GB/s", "frac": gbps / 8000.0,
-                         "traffic": None, "bytes_per_launch": bytes_sweep / max(launches, 1),
+        per_entry_b = 2.0 * w.f + 8.0
+        for k in kernels.values():
+            k["gathered_GBps"] = k["entries_per_launch"] * per_entry_b / (k["avg_launch_ms"] * 1e-3) / 1e9
+            k["frac"] = k["gathered_GBps"] / 8000.0
+            k["frac_of_16bit_mfma_peak"] = k["tflops"] / PEAK_16BIT_MFMA_TFLOPS
+        gbps_all = 2.0 * nnz_fit * per_entry_b / herm_s / 1e9
+        roofline.update({"bound": "hbm", "achieved": d["gathered_GBps"], "peak": 8000.0, "unit": "GB/s",
+                         "frac": d["frac"], "traffic": None, "traffic_source": None,
+                         "unit_of_work": f"stored entry: {per_entry_b:.0f} gathered bytes (16-bit factor row, column id, rating)",
+                         "bytes_per_launch": d["entries_per_launch"] * per_entry_b,
+                         "dominant_kernel": {"name": dom, "avg_launch_ms": d["avg_launch_ms"],
+                                             "units_per_launch": d["entries_per_launch"], "frac": d["frac"]},
+                         "all_get_hermitian": {"achieved": gbps_all, "frac": gbps_all / 8000.0,
+                                               "ms_per_sweep": (herm_ms + fused_ms) / K, "launches_per_sweep": launches},
                          "mfma": {"achieved_tflops": achieved, "peak_tflops": PEAK_16BIT_MFMA_TFLOPS,
                                   "frac": achieved / PEAK_16BIT_MFMA_TFLOPS}})
         roofline.pop("flops_per_launch", None)
@@ -288,6 +324,7 @@ def main():
                              "note": "8 wavefronts per SIMD issuing independent MFMAs; copy of 1 GiB, bytes read + written"}
     if roofline["bound"] == "mfma":
         roofline["frac_of_measured_peak"] = roofline["achieved"] / (mf32 / 1e12)
+        roofline["all_get_hermitian"]["frac_of_measured_peak"] = roofline["all_get_hermitian"]["achieved"] / (mf32 / 1e12)
     else:
         roofline["frac_of_measured_copy"] = roofline["achieved"] / (cp / 1e9)
     log(f"[bench] sustained on this box: fp32 MFMA {mf32 / 1e12:.1f} TFLOP/s, bf16 MFMA {mbf16 / 1e12:.0f} TFLOP/s, "

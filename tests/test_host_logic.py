@@ -1,8 +1,11 @@
 """Host-side behaviour of the C ABI that needs no GPU: argument checks happen before any device is touched,
 null handles are errors, and without a device the library says so instead of falling back to anything."""
 import ctypes
+import os
 
 import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 import paper_1808_03843_amd as P
 from paper_1808_03843_amd.binding import AlsConfig
@@ -80,3 +83,29 @@ def test_null_context_is_rejected_by_every_entry_point():
     assert lib.als_drop_plans(None) == EINVAL
     assert lib.als_check_matrix(None, None) == EINVAL
     assert lib.als_measure_peak(None, 0, ctypes.byref(d)) == EINVAL
+
+
+def test_bench_traffic_figures_agree_with_the_committed_counter_summary():
+    """bench.py reports roofline.traffic from a table typed in from a rocprofv3 counter run; the summary of that
+    run is committed under profiles/.  The two must agree: FETCH_SIZE counts 2 KiB and WRITE_SIZE 1 KiB per unit
+    on this machine (calibrated against a copy of known size, stated in the summary), summed per kernel over the
+    dispatches of one sweep and divided by its launches."""
+    import re
+    import bench
+    path = os.path.join(ROOT, bench.TRAFFIC_SOURCE)
+    text = open(path).read()
+    assert "1 unit = 2 KiB" in text and "1 unit = 1 KiB" in text          # the calibration the table relies on
+    sums, launches = {}, {}
+    for line in text.splitlines():
+        m = re.match(r"(k_hermitian(?:_cg)?)<.*?(FETCH_SIZE|WRITE_SIZE)=([0-9.e+]+)", line)
+        if not m or line.startswith("#"):
+            continue
+        kernel, counter, value = m.group(1), m.group(2), float(m.group(3))
+        sums[kernel] = sums.get(kernel, 0.0) + value * (2048 if counter == "FETCH_SIZE" else 1024)
+        if counter == "FETCH_SIZE":
+            launches[kernel] = launches.get(kernel, 0) + 1
+    table = bench.MEASURED_TRAFFIC_BYTES_PER_LAUNCH[("mid", 100, "cg", 6, "f32", 4096)]
+    assert set(table) == set(sums) == {"k_hermitian", "k_hermitian_cg"}
+    for kernel, per_launch in table.items():
+        assert launches[kernel] == 2                                       # one launch per side and sweep
+        assert per_launch == pytest.approx(sums[kernel] / launches[kernel], rel=1e-3)
