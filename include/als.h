@@ -85,10 +85,33 @@ typedef struct als_config {
     int64_t batch_slots;  /* work items whose partial A_u are held at once (0 = about 4 GB worth;
                              larger values than 4,194,303 are taken as that)                                      */
     int32_t profile;      /* 1: bracket every kernel with HIP events (see als_kernel_time)               */
+    /* Caller-owned work memory (optional).  workspace: DEVICE, 256-byte aligned, at least
+     * als_workspace_bytes(cfg, workspace_max_rows, workspace_max_nnz) bytes, owned by the caller and left alone by
+     * it until als_destroy.  With it the library takes no device memory of its own for the update, RMSE, implicit,
+     * Gram, check and synchronize calls: status words, work plans, partial Gram matrices and partial sums are all
+     * carved from it, and those calls run no hipMalloc / hipFree.  Matrices with more rows (of the compressed
+     * form passed in) or more stored entries than the two maxima are refused with ALS_EINVAL and the size that
+     * would be needed.  The helper calls outside the per-sweep path (als_hermitian, als_bin_rows, als_csr_to_csc,
+     * als_measure_peak) still take temporary device memory of their own for the duration of the call.
+     * NULL (and 0 for the three sizes): the library allocates with hipMalloc on first use, may
+     * free and reallocate when a larger matrix or batch shows up, and keeps the memory until als_destroy. */
+    void *workspace;
+    size_t workspace_bytes;
+    int64_t workspace_max_rows;
+    int64_t workspace_max_nnz;
 } als_config;
 
-/* Creates a context.  Allocates small bookkeeping only; work buffers are
- * allocated with hipMalloc on first use and kept until als_destroy. */
+/* Bytes of workspace a context with this configuration needs for matrices of at most max_rows rows (the larger
+ * of m and n when both the CSR and the CSC of R are used) and max_nnz stored entries: bookkeeping, the plans of
+ * two such matrices at once (more if they are smaller; when a new plan does not fit, all cached plans are
+ * dropped and rebuilt on demand), one partial sum per work item, and partial Gram matrices for
+ * min(batch_slots, 2 * max_nnz / chunk + 1) work items.  The workspace, workspace_bytes and workspace_max_* fields
+ * of cfg are ignored.  Returns 0 for a configuration als_create would refuse.  Needs no device. */
+size_t als_workspace_bytes(const als_config *cfg, int64_t max_rows, int64_t max_nnz);
+
+/* Creates a context.  Without a workspace: allocates small bookkeeping only; work buffers are allocated with
+ * hipMalloc on first use and kept until als_destroy.  With a workspace (see als_config): allocates nothing on
+ * the device, now or later; a workspace that is too small or misaligned gives ALS_EINVAL. */
 int als_create(als_ctx **out, const als_config *cfg);
 
 /* Frees everything the context allocated (waits for its stream first). NULL is allowed. */
@@ -103,9 +126,9 @@ const char *als_last_error(const als_ctx *ctx);
  * warm start of Algorithm 1.  Rows with n_u = 0 get x_u = 0.  f must equal the
  * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD).
  * The first call on a matrix (identified by its ptr, nrows, nnz) builds its work plan and sizes the work
- * buffers: it allocates and waits for the stream.  Later calls on the same matrix only enqueue kernels on the
- * context's stream (no allocation, no wait, no memset), so they may be captured in a HIP graph; the same holds
- * for als_update_cols and the implicit variants.  Errors found by the kernels (a non-positive pivot, a
+ * buffers: it waits for the stream and, without a caller's workspace, allocates.  Later calls on the same matrix
+ * only enqueue kernels on the context's stream (no allocation, no wait, no memset), so they may be captured in a
+ * HIP graph; the same holds for als_update_cols and the implicit variants.  Errors found by the kernels (a non-positive pivot, a
  * non-finite solution) are reported by the next als_synchronize. */
 int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X);
 

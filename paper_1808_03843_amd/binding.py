@@ -24,7 +24,7 @@ EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
     "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_measure_peak", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
-    "als_gram_static",
+    "als_gram_static", "als_workspace_bytes",
 ]
 
 
@@ -38,7 +38,9 @@ class AlsConfig(ctypes.Structure):
     _fields_ = [("f", ctypes.c_int32), ("solver", ctypes.c_int32), ("cg_iters", ctypes.c_int32),
                 ("cg_eps", ctypes.c_float), ("factor_dtype", ctypes.c_int32), ("herm_dtype", ctypes.c_int32),
                 ("device", ctypes.c_int32), ("stream", ctypes.c_void_p), ("chunk", ctypes.c_int32),
-                ("batch_slots", ctypes.c_int64), ("profile", ctypes.c_int32)]
+                ("batch_slots", ctypes.c_int64), ("profile", ctypes.c_int32),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                ("workspace_max_rows", ctypes.c_int64), ("workspace_max_nnz", ctypes.c_int64)]
 
 
 _lib = None
@@ -58,6 +60,8 @@ def load_library() -> ctypes.CDLL:
     vp, i32, i64, fl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     sp = ctypes.POINTER(AlsSparse)
     lib.als_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(AlsConfig)]
+    lib.als_workspace_bytes.argtypes = [ctypes.POINTER(AlsConfig), i64, i64]
+    lib.als_workspace_bytes.restype = ctypes.c_size_t
     lib.als_destroy.argtypes = [vp]
     lib.als_destroy.restype = None
     lib.als_last_error.argtypes = [vp]
@@ -122,12 +126,24 @@ class Als:
 
     def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
                  device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
-                 profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32):
+                 profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32,
+                 workspace_rows: int = 0, workspace_nnz: int = 0):
+        """workspace_rows / workspace_nnz > 0: the library works in a torch-allocated workspace sized for matrices of
+        at most that many rows and stored entries, and allocates no device memory itself."""
         self._lib = load_library()
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
         self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, herm_dtype, device, stream, chunk, batch_slots,
                              1 if profile else 0)
+        self.workspace = None
+        if workspace_rows > 0 or workspace_nnz > 0:
+            need = self._lib.als_workspace_bytes(ctypes.byref(self.cfg), workspace_rows, workspace_nnz)
+            if need == 0:
+                raise AlsError(ALS_EINVAL, "als_workspace_bytes refused the configuration")
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=f"cuda:{device}")   # torch owns the memory
+            assert self.workspace.data_ptr() % 256 == 0
+            self.cfg.workspace, self.cfg.workspace_bytes = self.workspace.data_ptr(), need
+            self.cfg.workspace_max_rows, self.cfg.workspace_max_nnz = workspace_rows, workspace_nnz
         self._ctx = ctypes.c_void_p()
         rc = self._lib.als_create(ctypes.byref(self._ctx), ctypes.byref(self.cfg))
         if rc != ALS_OK:

@@ -76,8 +76,7 @@ struct Plan {                     // per sparse matrix, built once and cached
     int32_t *task_row = nullptr;  // DEVICE [ntasks]
     int32_t *task_chunk = nullptr;// DEVICE [ntasks]
     unsigned long long *fingerprint = nullptr;   // DEVICE: fingerprint of the row offsets the plan was built from
-    int32_t *task_order = nullptr;// DEVICE [work items of the slot path]: launch order inside every batch (see ensure_order)
-    int64_t order_cap = -1;       // the batch capacity task_order was built for
+    int32_t *task_order = nullptr;// DEVICE [work items of the slot path]: launch order inside every batch (see build_order)
     int32_t *task_off_host = nullptr; // HOST copy of task_off
     int64_t ntasks = 0;
     int64_t split_pos = 0;        // perm positions [0, split_pos): rows with >= chunk entries (slot path)
@@ -107,7 +106,7 @@ hipError_t launch_solve_cg_wave(int f, bool ptr64, bool s16, int solver, hipStre
                                 int64_t pos0, int64_t npos, int64_t task0, const void *ptr, const float *slots,
                                 float lambda, int fs, float eps, float *Xout, int *status);
 // f = 256 (wide.hip): a system is shared by the wavefronts of one workgroup.  Same arguments as the
-// launchers above; Algorithm 1 only (the exact solver at this width works on slots in LDS, solve.hip).
+// launchers above; Algorithm 1 only (the exact solver at this width is in wide_ldlt.hip, declared below).
 hipError_t launch_hermitian_wide(bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                                  const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                                  const int32_t *idx, const float *val, const void *Theta, float *slots);
@@ -187,10 +186,18 @@ hipError_t launch_solve_wave_implicit(int f, bool ptr64, int solver, hipStream_t
                                       float eps, float *Xout, int *status);
 
 // plan.hip
+// scratch: a buffer the two calls below grow on demand (hipFree + hipMalloc), unless scratch_fixed: then it is part
+// of a caller's workspace, and a buffer smaller than plan_scratch_bytes(nrows, nclass) gives hipErrorOutOfMemory
+size_t plan_scratch_bytes(int64_t nrows, int nclass);
+hipError_t ensure_scratch(void **scratch, size_t *have, size_t need, bool fixed);
 hipError_t plan_bin_rows(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, int nclass, int32_t *perm,
-                         int32_t *class_start_dev /*nclass+1*/, void **scratch, size_t *scratch_bytes);
+                         int32_t *class_start_dev /*nclass+1*/, void **scratch, size_t *scratch_bytes, bool scratch_fixed);
 hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
-                      int32_t *task_off /*nrows+1*/, void **scratch, size_t *scratch_bytes);
+                      int32_t *task_off /*nrows+1*/, void **scratch, size_t *scratch_bytes, bool scratch_fixed);
+// order[first .. first+count) = the work items first .. first+count-1 sorted by key (stable); batches of more than
+// kMaxRankedItems items keep their natural order
+constexpr int64_t kMaxRankedItems = 1 << 18;
+hipError_t plan_rank_order(hipStream_t st, const int32_t *key, int64_t first, int64_t count, int32_t *order);
 hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);

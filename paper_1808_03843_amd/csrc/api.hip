@@ -22,10 +22,55 @@ bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
 }
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
+
+// ---- layout of a caller's workspace ---------------------------------------------------------------------------
+constexpr size_t kAlign = 256;
+constexpr size_t aligned(size_t n) { return (n + kAlign - 1) / kAlign * kAlign; }
+// upper bounds that hold for every matrix with `rows` rows and `nnz` stored entries: a row of n_u entries has
+// ceil(n_u / chunk) work items, and only rows with n_u >= chunk (fewer than 2 n_u / chunk items each) use slots
+int64_t max_tasks(int64_t rows, int64_t nnz, int chunk) { return rows + nnz / chunk; }
+int64_t max_slot_tasks(int64_t rows, int64_t nnz, int chunk) {
+    const int64_t a = max_tasks(rows, nnz, chunk), b = 2 * nnz / chunk;
+    return a < b ? a : b;
+}
+size_t plan_bytes_bound(int64_t rows, int64_t nnz, int chunk) {
+    const size_t t = (size_t)max_tasks(rows, nnz, chunk), s = (size_t)max_slot_tasks(rows, nnz, chunk);
+    return aligned(4 * (size_t)(rows > 0 ? rows : 1)) + aligned(4 * (size_t)(rows + 1)) + 2 * aligned(4 * (t > 0 ? t : 1)) +
+           aligned(4 * (s > 0 ? s : 1)) + aligned(16);
+}
+size_t slot_bytes(const als_config &c) {
+    return sizeof(float) * (size_t)(c.herm_dtype == ALS_BF16 ? slot_words16(c.f) : slot_floats(c.f));
+}
+struct WorkspaceLayout {   // byte offsets of the pieces; `total` is what als_workspace_bytes returns
+    size_t fixed_words, gram0, gram1, sse_partial, scratch, scratch_bytes, slots, arena, arena_bytes, total;
+    int64_t slot_capacity;
+};
+// cfg: chunk and batch_slots already resolved (no zeros)
+WorkspaceLayout workspace_layout(const als_config &c, int64_t rows, int64_t nnz) {
+    WorkspaceLayout L{};
+    size_t o = 0;
+    L.fixed_words = o; o += aligned(1024);   // status, check flags, fingerprint + counter, sums, class starts
+    L.gram0 = o; o += aligned(sizeof(float) * (size_t)slot_floats(c.f));
+    L.gram1 = o; o += aligned(sizeof(float) * (size_t)slot_floats(c.f));
+    L.sse_partial = o; o += aligned(sizeof(double) * (size_t)(max_tasks(rows, nnz, c.chunk) + 1));
+    // plan scratch; also holds the sort keys of the slot work items (one int each)
+    L.scratch_bytes = plan_scratch_bytes(rows, kPlanClasses);
+    const size_t keys = 4 * (size_t)(max_slot_tasks(rows, nnz, c.chunk) + 1);
+    if (keys > L.scratch_bytes) L.scratch_bytes = keys;
+    L.scratch_bytes = aligned(L.scratch_bytes);
+    L.scratch = o; o += L.scratch_bytes;
+    L.slot_capacity = max_slot_tasks(rows, nnz, c.chunk) + 1;
+    if (L.slot_capacity > c.batch_slots) L.slot_capacity = c.batch_slots;
+    L.slots = o; o += aligned((size_t)L.slot_capacity * slot_bytes(c));
+    L.arena_bytes = 2 * plan_bytes_bound(rows, nnz, c.chunk);
+    L.arena = o; o += L.arena_bytes;
+    L.total = o;
+    return L;
+}
 #ifndef ALS_TASK_ORDER
 #define ALS_TASK_ORDER 1
 #endif
-constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work items of a batch (ensure_order)
+constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work items of a batch (build_order)
 #ifndef ALS_DUAL_EXACT
 #define ALS_DUAL_EXACT 1
 #endif
@@ -55,6 +100,12 @@ struct als_ctx {
     float *gram[2] = {nullptr, nullptr};   // DEVICE, tile layout: G^T G of the gathered factor (implicit mode)
     double *gram_dot = nullptr;            // DEVICE, 3 doubles
     float *gram_static = nullptr;          // DEVICE: this device's copy of the file-scope scratch of als_gram_static
+    // caller-owned workspace (cfg.workspace != nullptr): every device buffer above is a piece of it
+    bool fixed = false;                    // true: nothing here is ever hipMalloc'ed or hipFree'd
+    int32_t *class_start_dev = nullptr;    // DEVICE [kPlanClasses + 1] (workspace mode; a temporary otherwise)
+    char *arena = nullptr;                 // the part of the workspace that holds the plans, filled front to back
+    size_t arena_bytes = 0, arena_used = 0;
+    int64_t slot_capacity = 0;             // workspace mode: slots the slot region holds (of the configured storage type)
     std::vector<TimedLaunch> timed;
     std::vector<hipEvent_t> free_events;
 };
@@ -92,10 +143,30 @@ int fail_hip(als_ctx *ctx, hipError_t e, const char *what) {
         if (e_ != hipSuccess) return fail_hip(ctx, e_, #expr); \
     } while (0)
 
-void free_plan(Plan &p) {
-    hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk); hipFree(p.task_order); hipFree(p.fingerprint);
+void free_plan(als_ctx *ctx, Plan &p) {
+    if (!ctx->fixed) {
+        hipFree(p.perm); hipFree(p.task_off); hipFree(p.task_row); hipFree(p.task_chunk); hipFree(p.task_order); hipFree(p.fingerprint);
+    }
     delete[] p.task_off_host;
     p = Plan();
+}
+
+// device memory of a plan: a piece of the arena (workspace mode; the caller has made sure the plan fits) or hipMalloc
+template <typename T>
+hipError_t plan_alloc(als_ctx *ctx, T **out, size_t bytes) {
+    if (!ctx->fixed) return hipMalloc(out, bytes);
+    if (ctx->arena_used + aligned(bytes) > ctx->arena_bytes) return hipErrorOutOfMemory;
+    *out = reinterpret_cast<T *>(ctx->arena + ctx->arena_used);
+    ctx->arena_used += aligned(bytes);
+    return hipSuccess;
+}
+
+std::string workspace_needed(als_ctx *ctx, int64_t rows, int64_t nnz) {
+    const int64_t r = rows > ctx->cfg.workspace_max_rows ? rows : ctx->cfg.workspace_max_rows;
+    const int64_t z = nnz > ctx->cfg.workspace_max_nnz ? nnz : ctx->cfg.workspace_max_nnz;
+    return "the workspace was sized for " + std::to_string(ctx->cfg.workspace_max_rows) + " rows and " +
+           std::to_string(ctx->cfg.workspace_max_nnz) + " entries; this matrix has " + std::to_string(rows) + " rows and " +
+           std::to_string(nnz) + " entries and needs " + std::to_string(workspace_layout(ctx->cfg, r, z).total) + " bytes";
 }
 
 int check_sparse(als_ctx *ctx, const als_sparse *a) {
@@ -105,6 +176,8 @@ int check_sparse(als_ctx *ctx, const als_sparse *a) {
     if (!a->ptr) return fail(ctx, ALS_EINVAL, "ptr is null");
     if (a->nnz > 0 && (!a->idx || !a->val)) return fail(ctx, ALS_EINVAL, "idx or val is null");
     if (!a->ptr_is_64 && a->nnz > 0x7fffffff) return fail(ctx, ALS_EINVAL, "nnz >= 2^31 needs 64-bit ptr");
+    if (ctx && ctx->fixed && (a->nrows > ctx->cfg.workspace_max_rows || a->nnz > ctx->cfg.workspace_max_nnz))
+        return fail(ctx, ALS_EINVAL, "workspace too small: " + workspace_needed(ctx, a->nrows, a->nnz));
     return ALS_OK;
 }
 
@@ -142,26 +215,78 @@ struct Timed {   // brackets one launch with events when profiling is on
 
 int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p);
 
-// Finds or builds the plan of a matrix: degree-class permutation, work items.
+// Finds or builds the plan of a matrix: degree-class permutation, work items, launch order of the slot work items.
 int get_plan(als_ctx *ctx, const als_sparse *a, Plan **out) {
     for (auto &p : ctx->plans)
         if (p.key_ptr == a->ptr && p.nrows == a->nrows && p.nnz == a->nnz && p.chunk == ctx->cfg.chunk) {
             *out = &p;
             return ALS_OK;
         }
+    if (ctx->fixed) {
+        // Plans fill the arena front to back.  When the table or the arena is full, every cached plan is dropped;
+        // the arena holds two plans of the largest matrix the workspace was sized for.  Kernels of earlier calls
+        // that still read the old plans are ahead of the new plan's kernels on the stream.
+        const bool table_full = ctx->plans[kMaxPlans - 1].key_ptr != nullptr;
+        if (table_full || ctx->arena_used + plan_bytes_bound(a->nrows, a->nnz, ctx->cfg.chunk) > ctx->arena_bytes) {
+            for (auto &p : ctx->plans) free_plan(ctx, p);
+            ctx->arena_used = 0;
+            ctx->next_plan = 0;
+        }
+    }
     Plan &p = ctx->plans[ctx->next_plan];
     ctx->next_plan = (ctx->next_plan + 1) % kMaxPlans;
-    if (p.key_ptr) {
+    if (p.key_ptr) {   // (never in workspace mode: the table was emptied above)
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        free_plan(p);
+        free_plan(ctx, p);
     }
+    const size_t arena_mark = ctx->arena_used;
     const int rc = build_plan(ctx, a, p);
     if (rc != ALS_OK) {   // nothing of a half-built plan stays behind
         (void)hipStreamSynchronize(ctx->stream);
-        free_plan(p);
+        free_plan(ctx, p);
+        ctx->arena_used = arena_mark;
+        ctx->next_plan = (ctx->next_plan + kMaxPlans - 1) % kMaxPlans;
         return rc;
     }
     *out = &p;
+    return ALS_OK;
+}
+
+// largest end with off[end] - off[pos] <= cap (at least pos + 1): the rows of one batch of the slot path
+int64_t batch_end(const int32_t *off, int64_t pos, int64_t slot_rows, int64_t cap) {
+    int64_t lo = pos + 1, hi = slot_rows;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// work items whose partial Gram matrices are held at once
+int64_t batch_capacity(const als_ctx *ctx) {
+    return ctx->fixed && ctx->slot_capacity < ctx->cfg.batch_slots ? ctx->slot_capacity : ctx->cfg.batch_slots;
+}
+
+// Launch order of the work items inside every batch of the slot path.  The entries of a row are sorted by
+// index, so a work item (a chunk of a long row) gathers from a band of the factor matrix that starts at its first
+// index; workgroups are dispatched in launch order, and ordering the work items of a batch by that first index
+// (instead of row by row, which puts disjoint bands side by side) makes the work items in flight gather from the
+// same band, which then stays in the L2.  The slot of a work item is still its index in the batch.  Sorted on the
+// device, batch by batch (the batches are those of update(): the capacity is fixed for the life of the context).
+int build_order(als_ctx *ctx, const als_sparse *a, Plan &p) {
+    const int32_t *off = p.task_off_host;
+    const int64_t slot_rows = p.split_pos, n = slot_rows > 0 ? off[slot_rows] : 0;
+    HIP_TRY(ctx, plan_alloc(ctx, &p.task_order, sizeof(int32_t) * (size_t)(n > 0 ? n : 1)));
+    if (n == 0) return ALS_OK;
+    HIP_TRY(ctx, ensure_scratch(&ctx->scratch, &ctx->scratch_bytes, sizeof(int32_t) * (size_t)n, ctx->fixed));
+    int32_t *key = static_cast<int32_t *>(ctx->scratch);
+    HIP_TRY(ctx, plan_task_keys(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->idx, p.task_row, p.task_chunk, n, p.chunk, key));
+    const int64_t cap = batch_capacity(ctx);
+    for (int64_t pos = 0; pos < slot_rows;) {
+        const int64_t end = batch_end(off, pos, slot_rows, cap);
+        HIP_TRY(ctx, plan_rank_order(ctx->stream, key, off[pos], (int64_t)off[end] - off[pos], p.task_order));
+        pos = end;
+    }
     return ALS_OK;
 }
 
@@ -169,17 +294,17 @@ int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
     Timed timed(ctx, ALS_K_PLAN);
     const int64_t m = a->nrows;
     const bool p64 = a->ptr_is_64 != 0;
-    HIP_TRY(ctx, hipMalloc(&p.perm, sizeof(int32_t) * (size_t)(m > 0 ? m : 1)));
-    HIP_TRY(ctx, hipMalloc(&p.task_off, sizeof(int32_t) * (size_t)(m + 1)));
-    int32_t *class_start_dev = nullptr;
-    HIP_TRY(ctx, hipMalloc(&class_start_dev, sizeof(int32_t) * (kPlanClasses + 1)));
+    HIP_TRY(ctx, plan_alloc(ctx, &p.perm, sizeof(int32_t) * (size_t)(m > 0 ? m : 1)));
+    HIP_TRY(ctx, plan_alloc(ctx, &p.task_off, sizeof(int32_t) * (size_t)(m + 1)));
+    int32_t *class_start_dev = ctx->class_start_dev;
+    if (!ctx->fixed) HIP_TRY(ctx, hipMalloc(&class_start_dev, sizeof(int32_t) * (kPlanClasses + 1)));
     hipError_t eb = plan_bin_rows(p64, ctx->stream, m, a->ptr, kPlanClasses, p.perm, class_start_dev, &ctx->scratch,
-                                  &ctx->scratch_bytes);
+                                  &ctx->scratch_bytes, ctx->fixed);
     int32_t class_start[kPlanClasses + 1];
     if (eb == hipSuccess)
         eb = hipMemcpyAsync(class_start, class_start_dev, sizeof(class_start), hipMemcpyDeviceToHost, ctx->stream);
     if (eb == hipSuccess) eb = hipStreamSynchronize(ctx->stream);
-    (void)hipFree(class_start_dev);
+    if (!ctx->fixed) (void)hipFree(class_start_dev);
     HIP_TRY(ctx, eb);
     {   // rows with >= chunk = 2^j entries are the classes >= j+1, i.e. the first class_start[...] positions
         int j = 0;
@@ -189,20 +314,23 @@ int build_plan(als_ctx *ctx, const als_sparse *a, Plan &p) {
     for (int c = 0; c <= 32; ++c)   // class c = 1 + floor(log2 n_u) (0 for empty rows), heaviest class first in perm
         p.rows_ge[c] = c == 0 ? m : (c < kPlanClasses ? class_start[kPlanClasses - c] : 0);
     HIP_TRY(ctx, plan_tasks(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, &ctx->scratch,
-                            &ctx->scratch_bytes));
+                            &ctx->scratch_bytes, ctx->fixed));
     p.task_off_host = new (std::nothrow) int32_t[(size_t)m + 1];
     if (!p.task_off_host) return fail(ctx, ALS_ENOMEM, "host allocation of the work-item offsets failed");
     HIP_TRY(ctx, hipMemcpyAsync(p.task_off_host, p.task_off, sizeof(int32_t) * (size_t)(m + 1), hipMemcpyDeviceToHost,
                                 ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     p.ntasks = p.task_off_host[m];
-    HIP_TRY(ctx, hipMalloc(&p.task_row, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
-    HIP_TRY(ctx, hipMalloc(&p.task_chunk, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
+    HIP_TRY(ctx, plan_alloc(ctx, &p.task_row, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
+    HIP_TRY(ctx, plan_alloc(ctx, &p.task_chunk, sizeof(int32_t) * (size_t)(p.ntasks > 0 ? p.ntasks : 1)));
     HIP_TRY(ctx, plan_emit(p64, ctx->stream, m, a->ptr, p.perm, ctx->cfg.chunk, p.task_off, p.task_row, p.task_chunk));
-    HIP_TRY(ctx, hipMalloc(&p.fingerprint, sizeof(unsigned long long)));
+    p.chunk = ctx->cfg.chunk;
+    const int rc = build_order(ctx, a, p);
+    if (rc != ALS_OK) return rc;
+    HIP_TRY(ctx, plan_alloc(ctx, &p.fingerprint, 2 * sizeof(unsigned long long)));
     HIP_TRY(ctx, fill_zero(ctx->stream, p.fingerprint, 2));
     HIP_TRY(ctx, plan_fingerprint(p64, ctx->stream, a->ptr, m + 1, p.fingerprint, ctx->fp_done, nullptr, ctx->status));
-    p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz; p.chunk = ctx->cfg.chunk;
+    p.key_ptr = a->ptr; p.nrows = m; p.nnz = a->nnz;
     return ALS_OK;
 }
 
@@ -228,52 +356,13 @@ int in_pieces(int64_t pos0, int64_t n, int64_t piece, L launch) {   // launch(fi
     return ALS_OK;
 }
 
-// largest end with off[end] - off[pos] <= cap (at least pos + 1): the rows of one batch of the slot path
-int64_t batch_end(const int32_t *off, int64_t pos, int64_t slot_rows, int64_t cap) {
-    int64_t lo = pos + 1, hi = slot_rows;
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) >> 1;
-        if ((int64_t)off[mid] - off[pos] <= cap) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
-// Launch order of the work items inside every batch of the slot path.  The entries of a row are sorted by
-// index, so a work item (a chunk of a long row) gathers from a band of the factor matrix that starts at its first
-// index; workgroups are dispatched in launch order, and ordering the work items of a batch by that first index
-// (instead of row by row, which puts disjoint bands side by side) makes the work items in flight gather from the
-// same band, which then stays in the L2.  The slot of a work item is still its index in the batch.
-int ensure_order(als_ctx *ctx, Plan *p, const als_sparse *a, int64_t cap) {
-    if (p->order_cap == cap) return ALS_OK;
-    const int32_t *off = p->task_off_host;
-    const int64_t slot_rows = p->split_pos, n = slot_rows > 0 ? off[slot_rows] : 0;
-    if (p->task_order) {
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        HIP_TRY(ctx, hipFree(p->task_order));
-        p->task_order = nullptr;
-    }
-    p->order_cap = cap;
-    if (n == 0) return ALS_OK;
-    HIP_TRY(ctx, hipMalloc(&p->task_order, sizeof(int32_t) * (size_t)n));
-    HIP_TRY(ctx, plan_task_keys(a->ptr_is_64 != 0, ctx->stream, a->ptr, a->idx, p->task_row, p->task_chunk, n, p->chunk,
-                                p->task_order));
-    std::vector<int32_t> key((size_t)n), order((size_t)n);
-    HIP_TRY(ctx, hipMemcpyAsync(key.data(), p->task_order, sizeof(int32_t) * (size_t)n, hipMemcpyDeviceToHost, ctx->stream));
-    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    for (int64_t pos = 0; pos < slot_rows;) {
-        const int64_t end = batch_end(off, pos, slot_rows, cap);
-        int32_t *first = order.data() + off[pos], *last = order.data() + off[end];
-        for (int32_t t = off[pos]; t < off[end]; ++t) order[(size_t)t] = t;
-        std::stable_sort(first, last, [&](int32_t x, int32_t y) { return key[(size_t)x] < key[(size_t)y]; });
-        pos = end;
-    }
-    HIP_TRY(ctx, hipMemcpy(p->task_order, order.data(), sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
-    return ALS_OK;
-}
-
 int ensure_slots(als_ctx *ctx, int64_t nslots, bool s16) {
     const size_t need = (size_t)nslots * (s16 ? slot_words16(ctx->cfg.f) : slot_floats(ctx->cfg.f)) * sizeof(float);
     if (ctx->slots_bytes >= need) return ALS_OK;
+    if (ctx->fixed)
+        return fail(ctx, ALS_EINVAL, "workspace too small: " + std::to_string(nslots) + " partial Gram matrices (" +
+                                         std::to_string(need) + " bytes) are needed at once, the workspace holds " +
+                                         std::to_string(ctx->slots_bytes) + " bytes of them");
     if (ctx->slots) {
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
         HIP_TRY(ctx, hipFree(ctx->slots));
@@ -295,6 +384,11 @@ int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
     // work items of `per` rows (a multiple of 4): enough of them to fill the chip, few enough to sum quickly
     int64_t items = (n + 255) / 256;
     if (items > 2048) items = 2048;
+    if (ctx->fixed) {   // no more work items than the workspace holds fp32 slots for
+        const int64_t room = (int64_t)(ctx->slots_bytes / (sizeof(float) * (size_t)slot_floats(f)));
+        if (room < 1) return fail(ctx, ALS_EINVAL, "workspace too small for one partial Gram matrix");
+        if (items > room) items = room;
+    }
     int64_t per = ((n + items - 1) / items + 3) & ~(int64_t)3;
     if (per > (1 << 28)) return fail(ctx, ALS_EINVAL, "factor matrix too tall for the Gram kernel");
     const int nslots = (int)((n + per - 1) / per);
@@ -341,7 +435,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     if (rc != ALS_OK) return rc;
     rc = check_plan(ctx, a, p);
     if (rc != ALS_OK) return rc;
-    const int64_t cap = ctx->cfg.batch_slots;
+    const int64_t cap = batch_capacity(ctx);
     const bool p64 = a->ptr_is_64 != 0;
     const int32_t *off = p->task_off_host;
     const int64_t m = a->nrows;
@@ -355,8 +449,6 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // rows shorter than a chunk are built and solved without leaving the registers (both solvers); longer
     // rows go through slots
     const int64_t slot_rows = p->split_pos;
-    rc = ensure_order(ctx, p, a, cap);
-    if (rc != ALS_OK) return rc;
     const int32_t *order = kTaskOrder ? p->task_order : nullptr;
     int64_t pos = 0;
     while (pos < slot_rows) {
@@ -455,50 +547,94 @@ int guarded(als_ctx *ctx, L body) {
 
 extern "C" {
 
+// Checks a configuration and fills in its defaults (chunk, batch_slots).  false: als_create refuses it.
+static bool resolve_config(const als_config *in, als_config *c) {
+    *c = *in;
+    if (!supported_f(c->f)) return false;
+    if (c->solver != ALS_SOLVER_CHOLESKY && c->solver != ALS_SOLVER_CG) return false;
+    if (c->solver == ALS_SOLVER_CG && c->cg_iters < 0) return false;
+    if (c->factor_dtype != ALS_F32 && c->factor_dtype != ALS_BF16 && c->factor_dtype != ALS_F16) return false;
+    // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
+    // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
+    if (c->herm_dtype != ALS_F32 &&
+        !(c->herm_dtype == ALS_BF16 && c->solver == ALS_SOLVER_CG &&
+          (single_wave_f(c->f) || c->factor_dtype == ALS_F32)))   // f = 256: with fp32 factor inputs only
+        return false;
+    if (c->chunk < 0 || c->batch_slots < 0) return false;
+    if (c->chunk != 0 && (c->chunk < 64 || c->chunk > (1 << 20) || (c->chunk & (c->chunk - 1)))) return false;
+    if (c->chunk == 0) c->chunk = 4096;
+    if (c->batch_slots > max_workgroups(kWideThreads)) c->batch_slots = max_workgroups(kWideThreads);
+    if (c->batch_slots == 0) {   // about 4 GB of slots
+        c->batch_slots = 131072;
+        while (c->batch_slots > 1024 && (size_t)c->batch_slots * slot_floats(c->f) * 4 > (4ull << 30)) c->batch_slots /= 2;
+    }
+    return true;
+}
+
+size_t als_workspace_bytes(const als_config *cfg, int64_t max_rows, int64_t max_nnz) {
+    als_config c;
+    if (!cfg || max_rows < 0 || max_nnz < 0 || max_rows > 0x7fffffff || !resolve_config(cfg, &c)) return 0;
+    return workspace_layout(c, max_rows, max_nnz).total;
+}
+
 int als_create(als_ctx **out, const als_config *cfg) {
     if (!out || !cfg) return ALS_EINVAL;
     *out = nullptr;
-    if (!supported_f(cfg->f)) return ALS_EINVAL;
-    if (cfg->solver != ALS_SOLVER_CHOLESKY && cfg->solver != ALS_SOLVER_CG) return ALS_EINVAL;
-    if (cfg->solver == ALS_SOLVER_CG && cfg->cg_iters < 0) return ALS_EINVAL;
-    if (cfg->factor_dtype != ALS_F32 && cfg->factor_dtype != ALS_BF16 && cfg->factor_dtype != ALS_F16) return ALS_EINVAL;
-    // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
-    // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
-    if (cfg->herm_dtype != ALS_F32 &&
-        !(cfg->herm_dtype == ALS_BF16 && cfg->solver == ALS_SOLVER_CG &&
-          (single_wave_f(cfg->f) || cfg->factor_dtype == ALS_F32)))   // f = 256: with fp32 factor inputs only
+    als_config c;
+    if (!resolve_config(cfg, &c)) return ALS_EINVAL;
+    const bool fixed = c.workspace != nullptr;
+    WorkspaceLayout L{};
+    if (fixed) {
+        if (c.workspace_max_rows < 0 || c.workspace_max_rows > 0x7fffffff || c.workspace_max_nnz < 0) return ALS_EINVAL;
+        if (reinterpret_cast<uintptr_t>(c.workspace) % kAlign != 0) return ALS_EINVAL;
+        L = workspace_layout(c, c.workspace_max_rows, c.workspace_max_nnz);
+        if (c.workspace_bytes < L.total) return ALS_EINVAL;
+    } else if (c.workspace_bytes != 0 || c.workspace_max_rows != 0 || c.workspace_max_nnz != 0) {
         return ALS_EINVAL;
-    if (cfg->chunk < 0 || cfg->batch_slots < 0) return ALS_EINVAL;
-    if (cfg->chunk != 0 && (cfg->chunk < 64 || cfg->chunk > (1 << 20) || (cfg->chunk & (cfg->chunk - 1)))) return ALS_EINVAL;
+    }
     int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return ALS_EHIP;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || c.device < 0 || c.device >= ndev) return ALS_EHIP;
     als_ctx *ctx = new (std::nothrow) als_ctx();
     if (!ctx) return ALS_ENOMEM;
-    ctx->cfg = *cfg;
-    if (ctx->cfg.chunk == 0) ctx->cfg.chunk = 4096;
-    if (ctx->cfg.batch_slots > max_workgroups(kWideThreads)) ctx->cfg.batch_slots = max_workgroups(kWideThreads);
-    if (ctx->cfg.batch_slots == 0) {   // about 4 GB of slots
-        ctx->cfg.batch_slots = 131072;
-        while (ctx->cfg.batch_slots > 1024 && (size_t)ctx->cfg.batch_slots * slot_floats(cfg->f) * 4 > (4ull << 30))
-            ctx->cfg.batch_slots /= 2;
-    }
-    ctx->stream = (hipStream_t)cfg->stream;
+    ctx->cfg = c;
+    ctx->fixed = fixed;
+    ctx->stream = (hipStream_t)c.stream;
     DeviceGuard on_device;
-    if (on_device.enter(cfg->device) != hipSuccess || hipMalloc(&ctx->status, sizeof(int)) != hipSuccess ||
-        hipMalloc(&ctx->sse_total, sizeof(double)) != hipSuccess ||
-        hipMalloc(&ctx->fp_now, 2 * sizeof(unsigned long long)) != hipSuccess ||
-        hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) != hipSuccess ||
-        hipMemsetAsync(ctx->fp_now, 0, 2 * sizeof(unsigned long long), ctx->stream) != hipSuccess) {
-        hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now);
+    bool ok = on_device.enter(c.device) == hipSuccess;
+    if (ok && fixed) {
+        char *w = static_cast<char *>(c.workspace);
+        char *fw = w + L.fixed_words;                       // 1 KiB of small words, 16 bytes apart at least
+        ctx->status = reinterpret_cast<int *>(fw);
+        ctx->check_flags = reinterpret_cast<int *>(fw + 16);
+        ctx->fp_now = reinterpret_cast<unsigned long long *>(fw + 32);   // fingerprint, then the counter
+        ctx->sse_total = reinterpret_cast<double *>(fw + 64);
+        ctx->gram_dot = reinterpret_cast<double *>(fw + 96);             // 3 doubles
+        ctx->class_start_dev = reinterpret_cast<int32_t *>(fw + 256);    // kPlanClasses + 1 ints
+        ctx->gram[0] = reinterpret_cast<float *>(w + L.gram0);
+        ctx->gram[1] = reinterpret_cast<float *>(w + L.gram1);
+        ctx->sse_partial = reinterpret_cast<double *>(w + L.sse_partial);
+        ctx->sse_partial_bytes = L.scratch - L.sse_partial;
+        ctx->scratch = w + L.scratch;
+        ctx->scratch_bytes = L.scratch_bytes;
+        ctx->slots = reinterpret_cast<float *>(w + L.slots);
+        ctx->slots_bytes = L.arena - L.slots;
+        ctx->slot_capacity = L.slot_capacity;
+        ctx->arena = w + L.arena;
+        ctx->arena_bytes = L.arena_bytes;
+        ok = fill_zero(ctx->stream, fw, 256) == hipSuccess;   // status, flags, fingerprint and counter start at zero
+    } else if (ok) {
+        ok = hipMalloc(&ctx->status, sizeof(int)) == hipSuccess && hipMalloc(&ctx->sse_total, sizeof(double)) == hipSuccess &&
+             hipMalloc(&ctx->fp_now, 2 * sizeof(unsigned long long)) == hipSuccess &&
+             hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) == hipSuccess &&
+             hipMemsetAsync(ctx->fp_now, 0, 2 * sizeof(unsigned long long), ctx->stream) == hipSuccess;
+    }
+    if (ok) ok = gram_static_scratch(&ctx->gram_static) == hipSuccess;   // the context's device is current here
+    if (!ok) {
+        if (!fixed) { hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now); }
         delete ctx;
         return ALS_EHIP;
     }
     ctx->fp_done = reinterpret_cast<unsigned int *>(ctx->fp_now + 1);
-    if (gram_static_scratch(&ctx->gram_static) != hipSuccess) {   // the context's device is current here
-        hipFree(ctx->status); hipFree(ctx->sse_total); hipFree(ctx->fp_now);
-        delete ctx;
-        return ALS_EHIP;
-    }
     *out = ctx;
     return ALS_OK;
 }
@@ -508,9 +644,11 @@ void als_destroy(als_ctx *ctx) {
     DeviceGuard on_device;
     (void)on_device.enter(ctx->cfg.device);
     hipStreamSynchronize(ctx->stream);
-    for (auto &p : ctx->plans) free_plan(p);
-    hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
-    hipFree(ctx->sse_total); hipFree(ctx->fp_now); hipFree(ctx->check_flags); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
+    for (auto &p : ctx->plans) free_plan(ctx, p);
+    if (!ctx->fixed) {
+        hipFree(ctx->slots); hipFree(ctx->scratch); hipFree(ctx->status); hipFree(ctx->sse_partial);
+        hipFree(ctx->sse_total); hipFree(ctx->fp_now); hipFree(ctx->check_flags); hipFree(ctx->gram[0]); hipFree(ctx->gram[1]); hipFree(ctx->gram_dot);
+    }
     for (auto &t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     for (auto e : ctx->free_events) hipEventDestroy(e);
     delete ctx;
@@ -638,6 +776,7 @@ static int sum_over_entries(als_ctx *ctx, const als_sparse *csr, const float *X,
     if (rc != ALS_OK) return rc;
     const size_t need = sizeof(double) * (size_t)(p->ntasks > 0 ? p->ntasks : 1);
     if (ctx->sse_partial_bytes < need) {
+        if (ctx->fixed) return fail(ctx, ALS_EINVAL, "workspace too small for the partial sums of this matrix");
         if (ctx->sse_partial) { HIP_TRY(ctx, hipStreamSynchronize(ctx->stream)); HIP_TRY(ctx, hipFree(ctx->sse_partial)); }
         ctx->sse_partial = nullptr; ctx->sse_partial_bytes = 0;
         HIP_TRY(ctx, hipMalloc(&ctx->sse_partial, need));
@@ -681,15 +820,20 @@ static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *T
         return fail_hip(ctx, e, "hipMalloc");
     }
     std::vector<int32_t> off((size_t)nrows + 1);
+    void *tmp = nullptr;     // scan scratch of this call (the context's may be a fixed piece of a workspace)
+    size_t tmp_bytes = 0;
+    auto cleanup_tmp = [&]() { hipFree(tmp); tmp = nullptr; };
     if ((e = fill_iota(ctx->stream, perm, nrows, (int32_t)row0)) != hipSuccess ||
-        (e = plan_tasks(p64, ctx->stream, nrows, csr->ptr, perm, ctx->cfg.chunk, task_off, &ctx->scratch,
-                        &ctx->scratch_bytes)) != hipSuccess ||
+        (e = plan_tasks(p64, ctx->stream, nrows, csr->ptr, perm, ctx->cfg.chunk, task_off, &tmp, &tmp_bytes, false)) !=
+            hipSuccess ||
         (e = hipMemcpyAsync(off.data(), task_off, sizeof(int32_t) * (size_t)(nrows + 1), hipMemcpyDeviceToHost,
                             ctx->stream)) != hipSuccess ||
         (e = hipStreamSynchronize(ctx->stream)) != hipSuccess) {
         cleanup();
+        cleanup_tmp();
         return fail_hip(ctx, e, "plan of the row range");
     }
+    cleanup_tmp();
     const int64_t ntasks = off[(size_t)nrows];
     if ((e = hipMalloc(&task_row, sizeof(int32_t) * (size_t)(ntasks > 0 ? ntasks : 1))) != hipSuccess ||
         (e = hipMalloc(&task_chunk, sizeof(int32_t) * (size_t)(ntasks > 0 ? ntasks : 1))) != hipSuccess ||
@@ -725,13 +869,16 @@ static int als_bin_rows_impl(als_ctx *ctx, const als_sparse *csr, int nclass, in
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     int32_t *cs_dev = nullptr;
     HIP_TRY(ctx, hipMalloc(&cs_dev, sizeof(int32_t) * 65));
+    void *tmp = nullptr;     // scratch of this call (the context's may be a fixed piece of a workspace)
+    size_t tmp_bytes = 0;
     hipError_t e = plan_bin_rows(csr->ptr_is_64 != 0, ctx->stream, csr->nrows, csr->ptr, nclass, perm_out, cs_dev,
-                                 &ctx->scratch, &ctx->scratch_bytes);
+                                 &tmp, &tmp_bytes, false);
     int32_t cs[65];
     if (e == hipSuccess)
         e = hipMemcpyAsync(cs, cs_dev, sizeof(int32_t) * (size_t)(nclass + 1), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     hipFree(cs_dev);
+    hipFree(tmp);
     if (e != hipSuccess) return fail_hip(ctx, e, "als_bin_rows");
     for (int c = 0; c <= nclass; ++c) class_start_out[c] = cs[c];
     return ALS_OK;
@@ -866,8 +1013,9 @@ static int als_drop_plans_impl(als_ctx *ctx) {
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    for (auto &p : ctx->plans) free_plan(p);
+    for (auto &p : ctx->plans) free_plan(ctx, p);
     ctx->next_plan = 0;
+    ctx->arena_used = 0;
     return ALS_OK;
 }
 

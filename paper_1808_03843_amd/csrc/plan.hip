@@ -76,8 +76,18 @@ static hipError_t exclusive_scan(hipStream_t st, int32_t *data, int64_t n, int32
     return hipGetLastError();
 }
 
-static hipError_t ensure_scratch(void **scratch, size_t *have, size_t need) {
+size_t plan_scratch_bytes(int64_t nrows, int nclass) {
+    const int64_t nseg = (nrows + 63) / 64;
+    const int64_t ncount = (int64_t)nclass * nseg + 1;
+    const size_t bin = (size_t)(ncount + scan_scratch_ints(ncount)) * sizeof(int32_t);
+    const size_t tasks = scan_scratch_ints(nrows + 1) * sizeof(int32_t);
+    return bin > tasks ? bin : tasks;
+}
+
+// fixed: the buffer belongs to a caller's workspace and can neither grow nor be freed here
+hipError_t ensure_scratch(void **scratch, size_t *have, size_t need, bool fixed) {
     if (*have >= need) return hipSuccess;
+    if (fixed) return hipErrorOutOfMemory;
     if (*scratch) {
         hipError_t e = hipFree(*scratch);
         if (e != hipSuccess) return e;
@@ -142,12 +152,12 @@ __global__ void k_class_start(const int32_t *__restrict__ offsets, int nclass, i
 __global__ void k_set_zero(int32_t *p) { *p = 0; }
 
 hipError_t plan_bin_rows(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, int nclass, int32_t *perm,
-                         int32_t *class_start_dev, void **scratch, size_t *scratch_bytes) {
+                         int32_t *class_start_dev, void **scratch, size_t *scratch_bytes, bool scratch_fixed) {
     if (nclass < 2 || nclass > 64) return hipErrorInvalidValue;
     const int64_t nseg = (nrows + 63) / 64;
     const int64_t ncount = (int64_t)nclass * nseg + 1;
     const size_t need = (size_t)(ncount + scan_scratch_ints(ncount)) * sizeof(int32_t);
-    hipError_t e = ensure_scratch(scratch, scratch_bytes, need);
+    hipError_t e = ensure_scratch(scratch, scratch_bytes, need, scratch_fixed);
     if (e != hipSuccess) return e;
     int32_t *counts = (int32_t *)*scratch;
     if (nseg > 0) {
@@ -192,9 +202,9 @@ __global__ __launch_bounds__(256) void k_count_items(const PtrT *__restrict__ pt
 }
 
 hipError_t plan_tasks(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
-                      int32_t *task_off, void **scratch, size_t *scratch_bytes) {
+                      int32_t *task_off, void **scratch, size_t *scratch_bytes, bool scratch_fixed) {
     const size_t need = scan_scratch_ints(nrows + 1) * sizeof(int32_t);
-    hipError_t e = ensure_scratch(scratch, scratch_bytes, need);
+    hipError_t e = ensure_scratch(scratch, scratch_bytes, need, scratch_fixed);
     if (e != hipSuccess) return e;
     const unsigned nb = (unsigned)((nrows + 1 + 255) / 256);
     if (ptr64)
@@ -248,6 +258,37 @@ hipError_t plan_task_keys(bool ptr64, hipStream_t st, const void *ptr, const int
     else
         hipLaunchKernelGGL(k_task_keys<int32_t>, grid, block, 0, st, (const int32_t *)ptr, idx, task_row, task_chunk, ntasks,
                            chunk, key);
+    return hipGetLastError();
+}
+
+// Stable sort of the work items [first, first + count) of one batch by key, by counting: the rank of item t is the
+// number of items with a smaller key, or the same key and a smaller index.  order[first + rank] = first + t.
+// Quadratic, but a batch has at most a few hundred thousand items, it runs once per matrix, and it needs no
+// temporary memory and no atomics.
+constexpr int kRankTile = 1024;
+__global__ __launch_bounds__(256) void k_rank_order(const int32_t *__restrict__ key, int64_t first, int count,
+                                                    int32_t *__restrict__ order) {
+    __shared__ int32_t tile[kRankTile];
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int32_t mine = t < count ? key[first + t] : 0;
+    int rank = 0;
+    for (int base = 0; base < count; base += kRankTile) {
+        __syncthreads();
+        for (int q = threadIdx.x; q < kRankTile; q += 256) tile[q] = base + q < count ? key[first + base + q] : 0;
+        __syncthreads();
+        const int lim = count - base < kRankTile ? count - base : kRankTile;
+        for (int q = 0; q < lim; ++q) {
+            const int32_t k = tile[q];
+            rank += (k < mine || (k == mine && base + q < t)) ? 1 : 0;
+        }
+    }
+    if (t < count) order[first + rank] = (int32_t)(first + t);
+}
+
+hipError_t plan_rank_order(hipStream_t st, const int32_t *key, int64_t first, int64_t count, int32_t *order) {
+    if (count <= 0) return hipSuccess;
+    if (count > kMaxRankedItems) return fill_iota(st, order + first, count, (int32_t)first);   // too many to rank: batch order
+    hipLaunchKernelGGL(k_rank_order, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, key, first, (int)count, order);
     return hipGetLastError();
 }
 

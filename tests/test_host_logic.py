@@ -109,3 +109,36 @@ def test_bench_traffic_figures_agree_with_the_committed_counter_summary():
     for kernel, per_launch in table.items():
         assert launches[kernel] == 2                                       # one launch per side and sweep
         assert per_launch == pytest.approx(sums[kernel] / launches[kernel], rel=1e-3)
+
+
+def test_workspace_bytes_needs_no_device_and_grows_with_the_matrix():
+    lib = P.load_library()
+    cfg = _cfg()
+    small = lib.als_workspace_bytes(ctypes.byref(cfg), 1000, 100_000)
+    mid = lib.als_workspace_bytes(ctypes.byref(cfg), 480_189, 99_072_112)
+    assert 0 < small < mid
+    assert small % 256 == 0 and mid % 256 == 0
+    # the slots dominate: min(batch_slots, 2 nnz / chunk + 1) partial Gram matrices of slot_floats(100) floats
+    slot = 4 * (28 * 256 + 7 * 16)
+    assert mid >= (2 * 99_072_112 // 4096 + 1) * slot
+    # a smaller batch bounds the slot region; bf16 storage halves it (nearly)
+    capped = lib.als_workspace_bytes(ctypes.byref(_cfg(batch_slots=1024)), 480_189, 99_072_112)
+    assert capped < mid and capped <= 1024 * slot + 64 * 2 ** 20
+    half = lib.als_workspace_bytes(ctypes.byref(_cfg(herm_dtype=P.BF16)), 480_189, 99_072_112)
+    assert 0.45 * mid < half < 0.6 * mid
+    # refused configurations and sizes give 0
+    assert lib.als_workspace_bytes(ctypes.byref(_cfg(f=17)), 10, 10) == 0
+    assert lib.als_workspace_bytes(ctypes.byref(cfg), -1, 10) == 0
+    assert lib.als_workspace_bytes(None, 10, 10) == 0
+
+
+def test_create_refuses_a_workspace_that_is_too_small_or_misaligned():
+    lib = P.load_library()
+    need = lib.als_workspace_bytes(ctypes.byref(_cfg()), 1000, 100_000)
+    for ptr, size, rows, nnz in [(0x1000, need - 1, 1000, 100_000),      # too small
+                                 (0x1010, need, 1000, 100_000),          # not 256-byte aligned
+                                 (0x1000, need, -1, 100_000),            # negative maximum
+                                 (0, need, 1000, 100_000)]:              # sizes without a workspace
+        cfg = _cfg()
+        cfg.workspace, cfg.workspace_bytes, cfg.workspace_max_rows, cfg.workspace_max_nnz = ptr, size, rows, nnz
+        assert _create(cfg) == EINVAL     # found before any device is touched
