@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libals_gfx950.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "hermitian.hip", "wide.hip", "wide_ldlt.hip", "wide_ldlt_bf16.hip", "wide_ldlt_f16.hip", "wide_ldlt_implicit.hip", "implicit.hip", "dual.hip", "solve.hip", "plan.hip", "metrics.hip", "transpose.hip", "peaks.hip"]
+SOURCES = ["api.hip", "hermitian.hip", "hermitian_x3.hip", "wide.hip", "wide_ldlt.hip", "wide_ldlt_bf16.hip", "wide_ldlt_f16.hip", "wide_ldlt_implicit.hip", "implicit.hip", "dual.hip", "solve.hip", "plan.hip", "metrics.hip", "transpose.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

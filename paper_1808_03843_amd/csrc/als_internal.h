@@ -92,13 +92,22 @@ constexpr int kStatusStalePlan = 4;   // the row offsets of a matrix differ from
 
 // ---- launchers (each defined next to its kernels) --------------------------------------------
 // wide: the gathered factor matrix is 4 GiB or larger (64-bit lane addresses)
-// et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16)
+// et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16; ALS_F32X3: fp32 in memory)
 // s16: slots hold bf16 tiles (slot_words16) instead of fp32 tiles (slot_floats)
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots);
 
-// solver: ALS_SOLVER_CG or ALS_SOLVER_CHOLESKY (the latter with fp32 factor inputs only)
+// factor_dtype = ALS_F32X3, f <= 128 (hermitian_x3.hip); launch_hermitian and launch_hermitian_cg forward to these
+hipError_t launch_hermitian_x3(int f, bool ptr64, bool wide, bool s16, hipStream_t st, const int32_t *task_row,
+                               const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks,
+                               int chunk, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                               float *slots);
+hipError_t launch_hermitian_cg_x3(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
+                                  int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                  const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
+
+// solver: ALS_SOLVER_CG or ALS_SOLVER_CHOLESKY
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);

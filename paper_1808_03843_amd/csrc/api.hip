@@ -20,6 +20,7 @@ bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
     if ((uint64_t)rows * pitch >= (1ull << 32)) return true;
     return (pitch & (pitch - 1)) != 0 && rows >= (1 << 24);
 }
+size_t factor_bytes(int factor_dtype) { return (factor_dtype == ALS_F32 || factor_dtype == ALS_F32X3) ? 4 : 2; }
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
 
@@ -441,7 +442,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     const int64_t m = a->nrows;
     const bool cg = ctx->cfg.solver == ALS_SOLVER_CG;
     const bool s16 = ctx->cfg.herm_dtype == ALS_BF16;
-    const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
+    const size_t esize = factor_bytes(ctx->cfg.factor_dtype);
     const bool wide = needs_wide_offsets(a->ncols, f, esize);
     // Rows with fewer than `chunk` entries are one work item each; with the CG solver they are built
     // and solved by one wavefront without leaving the registers.  Everything else goes through slots.
@@ -502,7 +503,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
             if (lo < fused_end) {
                 rc = in_pieces(lo, fused_end - lo, max_workgroups(64), [&](int64_t pos0, int64_t npos) {
-                    HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype, ctx->stream, p->perm, pos0, npos, a->ptr,
+                    HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype == ALS_F32X3 ? ALS_F32 : ctx->cfg.factor_dtype, ctx->stream, p->perm, pos0, npos, a->ptr,
                                                    a->idx, a->val, G, lambda, Out, ctx->status));
                     return (int)ALS_OK;
                 });
@@ -553,7 +554,10 @@ static bool resolve_config(const als_config *in, als_config *c) {
     if (!supported_f(c->f)) return false;
     if (c->solver != ALS_SOLVER_CHOLESKY && c->solver != ALS_SOLVER_CG) return false;
     if (c->solver == ALS_SOLVER_CG && c->cg_iters < 0) return false;
-    if (c->factor_dtype != ALS_F32 && c->factor_dtype != ALS_BF16 && c->factor_dtype != ALS_F16) return false;
+    if (c->factor_dtype != ALS_F32 && c->factor_dtype != ALS_BF16 && c->factor_dtype != ALS_F16 &&
+        c->factor_dtype != ALS_F32X3)
+        return false;
+    if (c->factor_dtype == ALS_F32X3 && !single_wave_f(c->f)) return false;   // the three-part route exists for f <= 128
     // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
     // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
     if (c->herm_dtype != ALS_F32 &&
@@ -809,7 +813,7 @@ static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *T
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     // a throw-away plan over the row range, in natural order
     const bool p64 = csr->ptr_is_64 != 0;
-    const size_t esize = ctx->cfg.factor_dtype == ALS_F32 ? 4 : 2;
+    const size_t esize = factor_bytes(ctx->cfg.factor_dtype);
     const bool wide = needs_wide_offsets(csr->ncols, f, esize);
     int32_t *perm = nullptr, *task_off = nullptr, *task_row = nullptr, *task_chunk = nullptr;
     auto cleanup = [&]() { hipFree(perm); hipFree(task_off); hipFree(task_row); hipFree(task_chunk); };

@@ -101,6 +101,9 @@ static hipError_t herm_f(bool wide, int et, bool s16, hipStream_t st, const int3
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
                             const int32_t *idx, const float *val, const void *Theta, float *slots) {
+    if (et == ALS_F32X3)
+        return launch_hermitian_x3(f, ptr64, wide, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val,
+                                   Theta, slots);
     if (f == 256)
         return launch_hermitian_wide(ptr64, wide, et, s16, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val,
                                      Theta, slots);
@@ -149,6 +152,9 @@ static hipError_t herm_cg_f(bool wide, int et, int solver, hipStream_t st, const
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                const void *Theta, float lambda, int fs, float eps, float *Xout, int *status) {
+    if (et == ALS_F32X3)
+        return launch_hermitian_cg_x3(f, ptr64, wide, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout,
+                                      status);
     if (f == 256 && solver != ALS_SOLVER_CG)
         return launch_hermitian_ldlt_wide(ptr64, wide, et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, Xout, status);
     if (f == 256)

@@ -3,6 +3,7 @@
 #pragma once
 #include "tiles.h"
 #include "tiles16.h"
+#include "tiles_x3.h"
 
 namespace als {
 
@@ -19,14 +20,19 @@ namespace als {
 constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
 // (f = 128 with 16-bit inputs: the operand sets of 32 entries and the extra b_u tiles need the whole file)
-constexpr int fused_waves(int F, int ET = ALS_F32) { return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2); }
+constexpr int fused_waves(int F, int ET = ALS_F32) {
+    if (ET == ALS_F32X3) return 1;   // three operand sets of 32 entries beside the accumulators
+    return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2);
+}
 
 // 16-bit factor inputs go to the 16-bit matrix cores where the width allows it (tiles16.h)
-constexpr bool use_tiles16(int F, int ET, int MODE) { return ET != ALS_F32 && MODE == kExplicit && has_tiles16(F); }
+constexpr bool use_tiles16(int F, int ET, int MODE) {
+    return (ET == ALS_BF16 || ET == ALS_F16) && MODE == kExplicit && has_tiles16(F);
+}
 
 // least number of wavefronts per SIMD k_hermitian is compiled for: with 16-bit inputs at f = 100 the allocator
 // otherwise lands just above the register budget of two and then spreads out to one
-constexpr int slot_waves(int F, int ET) { return (F == 100 && ET != ALS_F32) ? 2 : 1; }
+constexpr int slot_waves(int F, int ET) { return (F == 100 && (ET == ALS_BF16 || ET == ALS_F16)) ? 2 : 1; }
 
 // a value that is the same in every lane, moved to scalar registers
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -60,7 +66,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    if constexpr (use_tiles16(F, ET, MODE))
+    if constexpr (ET == ALS_F32X3)   // fp32 rows cut into three bf16 parts, 16-bit matrix cores (tiles_x3.h)
+        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
     else
         accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc,
@@ -150,7 +158,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     float b[NT];
-    if constexpr (use_tiles16(F, ET, MODE))
+    if constexpr (ET == ALS_F32X3)
+        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
     else
         accumulate_tiles<F, true, kDepthFused, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,

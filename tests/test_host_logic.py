@@ -142,3 +142,8 @@ def test_create_refuses_a_workspace_that_is_too_small_or_misaligned():
         cfg = _cfg()
         cfg.workspace, cfg.workspace_bytes, cfg.workspace_max_rows, cfg.workspace_max_nnz = ptr, size, rows, nnz
         assert _create(cfg) == EINVAL     # found before any device is touched
+
+
+def test_three_part_inputs_are_refused_where_they_do_not_exist():
+    assert _create(_cfg(f=256, factor_dtype=P.F32X3)) == EINVAL          # the route exists for f <= 128
+    assert _create(_cfg(f=100, factor_dtype=4)) == EINVAL                # no such element type
