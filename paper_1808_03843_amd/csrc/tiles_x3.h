@@ -55,6 +55,7 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
         return r;
     };
     auto load_ratings = [&](int t, float (&r)[8]) {
+        if constexpr (!WANT_B) return;
         const uint32_t o = eoff0 + 128u * (uint32_t)t;
         const v4u a = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o, 0, 0));
         const v4u c = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(val_rsrc, o + 16u, 0, 0));
@@ -64,10 +65,12 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             r[4 + j] = bits_to_float(c[j]);
         }
     };
-    // one gathered fp32 row -> one register per tile (entries beyond the work item read row 0 and are masked later)
-    auto gather = [&](uint32_t c, uint32_t (&w)[NT]) {
-        const char *p;
-        uint32_t ro;
+    // The loads of one gathered fp32 row come in three groups -- 16 bytes per lane (tiles 0 .. 4 N4 - 1), 8 bytes (the
+    // next 2 N2 tiles), 4 bytes (the last N1 tiles) -- and a group of the next step is issued as soon as the last
+    // tile it fills has been cut into parts.  (Entries beyond the work item read row 0 and are masked later.)
+    constexpr int first1 = 4 * N4 + 2 * N2;
+    constexpr int endA = N4 > 0 ? 4 * N4 - 1 : -1, endB = N2 > 0 ? first1 - 1 : -1, endC = N1 > 0 ? NT - 1 : -1;
+    auto row_base = [&](uint32_t c, const char *&p, uint32_t &ro) {
         if constexpr (WIDE) {
             p = reinterpret_cast<const char *>(Theta) + (int64_t)c * (4 * F);
             ro = lane_first;
@@ -75,7 +78,13 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             p = reinterpret_cast<const char *>(Theta);
             ro = row_offset<(uint32_t)(4 * F)>(c, lane_first);
         }
-        if constexpr (N4 > 0) {
+    };
+    auto gather_group = [&](auto gtag, uint32_t c, uint32_t (&w)[NT]) {
+        constexpr int G = decltype(gtag)::value;
+        const char *p;
+        uint32_t ro;
+        row_base(c, p, ro);
+        if constexpr (G == 0 && N4 > 0) {
             const uint32_t o = ro + (lane_a - lane_first);
 #pragma unroll
             for (int q = 0; q < N4; ++q) {
@@ -83,25 +92,29 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
                 w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
             }
         }
-        if constexpr (N2 > 0) {
+        if constexpr (G == 1 && N2 > 0) {
             const uint2 v = *reinterpret_cast<const uint2 *>(p + (ro + (lane_b - lane_first)));
             w[4 * N4] = v.x; w[4 * N4 + 1] = v.y;
         }
-        constexpr int first1 = 4 * N4 + 2 * N2;
-        if constexpr (N1 > 1) {
-            const uint32_t o = ro + (lane_c - lane_first);
+        if constexpr (G == 2 && N1 > 0) {
+            if constexpr (N1 > 1) {
+                const uint32_t o = ro + (lane_c - lane_first);
 #pragma unroll
-            for (int k = 0; k < N1 - 1; ++k) w[first1 + k] = *reinterpret_cast<const uint32_t *>(p + o + 64 * k);
+                for (int k = 0; k < N1 - 1; ++k) w[first1 + k] = *reinterpret_cast<const uint32_t *>(p + o + 64 * k);
+            }
+            w[first1 + N1 - 1] = *reinterpret_cast<const uint32_t *>(p + (ro + (lane_l - lane_first)));
         }
-        if constexpr (N1 > 0) w[first1 + N1 - 1] = *reinterpret_cast<const uint32_t *>(p + (ro + (lane_l - lane_first)));
     };
-    auto gather8 = [&](const Ids &ids, uint32_t (&raw)[8][NT]) {
+    auto gather8_group = [&](auto gtag, const Ids &ids, uint32_t (&raw)[8][NT]) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            gather(ids.lo[j], raw[j]);
-            gather(ids.hi[j], raw[4 + j]);
+            gather_group(gtag, ids.lo[j], raw[j]);
+            gather_group(gtag, ids.hi[j], raw[4 + j]);
         }
     };
+    using G0 = std::integral_constant<int, 0>;
+    using G1 = std::integral_constant<int, 1>;
+    using G2 = std::integral_constant<int, 2>;
 
     const bool is_rating = i == RI, is_feat = i < RI;
     const bool is_r0 = i == 0, is_r1 = i == 1, is_r2 = i == 2;
@@ -109,7 +122,6 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
 #pragma unroll
     for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // operands of step t: for every tile the leading (h), middle (m) and trailing (l) bf16 parts of the 8 entries
     // the last step may hold fewer than 32 entries: the others count as zero (a wave-uniform branch)
     auto mask_tail = [&](uint32_t (&raw)[8][NT], float (&r)[8], int t) {
         const int e0 = 32 * t + 8 * kq;
@@ -121,26 +133,26 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             r[e] = ok ? r[e] : 0.f;
         }
     };
-    auto operands = [&](const uint32_t (&raw)[8][NT], float (&r)[8], int t, v4u (&h)[NT], v4u (&m)[NT], v4u (&l)[NT],
-                        v4u &gr) {
-        (void)t;
-        gr = (v4u){0u, 0u, 0u, 0u};
+    // operands of one tile: the leading (h), middle (m) and trailing (l) bf16 parts of the lane's 8 entries
+    auto split_tile = [&](auto ttag, const uint32_t (&raw)[8][NT], const float (&r)[8], v4u &h, v4u &m, v4u &l) {
+        constexpr int T = decltype(ttag)::value;
 #pragma unroll
         for (int pr = 0; pr < 4; ++pr) {
-#pragma unroll
-            for (int T = 0; T < NT; ++T) {
-                float x0 = bits_to_float(raw[2 * pr][T]), x1 = bits_to_float(raw[2 * pr + 1][T]);
-                if constexpr (!BX) {
-                    if (T == NT - 1) {   // the rating lane and the zero lanes of the last tile
-                        x0 = is_feat ? x0 : ((WANT_B && is_rating) ? r[2 * pr] : 0.f);
-                        x1 = is_feat ? x1 : ((WANT_B && is_rating) ? r[2 * pr + 1] : 0.f);
-                    }
-                }
-                h[T][pr] = split16<ALS_BF16>(x0, x1);
-                m[T][pr] = split16<ALS_BF16>(x0, x1);
-                l[T][pr] = split16<ALS_BF16>(x0, x1);
+            float x0 = bits_to_float(raw[2 * pr][T]), x1 = bits_to_float(raw[2 * pr + 1][T]);
+            if constexpr (!BX && T == NT - 1) {   // the rating lane and the zero lanes of the last tile
+                x0 = is_feat ? x0 : ((WANT_B && is_rating) ? r[2 * pr] : 0.f);
+                x1 = is_feat ? x1 : ((WANT_B && is_rating) ? r[2 * pr + 1] : 0.f);
             }
-            if constexpr (BX && WANT_B) {
+            h[pr] = split16<ALS_BF16>(x0, x1);
+            m[pr] = split16<ALS_BF16>(x0, x1);
+            l[pr] = split16<ALS_BF16>(x0, x1);
+        }
+    };
+    auto rating_operand = [&](const float (&r)[8], v4u &gr) {
+        gr = (v4u){0u, 0u, 0u, 0u};
+        if constexpr (BX && WANT_B) {
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
                 float r0 = r[2 * pr], r1 = r[2 * pr + 1];
                 const uint32_t p0 = split16<ALS_BF16>(r0, r1);
                 const uint32_t p1 = split16<ALS_BF16>(r0, r1);
@@ -149,52 +161,57 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             }
         }
     };
-    // the six products, one kind after the other, so that consecutive MFMAs write different accumulators
-    auto multiply = [&](const v4u (&h)[NT], const v4u (&m)[NT], const v4u (&l)[NT], const v4u &gr) {
-        if constexpr (BX && WANT_B) {
-#pragma unroll
-            for (int C = 0; C < NT; ++C)
-                if ((ROWS >> C) & 1u) {
-                    mfma_16x16x32<ALS_BF16>(bt[C], gr, l[C]);
-                    mfma_16x16x32<ALS_BF16>(bt[C], gr, m[C]);
-                    mfma_16x16x32<ALS_BF16>(bt[C], gr, h[C]);
-                }
-        }
-        auto kind = [&](const v4u (&a)[NT], const v4u (&bb)[NT]) {
-#pragma unroll
-            for (int R = 0; R < NT; ++R)
-                if ((ROWS >> R) & 1u) {
-#pragma unroll
-                    for (int C = 0; C <= R; ++C) mfma_16x16x32<ALS_BF16>(acc[tiles_below(ROWS, R) + C], a[R], bb[C]);
-                }
-        };
-        kind(h, l);
-        kind(l, h);
-        kind(m, m);
-        kind(h, m);
-        kind(m, h);
-        kind(h, h);
-    };
 
-    // One set of row registers: the rows of step t are cut into operands as soon as they have arrived, the gathers
-    // of step t+1 are issued into the same registers and are in flight during the MFMAs of step t; the column
-    // ids run one step further ahead.
+    // One step, tile row by tile row: the MFMAs of tile row T (six per tile, 16 matrix-pipeline cycles each) need the
+    // parts of the tiles 0 .. T only, so the vector-ALU work that cuts tile T+1 into parts is placed among them and
+    // runs in their shadow; only tile 0 is cut with the matrix pipeline idle.  The scheduling barriers keep the
+    // compiler from collecting the vector-ALU work of a step in front of its MFMAs.
     uint32_t raw[8][NT];
     float rat[8];
     Ids ids = load_ids(0);
-    gather8(ids, raw);
+    gather8_group(G0{}, ids, raw);
+    gather8_group(G1{}, ids, raw);
+    gather8_group(G2{}, ids, raw);
     load_ratings(0, rat);
     ids = load_ids(1);
     for (int t = 0; t < nsteps; ++t) {
         v4u h[NT], m[NT], l[NT], gr;
         if (t == nsteps - 1) mask_tail(raw, rat, t);
-        operands(raw, rat, t, h, m, l, gr);
-        if (t + 1 < nsteps) {
-            gather8(ids, raw);
-            load_ratings(t + 1, rat);
-            ids = load_ids(t + 2);   // (beyond the end: zeros, never used)
-        }
-        multiply(h, m, l, gr);
+        rating_operand(rat, gr);
+        split_tile(std::integral_constant<int, 0>{}, raw, rat, h[0], m[0], l[0]);
+        [&]<int... T>(std::integer_sequence<int, T...>) {
+            ([&] {
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr ((ROWS >> T) & 1u) {
+#pragma unroll
+                    for (int C = 0; C <= T; ++C) {
+                        v4f &a = acc[tiles_below(ROWS, T) + C];
+                        mfma_16x16x32<ALS_BF16>(a, h[T], l[C]);
+                        mfma_16x16x32<ALS_BF16>(a, l[T], h[C]);
+                        mfma_16x16x32<ALS_BF16>(a, m[T], m[C]);
+                        mfma_16x16x32<ALS_BF16>(a, h[T], m[C]);
+                        mfma_16x16x32<ALS_BF16>(a, m[T], h[C]);
+                        mfma_16x16x32<ALS_BF16>(a, h[T], h[C]);
+                    }
+                    if constexpr (BX && WANT_B) {
+                        mfma_16x16x32<ALS_BF16>(bt[T], gr, l[T]);
+                        mfma_16x16x32<ALS_BF16>(bt[T], gr, m[T]);
+                        mfma_16x16x32<ALS_BF16>(bt[T], gr, h[T]);
+                    }
+                }
+                if constexpr (T + 1 < NT) split_tile(std::integral_constant<int, T + 1>{}, raw, rat, h[T + 1], m[T + 1], l[T + 1]);
+                // rows of the next step: a group of loads goes out once the last tile it fills is in parts (tile T+1
+                // has just been cut; tile 0 was cut before the first tile row)
+                constexpr auto due = [](int end_tile, int T_) { return (end_tile == T_ + 1 && T_ + 1 < NT) || (end_tile == 0 && T_ == 0); };
+                if constexpr (due(endA, T)) gather8_group(G0{}, ids, raw);
+                if constexpr (due(endB, T)) gather8_group(G1{}, ids, raw);
+                if constexpr (due(endC, T)) gather8_group(G2{}, ids, raw);
+                // the ratings are last used by the rating operand (at the start of the step) or by the last tile
+                if constexpr (BX ? T == 0 : T == NT - 1) load_ratings(t + 1, rat);
+                if constexpr (T == NT - 1) ids = load_ids(t + 2);   // (beyond the end: zeros, never used)
+            }(), ...);
+        }(std::make_integer_sequence<int, NT>{});
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // b_u = row RI of the last tile row (or rows 0 .. 2 of the extra tiles), then zero the padding
