@@ -46,17 +46,7 @@ class AlsConfig(ctypes.Structure):
 _lib = None
 
 
-def load_library() -> ctypes.CDLL:
-    """Loads the in-tree library, building it first only if it was never built."""
-    global _lib
-    if _lib is not None:
-        return _lib
-    path = os.environ.get("ALS_LIBRARY", _build.LIB)   # ALS_LIBRARY: an alternative build, for tuning runs
-    if not os.path.exists(path):
-        if path != _build.LIB:
-            raise FileNotFoundError(path)
-        _build.build()
-    lib = ctypes.CDLL(path)
+def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
     vp, i32, i64, fl = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
     sp = ctypes.POINTER(AlsSparse)
     lib.als_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(AlsConfig)]
@@ -83,8 +73,26 @@ def load_library() -> ctypes.CDLL:
     lib.als_drop_plans.argtypes = [vp]
     lib.als_check_matrix.argtypes = [vp, sp]
     lib.als_measure_peak.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
-    _lib = lib
     return lib
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Loads the in-tree library, building it first only if it was never built.  With `path`: another build of the
+    same library (e.g. build.LIB_DRAINED), loaded beside the default one and handed to Als(library=...)."""
+    global _lib
+    if path is not None:
+        if not os.path.exists(path):
+            raise FileNotFoundError(path)
+        return _declare(ctypes.CDLL(path))
+    if _lib is not None:
+        return _lib
+    path = os.environ.get("ALS_LIBRARY", _build.LIB)   # ALS_LIBRARY: an alternative build, for tuning runs
+    if not os.path.exists(path):
+        if path != _build.LIB:
+            raise FileNotFoundError(path)
+        _build.build()
+    _lib = _declare(ctypes.CDLL(path))
+    return _lib
 
 
 class AlsError(RuntimeError):
@@ -127,10 +135,11 @@ class Als:
     def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
                  device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
                  profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32,
-                 workspace_rows: int = 0, workspace_nnz: int = 0):
+                 workspace_rows: int = 0, workspace_nnz: int = 0, library: Optional[ctypes.CDLL] = None):
         """workspace_rows / workspace_nnz > 0: the library works in a torch-allocated workspace sized for matrices of
-        at most that many rows and stored entries, and allocates no device memory itself."""
-        self._lib = load_library()
+        at most that many rows and stored entries, and allocates no device memory itself.
+        library: another build of the library from load_library(path) (default: the in-tree build)."""
+        self._lib = library if library is not None else load_library()
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
         self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, herm_dtype, device, stream, chunk, batch_slots,

@@ -9,18 +9,23 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libals_gfx950.so")
 OBJ_DIR = os.path.join(HERE, "_build")
+# canary build: every hand-written MFMA waits for its operands and for its result (csrc/tiles.h, ALS_DRAINED_MFMA);
+# tests/test_gpu_drained.py compares it with the production library bit for bit
+LIB_DRAINED = os.path.join(HERE, "libals_gfx950_drained.so")
+OBJ_DIR_DRAINED = os.path.join(HERE, "_build_drained")
 SOURCES = ["api.hip", "hermitian.hip", "hermitian_x3.hip", "wide.hip", "wide_ldlt.hip", "wide_ldlt_bf16.hip", "wide_ldlt_f16.hip", "wide_ldlt_implicit.hip", "implicit.hip", "dual.hip", "solve.hip", "plan.hip", "metrics.hip", "transpose.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+def _compile(job) -> str:
+    src, obj_dir, defines = job
+    obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
     extra = os.environ.get("ALS_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -DALS_DEPTH_SLOTS=4 for tuning runs
-    # the register / scratch / occupancy report of every kernel is kept beside the object: the MFMAs are
-    # inline asm that the compiler cannot protect, so a kernel that spills is a kernel that may be wrong
-    cmd = [HIPCC, *FLAGS, *extra, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
+    # the register / scratch / occupancy report of every kernel is kept beside the object: the fp32 MFMAs are
+    # inline asm that the compiler cannot protect, so a kernel that spills may be wrong
+    cmd = [HIPCC, *FLAGS, *defines, *extra, "-Rpass-analysis=kernel-resource-usage", "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
@@ -56,16 +61,40 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, lib: str = LIB) -> str:
-    if not force and not stale():
-        return lib
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs],
-                       capture_output=True, text=True)
+def _link(lib: str, objs) -> None:
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+
+
+def check_resources(obj_dir: str = None) -> None:
+    """Raises if a kernel of the library spills registers or uses scratch memory: a spill store next to an inline-asm
+    MFMA can save a register whose new value has not arrived yet, so such a build must not be loaded."""
+    bad = {k: v for k, v in kernel_resources(obj_dir).items() if k.startswith("_ZN3als") and (v["spill"] or v["scratch"])}
+    if bad:
+        raise RuntimeError("kernels that spill or use scratch (the build is refused): "
+                           + "; ".join(f"{k}: {v}" for k, v in sorted(bad.items())))
+
+
+def build(force: bool = True, lib: str = LIB, drained: bool = True) -> str:
+    """Compiles every source for gfx950 and links the library; with `drained` also the canary library."""
+    if not force and not stale() and (not drained or os.path.exists(LIB_DRAINED)):
+        return lib
+    jobs = [(src, OBJ_DIR, []) for src in SOURCES]
+    if drained:
+        jobs += [(src, OBJ_DIR_DRAINED, ["-DALS_DRAINED_MFMA"]) for src in SOURCES]
+        os.makedirs(OBJ_DIR_DRAINED, exist_ok=True)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    # the slowest translation units first, so that they do not end up alone at the tail of the pool
+    slow = {"wide.hip": 0, "wide_ldlt_implicit.hip": 1, "wide_ldlt.hip": 2, "wide_ldlt_f16.hip": 3, "wide_ldlt_bf16.hip": 4,
+            "hermitian.hip": 5}
+    jobs.sort(key=lambda j: slow.get(j[0], 99))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
+        objs = dict(zip([(j[0], j[1]) for j in jobs], ex.map(_compile, jobs)))
+    check_resources(OBJ_DIR)
+    _link(lib, [objs[(src, OBJ_DIR)] for src in SOURCES])
+    if drained:
+        _link(LIB_DRAINED, [objs[(src, OBJ_DIR_DRAINED)] for src in SOURCES])
     return lib
 
 

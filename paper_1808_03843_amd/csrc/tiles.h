@@ -10,6 +10,19 @@ namespace als {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
+// The fp32 MFMAs below are inline asm: the compiler inserts none of the wait states that the hardware needs between
+// a vector-ALU write and an MFMA read of the same register, or between an MFMA and a read of its result; the code
+// keeps those distances by hand (mfma_settle, mfma_drain, the s_nop tied to operands).  ALS_DRAINED_MFMA builds a
+// canary library in which every hand-written MFMA waits for its operands before it issues and for its result
+// after: several times slower, but free of any hazard by construction.  A test compares the two libraries bit for bit.
+#ifdef ALS_DRAINED_MFMA
+#define ALS_MFMA_PRE "s_nop 7\n\ts_nop 7\n\t"
+#define ALS_MFMA_POST "\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
+#else
+#define ALS_MFMA_PRE ""
+#define ALS_MFMA_POST ""
+#endif
+
 // acc += a (16x4, one stored entry per 16 lanes) * b (4x16).  Written as an in-place instruction so
 // that the accumulators stay where they are across the loop (the builtin form let the register
 // allocator shuffle them through copies).  IN_VGPR picks architectural registers (needed when the
@@ -17,9 +30,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 template <bool IN_VGPR>
 __device__ __forceinline__ void mfma_16x16x4(v4f &acc, float a, float b) {
     if constexpr (IN_VGPR)
-        asm("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+        asm(ALS_MFMA_PRE "v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+v"(acc) : "v"(a), "v"(b));
     else
-        asm("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+        asm(ALS_MFMA_PRE "v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+a"(acc) : "v"(a), "v"(b));
 }
 
 // acc (16 blocks of 4x4) += a (4x1 per block) * b (1x4 per block): block q = lanes 4q..4q+3, register r of
@@ -31,9 +44,9 @@ __device__ __forceinline__ void mfma_16x16x4(v4f &acc, float a, float b) {
 template <bool IN_VGPR>
 __device__ __forceinline__ void mfma_4x4x1(v4f &acc, float a, float b) {
     if constexpr (IN_VGPR)
-        asm("v_mfma_f32_4x4x1_16b_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+        asm(ALS_MFMA_PRE "v_mfma_f32_4x4x1_16b_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+v"(acc) : "v"(a), "v"(b));
     else
-        asm("v_mfma_f32_4x4x1_16b_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+        asm(ALS_MFMA_PRE "v_mfma_f32_4x4x1_16b_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+a"(acc) : "v"(a), "v"(b));
 }
 
 // The MFMAs above are opaque to the compiler's hazard recogniser: leave the matrix pipeline time to
@@ -600,7 +613,7 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
 //   product per tile to its left.
 template <bool IN_VGPR>
 __device__ __forceinline__ void mfma_16x16x4_ordered(v4f &acc, float a, float b) {
-    asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+    asm volatile(ALS_MFMA_PRE "v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+v"(acc) : "v"(a), "v"(b));
 }
 
 template <int F>

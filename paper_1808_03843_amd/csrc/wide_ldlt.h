@@ -58,12 +58,12 @@ __device__ __forceinline__ void mfma4(v4f &acc, float (&a)[4], float (&b)[4]) {
         asm volatile("s_nop 7" : "+v"(acc), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]),
                      "+v"(b[2]), "+v"(b[3]));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc) : "v"(a[s]), "v"(b[s]));
+        for (int s = 0; s < 4; ++s) asm volatile(ALS_MFMA_PRE "v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+v"(acc) : "v"(a[s]), "v"(b[s]));
     } else {
         asm volatile("s_nop 7" : "+a"(acc), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(b[0]), "+v"(b[1]),
                      "+v"(b[2]), "+v"(b[3]));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+a"(acc) : "v"(a[s]), "v"(b[s]));
+        for (int s = 0; s < 4; ++s) asm volatile(ALS_MFMA_PRE "v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" ALS_MFMA_POST : "+a"(acc) : "v"(a[s]), "v"(b[s]));
     }
 }
 template <bool IN_VGPR>

@@ -15,6 +15,18 @@ def res():
     return r
 
 
+def test_build_refuses_a_kernel_that_spills(tmp_path):
+    # build() itself raises on such a report; fed a made-up report with one spilled register
+    import os
+    text = ("remark: Function Name: _ZN3als6k_fakeEv\nremark:     VGPRs: 10\nremark:     AGPRs: 0\n"
+            "remark:     ScratchSize [bytes/lane]: 0\nremark:     Occupancy [waves/SIMD]: 8\nremark:     VGPRs Spill: 1\n")
+    for src in B.SOURCES[:1]:
+        with open(os.path.join(tmp_path, src.replace(".hip", ".o") + ".resources"), "w") as fh:
+            fh.write(text)
+    with pytest.raises(RuntimeError, match="k_fake"):
+        B.check_resources(str(tmp_path))
+
+
 def test_no_kernel_spills_or_uses_scratch(res):
     # the library's own kernels (namespace als); rocPRIM's sort kernels use a little scratch by design
     bad = {k: v for k, v in res.items() if k.startswith("_ZN3als") and (v["spill"] or v["scratch"])}
@@ -24,8 +36,9 @@ def test_no_kernel_spills_or_uses_scratch(res):
 def test_dominant_kernel_occupancy(res):
     import re
     # fp32 slot storage (the bf16-slot variants need 9 more registers and run one wavefront per SIMD)
-    slots = [v for k, v in res.items() if re.search(r"11k_hermitianILi100E[il]Lb[01]ELi\dELb0E", k)]
-    fused = [v for k, v in res.items() if "14k_hermitian_cgILi100E" in k]
+    # (element types 0..2: fp32 and the 16-bit inputs; the three-part route, type 3, runs one wavefront per SIMD)
+    slots = [v for k, v in res.items() if re.search(r"11k_hermitianILi100E[il]Lb[01]ELi[012]ELb0E", k)]
+    fused = [v for k, v in res.items() if re.search(r"14k_hermitian_cgILi100E[il]Lb[01]ELi[012]E", k)]
     assert slots and fused
     assert all(v["occupancy"] >= 2 for v in slots), slots
     assert all(v["occupancy"] >= 2 for v in fused), fused
