@@ -156,8 +156,10 @@ int als_rmse(als_ctx *ctx, const als_sparse *csr, const float *X, const float *T
  *     A_u = Theta^T Theta + sum_{v in Omega_u} (c_uv - 1) theta_v theta_v^T + lambda I,
  *     b_u = sum_{v in Omega_u, r_uv > 0} c_uv theta_v,     x_u = A_u^-1 b_u
  * which equals the sum over all n columns.  Theta^T Theta is computed once per call by the same
- * gathered kernel.  Arguments as for als_update_rows; alpha >= 0; requires fp32 factors and fp32
- * storage of A_u.  Rows with n_u = 0 get x_u = 0. */
+ * gathered kernel.  Arguments as for als_update_rows; alpha >= 0; fp32 storage of A_u.  The gathered factor is
+ * fp32, or for f <= 128 bf16 / fp16 (config's factor_dtype): then the columns of a tile get the 16-bit theta and its
+ * rows the fp32 product (c_uv - 1) theta cut into three 16-bit parts that add up to it, on the 16-bit matrix cores,
+ * and Theta^T Theta is formed from the same 16-bit values.  Rows with n_u = 0 get x_u = 0. */
 int als_update_rows_implicit(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, float alpha,
                              int f, float *X);
 

@@ -206,12 +206,12 @@ class Als:
 
     def update_rows_implicit(self, csr: SparseMatrix, Theta: torch.Tensor, lam: float, alpha: float, X: torch.Tensor):
         self._check(self._lib.als_update_rows_implicit(self._ctx, self._matrix(csr),
-                                                       self._factor(Theta, csr.ncols, self.f), lam, alpha, self.f,
+                                                       self._gathered(Theta, csr.ncols), lam, alpha, self.f,
                                                        self._factor(X, csr.nrows, self.f)))
 
     def update_cols_implicit(self, csc: SparseMatrix, X: torch.Tensor, lam: float, alpha: float, Theta: torch.Tensor):
         self._check(self._lib.als_update_cols_implicit(self._ctx, self._matrix(csc),
-                                                       self._factor(X, csc.ncols, self.f), lam, alpha, self.f,
+                                                       self._gathered(X, csc.ncols), lam, alpha, self.f,
                                                        self._factor(Theta, csc.nrows, self.f)))
 
     def implicit_loss(self, csr: SparseMatrix, X: torch.Tensor, Theta: torch.Tensor, lam: float, alpha: float) -> float:

@@ -170,10 +170,11 @@ hipError_t launch_sse(int f, bool ptr64, bool implicit, float alpha, hipStream_t
                       const int32_t *task_chunk, int64_t ntasks, int chunk, const void *ptr, const int32_t *idx,
                       const float *val, const float *X, const float *Theta, double *partial, double *total);
 
-// implicit feedback (Section 5.6), f <= 128, fp32 factors and slots
+// implicit feedback (Section 5.6), f <= 128, fp32 slots; et: element type of the gathered factor
 // G^T G of the n x f matrix G: nslots work items of `per` rows each (per a multiple of 4) -> slots -> out (tile layout)
-hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
-                       float *out);
+// et: element type of G (16-bit only for f <= 128)
+hipError_t launch_gram(int f, bool wide, int et, hipStream_t st, const void *G, int64_t n, int per, int nslots,
+                       float *slots, float *out);
 hipError_t launch_tiles_to_dense(int f, hipStream_t st, const float *tiles, float *out);
 // als_gram_static: a file-scope device array of kGramStaticFloats floats (16 MiB) holds the slots and, after
 // them, the summed tiles.  gram_static_scratch returns its address on the CURRENT device.
@@ -181,11 +182,20 @@ constexpr size_t kGramStaticFloats = (size_t)4 << 20;
 constexpr int kGramStaticMaxSlots = 512;
 hipError_t gram_static_scratch(float **ptr);
 hipError_t launch_gram_dot(int f, hipStream_t st, const float *A, const float *B, double *out3);
-hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+// 16-bit factor inputs, f <= 128 (implicit16.hip); the two launchers below forward to these
+hipError_t launch_hermitian_implicit16(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
+                                       const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks,
+                                       int chunk, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                                       float alpha, float *slots);
+hipError_t launch_hermitian_cg_implicit16(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st,
+                                          const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
+                                          const int32_t *idx, const float *val, const void *Theta, float lambda,
+                                          float alpha, const float *gram, int fs, float eps, float *Xout, int *status);
+hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
                                      const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                      const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                      float alpha, float *slots);
-hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
+hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                         int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx,
                                         const float *val, const void *Theta, float lambda, float alpha,
                                         const float *gram, int fs, float eps, float *Xout, int *status);

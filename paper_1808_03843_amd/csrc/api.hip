@@ -378,7 +378,7 @@ int ensure_slots(als_ctx *ctx, int64_t nslots, bool s16) {
 }
 
 // G^T G (n x f fp32 rows) into ctx->gram[which], tile layout.  Uses the slot workspace.
-int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
+int compute_gram(als_ctx *ctx, const void *G, int et, int64_t n, int which) {
     const int f = ctx->cfg.f;
     if (!ctx->gram[which]) HIP_TRY(ctx, hipMalloc(&ctx->gram[which], sizeof(float) * (size_t)slot_floats(f)));
     if (n == 0) {
@@ -398,15 +398,19 @@ int compute_gram(als_ctx *ctx, const float *G, int64_t n, int which) {
     const int nslots = (int)((n + per - 1) / per);
     int rc = ensure_slots(ctx, nslots, false);
     if (rc != ALS_OK) return rc;
-    const bool wide = needs_wide_offsets(n, f, 4);
+    const bool wide = needs_wide_offsets(n, f, factor_bytes(et));
     Timed t(ctx, ALS_K_GRAM);
-    HIP_TRY(ctx, launch_gram(f, wide, ctx->stream, G, n, (int)per, nslots, ctx->slots, ctx->gram[which]));
+    HIP_TRY(ctx, launch_gram(f, wide, et, ctx->stream, G, n, (int)per, nslots, ctx->slots, ctx->gram[which]));
     return ALS_OK;
 }
 
-int check_implicit(als_ctx *ctx, float alpha) {
-    if (ctx->cfg.factor_dtype != ALS_F32 || ctx->cfg.herm_dtype != ALS_F32)
-        return fail(ctx, ALS_EINVAL, "implicit feedback needs fp32 factors and fp32 storage of A_u");
+// gathered: the call gathers a factor of the configured element type (the updates; not the cost, which takes fp32)
+int check_implicit(als_ctx *ctx, float alpha, bool gathered) {
+    const int et = ctx->cfg.factor_dtype;
+    const bool sixteen = (et == ALS_BF16 || et == ALS_F16) && single_wave_f(ctx->cfg.f);
+    if ((et != ALS_F32 && !(gathered && sixteen)) || ctx->cfg.herm_dtype != ALS_F32)
+        return fail(ctx, ALS_EINVAL, "implicit feedback needs fp32 factors (bf16 / fp16 for the updates at f <= 128) and "
+                                     "fp32 storage of A_u");
     if (!(alpha >= 0.f)) return fail(ctx, ALS_EINVAL, "alpha must be >= 0");
     return ALS_OK;
 }
@@ -427,10 +431,10 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
     const bool implicit = mode == kImplicit;
     if (implicit) {
-        rc = check_implicit(ctx, alpha);
+        rc = check_implicit(ctx, alpha, true);
         if (rc != ALS_OK) return rc;
         if (!G) return fail(ctx, ALS_EINVAL, "factor pointer is null");
-        rc = compute_gram(ctx, (const float *)G, a->ncols, 0);
+        rc = compute_gram(ctx, G, ctx->cfg.factor_dtype, a->ncols, 0);
         if (rc != ALS_OK) return rc;
     }
     const float *gram = ctx->gram[0];
@@ -464,7 +468,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         {
             Timed t(ctx, ALS_K_HERMITIAN);
             if (implicit)
-                HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->stream, p->task_row, p->task_chunk, order, task0,
+                HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->task_row, p->task_chunk, order, task0,
                                                        ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G, alpha,
                                                        ctx->slots));
             else
@@ -533,7 +537,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             if (lo >= hi) continue;
             rc = in_pieces(lo, hi - lo, piece, [&](int64_t pos0, int64_t npos) {
                 if (implicit)
-                    HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos,
+                    HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos,
                                                               a->ptr, a->idx, a->val, G, lambda, alpha, gram, ctx->cfg.cg_iters,
                                                               ctx->cfg.cg_eps, Out, ctx->status));
                 else
@@ -704,7 +708,7 @@ static int als_gram_impl(als_ctx *ctx, const float *G, int64_t n, int f, float *
     if (!aligned16(G)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
-    int rc = compute_gram(ctx, G, n, 0);
+    int rc = compute_gram(ctx, G, ALS_F32, n, 0);
     if (rc != ALS_OK) return rc;
     HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, ctx->gram[0], out));
     return ALS_OK;
@@ -732,7 +736,7 @@ static int als_gram_static_impl(als_ctx *ctx, const float *G, int64_t n, int f, 
         if (items > cap) items = cap;
         const int64_t per = ((n + items - 1) / items + 3) & ~(int64_t)3;   // <= 2^30 / 116 + 3 rows
         const int nslots = (int)((n + per - 1) / per);
-        HIP_TRY(ctx, launch_gram(f, needs_wide_offsets(n, f, 4), ctx->stream, G, n, (int)per, nslots, slots, tiles));
+        HIP_TRY(ctx, launch_gram(f, needs_wide_offsets(n, f, 4), ALS_F32, ctx->stream, G, n, (int)per, nslots, slots, tiles));
     }
     HIP_TRY(ctx, launch_tiles_to_dense(f, ctx->stream, tiles, out));
     return ALS_OK;
@@ -749,7 +753,7 @@ static int als_implicit_loss_impl(als_ctx *ctx, const als_sparse *csr, const flo
     if (f != ctx->cfg.f) return fail(ctx, ALS_EINVAL, "f differs from the f given at als_create");
     if (!loss_out || !X || !Theta) return fail(ctx, ALS_EINVAL, "null pointer");
     if (!aligned16(X) || !aligned16(Theta)) return fail(ctx, ALS_EINVAL, "factor matrices must be 16-byte aligned");
-    rc = check_implicit(ctx, alpha);
+    rc = check_implicit(ctx, alpha, false);
     if (rc != ALS_OK) return rc;
     DeviceGuard on_device;
     HIP_TRY(ctx, on_device.enter(ctx->cfg.device));
@@ -758,9 +762,9 @@ static int als_implicit_loss_impl(als_ctx *ctx, const als_sparse *csr, const flo
         rc = sum_over_entries(ctx, csr, X, Theta, f, true, alpha, &entries);
         if (rc != ALS_OK) return rc;
     }
-    rc = compute_gram(ctx, X, csr->nrows, 0);
+    rc = compute_gram(ctx, X, ALS_F32, csr->nrows, 0);
     if (rc != ALS_OK) return rc;
-    rc = compute_gram(ctx, Theta, csr->ncols, 1);
+    rc = compute_gram(ctx, Theta, ALS_F32, csr->ncols, 1);
     if (rc != ALS_OK) return rc;
     if (!ctx->gram_dot) HIP_TRY(ctx, hipMalloc(&ctx->gram_dot, 3 * sizeof(double)));
     HIP_TRY(ctx, launch_gram_dot(f, ctx->stream, ctx->gram[0], ctx->gram[1], ctx->gram_dot));

@@ -27,7 +27,7 @@ constexpr int fused_waves(int F, int ET = ALS_F32) {
 
 // 16-bit factor inputs go to the 16-bit matrix cores where the width allows it (tiles16.h)
 constexpr bool use_tiles16(int F, int ET, int MODE) {
-    return (ET == ALS_BF16 || ET == ALS_F16) && MODE == kExplicit && has_tiles16(F);
+    return (ET == ALS_BF16 || ET == ALS_F16) && (MODE == kExplicit || MODE == kImplicit) && has_tiles16(F);
 }
 
 // least number of wavefronts per SIMD k_hermitian is compiled for: with 16-bit inputs at f = 100 the allocator
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
     if constexpr (ET == ALS_F32X3)   // fp32 rows cut into three bf16 parts, 16-bit matrix cores (tiles_x3.h)
         accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
     else if constexpr (use_tiles16(F, ET, MODE))
-        accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);
     else
         accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc,
                                                                                    b, alpha);
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
     if constexpr (ET == ALS_F32X3)
         accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
     else if constexpr (use_tiles16(F, ET, MODE))
-        accumulate_tiles16<F, WIDE, ET, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+        accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);
     else
         accumulate_tiles<F, true, kDepthFused, WIDE, ET, rows_all(F), true, MODE>(idx, val, Theta, uniform64(s0), len, acc, b,
                                                                                   alpha);

@@ -13,8 +13,9 @@
 
 namespace als {
 
-template <int F, bool WIDE>
-__global__ __launch_bounds__(64) void k_gram(const float *__restrict__ G, int64_t n, int per,
+// ET: element type of G (16-bit rows are widened in registers; the MFMAs are the fp32 ones)
+template <int F, bool WIDE, int ET>
+__global__ __launch_bounds__(64) void k_gram(const void *__restrict__ G, int64_t n, int per,
                                              float *__restrict__ slots) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = slot_floats(F);
     const int lane = threadIdx.x;
@@ -24,8 +25,7 @@ __global__ __launch_bounds__(64) void k_gram(const float *__restrict__ G, int64_
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    accumulate_tiles<F, false, kDepthSlots, WIDE, ALS_F32, rows_all(F), false, kGram>(nullptr, nullptr, G, uniform64(s0), len,
-                                                                                acc, b);
+    accumulate_tiles<F, false, kDepthSlots, WIDE, ET, rows_all(F), false, kGram>(nullptr, nullptr, G, uniform64(s0), len, acc, b);
     float *out = slots + (int64_t)blockIdx.x * SLOT;
 #pragma unroll
     for (int q = 0; q < NTILES; ++q)
@@ -110,23 +110,27 @@ __global__ __launch_bounds__(256) void k_gram_dot(const float *__restrict__ A, c
     }
 
 template <int F>
-static hipError_t gram_f(bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
+static hipError_t gram_f(bool wide, int et, hipStream_t st, const void *G, int64_t n, int per, int nslots, float *slots,
                          float *out) {
-    if (wide) hipLaunchKernelGGL((k_gram<F, true>), dim3(nslots), dim3(64), 0, st, G, n, per, slots);
-    else hipLaunchKernelGGL((k_gram<F, false>), dim3(nslots), dim3(64), 0, st, G, n, per, slots);
+#define LAUNCH(W, E) hipLaunchKernelGGL((k_gram<F, W, E>), dim3(nslots), dim3(64), 0, st, G, n, per, slots)
+    if (et == ALS_F32) { if (wide) LAUNCH(true, ALS_F32); else LAUNCH(false, ALS_F32); }
+    else if (et == ALS_BF16) { if (wide) LAUNCH(true, ALS_BF16); else LAUNCH(false, ALS_BF16); }
+    else { if (wide) LAUNCH(true, ALS_F16); else LAUNCH(false, ALS_F16); }
+#undef LAUNCH
     hipLaunchKernelGGL((k_sum_slots<F>), dim3((tiles_tri(F) * 64 + 255) / 256), dim3(256), 0, st, slots, nslots, out);
     return hipGetLastError();
 }
 
-hipError_t launch_gram(int f, bool wide, hipStream_t st, const float *G, int64_t n, int per, int nslots, float *slots,
-                       float *out) {
+hipError_t launch_gram(int f, bool wide, int et, hipStream_t st, const void *G, int64_t n, int per, int nslots,
+                       float *slots, float *out) {
     if (f == 256) {   // the wavefronts of a workgroup share the matrix (wide.hip); the sum of the slots is the same
-        const hipError_t e = launch_gram_wide(wide, st, G, n, per, nslots, slots);
+        if (et != ALS_F32) return hipErrorInvalidValue;
+        const hipError_t e = launch_gram_wide(wide, st, (const float *)G, n, per, nslots, slots);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((k_sum_slots<256>), dim3((tiles_tri(256) * 64 + 255) / 256), dim3(256), 0, st, slots, nslots, out);
         return hipGetLastError();
     }
-#define CALL(FF) gram_f<FF>(wide, st, G, n, per, nslots, slots, out)
+#define CALL(FF) gram_f<FF>(wide, et, st, G, n, per, nslots, slots, out)
     ALS_FOR_F(CALL)
 #undef CALL
 }
@@ -185,10 +189,13 @@ static hipError_t herm_imp_f(bool wide, hipStream_t st, const int32_t *task_row,
     return hipGetLastError();
 }
 
-hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, hipStream_t st, const int32_t *task_row,
+hipError_t launch_hermitian_implicit(int f, bool ptr64, bool wide, int et, hipStream_t st, const int32_t *task_row,
                                      const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk,
                                      const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                                      float alpha, float *slots) {
+    if (et != ALS_F32)
+        return launch_hermitian_implicit16(f, ptr64, wide, et, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr,
+                                           idx, val, Theta, alpha, slots);
     if (f == 256)
         return launch_hermitian_wide_implicit(ptr64, wide, st, task_row, task_chunk, task_order, task0, ntasks, chunk, ptr, idx, val,
                                               Theta, alpha, slots);
@@ -227,10 +234,13 @@ static hipError_t fused_imp_f(bool wide, int solver, hipStream_t st, const int32
                                               fs, eps, Xout, status);
 }
 
-hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
+hipError_t launch_hermitian_cg_implicit(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,
                                         int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx,
                                         const float *val, const void *Theta, float lambda, float alpha,
                                         const float *gram, int fs, float eps, float *Xout, int *status) {
+    if (et != ALS_F32)
+        return launch_hermitian_cg_implicit16(f, ptr64, wide, et, solver, st, perm, pos0, npos, ptr, idx, val, Theta, lambda,
+                                              alpha, gram, fs, eps, Xout, status);
     if (f == 256)
         return solver == ALS_SOLVER_CG
                    ? launch_hermitian_cg_wide_implicit(ptr64, wide, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, alpha,

@@ -58,11 +58,19 @@ __device__ __forceinline__ uint32_t split16(float &x0, float &x1) {
 // Same contract as accumulate_tiles<F, ..., ROWS, WANT_B, kExplicit>: acc += the tiles of the tile rows ROWS of
 // sum theta theta^T over the entries [s0, s0+len), b = sum r theta in column layout (tile rows of ROWS; zero
 // elsewhere), padding zeroed.
-template <int F, bool WIDE, int ET, bool WANT_B, uint32_t ROWS = rows_all(F)>
+//
+// MODE = kImplicit (Section 5.6): entry (u, v) enters A_u with the weight w = alpha * max(r_uv, 0) and b_u with
+// c = 1 + w if r_uv > 0.  A weight does not fit into 16 bits together with the value, so the two operands of a tile
+// differ: its columns get the plain 16-bit theta, its rows w * theta -- an fp32 product, cut into three 16-bit parts
+// that add up to it (three MFMAs per tile instead of one).  The rating lanes (rows) carry the parts of c.
+template <int F, bool WIDE, int ET, bool WANT_B, uint32_t ROWS = rows_all(F), int MODE = kExplicit>
 __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                    const void *__restrict__ Theta, int64_t s0, int len,
-                                                   v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)]) {
+                                                   v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)],
+                                                   float alpha = 0.f) {
     static_assert(ET == ALS_BF16 || ET == ALS_F16);
+    static_assert(MODE == kExplicit || MODE == kImplicit);
+    constexpr bool IMP = MODE == kImplicit;
     static_assert(has_tiles16(F));
     static_assert(ROWS == rows_all(F) || (F % 16) == 0, "partial sets of tile rows need f to be a multiple of 16");
     constexpr int NT = tiles_1d(F), RI = F % 16;
@@ -164,24 +172,34 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
     v4f bt[BX ? NT : 1];   // BX: rows 0..2 of these tiles are the three parts of b_u
 #pragma unroll
     for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
-    // operands of step t from the gathered rows and ratings
-    auto operands = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t, v4u (&g)[NT], v4u &gr) {
+    // operands of step t from the gathered rows and ratings; gw (implicit mode): the three parts of w * theta
+    auto operands = [&](const uint32_t (&raw)[8][RWE], float (&r)[8], int t, v4u (&g)[NT], v4u &gr,
+                        v4u (&gw)[IMP ? 3 : 1][IMP ? NT : 1]) {
         pack(raw, g);
+        float wv[8];
+        if constexpr (IMP) {   // the rating becomes the weight of b_u, c = 1 + w for r > 0 (0 beyond the work item: r = 0)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                wv[j] = alpha * fmaxf(r[j], 0.f);
+                r[j] = r[j] > 0.f ? 1.f + wv[j] : 0.f;
+            }
+        }
         // the rating lanes: of the last tile, or of the extra operand
         gr = (v4u){0u, 0u, 0u, 0u};
+        uint32_t rp[4] = {0u, 0u, 0u, 0u};
         if constexpr (WANT_B) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
                 const uint32_t p0 = split16<ET>(r[2 * m], r[2 * m + 1]);
                 const uint32_t p1 = split16<ET>(r[2 * m], r[2 * m + 1]);
                 const uint32_t p2 = split16<ET>(r[2 * m], r[2 * m + 1]);
-                const uint32_t rp = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
-                if constexpr (BX) gr[m] = rp;
-                else g[NT - 1][m] = is_feat ? g[NT - 1][m] : rp;
+                rp[m] = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
+                if constexpr (BX) gr[m] = rp[m];
             }
-        } else if constexpr (!BX) {
+        }
+        if constexpr (!BX) {   // (implicit mode: the columns of the padding stay zero, the rating lanes are rows only)
 #pragma unroll
-            for (int m = 0; m < 4; ++m) g[NT - 1][m] = is_feat ? g[NT - 1][m] : 0u;
+            for (int m = 0; m < 4; ++m) g[NT - 1][m] = is_feat ? g[NT - 1][m] : (IMP ? 0u : rp[m]);
         }
         if (t == nsteps - 1) {   // the last step may hold fewer than 32 entries: zero the others
             const int e0 = 32 * t + 8 * kq;
@@ -192,8 +210,23 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
                 for (int T = 0; T < NT; ++T) g[T][m] &= mask;
             }
         }
+        if constexpr (IMP) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int T = 0; T < NT; ++T) {
+                    float x0 = widen_lo<ET>(g[T][m]) * wv[2 * m], x1 = widen_hi<ET>(g[T][m]) * wv[2 * m + 1];
+                    const uint32_t q0 = split16<ET>(x0, x1);
+                    const uint32_t q1 = split16<ET>(x0, x1);
+                    const uint32_t q2 = split16<ET>(x0, x1);
+                    const bool keep = BX || T < NT - 1 || is_feat;
+                    gw[0][T][m] = keep ? q0 : rp[m];   // rows f .. f+2 of the last tile row: the parts of c
+                    gw[1][T][m] = keep ? q1 : 0u;
+                    gw[2][T][m] = keep ? q2 : 0u;
+                }
+        }
     };
-    auto multiply = [&](const v4u (&g)[NT], const v4u &gr) {
+    auto multiply = [&](const v4u (&g)[NT], const v4u &gr, const v4u (&gw)[IMP ? 3 : 1][IMP ? NT : 1]) {
         if constexpr (BX && WANT_B) {
 #pragma unroll
             for (int C = 0; C < NT; ++C)
@@ -203,7 +236,14 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
         for (int R = 0; R < NT; ++R)
             if ((ROWS >> R) & 1u) {
 #pragma unroll
-                for (int C = 0; C <= R; ++C) mfma_16x16x32<ET>(acc[tiles_below(ROWS, R) + C], g[R], g[C]);
+                for (int C = 0; C <= R; ++C) {
+                    if constexpr (IMP) {
+#pragma unroll
+                        for (int k = 2; k >= 0; --k) mfma_16x16x32<ET>(acc[tiles_below(ROWS, R) + C], gw[k][R], g[C]);
+                    } else {
+                        mfma_16x16x32<ET>(acc[tiles_below(ROWS, R) + C], g[R], g[C]);
+                    }
+                }
             }
     };
 
@@ -217,14 +257,14 @@ __device__ __forceinline__ void accumulate_tiles16(const int32_t *__restrict__ i
     load_ratings(0, rat);
     ids = load_ids(1);
     for (int t = 0; t < nsteps; ++t) {
-        v4u g[NT], gr;
-        operands(raw, rat, t, g, gr);
+        v4u g[NT], gr, gw[IMP ? 3 : 1][IMP ? NT : 1];
+        operands(raw, rat, t, g, gr, gw);
         if (t + 1 < nsteps) {
             gather8(ids, raw);
             load_ratings(t + 1, rat);
             ids = load_ids(t + 2);   // (beyond the end: zeros, never used)
         }
-        multiply(g, gr);
+        multiply(g, gr, gw);
     }
 
     // b_u = rows RI .. RI+2 of the last tile row (or rows 0 .. 2 of the extra tiles), then zero the padding

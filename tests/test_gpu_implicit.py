@@ -183,12 +183,74 @@ def test_implicit_argument_errors(P):
     with pytest.raises(P.AlsError):
         als.update_rows_implicit(csr, T, LAM, -1.0, X)
     als.close()
-    als = P.Als(w.f, solver=P.SOLVER_CG, factor_dtype=P.BF16)
+    als = P.Als(w.f, solver=P.SOLVER_CG, factor_dtype=P.F32X3)      # the three-part route is explicit feedback only
     with pytest.raises(P.AlsError):
-        als._check(als._lib.als_update_rows_implicit(als._ctx, __import__("ctypes").byref(csr.desc), T.data_ptr(), LAM,
-                                                     ALPHA, w.f, X.data_ptr()))
+        als.update_rows_implicit(csr, T, LAM, ALPHA, X)
+    als.close()
+    als = P.Als(256, solver=P.SOLVER_CG, factor_dtype=P.BF16)        # 16-bit implicit updates exist for f <= 128
+    with pytest.raises(P.AlsError):
+        als.update_rows_implicit(csr, torch.zeros((w.n, 256), device="cuda:0", dtype=torch.bfloat16), LAM, ALPHA,
+                                 torch.zeros((w.m, 256), device="cuda:0"))
     als.close()
     als = P.Als(w.f, solver=P.SOLVER_CG, herm_dtype=P.BF16)   # reduced-precision storage of A_u: explicit mode only
     with pytest.raises(P.AlsError):
         als.update_rows_implicit(csr, T, LAM, ALPHA, X)
     als.close()
+
+
+@pytest.mark.parametrize("f,name,chunk", [(f, n, c) for f in (16, 32, 64, 100, 128) for n in ("bf16", "f16") for c in (0, 128)])
+def test_implicit_with_sixteen_bit_factor_inputs(P, f, name, chunk):
+    """The gathered factor in 16 bits (f <= 128): the weighted sum runs on the 16-bit matrix cores with w * theta cut
+    into three 16-bit parts, Theta^T Theta from the same rounded factor.  Against the all-columns oracle on the
+    rounded factor: exact solver at 1e-4 per row, and Algorithm 1 with f iterations (exact then) at 1e-3."""
+    ncols = 3000
+    rng = np.random.default_rng(77)
+    degrees = [0, 1, 2, 3, 5, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 129, 255, 257, 511, 1000, 1025, 2049, 2900]
+    degrees += [int(np.exp(rng.uniform(0, np.log(2500)))) for _ in range(25)]
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(ncols, d, replace=False)) for d in degrees] + [np.zeros(0, int)]).astype(np.int32)
+    val = (rng.integers(0, 6, size=int(ptr[-1])) * 1.37).astype(np.float32)     # stored zeros, non-integer counts
+    tdt, code = (torch.bfloat16, P.BF16) if name == "bf16" else (torch.float16, P.F16)
+    T16 = torch.from_numpy(W.random_factors(ncols, f, seed=67 + f, scale=0.3)).cuda().to(tdt)
+    T_rounded = T16.to(torch.float32).cpu().numpy()
+    warm = W.random_factors(len(degrees), f, seed=68 + f, scale=0.05)
+    sp = P.SparseMatrix.from_host(len(degrees), ncols, ptr, idx, val)
+    ref = oracle.implicit_update_rows(ptr, idx, val, T_rounded, LAM, ALPHA)
+    for solver, fs, tol in ((P.SOLVER_CHOLESKY, 0, TOL_EXACT), (P.SOLVER_CG, f, 1e-3)):
+        als = P.Als(f, solver=solver, cg_iters=fs, chunk=chunk, factor_dtype=code)
+        X = _dev(warm.copy())
+        als.update_rows_implicit(sp, T16, LAM, ALPHA, X)
+        als.synchronize()
+        got = X.cpu().numpy()
+        als.close()
+        assert np.all(got[0] == 0.0)
+        err = _rel(got[1:], ref[1:])
+        assert err.max() <= tol, (name, int(err.argmax()) + 1, float(err.max()))
+
+
+def test_implicit_cg_sweeps_with_bf16_inputs_reach_the_exact_cost(P):
+    """Ten implicit sweeps of the tiny workload with CG(6) and bf16 factor inputs end within 2e-3 (relative) of the
+    cost the exact double-precision oracle sweeps reach (the all-columns oracle is O(m n f^2) per half-sweep)."""
+    w = W.TINY
+    a = W.generate(w)
+    c = W.transpose(a)
+    X0, T0 = W.init_factors(w)
+    Xo, To = X0.astype(np.float64), T0.astype(np.float64)
+    for _ in range(10):
+        Xo = oracle.implicit_update_rows(a.ptr, a.idx, a.val, To, LAM, ALPHA)
+        To = oracle.implicit_update_rows(c.ptr, c.idx, c.val, Xo, LAM, ALPHA)
+    cost_o = oracle.implicit_objective(a.ptr, a.idx, a.val, Xo, To, LAM, ALPHA)
+    als = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.BF16)
+    ev = P.Als(w.f)
+    csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
+    csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
+    X, T = _dev(X0), _dev(T0)
+    for _ in range(10):
+        als.update_rows_implicit(csr, T.to(torch.bfloat16), LAM, ALPHA, X)
+        als.update_cols_implicit(csc, X.to(torch.bfloat16), LAM, ALPHA, T)
+    als.synchronize()
+    cost = ev.implicit_loss(csr, X, T, LAM, ALPHA)
+    print(f"tiny implicit, bf16 inputs, CG(6): cost {cost:.4f}, exact oracle {cost_o:.4f}")
+    assert abs(cost - cost_o) <= 2e-3 * cost_o
+    als.close()
+    ev.close()
