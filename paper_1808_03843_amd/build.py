@@ -76,23 +76,24 @@ def check_resources(obj_dir: str = None) -> None:
                            + "; ".join(f"{k}: {v}" for k, v in sorted(bad.items())))
 
 
-def build(force: bool = True, lib: str = LIB, drained: bool = True) -> str:
-    """Compiles every source for gfx950 and links the library; with `drained` also the canary library."""
+def build(force: bool = True, lib: str = LIB, drained: bool = True, obj_dir: str = OBJ_DIR) -> str:
+    """Compiles every source for gfx950 and links the library; with `drained` also the canary library.
+    lib / obj_dir: another place for a variant build (ALS_EXTRA_HIPCC_FLAGS), e.g. the timing variants of profiles/."""
     if not force and not stale() and (not drained or os.path.exists(LIB_DRAINED)):
         return lib
-    jobs = [(src, OBJ_DIR, []) for src in SOURCES]
+    jobs = [(src, obj_dir, []) for src in SOURCES]
     if drained:
         jobs += [(src, OBJ_DIR_DRAINED, ["-DALS_DRAINED_MFMA"]) for src in SOURCES]
         os.makedirs(OBJ_DIR_DRAINED, exist_ok=True)
-    os.makedirs(OBJ_DIR, exist_ok=True)
+    os.makedirs(obj_dir, exist_ok=True)
     # the slowest translation units first, so that they do not end up alone at the tail of the pool
     slow = {"wide.hip": 0, "wide_ldlt_implicit.hip": 1, "wide_ldlt.hip": 2, "wide_ldlt_f16.hip": 3, "wide_ldlt_bf16.hip": 4,
             "hermitian.hip": 5}
     jobs.sort(key=lambda j: slow.get(j[0], 99))
     with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(jobs))) as ex:
         objs = dict(zip([(j[0], j[1]) for j in jobs], ex.map(_compile, jobs)))
-    check_resources(OBJ_DIR)
-    _link(lib, [objs[(src, OBJ_DIR)] for src in SOURCES])
+    check_resources(obj_dir)
+    _link(lib, [objs[(src, obj_dir)] for src in SOURCES])
     if drained:
         _link(LIB_DRAINED, [objs[(src, OBJ_DIR_DRAINED)] for src in SOURCES])
     return lib

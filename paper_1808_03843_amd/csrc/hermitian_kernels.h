@@ -167,6 +167,18 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
                                                                                   alpha);
     add_diagonal<F>(acc, MODE == kImplicit ? lambda : lambda * (float)len);
     float x[NT];
+#ifdef ALS_TIMING_SKIP_SOLVER
+    // Timing experiment only (wrong results): the fused kernel without its solver, to split its time into
+    // get_hermitian and solve.  x_u = a bounded function of b_u and of every tile, so that nothing is optimised away
+    // and the factors keep an ordinary magnitude over the sweeps of a timing run.
+#pragma unroll
+    for (int q = 0; q < NT; ++q) x[q] = b[q];
+#pragma unroll
+    for (int q = 0; q < NTILES; ++q) x[q % NT] += acc[q][0] + acc[q][1] + acc[q][2] + acc[q][3];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) x[q] = x[q] / (1.f + fabsf(x[q]));
+    (void)fs; (void)eps; (void)lane;
+#else
     if constexpr (SOLVER == ALS_SOLVER_CG) {
         load_vec<F>(xg, x);
         cg_tiles<F>(acc, b, x, fs, eps);
@@ -174,6 +186,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         __shared__ float tbuf[16 * 17];   // one wavefront per workgroup
         if (!ldlt_tiles<F>(acc, b, x, tbuf) && lane == 0) atomicOr(status, kStatusBadPivot);
     }
+#endif
     store_vec<F>(xg, x, status);
 }
 
