@@ -305,31 +305,41 @@ def main():
         "roofline": roofline,
     }
     if args.factor_dtype == "f32" and args.implicit is None and not args.no_reduced:
-        # the same sweeps with bf16 factor inputs (Section 4.2 taken to the matrix cores), continuing from the
-        # factors reached above; reported beside the fp32 figure, never as `value`
-        a16 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
-                    factor_dtype=P.BF16)
-        X16, T16 = X.clone(), T.clone()
+        # The same sweeps in the two other input modes, continuing from the factors reached above; reported beside the
+        # fp32 figure, never as `value`.  f32x3: the fp32 factor itself, multiplied on the 16-bit matrix cores as three
+        # bf16 parts (fp32 accuracy, f <= 128).  bf16: the factor rounded to bf16 each half-sweep (Section 4.2 taken to
+        # the matrix cores; reduced precision).
+        modes = [("bf16_factor_inputs", P.BF16, torch.bfloat16,
+                  "gathered factor rounded to bf16 each half-sweep (conversion timed), v_mfma_f32_16x16x32_bf16 with fp32 "
+                  "accumulate, fp32 solver and output")]
+        if w.f <= 128:
+            modes.insert(0, ("f32x3_factor_inputs", P.F32X3, None,
+                             "fp32 factor cut into three bf16 parts in registers, six products per pair on "
+                             "v_mfma_f32_16x16x32_bf16, fp32 accumulate: the tolerances of the fp32 path; fused rows with "
+                             "fewer than 256 entries run the fp32 kernel"))
+        for key, code, tdt, note in modes:
+            a2 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
+                       factor_dtype=code)
+            X2, T2 = X.clone(), T.clone()
 
-        def sweep16():
-            a16.update_rows(csr, T16.to(torch.bfloat16), w.lam, X16)
-            a16.update_cols(csc, X16.to(torch.bfloat16), w.lam, T16)
-        sweep16()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            sweep16()
-        torch.cuda.synchronize()
-        ms16 = (time.perf_counter() - t1) / args.steps * 1e3
-        ev = P.Als(w.f)
-        rmse16 = ev.rmse(csr, X16, T16)
-        ev.close()
-        a16.close()
-        del X16, T16
-        out["bf16_factor_inputs"] = {"ms_per_step": ms16, "train_rmse": rmse16, "sweeps_after_fp32": args.steps + 1,
-                                     "note": "gathered factor rounded to bf16 each half-sweep (conversion timed), "
-                                             "v_mfma_f32_16x16x32_bf16 with fp32 accumulate, fp32 solver and output"}
-        log(f"[bench] bf16 factor inputs: {ms16:.2f} ms per sweep, rmse {rmse16:.5f}")
+            def sweep2():
+                a2.update_rows(csr, T2 if tdt is None else T2.to(tdt), w.lam, X2)
+                a2.update_cols(csc, X2 if tdt is None else X2.to(tdt), w.lam, T2)
+            sweep2()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                sweep2()
+            torch.cuda.synchronize()
+            ms2 = (time.perf_counter() - t1) / args.steps * 1e3
+            a2.synchronize()
+            ev = P.Als(w.f)
+            rmse2 = ev.rmse(csr, X2, T2)
+            ev.close()
+            a2.close()
+            del X2, T2
+            out[key] = {"ms_per_step": ms2, "train_rmse": rmse2, "sweeps_after_fp32": args.steps + 1, "note": note}
+            log(f"[bench] {key}: {ms2:.2f} ms per sweep, rmse {rmse2:.5f}")
     # what the machine sustains on the simplest kernels (back-to-back MFMAs, a streaming copy): the reachable
     # counterparts of the published peaks the roofline is quoted against
     pk = P.Als(w.f)

@@ -20,8 +20,9 @@ namespace als {
 constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
 // (f = 128 with 16-bit inputs: the operand sets of 32 entries and the extra b_u tiles need the whole file)
-constexpr int fused_waves(int F, int ET = ALS_F32) {
+constexpr int fused_waves(int F, int ET = ALS_F32, int MODE = kExplicit) {
     if (ET == ALS_F32X3) return 1;   // three operand sets of 32 entries beside the accumulators
+    if ((ET == ALS_BF16 || ET == ALS_F16) && MODE == kImplicit && F > 64) return 1;   // likewise: w * theta in three parts
     return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2);
 }
 
@@ -32,7 +33,9 @@ constexpr bool use_tiles16(int F, int ET, int MODE) {
 
 // least number of wavefronts per SIMD k_hermitian is compiled for: with 16-bit inputs at f = 100 the allocator
 // otherwise lands just above the register budget of two and then spreads out to one
-constexpr int slot_waves(int F, int ET) { return (F == 100 && (ET == ALS_BF16 || ET == ALS_F16)) ? 2 : 1; }
+constexpr int slot_waves(int F, int ET, int MODE = kExplicit) {
+    return (F == 100 && (ET == ALS_BF16 || ET == ALS_F16) && MODE == kExplicit) ? 2 : 1;
+}
 
 // a value that is the same in every lane, moved to scalar registers
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -44,7 +47,7 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 // MODE: kExplicit (eq. (2)) or kImplicit (Section 5.6: every stored entry weighted by alpha * r_uv, b_u by
 // 1 + alpha * r_uv; the dense Theta^T Theta term is added by the solver kernels).
 template <int F, typename PtrT, bool WIDE, int ET, bool S16, int MODE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F, ET)))) void k_hermitian(const int32_t *__restrict__ task_row,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F, ET, MODE)))) void k_hermitian(const int32_t *__restrict__ task_row,
                                                   const int32_t *__restrict__ task_chunk, const int32_t *__restrict__ task_order, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                   const float *__restrict__ val, const void *__restrict__ Theta,
@@ -136,7 +139,7 @@ __device__ __forceinline__ void load_tiles(const float *__restrict__ src, v4f (&
 
 // gram (kImplicit only): tiles of Theta^T Theta, the starting value of the accumulators
 template <int F, typename PtrT, bool WIDE, int ET, int SOLVER, int MODE>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F, ET), fused_waves(F, ET)))) void k_hermitian_cg(
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F, ET, MODE), fused_waves(F, ET, MODE)))) void k_hermitian_cg(
     const int32_t *__restrict__ perm, int64_t pos0, const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
     const float *__restrict__ val, const void *__restrict__ Theta, float lambda, float alpha,
     const float *__restrict__ gram, int fs, float eps, float *__restrict__ Xout, int *__restrict__ status) {

@@ -36,9 +36,10 @@ def test_no_kernel_spills_or_uses_scratch(res):
 def test_dominant_kernel_occupancy(res):
     import re
     # fp32 slot storage (the bf16-slot variants need 9 more registers and run one wavefront per SIMD)
-    # (element types 0..2: fp32 and the 16-bit inputs; the three-part route, type 3, runs one wavefront per SIMD)
-    slots = [v for k, v in res.items() if re.search(r"11k_hermitianILi100E[il]Lb[01]ELi[012]ELb0E", k)]
-    fused = [v for k, v in res.items() if re.search(r"14k_hermitian_cgILi100E[il]Lb[01]ELi[012]E", k)]
+    # (element types 0..2: fp32 and the 16-bit inputs; the three-part route, type 3, runs one wavefront per SIMD;
+    # last template argument 0: explicit feedback)
+    slots = [v for k, v in res.items() if re.search(r"11k_hermitianILi100E[il]Lb[01]ELi[012]ELb0ELi0E", k)]
+    fused = [v for k, v in res.items() if re.search(r"14k_hermitian_cgILi100E[il]Lb[01]ELi[012]ELi[01]ELi0E", k)]
     assert slots and fused
     assert all(v["occupancy"] >= 2 for v in slots), slots
     assert all(v["occupancy"] >= 2 for v in fused), fused
