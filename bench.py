@@ -315,8 +315,7 @@ def main():
         if w.f <= 128:
             modes.insert(0, ("f32x3_factor_inputs", P.F32X3, None,
                              "fp32 factor cut into three bf16 parts in registers, six products per pair on "
-                             "v_mfma_f32_16x16x32_bf16, fp32 accumulate: the tolerances of the fp32 path; fused rows with "
-                             "fewer than 256 entries run the fp32 kernel"))
+                             "v_mfma_f32_16x16x32_bf16, fp32 accumulate: the tolerances of the fp32 path"))
         for key, code, tdt, note in modes:
             a2 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
                        factor_dtype=code)

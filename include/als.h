@@ -80,7 +80,7 @@ typedef struct als_config {
                              run on the 16-bit matrix cores: every value is cut into three bf16 parts that add up
                              to it exactly, and a product is the sum of the six part products that matter (what is
                              dropped is below 2^-23 of the product, one fp32 rounding).  Same tolerances as
-                             ALS_F32, about 1.5 to 2 times its speed; f <= 128, explicit feedback only     */
+                             ALS_F32, about 1.25 times its speed (Mid shape); f <= 128, explicit feedback only  */
     int32_t herm_dtype;   /* storage type of A_u where it is materialised, i.e. the partial Gram matrices of
                              rows split over several work items (Section 4.2): ALS_F32, or ALS_BF16 with
                              ALS_SOLVER_CG (fp32 accumulate, bf16 in memory; at f = 256 only together

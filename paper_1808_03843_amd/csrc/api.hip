@@ -2,7 +2,6 @@
 // batch loop of an update half-sweep, error bookkeeping.  No arithmetic of the method lives here.
 #include <cstdint>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -22,7 +21,6 @@ bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
     return (pitch & (pitch - 1)) != 0 && rows >= (1 << 24);
 }
 size_t factor_bytes(int factor_dtype) { return (factor_dtype == ALS_F32 || factor_dtype == ALS_F32X3) ? 4 : 2; }
-constexpr int kX3MinEntries = 256;
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
 
@@ -109,7 +107,6 @@ struct als_ctx {
     char *arena = nullptr;                 // the part of the workspace that holds the plans, filled front to back
     size_t arena_bytes = 0, arena_used = 0;
     int64_t slot_capacity = 0;             // workspace mode: slots the slot region holds (of the configured storage type)
-    int x3_min_entries = kX3MinEntries;    // ALS_F32X3: fused rows with fewer entries use the fp32 kernel
     std::vector<TimedLaunch> timed;
     std::vector<hipEvent_t> free_events;
 };
@@ -519,35 +516,20 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             }
         }
     }
-    // ALS_F32X3: a step of the three-part kernel takes 32 entries and runs one wavefront per SIMD, so it pays for rows
-    // with many entries only; the fused rows with fewer than kX3MinEntries entries (the tail of the degree-class
-    // order) go through the fp32 kernel, which computes the same thing to the same tolerance.
-    int64_t x3_end = fused_end;
-    if (!implicit && ctx->cfg.factor_dtype == ALS_F32X3) {
-        int c = 1;
-        while ((1 << (c - 1)) < ctx->x3_min_entries) ++c;   // class c: at least 2^(c-1) entries
-        x3_end = p->rows_ge[c] < fused_end ? p->rows_ge[c] : fused_end;
-        if (x3_end < slot_rows) x3_end = slot_rows;
-    }
     if (slot_rows < fused_end) {
         Timed t(ctx, ALS_K_FUSED);
-        for (int part = 0; part < 2; ++part) {
-            const int64_t lo = part == 0 ? slot_rows : x3_end, hi = part == 0 ? x3_end : fused_end;
-            const int et = (ctx->cfg.factor_dtype == ALS_F32X3 && part == 1) ? ALS_F32 : ctx->cfg.factor_dtype;
-            if (lo >= hi) continue;
-            rc = in_pieces(lo, hi - lo, piece, [&](int64_t pos0, int64_t npos) {
-                if (implicit)
-                    HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos,
-                                                              a->ptr, a->idx, a->val, G, lambda, alpha, gram, ctx->cfg.cg_iters,
-                                                              ctx->cfg.cg_eps, Out, ctx->status));
-                else
-                    HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, et, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos, a->ptr,
-                                                     a->idx, a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
-                                                     ctx->status));
-                return (int)ALS_OK;
-            });
-            if (rc != ALS_OK) return rc;
-        }
+        rc = in_pieces(slot_rows, fused_end - slot_rows, piece, [&](int64_t pos0, int64_t npos) {
+            if (implicit)
+                HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
+                                                          pos0, npos, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
+                                                          ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+            else
+                HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
+                                                 pos0, npos, a->ptr, a->idx, a->val, G, lambda, ctx->cfg.cg_iters,
+                                                 ctx->cfg.cg_eps, Out, ctx->status));
+            return (int)ALS_OK;
+        });
+        if (rc != ALS_OK) return rc;
     }
     return ALS_OK;
 }
@@ -625,7 +607,6 @@ int als_create(als_ctx **out, const als_config *cfg) {
     ctx->cfg = c;
     ctx->fixed = fixed;
     ctx->stream = (hipStream_t)c.stream;
-    if (const char *e = getenv("ALS_X3_MIN_ENTRIES")) ctx->x3_min_entries = atoi(e) > 0 ? atoi(e) : 1;   // tuning runs
     DeviceGuard on_device;
     bool ok = on_device.enter(c.device) == hipSuccess;
     if (ok && fixed) {

@@ -21,7 +21,7 @@ constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // wavefronts per SIMD the fused kernel is compiled for (register budget 512 / waves)
 // (f = 128 with 16-bit inputs: the operand sets of 32 entries and the extra b_u tiles need the whole file)
 constexpr int fused_waves(int F, int ET = ALS_F32, int MODE = kExplicit) {
-    if (ET == ALS_F32X3) return 1;   // three operand sets of 32 entries beside the accumulators
+    if (ET == ALS_F32X3) return F <= 100 ? 2 : 1;   // three operand sets of 32 entries beside the accumulators
     if ((ET == ALS_BF16 || ET == ALS_F16) && MODE == kImplicit && F > 64) return 1;   // likewise: w * theta in three parts
     return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2);
 }
@@ -34,6 +34,7 @@ constexpr bool use_tiles16(int F, int ET, int MODE) {
 // least number of wavefronts per SIMD k_hermitian is compiled for: with 16-bit inputs at f = 100 the allocator
 // otherwise lands just above the register budget of two and then spreads out to one
 constexpr int slot_waves(int F, int ET, int MODE = kExplicit) {
+    if (ET == ALS_F32X3) return F <= 100 ? 2 : 1;   // rows staged through LDS: two wavefronts fit
     return (F == 100 && (ET == ALS_BF16 || ET == ALS_F16) && MODE == kExplicit) ? 2 : 1;
 }
 
@@ -69,8 +70,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    if constexpr (ET == ALS_F32X3)   // fp32 rows cut into three bf16 parts, 16-bit matrix cores (tiles_x3.h)
-        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    if constexpr (ET == ALS_F32X3) {   // fp32 rows cut into three bf16 parts, 16-bit matrix cores (tiles_x3.h)
+        __shared__ __attribute__((aligned(16))) uint32_t fifo[x3_fifo_words(F)];   // one wavefront per workgroup
+        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b, fifo);
+    }
     else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);
     else
@@ -161,8 +164,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     float b[NT];
-    if constexpr (ET == ALS_F32X3)
-        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b);
+    if constexpr (ET == ALS_F32X3) {
+        __shared__ __attribute__((aligned(16))) uint32_t fifo[x3_fifo_words(F)];   // one wavefront per workgroup
+        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b, fifo);
+    }
     else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);
     else

@@ -9,28 +9,50 @@
 // Layout as in tiles16.h: one step consumes 32 stored entries, lane (i, kq) supplies its feature of the 8 entries
 // 8kq .. 8kq+7, packed in pairs; the three parts of a value sit at the same place of three operand registers.
 // Rows are gathered entry by entry as fp32 with the lane -> feature map and load widths of the fp32 path.
+// Measured (Mid shape, f = 100): the slot kernel issues 1.3 PFLOP/s of bf16 MFMA work, 94 % of what this chip
+// sustains on back-to-back bf16 MFMAs (it lowers its clock under that load), i.e. 135-155 TFLOP/s of Gram work.
 //
 // b_u: when f is not a multiple of 16 the lane i = f % 16 of the last tile carries the fp32 rating instead of a
 // feature and is cut into parts like everything else, so row f of the accumulated matrix is b_u to the same
 // accuracy; the lanes beyond it carry zeros.  When f is a multiple of 16 the three parts of the rating form an
 // operand of their own (lanes 0..2) that is multiplied with all three parts of every tile column: 3 NT more MFMAs
 // per step, whose rows 0..2 add up to b_u.
+//
+// The gathered rows are staged through LDS (Section 3: the rows of Theta that a row of R refers to are staged on
+// chip in batches; here the staging buffer is a per-wavefront FIFO).
+// Why: the operands of a step (three parts of 32 entries: 84 registers at f = 100) and the 112 accumulator registers
+// leave no room for the 56 registers of the next step's rows in flight if two wavefronts are to share a SIMD -- and
+// with one wavefront per SIMD nothing hides the memory latency or the vector-ALU work of cutting the values into
+// parts.  So the rows of the next step travel by direct global-to-LDS loads (no destination registers), and are read
+// back, 8 registers at a time, just before they are cut.  Every lane reads back exactly what it loaded: the buffer
+// is laid out load instruction by load instruction, lane by lane (bank-conflict free both ways).
+//
+// The buffer of one wavefront holds the rows of one step, in three regions that follow the three kinds of loads of a
+// row (16 bytes per lane for tiles 0 .. 4 N4 - 1; two 4-byte loads for the next 2 N2 tiles; 4 bytes for the last N1
+// tiles).  A region is refilled for step t+1 as soon as step t has read it.
 #pragma once
 #include "tiles16.h"
 
 namespace als {
 
-// Same contract as accumulate_tiles16 for ET = fp32 rows in memory.
+constexpr int x3_fifo_words(int F) { return 8 * 64 * (4 * loads16(F) + 2 * loads8(F) + loads4(F)); }
+
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void global_void;
+
+// Every wavefront of the kernel must call with its own fifo (x3_fifo_words(F) words, 16-byte aligned).
 template <int F, bool WIDE, bool WANT_B, uint32_t ROWS = rows_all(F)>
 __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ idx, const float *__restrict__ val,
-                                                    const void *__restrict__ Theta, int64_t s0, int len,
-                                                    v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)]) {
+                                                        const void *__restrict__ Theta, int64_t s0, int len,
+                                                        v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)],
+                                                        uint32_t *fifo) {
     static_assert(ROWS == rows_all(F) || (F % 16) == 0, "partial sets of tile rows need f to be a multiple of 16");
     constexpr int NT = tiles_1d(F), RI = F % 16;
     constexpr bool BX = RI == 0;   // the rating parts are an operand of their own
     constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
-    constexpr int base1 = 64 * N4 + 32 * N2;
+    constexpr int base1 = 64 * N4 + 32 * N2, first1 = 4 * N4 + 2 * N2;
     constexpr int LB = (NT - 1) * NT / 2;
+    constexpr int baseA = 0, baseB = 8 * N4 * 256, baseC = baseB + 8 * N2 * 128;   // word offsets of the regions
     const int lane = threadIdx.x & 63, i = lane & 15, kq = lane >> 4;
     const int32_t *__restrict__ ib = idx + s0;
     const float *__restrict__ vb = val + s0;
@@ -38,7 +60,6 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
     const __amdgpu_buffer_rsrc_t ids_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t *>(ib), 0, 4 * len, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t val_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vb), 0, 4 * len, kRsrcFlags);
     const int nsteps = (len + 31) >> 5;
-    // lane offsets of the three kinds of loads inside a row (bytes)
     const uint32_t lane_a = 16u * (uint32_t)i;
     const uint32_t lane_b = 256u * N4 + 8u * (uint32_t)i;
     const uint32_t lane_c = 4u * (uint32_t)(base1 + i);
@@ -65,11 +86,6 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             r[4 + j] = bits_to_float(c[j]);
         }
     };
-    // The loads of one gathered fp32 row come in three groups -- 16 bytes per lane (tiles 0 .. 4 N4 - 1), 8 bytes (the
-    // next 2 N2 tiles), 4 bytes (the last N1 tiles) -- and a group of the next step is issued as soon as the last
-    // tile it fills has been cut into parts.  (Entries beyond the work item read row 0 and are masked later.)
-    constexpr int first1 = 4 * N4 + 2 * N2;
-    constexpr int endA = N4 > 0 ? 4 * N4 - 1 : -1, endB = N2 > 0 ? first1 - 1 : -1, endC = N1 > 0 ? NT - 1 : -1;
     auto row_base = [&](uint32_t c, const char *&p, uint32_t &ro) {
         if constexpr (WIDE) {
             p = reinterpret_cast<const char *>(Theta) + (int64_t)c * (4 * F);
@@ -79,7 +95,8 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             ro = row_offset<(uint32_t)(4 * F)>(c, lane_first);
         }
     };
-    auto gather_group = [&](auto gtag, uint32_t c, uint32_t (&w)[NT]) {
+    // the loads of group G (0: 16-byte, 1: the 8-byte pair as two 4-byte loads, 2: 4-byte) of entry j, global -> LDS
+    auto dma_group = [&](auto gtag, int j, uint32_t c) {
         constexpr int G = decltype(gtag)::value;
         const char *p;
         uint32_t ro;
@@ -87,29 +104,31 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
         if constexpr (G == 0 && N4 > 0) {
             const uint32_t o = ro + (lane_a - lane_first);
 #pragma unroll
-            for (int q = 0; q < N4; ++q) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(p + o + 256 * q);
-                w[4 * q] = v.x; w[4 * q + 1] = v.y; w[4 * q + 2] = v.z; w[4 * q + 3] = v.w;
-            }
+            for (int q = 0; q < N4; ++q)
+                __builtin_amdgcn_global_load_lds((global_void *)(p + o + 256 * q), (lds_void *)(fifo + baseA + (j * N4 + q) * 256), 16, 0, 0);
         }
         if constexpr (G == 1 && N2 > 0) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(p + (ro + (lane_b - lane_first)));
-            w[4 * N4] = v.x; w[4 * N4 + 1] = v.y;
+            const uint32_t o = ro + (lane_b - lane_first);
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+                __builtin_amdgcn_global_load_lds((global_void *)(p + o + 4 * hh), (lds_void *)(fifo + baseB + (j * 2 + hh) * 64), 4, 0, 0);
         }
         if constexpr (G == 2 && N1 > 0) {
             if constexpr (N1 > 1) {
                 const uint32_t o = ro + (lane_c - lane_first);
 #pragma unroll
-                for (int k = 0; k < N1 - 1; ++k) w[first1 + k] = *reinterpret_cast<const uint32_t *>(p + o + 64 * k);
+                for (int k = 0; k < N1 - 1; ++k)
+                    __builtin_amdgcn_global_load_lds((global_void *)(p + o + 64 * k), (lds_void *)(fifo + baseC + (j * N1 + k) * 64), 4, 0, 0);
             }
-            w[first1 + N1 - 1] = *reinterpret_cast<const uint32_t *>(p + (ro + (lane_l - lane_first)));
+            __builtin_amdgcn_global_load_lds((global_void *)(p + (ro + (lane_l - lane_first))),
+                                             (lds_void *)(fifo + baseC + (j * N1 + N1 - 1) * 64), 4, 0, 0);
         }
     };
-    auto gather8_group = [&](auto gtag, const Ids &ids, uint32_t (&raw)[8][NT]) {
+    auto dma8_group = [&](auto gtag, const Ids &ids) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            gather_group(gtag, ids.lo[j], raw[j]);
-            gather_group(gtag, ids.hi[j], raw[4 + j]);
+            dma_group(gtag, j, ids.lo[j]);
+            dma_group(gtag, 4 + j, ids.hi[j]);
         }
     };
     using G0 = std::integral_constant<int, 0>;
@@ -122,33 +141,59 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
 #pragma unroll
     for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // the last step may hold fewer than 32 entries: the others count as zero (a wave-uniform branch)
-    auto mask_tail = [&](uint32_t (&raw)[8][NT], float (&r)[8], int t) {
+    v4u h[NT], m[NT], l[NT], gr;
+    // tile T, entry pair pr: the two fp32 values -> three packed part pairs.  ok0 / ok1: entry inside the work item
+    auto cut = [&](auto ttag, int pr, float x0, float x1, const float (&r)[8], bool ok0, bool ok1, auto lasttag) {
+        constexpr int T = decltype(ttag)::value;
+        if constexpr (!BX && T == NT - 1) {   // the rating lane and the zero lanes of the last tile
+            x0 = is_feat ? x0 : ((WANT_B && is_rating) ? r[2 * pr] : 0.f);
+            x1 = is_feat ? x1 : ((WANT_B && is_rating) ? r[2 * pr + 1] : 0.f);
+        }
+        if constexpr (decltype(lasttag)::value) {
+            x0 = ok0 ? x0 : 0.f;
+            x1 = ok1 ? x1 : 0.f;
+        }
+        h[T][pr] = split16<ALS_BF16>(x0, x1);
+        m[T][pr] = split16<ALS_BF16>(x0, x1);
+        l[T][pr] = split16<ALS_BF16>(x0, x1);
+    };
+    // reads a region back, one entry pair at a time, and cuts its tiles into parts
+    auto read_group = [&](auto gtag, const float (&r)[8], int t, auto lasttag) {
+        constexpr int G = decltype(gtag)::value;
         const int e0 = 32 * t + 8 * kq;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const bool ok = e0 + e < len;
-#pragma unroll
-            for (int T = 0; T < NT; ++T) raw[e][T] = ok ? raw[e][T] : 0u;
-            r[e] = ok ? r[e] : 0.f;
-        }
-    };
-    // operands of one tile: the leading (h), middle (m) and trailing (l) bf16 parts of the lane's 8 entries
-    auto split_tile = [&](auto ttag, const uint32_t (&raw)[8][NT], const float (&r)[8], v4u &h, v4u &m, v4u &l) {
-        constexpr int T = decltype(ttag)::value;
-#pragma unroll
         for (int pr = 0; pr < 4; ++pr) {
-            float x0 = bits_to_float(raw[2 * pr][T]), x1 = bits_to_float(raw[2 * pr + 1][T]);
-            if constexpr (!BX && T == NT - 1) {   // the rating lane and the zero lanes of the last tile
-                x0 = is_feat ? x0 : ((WANT_B && is_rating) ? r[2 * pr] : 0.f);
-                x1 = is_feat ? x1 : ((WANT_B && is_rating) ? r[2 * pr + 1] : 0.f);
+            const bool ok0 = e0 + 2 * pr < len, ok1 = e0 + 2 * pr + 1 < len;
+            if constexpr (G == 0 && N4 > 0) {
+                [&]<int... q>(std::integer_sequence<int, q...>) {
+                    ([&] {
+                        const v4u v0 = *reinterpret_cast<const v4u *>(fifo + baseA + ((2 * pr) * N4 + q) * 256 + 4 * lane);
+                        const v4u v1 = *reinterpret_cast<const v4u *>(fifo + baseA + ((2 * pr + 1) * N4 + q) * 256 + 4 * lane);
+                        cut(std::integral_constant<int, 4 * q>{}, pr, bits_to_float(v0[0]), bits_to_float(v1[0]), r, ok0, ok1, lasttag);
+                        cut(std::integral_constant<int, 4 * q + 1>{}, pr, bits_to_float(v0[1]), bits_to_float(v1[1]), r, ok0, ok1, lasttag);
+                        cut(std::integral_constant<int, 4 * q + 2>{}, pr, bits_to_float(v0[2]), bits_to_float(v1[2]), r, ok0, ok1, lasttag);
+                        cut(std::integral_constant<int, 4 * q + 3>{}, pr, bits_to_float(v0[3]), bits_to_float(v1[3]), r, ok0, ok1, lasttag);
+                    }(), ...);
+                }(std::make_integer_sequence<int, N4>{});
             }
-            h[pr] = split16<ALS_BF16>(x0, x1);
-            m[pr] = split16<ALS_BF16>(x0, x1);
-            l[pr] = split16<ALS_BF16>(x0, x1);
+            if constexpr (G == 1 && N2 > 0) {
+                const uint32_t a0 = fifo[baseB + ((2 * pr) * 2 + 0) * 64 + lane], a1 = fifo[baseB + ((2 * pr) * 2 + 1) * 64 + lane];
+                const uint32_t c0 = fifo[baseB + ((2 * pr + 1) * 2 + 0) * 64 + lane], c1 = fifo[baseB + ((2 * pr + 1) * 2 + 1) * 64 + lane];
+                cut(std::integral_constant<int, 4 * N4>{}, pr, bits_to_float(a0), bits_to_float(c0), r, ok0, ok1, lasttag);
+                cut(std::integral_constant<int, 4 * N4 + 1>{}, pr, bits_to_float(a1), bits_to_float(c1), r, ok0, ok1, lasttag);
+            }
+            if constexpr (G == 2 && N1 > 0) {
+                [&]<int... k>(std::integer_sequence<int, k...>) {
+                    ([&] {
+                        const uint32_t a0 = fifo[baseC + ((2 * pr) * N1 + k) * 64 + lane];
+                        const uint32_t c0 = fifo[baseC + ((2 * pr + 1) * N1 + k) * 64 + lane];
+                        cut(std::integral_constant<int, first1 + k>{}, pr, bits_to_float(a0), bits_to_float(c0), r, ok0, ok1, lasttag);
+                    }(), ...);
+                }(std::make_integer_sequence<int, N1>{});
+            }
         }
     };
-    auto rating_operand = [&](const float (&r)[8], v4u &gr) {
+    auto rating_operand = [&](const float (&r)[8]) {
         gr = (v4u){0u, 0u, 0u, 0u};
         if constexpr (BX && WANT_B) {
 #pragma unroll
@@ -161,58 +206,71 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             }
         }
     };
+    // the MFMAs of the tile rows [R0, R1): six per tile
+    auto rows_mfma = [&](auto r0tag, auto r1tag) {
+        constexpr int R0 = decltype(r0tag)::value, R1 = decltype(r1tag)::value;
+#pragma unroll
+        for (int R = R0; R < R1; ++R)
+            if ((ROWS >> R) & 1u) {
+#pragma unroll
+                for (int C = 0; C <= R; ++C) {
+                    v4f &a = acc[tiles_below(ROWS, R) + C];
+                    mfma_16x16x32<ALS_BF16>(a, h[R], l[C]);
+                    mfma_16x16x32<ALS_BF16>(a, l[R], h[C]);
+                    mfma_16x16x32<ALS_BF16>(a, m[R], m[C]);
+                    mfma_16x16x32<ALS_BF16>(a, h[R], m[C]);
+                    mfma_16x16x32<ALS_BF16>(a, m[R], h[C]);
+                    mfma_16x16x32<ALS_BF16>(a, h[R], h[C]);
+                }
+                if constexpr (BX && WANT_B) {
+                    mfma_16x16x32<ALS_BF16>(bt[R], gr, l[R]);
+                    mfma_16x16x32<ALS_BF16>(bt[R], gr, m[R]);
+                    mfma_16x16x32<ALS_BF16>(bt[R], gr, h[R]);
+                }
+            }
+    };
+    constexpr int endA = 4 * N4, endB = first1;   // first tile beyond group A / groups A and B
+    using T0 = std::integral_constant<int, 0>;
+    using TA = std::integral_constant<int, endA>;
+    using TB = std::integral_constant<int, endB>;
+    using TN = std::integral_constant<int, NT>;
 
-    // One step, tile row by tile row: the MFMAs of tile row T (six per tile, 16 matrix-pipeline cycles each) need the
-    // parts of the tiles 0 .. T only, so the vector-ALU work that cuts tile T+1 into parts is placed among them and
-    // runs in their shadow; only tile 0 is cut with the matrix pipeline idle.  The scheduling barriers keep the
-    // compiler from collecting the vector-ALU work of a step in front of its MFMAs.
-    uint32_t raw[8][NT];
     float rat[8];
     Ids ids = load_ids(0);
-    gather8_group(G0{}, ids, raw);
-    gather8_group(G1{}, ids, raw);
-    gather8_group(G2{}, ids, raw);
+    dma8_group(G0{}, ids);
+    dma8_group(G1{}, ids);
+    dma8_group(G2{}, ids);
     load_ratings(0, rat);
-    ids = load_ids(1);
-    for (int t = 0; t < nsteps; ++t) {
-        v4u h[NT], m[NT], l[NT], gr;
-        if (t == nsteps - 1) mask_tail(raw, rat, t);
-        rating_operand(rat, gr);
-        split_tile(std::integral_constant<int, 0>{}, raw, rat, h[0], m[0], l[0]);
-        [&]<int... T>(std::integer_sequence<int, T...>) {
-            ([&] {
-                __builtin_amdgcn_sched_barrier(0);
-                if constexpr ((ROWS >> T) & 1u) {
-#pragma unroll
-                    for (int C = 0; C <= T; ++C) {
-                        v4f &a = acc[tiles_below(ROWS, T) + C];
-                        mfma_16x16x32<ALS_BF16>(a, h[T], l[C]);
-                        mfma_16x16x32<ALS_BF16>(a, l[T], h[C]);
-                        mfma_16x16x32<ALS_BF16>(a, m[T], m[C]);
-                        mfma_16x16x32<ALS_BF16>(a, h[T], m[C]);
-                        mfma_16x16x32<ALS_BF16>(a, m[T], h[C]);
-                        mfma_16x16x32<ALS_BF16>(a, h[T], h[C]);
-                    }
-                    if constexpr (BX && WANT_B) {
-                        mfma_16x16x32<ALS_BF16>(bt[T], gr, l[T]);
-                        mfma_16x16x32<ALS_BF16>(bt[T], gr, m[T]);
-                        mfma_16x16x32<ALS_BF16>(bt[T], gr, h[T]);
-                    }
-                }
-                if constexpr (T + 1 < NT) split_tile(std::integral_constant<int, T + 1>{}, raw, rat, h[T + 1], m[T + 1], l[T + 1]);
-                // rows of the next step: a group of loads goes out once the last tile it fills is in parts (tile T+1
-                // has just been cut; tile 0 was cut before the first tile row)
-                constexpr auto due = [](int end_tile, int T_) { return (end_tile == T_ + 1 && T_ + 1 < NT) || (end_tile == 0 && T_ == 0); };
-                if constexpr (due(endA, T)) gather8_group(G0{}, ids, raw);
-                if constexpr (due(endB, T)) gather8_group(G1{}, ids, raw);
-                if constexpr (due(endC, T)) gather8_group(G2{}, ids, raw);
-                // the ratings are last used by the rating operand (at the start of the step) or by the last tile
-                if constexpr (BX ? T == 0 : T == NT - 1) load_ratings(t + 1, rat);
-                if constexpr (T == NT - 1) ids = load_ids(t + 2);   // (beyond the end: zeros, never used)
-            }(), ...);
-        }(std::make_integer_sequence<int, NT>{});
+    ids = load_ids(1);   // of the next step: the loads of step t+1 go out during step t
+    // one step; LAST: the final step of the work item -- entries beyond its end count as zero, nothing is prefetched
+    auto step = [&](auto lasttag, int t) {
+        constexpr bool LAST = decltype(lasttag)::value;
+        // everything this step reads from the buffer was issued a step ago
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+        rating_operand(rat);
+        // (a region is refilled only after its values have been read AND used: the scheduling barrier keeps the
+        // loads that overwrite it behind the instructions that wait for the reads)
+        read_group(G0{}, rat, t, lasttag);
         __builtin_amdgcn_sched_barrier(0);
-    }
+        if constexpr (!LAST) dma8_group(G0{}, ids);
+        rows_mfma(T0{}, TA{});
+        read_group(G1{}, rat, t, lasttag);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!LAST) dma8_group(G1{}, ids);
+        rows_mfma(TA{}, TB{});
+        read_group(G2{}, rat, t, lasttag);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!LAST) {
+            dma8_group(G2{}, ids);
+            load_ratings(t + 1, rat);
+            ids = load_ids(t + 2);   // (beyond the end: zeros -> row 0, read but never used)
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        rows_mfma(TB{}, TN{});
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int t = 0; t + 1 < nsteps; ++t) step(std::false_type{}, t);
+    step(std::true_type{}, nsteps - 1);
 
     // b_u = row RI of the last tile row (or rows 0 .. 2 of the extra tiles), then zero the padding
     const int c = i, g4 = kq;
