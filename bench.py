@@ -118,9 +118,10 @@ def main():
     ap.add_argument("--batch-slots", type=int, default=0)
     ap.add_argument("--cpu-stride", type=int, default=1, help="oracle baseline on every k-th row/column (1 = one whole exact sweep, about 20 s on 16 host threads); 0 = skip")
     ap.add_argument("--f", type=int, default=0, help="override the workload's factor width (factor-width sweep)")
-    ap.add_argument("--factor-dtype", default="f32", choices=["f32", "bf16", "f16", "f32x3"],
+    ap.add_argument("--factor-dtype", default="f32", choices=["f32", "bf16", "f16", "f32x3", "f32x2"],
                     help="element type of the gathered factor matrix (16-bit: multiplied on the 16-bit matrix cores, fp32 accumulate; "
-                         "f32x3: fp32 in memory, cut into three bf16 parts and multiplied on the 16-bit matrix cores at fp32 accuracy)")
+                         "f32x3: fp32 in memory, cut into three bf16 parts and multiplied on the 16-bit matrix cores at fp32 accuracy; "
+                         "f32x2: fp32 in memory, scaled and cut into two fp16 parts, three products per pair)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device copy five times (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -156,9 +157,9 @@ def main():
         a, held_out = W.split(a, args.test_frac, seed=w.seed)
         log(f"[bench] held out {held_out.nnz} entries, fitting on {a.nnz}")
     solver = P.SOLVER_CG if args.solver == "cg" else P.SOLVER_CHOLESKY
-    fcode = {"f32": P.F32, "bf16": P.BF16, "f16": P.F16, "f32x3": P.F32X3}[args.factor_dtype]
-    ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16, "f32x3": torch.float32}[args.factor_dtype]
-    in_fp32 = args.factor_dtype in ("f32", "f32x3")   # the gathered factor is the fp32 matrix itself
+    fcode = {"f32": P.F32, "bf16": P.BF16, "f16": P.F16, "f32x3": P.F32X3, "f32x2": P.F32X2}[args.factor_dtype]
+    ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16, "f32x3": torch.float32, "f32x2": torch.float32}[args.factor_dtype]
+    in_fp32 = args.factor_dtype in ("f32", "f32x3", "f32x2")   # the gathered factor is the fp32 matrix itself
     als = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
                 profile=True, factor_dtype=fcode, herm_dtype=P.BF16 if args.herm_dtype == "bf16" else P.F32)
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, device=dev)
@@ -248,15 +249,16 @@ def main():
                                       "ms_per_sweep": (herm_ms + fused_ms) / K, "launches_per_sweep": launches,
                                       "flops_per_sweep": flops_sweep},
                 **kernels}
-    if args.factor_dtype == "f32x3":
-        # fp32 values as three bf16 parts on the 16-bit matrix cores: the numerator stays the algorithmic flops of the
+    if args.factor_dtype in ("f32x3", "f32x2"):
+        # fp32 values as 16-bit parts on the 16-bit matrix cores: the numerator stays the algorithmic flops of the
         # fp32 Gram matrix, the denominator is the peak of the instruction that runs, the 16-bit dense MFMA peak
         for k in kernels.values():
             k["frac"] = k["tflops"] / PEAK_16BIT_MFMA_TFLOPS
             k["frac_of_fp32_mfma_peak"] = k["tflops"] / PEAK_FP32_MFMA_TFLOPS
         roofline.update({"peak": PEAK_16BIT_MFMA_TFLOPS, "frac": d["frac"],
-                         "note": "algorithmic fp32 flops against the bf16 MFMA peak: six bf16 products per fp32 product, "
-                                 "so the ceiling of the mode is 1/6 of the 16-bit peak = 417 TFLOP/s of Gram work"})
+                         "note": "algorithmic fp32 flops against the 16-bit MFMA peak: six bf16 (f32x3) or three fp16 (f32x2) "
+                                 "products per fp32 product, so the ceiling of the mode is 1/6 (1/3) of the 16-bit peak = "
+                                 "417 (833) TFLOP/s of Gram work"})
         roofline["dominant_kernel"]["frac"] = d["frac"]
         roofline["all_get_hermitian"]["frac"] = achieved / PEAK_16BIT_MFMA_TFLOPS
         roofline["all_get_hermitian"]["frac_of_fp32_mfma_peak"] = achieved / PEAK_FP32_MFMA_TFLOPS
@@ -285,7 +287,7 @@ def main():
         "value": sec_per_sweep, "unit": "s/sweep",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_sweep * 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.factor_dtype == "f32x3" else args.factor_dtype, "data": "synthetic",
+        "dtype": "f32" if args.factor_dtype in ("f32x3", "f32x2") else args.factor_dtype, "data": "synthetic",
         "factor_dtype": args.factor_dtype, "herm_dtype": args.herm_dtype,
         "config": {"workload": f"{w.name}: m={w.m} n={w.n} nnz={nnz_fit} f={w.f} lambda={w.lam}",
                    "solver": args.solver + (f"({args.cg_iters})" if args.solver == "cg" else ""),
@@ -316,6 +318,10 @@ def main():
             modes.insert(0, ("f32x3_factor_inputs", P.F32X3, None,
                              "fp32 factor cut into three bf16 parts in registers, six products per pair on "
                              "v_mfma_f32_16x16x32_bf16, fp32 accumulate: the tolerances of the fp32 path"))
+            modes.insert(1, ("f32x2_factor_inputs", P.F32X2, None,
+                             "fp32 factor scaled by a power of two and cut into two fp16 parts in registers (to nearest), "
+                             "three products per pair on v_mfma_f32_16x16x32_f16, fp32 accumulate: held to the tolerances "
+                             "of the fp32 path"))
         for key, code, tdt, note in modes:
             a2 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
                        factor_dtype=code)
@@ -347,7 +353,7 @@ def main():
     out["measured_peaks"] = {"mfma_f32_TFLOPs": mf32 / 1e12, "mfma_bf16_TFLOPs": mbf16 / 1e12, "copy_GBps": cp / 1e9,
                              "note": "8 wavefronts per SIMD issuing independent MFMAs; copy of 1 GiB, bytes read + written"}
     if roofline["bound"] == "mfma":
-        reach = (mbf16 if args.factor_dtype == "f32x3" else mf32) / 1e12
+        reach = (mbf16 if args.factor_dtype in ("f32x3", "f32x2") else mf32) / 1e12
         roofline["frac_of_measured_peak"] = roofline["achieved"] / reach
         roofline["all_get_hermitian"]["frac_of_measured_peak"] = roofline["all_get_hermitian"]["achieved"] / reach
     else:

@@ -52,6 +52,8 @@ extern "C" {
 #define ALS_F16 2
 #define ALS_F32X3 3 /* factor_dtype only: fp32 factors in memory, multiplied on the 16-bit matrix cores as three
                        bf16 parts each (six products per pair, fp32 accumulate): fp32 accuracy, see als_config */
+#define ALS_F32X2 4 /* factor_dtype only: fp32 factors in memory, multiplied on the 16-bit matrix cores as two
+                       fp16 parts each (three products per pair, fp32 accumulate), see als_config              */
 
 typedef struct als_ctx als_ctx; /* opaque; one per (device, stream); not thread-safe */
 /* Every call makes the context's device current while it runs and restores the caller's current device on return. */
@@ -80,7 +82,14 @@ typedef struct als_config {
                              run on the 16-bit matrix cores: every value is cut into three bf16 parts that add up
                              to it exactly, and a product is the sum of the six part products that matter (what is
                              dropped is below 2^-23 of the product, one fp32 rounding).  Same tolerances as
-                             ALS_F32, about 1.25 times its speed (Mid shape); f <= 128, explicit feedback only  */
+                             ALS_F32, about 1.25 times its speed (Mid shape); f <= 128, explicit feedback only.
+                             ALS_F32X2: likewise fp32 in memory, but two fp16 parts per value, h = fp16(s x) and
+                             l = fp16(s x - h), rounded to nearest (|s x - h - l| <= 2^-22 |s x|), and the three
+                             products h h' + h l' + l h'.  s is a power of two chosen per call from max |x| of the
+                             gathered matrix (a reduction that runs before the kernels), so any finite factor is in
+                             range; ratings are not scaled and must stay below 65504 in magnitude.  The error of a
+                             product is a few 2^-22 of it, of the size of fp32 accumulation rounding: held to the
+                             tolerances of ALS_F32.  f <= 128, explicit feedback only                             */
     int32_t herm_dtype;   /* storage type of A_u where it is materialised, i.e. the partial Gram matrices of
                              rows split over several work items (Section 4.2): ALS_F32, or ALS_BF16 with
                              ALS_SOLVER_CG (fp32 accumulate, bf16 in memory; at f = 256 only together

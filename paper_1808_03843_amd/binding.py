@@ -16,7 +16,7 @@ from . import build as _build
 
 ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
 SOLVER_CHOLESKY, SOLVER_CG = 0, 1
-F32, BF16, F16, F32X3 = 0, 1, 2, 3
+F32, BF16, F16, F32X3, F32X2 = 0, 1, 2, 3, 4
 PEAK_MFMA_F32, PEAK_MFMA_BF16, PEAK_MFMA_F16, PEAK_COPY = 0, 1, 2, 3   # ids of als_measure_peak
 K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM = 0, 1, 2, 3, 4, 5
 
@@ -160,7 +160,7 @@ class Als:
             raise AlsError(rc, "als_create failed (unsupported f / solver / dtype, or no such device)")
         self.f = f
         self._plan_owner = {}
-        self.factor_torch_dtype = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16, F32X3: torch.float32}[factor_dtype]
+        self.factor_torch_dtype = {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16, F32X3: torch.float32, F32X2: torch.float32}[factor_dtype]
 
     def close(self):
         if getattr(self, "_ctx", None) is not None and self._ctx:

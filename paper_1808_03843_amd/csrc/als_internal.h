@@ -92,7 +92,7 @@ constexpr int kStatusStalePlan = 4;   // the row offsets of a matrix differ from
 
 // ---- launchers (each defined next to its kernels) --------------------------------------------
 // wide: the gathered factor matrix is 4 GiB or larger (64-bit lane addresses)
-// et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16; ALS_F32X3: fp32 in memory)
+// et: element type of the gathered factor matrix (ALS_F32 / ALS_BF16 / ALS_F16; ALS_F32X3: fp32 in memory; ALS_F32X2 has launchers of its own)
 // s16: slots hold bf16 tiles (slot_words16) instead of fp32 tiles (slot_floats)
 hipError_t launch_hermitian(int f, bool ptr64, bool wide, int et, bool s16, hipStream_t st, const int32_t *task_row,
                             const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks, int chunk, const void *ptr,
@@ -106,6 +106,18 @@ hipError_t launch_hermitian_x3(int f, bool ptr64, bool wide, bool s16, hipStream
 hipError_t launch_hermitian_cg_x3(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
                                   int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
                                   const void *Theta, float lambda, int fs, float eps, float *Xout, int *status);
+
+// factor_dtype = ALS_F32X2, f <= 128 (hermitian_x2.hip): as above with two fp16 parts.  absmax: DEVICE, one word,
+// the bits of max |Theta| (launch_absmax on the same stream, before these)
+hipError_t launch_absmax(hipStream_t st, const float *x, int64_t n, uint32_t *absmax);
+hipError_t launch_hermitian_x2(int f, bool ptr64, bool wide, bool s16, hipStream_t st, const int32_t *task_row,
+                               const int32_t *task_chunk, const int32_t *task_order, int64_t task0, int64_t ntasks,
+                               int chunk, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                               float *slots, const uint32_t *absmax);
+hipError_t launch_hermitian_cg_x2(int f, bool ptr64, bool wide, int solver, hipStream_t st, const int32_t *perm,
+                                  int64_t pos0, int64_t npos, const void *ptr, const int32_t *idx, const float *val,
+                                  const void *Theta, float lambda, int fs, float eps, float *Xout, int *status,
+                                  const uint32_t *absmax);
 
 // solver: ALS_SOLVER_CG or ALS_SOLVER_CHOLESKY
 hipError_t launch_hermitian_cg(int f, bool ptr64, bool wide, int et, int solver, hipStream_t st, const int32_t *perm,

@@ -20,7 +20,8 @@ bool needs_wide_offsets(int64_t rows, int f, size_t esize) {
     if ((uint64_t)rows * pitch >= (1ull << 32)) return true;
     return (pitch & (pitch - 1)) != 0 && rows >= (1 << 24);
 }
-size_t factor_bytes(int factor_dtype) { return (factor_dtype == ALS_F32 || factor_dtype == ALS_F32X3) ? 4 : 2; }
+bool fp32_in_memory(int factor_dtype) { return factor_dtype == ALS_F32 || factor_dtype == ALS_F32X3 || factor_dtype == ALS_F32X2; }
+size_t factor_bytes(int factor_dtype) { return fp32_in_memory(factor_dtype) ? 4 : 2; }
 constexpr int kPlanClasses = 24;
 constexpr int kMaxPlans = 4;
 
@@ -95,6 +96,7 @@ struct als_ctx {
     unsigned long long *fp_now = nullptr;   // DEVICE: fingerprint of the row offsets of the current call (zero between calls),
                                             // followed by the 32-bit count of finished workgroups (fp_done)
     unsigned int *fp_done = nullptr;
+    uint32_t *absmax = nullptr;  // DEVICE: bits of max |gathered factor| of the current update (factor_dtype ALS_F32X2)
     double *sse_partial = nullptr;
     size_t sse_partial_bytes = 0;
     double *sse_total = nullptr; // DEVICE
@@ -455,6 +457,9 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
     // rows go through slots
     const int64_t slot_rows = p->split_pos;
     const int32_t *order = kTaskOrder ? p->task_order : nullptr;
+    const bool x2 = ctx->cfg.factor_dtype == ALS_F32X2;
+    if (x2 && !implicit)   // the power-of-two scale of the two-part route follows max |G|
+        HIP_TRY(ctx, launch_absmax(ctx->stream, static_cast<const float *>(G), a->ncols * (int64_t)f, ctx->absmax));
     int64_t pos = 0;
     while (pos < slot_rows) {
         // rows [pos, end): as many as fit in `cap` slots, at least one row
@@ -468,6 +473,9 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                 HIP_TRY(ctx, launch_hermitian_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->stream, p->task_row, p->task_chunk, order, task0,
                                                        ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G, alpha,
                                                        ctx->slots));
+            else if (x2)
+                HIP_TRY(ctx, launch_hermitian_x2(f, p64, wide, s16, ctx->stream, p->task_row, p->task_chunk, order, task0,
+                                                 ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G, ctx->slots, ctx->absmax));
             else
                 HIP_TRY(ctx, launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, s16, ctx->stream, p->task_row,
                                               p->task_chunk, order, task0, ntasks, ctx->cfg.chunk, a->ptr, a->idx, a->val, G,
@@ -507,7 +515,7 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
             if (lo < fused_end) {
                 rc = in_pieces(lo, fused_end - lo, max_workgroups(64), [&](int64_t pos0, int64_t npos) {
-                    HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, ctx->cfg.factor_dtype == ALS_F32X3 ? ALS_F32 : ctx->cfg.factor_dtype, ctx->stream, p->perm, pos0, npos, a->ptr,
+                    HIP_TRY(ctx, launch_dual_exact(f, ntd, p64, fp32_in_memory(ctx->cfg.factor_dtype) ? ALS_F32 : ctx->cfg.factor_dtype, ctx->stream, p->perm, pos0, npos, a->ptr,
                                                    a->idx, a->val, G, lambda, Out, ctx->status));
                     return (int)ALS_OK;
                 });
@@ -523,6 +531,10 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
                 HIP_TRY(ctx, launch_hermitian_cg_implicit(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
                                                           pos0, npos, a->ptr, a->idx, a->val, G, lambda, alpha, gram,
                                                           ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
+            else if (x2)
+                HIP_TRY(ctx, launch_hermitian_cg_x2(f, p64, wide, ctx->cfg.solver, ctx->stream, p->perm, pos0, npos, a->ptr,
+                                                    a->idx, a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out,
+                                                    ctx->status, ctx->absmax));
             else
                 HIP_TRY(ctx, launch_hermitian_cg(f, p64, wide, ctx->cfg.factor_dtype, ctx->cfg.solver, ctx->stream, p->perm,
                                                  pos0, npos, a->ptr, a->idx, a->val, G, lambda, ctx->cfg.cg_iters,
@@ -559,9 +571,10 @@ static bool resolve_config(const als_config *in, als_config *c) {
     if (c->solver != ALS_SOLVER_CHOLESKY && c->solver != ALS_SOLVER_CG) return false;
     if (c->solver == ALS_SOLVER_CG && c->cg_iters < 0) return false;
     if (c->factor_dtype != ALS_F32 && c->factor_dtype != ALS_BF16 && c->factor_dtype != ALS_F16 &&
-        c->factor_dtype != ALS_F32X3)
+        c->factor_dtype != ALS_F32X3 && c->factor_dtype != ALS_F32X2)
         return false;
-    if (c->factor_dtype == ALS_F32X3 && !single_wave_f(c->f)) return false;   // the three-part route exists for f <= 128
+    // the routes through 16-bit parts exist for f <= 128
+    if ((c->factor_dtype == ALS_F32X3 || c->factor_dtype == ALS_F32X2) && !single_wave_f(c->f)) return false;
     // reduced-precision storage of A_u only makes sense with the approximate solver; fp16 cannot hold the
     // sums of 10^5 squares that heavy rows reach, so bf16 is the reduced type
     if (c->herm_dtype != ALS_F32 &&
@@ -617,6 +630,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
         ctx->fp_now = reinterpret_cast<unsigned long long *>(fw + 32);   // fingerprint, then the counter
         ctx->sse_total = reinterpret_cast<double *>(fw + 64);
         ctx->gram_dot = reinterpret_cast<double *>(fw + 96);             // 3 doubles
+        ctx->absmax = reinterpret_cast<uint32_t *>(fw + 128);
         ctx->class_start_dev = reinterpret_cast<int32_t *>(fw + 256);    // kPlanClasses + 1 ints
         ctx->gram[0] = reinterpret_cast<float *>(w + L.gram0);
         ctx->gram[1] = reinterpret_cast<float *>(w + L.gram1);
@@ -632,7 +646,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
         ok = fill_zero(ctx->stream, fw, 256) == hipSuccess;   // status, flags, fingerprint and counter start at zero
     } else if (ok) {
         ok = hipMalloc(&ctx->status, sizeof(int)) == hipSuccess && hipMalloc(&ctx->sse_total, sizeof(double)) == hipSuccess &&
-             hipMalloc(&ctx->fp_now, 2 * sizeof(unsigned long long)) == hipSuccess &&
+             hipMalloc(&ctx->fp_now, 3 * sizeof(unsigned long long)) == hipSuccess &&   // + the word of absmax
              hipMemsetAsync(ctx->status, 0, sizeof(int), ctx->stream) == hipSuccess &&
              hipMemsetAsync(ctx->fp_now, 0, 2 * sizeof(unsigned long long), ctx->stream) == hipSuccess;
     }
@@ -643,6 +657,7 @@ int als_create(als_ctx **out, const als_config *cfg) {
         return ALS_EHIP;
     }
     ctx->fp_done = reinterpret_cast<unsigned int *>(ctx->fp_now + 1);
+    if (!fixed) ctx->absmax = reinterpret_cast<uint32_t *>(ctx->fp_now + 2);
     *out = ctx;
     return ALS_OK;
 }
@@ -854,8 +869,15 @@ static int als_hermitian_impl(als_ctx *ctx, const als_sparse *csr, const void *T
     if (rc != ALS_OK) { cleanup(); return rc; }
     {
         Timed t(ctx, ALS_K_HERMITIAN);
-        e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, false, ctx->stream, task_row, task_chunk, nullptr, 0, ntasks, ctx->cfg.chunk, csr->ptr, csr->idx,
-                             csr->val, Theta, ctx->slots);
+        if (ctx->cfg.factor_dtype == ALS_F32X2) {
+            e = launch_absmax(ctx->stream, static_cast<const float *>(Theta), csr->ncols * (int64_t)f, ctx->absmax);
+            if (e == hipSuccess)
+                e = launch_hermitian_x2(f, p64, wide, false, ctx->stream, task_row, task_chunk, nullptr, 0, ntasks,
+                                        ctx->cfg.chunk, csr->ptr, csr->idx, csr->val, Theta, ctx->slots, ctx->absmax);
+        } else {
+            e = launch_hermitian(f, p64, wide, ctx->cfg.factor_dtype, false, ctx->stream, task_row, task_chunk, nullptr, 0,
+                                 ntasks, ctx->cfg.chunk, csr->ptr, csr->idx, csr->val, Theta, ctx->slots);
+        }
     }
     if (e == hipSuccess)
         e = launch_export_dense(f, p64, ctx->stream, perm, task_off, 0, nrows, 0, csr->ptr, ctx->slots, lambda, row0,

@@ -22,6 +22,7 @@ constexpr int kDepthSlots = ALS_DEPTH_SLOTS, kDepthFused = ALS_DEPTH_FUSED;
 // (f = 128 with 16-bit inputs: the operand sets of 32 entries and the extra b_u tiles need the whole file)
 constexpr int fused_waves(int F, int ET = ALS_F32, int MODE = kExplicit) {
     if (ET == ALS_F32X3) return F <= 100 ? 2 : 1;   // three operand sets of 32 entries beside the accumulators
+    if (ET == ALS_F32X2) return F <= 100 ? 2 : 1;   // two operand sets (f = 128: 144 accumulator registers)
     if ((ET == ALS_BF16 || ET == ALS_F16) && MODE == kImplicit && F > 64) return 1;   // likewise: w * theta in three parts
     return F <= 100 ? ALS_FUSED_WAVES : (ET != ALS_F32 ? 1 : 2);
 }
@@ -35,6 +36,7 @@ constexpr bool use_tiles16(int F, int ET, int MODE) {
 // otherwise lands just above the register budget of two and then spreads out to one
 constexpr int slot_waves(int F, int ET, int MODE = kExplicit) {
     if (ET == ALS_F32X3) return F <= 100 ? 2 : 1;   // rows staged through LDS: two wavefronts fit
+    if (ET == ALS_F32X2) return F <= 100 ? 2 : 1;
     return (F == 100 && (ET == ALS_BF16 || ET == ALS_F16) && MODE == kExplicit) ? 2 : 1;
 }
 
@@ -52,7 +54,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
                                                   const int32_t *__restrict__ task_chunk, const int32_t *__restrict__ task_order, int64_t task0, int chunk,
                                                   const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                   const float *__restrict__ val, const void *__restrict__ Theta,
-                                                  float alpha, float *__restrict__ slots) {
+                                                  float alpha, float *__restrict__ slots,
+                                                  const uint32_t *__restrict__ absmax = nullptr) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F), SLOT = S16 ? slot_words16(F) : slot_floats(F);
     const int lane = threadIdx.x;
     // task_order (optional): the work item each workgroup of the launch takes (a permutation of the batch)
@@ -70,9 +73,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(slot_waves(F
 #pragma unroll
     for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     float b[NT];
-    if constexpr (ET == ALS_F32X3) {   // fp32 rows cut into three bf16 parts, 16-bit matrix cores (tiles_x3.h)
+    if constexpr (ET == ALS_F32X3 || ET == ALS_F32X2) {   // fp32 rows cut into 16-bit parts, 16-bit matrix cores (tiles_x3.h)
         __shared__ __attribute__((aligned(16))) uint32_t fifo[x3_fifo_words(F)];   // one wavefront per workgroup
-        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b, fifo);
+        // absmax (two-part route): the bits of max |Theta|, left by a reduction that ran before this launch
+        const uint32_t mx = ET == ALS_F32X2 ? __builtin_amdgcn_readfirstlane(absmax[0]) : 0u;
+        accumulate_tiles_x3<F, WIDE, true, rows_all(F), ET == ALS_F32X3 ? 3 : 2>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                   fifo, mx);
     }
     else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);
@@ -145,7 +151,8 @@ template <int F, typename PtrT, bool WIDE, int ET, int SOLVER, int MODE>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(F, ET, MODE), fused_waves(F, ET, MODE)))) void k_hermitian_cg(
     const int32_t *__restrict__ perm, int64_t pos0, const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
     const float *__restrict__ val, const void *__restrict__ Theta, float lambda, float alpha,
-    const float *__restrict__ gram, int fs, float eps, float *__restrict__ Xout, int *__restrict__ status) {
+    const float *__restrict__ gram, int fs, float eps, float *__restrict__ Xout, int *__restrict__ status,
+    const uint32_t *__restrict__ absmax = nullptr) {
     constexpr int NT = tiles_1d(F), NTILES = tiles_tri(F);
     const int lane = threadIdx.x;
     const int row = perm[pos0 + blockIdx.x];
@@ -164,9 +171,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(fused_waves(
         for (int q = 0; q < NTILES; ++q) acc[q] = (v4f){0.f, 0.f, 0.f, 0.f};
     }
     float b[NT];
-    if constexpr (ET == ALS_F32X3) {
+    if constexpr (ET == ALS_F32X3 || ET == ALS_F32X2) {
         __shared__ __attribute__((aligned(16))) uint32_t fifo[x3_fifo_words(F)];   // one wavefront per workgroup
-        accumulate_tiles_x3<F, WIDE, true>(idx, val, Theta, uniform64(s0), len, acc, b, fifo);
+        const uint32_t mx = ET == ALS_F32X2 ? __builtin_amdgcn_readfirstlane(absmax[0]) : 0u;
+        accumulate_tiles_x3<F, WIDE, true, rows_all(F), ET == ALS_F32X3 ? 3 : 2>(idx, val, Theta, uniform64(s0), len, acc, b,
+                                                                                   fifo, mx);
     }
     else if constexpr (use_tiles16(F, ET, MODE))
         accumulate_tiles16<F, WIDE, ET, true, rows_all(F), MODE>(idx, val, Theta, uniform64(s0), len, acc, b, alpha);

@@ -40,13 +40,34 @@ constexpr int x3_fifo_words(int F) { return 8 * 64 * (4 * loads16(F) + 2 * loads
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void global_void;
 
+// PARTS = 2 (factor_dtype = ALS_F32X2): the value is cut into two fp16 parts instead, h = fp16(s x) and
+// l = fp16(s x - h), both rounded to nearest, so |s x - (h + l)| <= 2^-22 |s x|; a product is the three fp16 products
+//     h*h' + h*l' + l*h'      (what is dropped, l*l', is below 2^-22 |x*y|)
+// on v_mfma_f32_16x16x32_f16: half the matrix-core work and well under half the cutting work of the three-part route,
+// at a representation error of the size of fp32 accumulation rounding instead of none.  fp16 has a narrow exponent
+// range, so the factor is scaled by a power of two s with 2^14 <= s * max|Theta| < 2^15 (absmax_bits: the bits of
+// max |Theta|, found by a reduction before the launch); the sums are scaled back exactly at the end.  The rating is
+// not scaled: |r_uv| must stay below 65504, and a rating that is no fp16 number carries an absolute error of up to
+// 2^-25 beside the relative 2^-22.
+//
 // Every wavefront of the kernel must call with its own fifo (x3_fifo_words(F) words, 16-byte aligned).
-template <int F, bool WIDE, bool WANT_B, uint32_t ROWS = rows_all(F)>
+template <int F, bool WIDE, bool WANT_B, uint32_t ROWS = rows_all(F), int PARTS = 3>
 __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ idx, const float *__restrict__ val,
                                                         const void *__restrict__ Theta, int64_t s0, int len,
                                                         v4f (&acc)[tiles_in(ROWS)], float (&b)[tiles_1d(F)],
-                                                        uint32_t *fifo) {
+                                                        uint32_t *fifo, uint32_t absmax_bits = 0u) {
     static_assert(ROWS == rows_all(F) || (F % 16) == 0, "partial sets of tile rows need f to be a multiple of 16");
+    static_assert(PARTS == 2 || PARTS == 3, "two fp16 parts or three bf16 parts");
+    constexpr int PT = PARTS == 3 ? ALS_BF16 : ALS_F16;   // element type of the parts
+    // the power-of-two scale of the two-part route (uniform: scalar registers)
+    float scale = 1.f, inv_scale = 1.f;
+    if constexpr (PARTS == 2) {
+        const uint32_t e = (absmax_bits >> 23) & 0xffu;
+        uint32_t se = (e == 0u || e == 255u) ? 127u : 268u - e;   // s * max in [2^14, 2^15)
+        se = se > 187u ? 187u : se;                               // (a factor of all-tiny values: s stays at 2^60)
+        scale = bits_to_float(se << 23);
+        inv_scale = bits_to_float((254u - se) << 23);
+    }
     constexpr int NT = tiles_1d(F), RI = F % 16;
     constexpr bool BX = RI == 0;   // the rating parts are an operand of their own
     constexpr int N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
@@ -141,21 +162,36 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
 #pragma unroll
     for (int T = 0; T < (BX ? NT : 1); ++T) bt[T] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    v4u h[NT], m[NT], l[NT], gr;
+    typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    auto round_pair = [](float a, float c) -> v2h { return __builtin_convertvector((v2f){a, c}, v2h); };   // to nearest
+    v4u h[NT], m[PARTS == 3 ? NT : 1], l[NT], gr;
     // tile T, entry pair pr: the two fp32 values -> three packed part pairs.  ok0 / ok1: entry inside the work item
     auto cut = [&](auto ttag, int pr, float x0, float x1, const float (&r)[8], bool ok0, bool ok1, auto lasttag) {
         constexpr int T = decltype(ttag)::value;
         if constexpr (!BX && T == NT - 1) {   // the rating lane and the zero lanes of the last tile
-            x0 = is_feat ? x0 : ((WANT_B && is_rating) ? r[2 * pr] : 0.f);
-            x1 = is_feat ? x1 : ((WANT_B && is_rating) ? r[2 * pr + 1] : 0.f);
+            // (two parts: r / s here, so that the scaling below gives the rating back exactly; applied here and not
+            // where the rating is loaded, which would make the load wait)
+            const float rs0 = PARTS == 2 ? r[2 * pr] * inv_scale : r[2 * pr];
+            const float rs1 = PARTS == 2 ? r[2 * pr + 1] * inv_scale : r[2 * pr + 1];
+            x0 = is_feat ? x0 : ((WANT_B && is_rating) ? rs0 : 0.f);
+            x1 = is_feat ? x1 : ((WANT_B && is_rating) ? rs1 : 0.f);
         }
         if constexpr (decltype(lasttag)::value) {
             x0 = ok0 ? x0 : 0.f;
             x1 = ok1 ? x1 : 0.f;
         }
-        h[T][pr] = split16<ALS_BF16>(x0, x1);
-        m[T][pr] = split16<ALS_BF16>(x0, x1);
-        l[T][pr] = split16<ALS_BF16>(x0, x1);
+        if constexpr (PARTS == 3) {
+            h[T][pr] = split16<ALS_BF16>(x0, x1);
+            m[T][pr] = split16<ALS_BF16>(x0, x1);
+            l[T][pr] = split16<ALS_BF16>(x0, x1);
+        } else {
+            x0 *= scale;
+            x1 *= scale;
+            const v2h hh = round_pair(x0, x1);
+            h[T][pr] = __builtin_bit_cast(uint32_t, hh);
+            l[T][pr] = __builtin_bit_cast(uint32_t, round_pair(x0 - (float)hh.x, x1 - (float)hh.y));
+        }
     };
     // reads a region back, one entry pair at a time, and cuts its tiles into parts
     auto read_group = [&](auto gtag, const float (&r)[8], int t, auto lasttag) {
@@ -199,14 +235,21 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
 #pragma unroll
             for (int pr = 0; pr < 4; ++pr) {
                 float r0 = r[2 * pr], r1 = r[2 * pr + 1];
-                const uint32_t p0 = split16<ALS_BF16>(r0, r1);
-                const uint32_t p1 = split16<ALS_BF16>(r0, r1);
-                const uint32_t p2 = split16<ALS_BF16>(r0, r1);
-                gr[pr] = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
+                if constexpr (PARTS == 3) {
+                    const uint32_t p0 = split16<ALS_BF16>(r0, r1);
+                    const uint32_t p1 = split16<ALS_BF16>(r0, r1);
+                    const uint32_t p2 = split16<ALS_BF16>(r0, r1);
+                    gr[pr] = is_r0 ? p0 : (is_r1 ? p1 : (is_r2 ? p2 : 0u));
+                } else {   // (the rating itself: this operand is not scaled)
+                    const v2h hh = round_pair(r0, r1);
+                    const uint32_t p0 = __builtin_bit_cast(uint32_t, hh);
+                    const uint32_t p1 = __builtin_bit_cast(uint32_t, round_pair(r0 - (float)hh.x, r1 - (float)hh.y));
+                    gr[pr] = is_r0 ? p0 : (is_r1 ? p1 : 0u);
+                }
             }
         }
     };
-    // the MFMAs of the tile rows [R0, R1): six per tile
+    // the MFMAs of the tile rows [R0, R1): six per tile (three with two parts)
     auto rows_mfma = [&](auto r0tag, auto r1tag) {
         constexpr int R0 = decltype(r0tag)::value, R1 = decltype(r1tag)::value;
 #pragma unroll
@@ -215,17 +258,19 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
 #pragma unroll
                 for (int C = 0; C <= R; ++C) {
                     v4f &a = acc[tiles_below(ROWS, R) + C];
-                    mfma_16x16x32<ALS_BF16>(a, h[R], l[C]);
-                    mfma_16x16x32<ALS_BF16>(a, l[R], h[C]);
-                    mfma_16x16x32<ALS_BF16>(a, m[R], m[C]);
-                    mfma_16x16x32<ALS_BF16>(a, h[R], m[C]);
-                    mfma_16x16x32<ALS_BF16>(a, m[R], h[C]);
-                    mfma_16x16x32<ALS_BF16>(a, h[R], h[C]);
+                    mfma_16x16x32<PT>(a, h[R], l[C]);
+                    mfma_16x16x32<PT>(a, l[R], h[C]);
+                    if constexpr (PARTS == 3) {
+                        mfma_16x16x32<PT>(a, m[R], m[C]);
+                        mfma_16x16x32<PT>(a, h[R], m[C]);
+                        mfma_16x16x32<PT>(a, m[R], h[C]);
+                    }
+                    mfma_16x16x32<PT>(a, h[R], h[C]);
                 }
                 if constexpr (BX && WANT_B) {
-                    mfma_16x16x32<ALS_BF16>(bt[R], gr, l[R]);
-                    mfma_16x16x32<ALS_BF16>(bt[R], gr, m[R]);
-                    mfma_16x16x32<ALS_BF16>(bt[R], gr, h[R]);
+                    mfma_16x16x32<PT>(bt[R], gr, l[R]);
+                    if constexpr (PARTS == 3) mfma_16x16x32<PT>(bt[R], gr, m[R]);
+                    mfma_16x16x32<PT>(bt[R], gr, h[R]);
                 }
             }
     };
@@ -280,12 +325,20 @@ __device__ __forceinline__ void accumulate_tiles_x3(const int32_t *__restrict__ 
             float s = 0.f;
             if constexpr (BX) {
 #pragma unroll
-                for (int k = 0; k < 3; ++k) s += bperm(4 * c, bt[T][k]);   // rows 0..2: lane row 0, registers 0..2
+                for (int k = 0; k < PARTS; ++k) s += bperm(4 * c, bt[T][k]);   // rows 0..2: lane row 0, registers 0..2
             } else {
                 s = bperm(4 * (16 * (RI / 4) + c), acc[LB + T][RI % 4]);   // row RI: lane row RI/4, register RI%4
             }
+            if constexpr (PARTS == 2) s *= inv_scale;   // sum of r * (s theta)
             b[T] = (((ROWS >> T) & 1u) && (BX || T < NT - 1 || c < RI)) ? s : 0.f;
         }
+    }
+    if constexpr (PARTS == 2) {   // sums of (s theta)(s theta'): back to the caller's scale, exactly
+        const float inv2 = inv_scale * inv_scale;
+#pragma unroll
+        for (int q = 0; q < tiles_in(ROWS); ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[q][r] *= inv2;
     }
     if constexpr (!BX) {
 #pragma unroll

@@ -41,7 +41,7 @@ def _run(P, lib, mat, f, solver, chunk, mode, dtype):
     Theta = torch.from_numpy(W.random_factors(N_COLS, f, seed=57 + f, scale=0.3)).cuda()
     warm = torch.from_numpy(W.random_factors(len(degrees), f, seed=58 + f, scale=0.05)).cuda()
     sp = P.SparseMatrix.from_host(len(degrees), N_COLS, ptr, idx, val)
-    code, tdt = {"f32": (P.F32, torch.float32), "bf16": (P.BF16, torch.bfloat16), "f32x3": (P.F32X3, torch.float32)}[dtype]
+    code, tdt = {"f32": (P.F32, torch.float32), "bf16": (P.BF16, torch.bfloat16), "f32x3": (P.F32X3, torch.float32), "f32x2": (P.F32X2, torch.float32)}[dtype]
     als = P.Als(f, solver=P.SOLVER_CHOLESKY if solver == "cholesky" else P.SOLVER_CG, cg_iters=5, chunk=chunk,
                 factor_dtype=code, library=lib)
     X = warm.clone()
@@ -57,8 +57,8 @@ def _run(P, lib, mat, f, solver, chunk, mode, dtype):
 
 GRID = [(f, solver, chunk, mode, dtype)
         for f in (16, 32, 64, 100, 128, 256) for solver in ("cholesky", "cg") for chunk in (0, 64)
-        for mode, dtype in (("explicit", "f32"), ("implicit", "f32"), ("explicit", "bf16"), ("explicit", "f32x3"))
-        if not (dtype == "f32x3" and f == 256)]     # the three-part route exists for f <= 128
+        for mode, dtype in (("explicit", "f32"), ("implicit", "f32"), ("explicit", "bf16"), ("explicit", "f32x3"), ("explicit", "f32x2"))
+        if not (dtype in ("f32x3", "f32x2") and f == 256)]     # the three-part route exists for f <= 128
 
 
 @pytest.mark.parametrize("f,solver,chunk,mode,dtype", GRID)

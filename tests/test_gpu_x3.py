@@ -1,5 +1,6 @@
-"""factor_dtype = F32X3: fp32 factors multiplied on the 16-bit matrix cores as three bf16 parts (six products).
-The mode claims fp32 accuracy, so it is held to the bars of the fp32 path: A_u and b_u element by element, the exact
+"""factor_dtype = F32X3 / F32X2: fp32 factors multiplied on the 16-bit matrix cores as three bf16 parts (six products)
+or, scaled by a power of two, as two fp16 parts (three products).
+Both modes claim the accuracy of the fp32 path, so they are held to its bars: A_u and b_u element by element, the exact
 solver at 1e-4 per row, Algorithm 1 against its double-precision run, the stored Mid trajectory."""
 import numpy as np
 import pytest
@@ -25,8 +26,16 @@ def P():
     return pkg
 
 
+MODES = ["f32x3", "f32x2"]
+
+
+def _code(P, mode):
+    return {"f32x3": P.F32X3, "f32x2": P.F32X2}[mode]
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
-def test_hermitian_and_bias_from_three_bf16_parts(P, f):
+def test_hermitian_and_bias_from_16_bit_parts(P, f, mode):
     """A_u and b_u against the oracle: degrees around the step size (32) and the chunk size, ratings and factors that
     use all 24 significant bits, values of very different magnitude in one row."""
     n = 5000
@@ -38,7 +47,7 @@ def test_hermitian_and_bias_from_three_bf16_parts(P, f):
     Theta = W.random_factors(n, f, seed=5, scale=0.5)
     Theta[::7] *= np.float32(1e-3)        # rows of small magnitude next to ordinary ones
     Theta[3::11] *= np.float32(250.0)
-    als = P.Als(f, chunk=256, factor_dtype=P.F32X3)
+    als = P.Als(f, chunk=256, factor_dtype=_code(P, mode))
     sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
     A, b = als.hermitian(sp, _dev(Theta), 0.05, 0, len(degrees))
     A, b = A.cpu().numpy(), b.cpu().numpy()
@@ -52,7 +61,7 @@ def test_hermitian_and_bias_from_three_bf16_parts(P, f):
         assert np.array_equal(A[u], A[u].T)
         if d:
             worst = max(worst, np.abs(A[u] - Ao).max() / np.abs(Ao).max())
-    print(f"f={f}: worst |dA| / max|A| = {worst:.2e}")
+    print(f"{mode} f={f}: worst |dA| / max|A| = {worst:.2e}")
     als.close()
 
 
@@ -67,9 +76,10 @@ def _matrix(seed, ncols):
     return degrees, ptr, idx, val
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("f,solver,chunk,p64", [(f, s, c, p) for f in (16, 32, 64, 100, 128) for s in ("cholesky", "cg")
                                                 for c, p in ((0, False), (256, True), (64, False))])
-def test_half_sweep_with_three_part_inputs(P, f, solver, chunk, p64):
+def test_half_sweep_with_inputs_in_16_bit_parts(P, f, solver, chunk, p64, mode):
     """Every kernel the mode dispatches to (fused rows, slot rows, both solvers, both offset widths), rows from empty
     to split over several work items, against the oracle at the bars of the fp32 path."""
     ncols, lam = 4000, 0.3
@@ -78,7 +88,7 @@ def test_half_sweep_with_three_part_inputs(P, f, solver, chunk, p64):
     warm = W.random_factors(len(degrees), f, seed=48 + f, scale=0.05)
     sp = P.SparseMatrix.from_host(len(degrees), ncols, ptr, idx, val, ptr64=p64)
     code = P.SOLVER_CHOLESKY if solver == "cholesky" else P.SOLVER_CG
-    als = P.Als(f, solver=code, cg_iters=5, chunk=chunk, factor_dtype=P.F32X3)
+    als = P.Als(f, solver=code, cg_iters=5, chunk=chunk, factor_dtype=_code(P, mode))
     X = _dev(warm.copy())
     als.update_rows(sp, _dev(Theta), lam, X)
     als.synchronize()
@@ -95,13 +105,14 @@ def test_half_sweep_with_three_part_inputs(P, f, solver, chunk, p64):
     assert err[1:].max() <= tol, (int(err[1:].argmax()) + 1, float(err.max()))
 
 
-def test_one_exact_sweep_on_mid_small_with_three_part_inputs(P):
+@pytest.mark.parametrize("mode", MODES)
+def test_one_exact_sweep_on_mid_small_with_inputs_in_16_bit_parts(P, mode):
     """A whole exact sweep (rows, then columns from the oracle's X) of the reduced Mid shape at 1e-4 per row."""
     w = W.MID_SMALL
     a = W.generate(w)
     c = W.transpose(a)
     X0, T0 = W.init_factors(w)
-    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY, factor_dtype=P.F32X3)
+    als = P.Als(w.f, solver=P.SOLVER_CHOLESKY, factor_dtype=_code(P, mode))
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
     csc = P.SparseMatrix.from_host(c.nrows, c.ncols, c.ptr, c.idx, c.val)
     X = torch.zeros((w.m, w.f), device="cuda:0")
@@ -112,13 +123,14 @@ def test_one_exact_sweep_on_mid_small_with_three_part_inputs(P):
     als.synchronize()
     To = oracle.update_rows(c.ptr, c.idx, c.val, Xo.astype(np.float32), w.lam)
     ex, et = _rel(X.cpu().numpy(), Xo), _rel(T.cpu().numpy(), To)
-    print(f"mid_small, three-part inputs: X max {ex.max():.2e}, Theta max {et.max():.2e}")
+    print(f"mid_small, {mode} inputs: X max {ex.max():.2e}, Theta max {et.max():.2e}")
     assert ex.max() <= 1e-4 and et.max() <= 1e-4
     als.close()
 
 
-def test_mid_ten_sweeps_with_three_part_inputs_follow_the_stored_oracle_trajectory(P):
-    """Mid at full size: the exact solver with three-part inputs follows the stored fp64 trajectory like the fp32 path
+@pytest.mark.parametrize("mode", MODES)
+def test_mid_ten_sweeps_with_inputs_in_16_bit_parts_follow_the_stored_oracle_trajectory(P, mode):
+    """Mid at full size: the exact solver with inputs in 16-bit parts follows the stored fp64 trajectory like the fp32 path
     (2e-5 relative per sweep, stored rows at 5e-4), and CG(6) ends within 2e-3 of the exact oracle's RMSE."""
     from test_gpu_full_size import _follow_trajectory, _golden
     gold = _golden("mid")
@@ -127,6 +139,29 @@ def test_mid_ten_sweeps_with_three_part_inputs_follow_the_stored_oracle_trajecto
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val)
     del a
     _follow_trajectory(P, w, gold, csr, [
-        ("exact, three-part inputs", dict(solver=P.SOLVER_CHOLESKY, factor_dtype=P.F32X3), None),
-        ("CG(6), three-part inputs", dict(solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.F32X3), None),
+        (f"exact, {mode} inputs", dict(solver=P.SOLVER_CHOLESKY, factor_dtype=_code(P, mode)), None),
+        (f"CG(6), {mode} inputs", dict(solver=P.SOLVER_CG, cg_iters=6, factor_dtype=_code(P, mode)), None),
     ])
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -40, 1e-6, 1.0, 3e4, 2.0 ** 50])
+def test_two_part_route_follows_the_magnitude_of_the_factor(P, scale):
+    """The two fp16 parts are cut after a power-of-two scaling found from max |Theta| on the device, so a factor matrix
+    of any magnitude gives the A_u of the fp32 path to the same relative accuracy (fp16 alone spans 6e-8 .. 65504)."""
+    f, n = 100, 3000
+    degrees = [1, 5, 40, 300, 1500]
+    rng = np.random.default_rng(3)
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    idx = np.concatenate([np.sort(rng.choice(n, d, replace=False)) for d in degrees]).astype(np.int32)
+    val = rng.integers(1, 6, size=int(ptr[-1])).astype(np.float32)
+    Theta = (W.random_factors(n, f, seed=9, scale=0.5).astype(np.float64) * scale).astype(np.float32)
+    als = P.Als(f, chunk=256, factor_dtype=P.F32X2)
+    sp = P.SparseMatrix.from_host(len(degrees), n, ptr, idx, val)
+    A, b = als.hermitian(sp, _dev(Theta), 0.0, 0, len(degrees))
+    A, b = A.cpu().numpy().astype(np.float64), b.cpu().numpy().astype(np.float64)
+    for u, d in enumerate(degrees):
+        s, e = ptr[u], ptr[u + 1]
+        Ao, bo = oracle.normal_eq(idx[s:e], val[s:e], Theta, 0.0)
+        assert np.abs(A[u] - Ao).max() <= 2e-6 * np.abs(Ao).max() * np.sqrt(d), (scale, d)
+        assert np.abs(b[u] - bo).max() <= 2e-6 * np.abs(bo).max() * np.sqrt(d), (scale, d)
+    als.close()

@@ -146,4 +146,5 @@ def test_create_refuses_a_workspace_that_is_too_small_or_misaligned():
 
 def test_three_part_inputs_are_refused_where_they_do_not_exist():
     assert _create(_cfg(f=256, factor_dtype=P.F32X3)) == EINVAL          # the route exists for f <= 128
-    assert _create(_cfg(f=100, factor_dtype=4)) == EINVAL                # no such element type
+    assert _create(_cfg(f=256, factor_dtype=P.F32X2)) == EINVAL
+    assert _create(_cfg(f=100, factor_dtype=5)) == EINVAL                # no such element type
