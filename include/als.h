@@ -217,7 +217,8 @@ int als_bin_rows(als_ctx *ctx, const als_sparse *csr, int nclass, int32_t *perm_
  * als_update_cols), rows ascending inside every column.  cptr_out: DEVICE,
  * ncols+1 offsets of the same width as csr->ptr; cidx_out / cval_out: DEVICE,
  * nnz entries.  Requires nnz < 2^32 (and 64-bit ptr from 2^31 on); allocates
- * about 16 bytes per entry of temporary device memory and waits for the result. */
+ * about 16 bytes per entry of temporary device memory (8 when the column ids
+ * fit into 11 bits) plus at most 130 MB of counters, and waits for the result. */
 int als_csr_to_csc(als_ctx *ctx, const als_sparse *csr, void *cptr_out, int32_t *cidx_out, float *cval_out);
 
 /* Waits for the stream and reports ALS_ENUMERIC if any kernel since the last

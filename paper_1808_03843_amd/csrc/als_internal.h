@@ -232,6 +232,10 @@ hipError_t plan_rank_order(hipStream_t st, const int32_t *key, int64_t first, in
 hipError_t plan_emit(bool ptr64, hipStream_t st, int64_t nrows, const void *ptr, const int32_t *perm, int chunk,
                      const int32_t *task_off, int32_t *task_row, int32_t *task_chunk);
 hipError_t fill_iota(hipStream_t st, int32_t *p, int64_t n, int32_t first);
+// data[0 .. n) -> its exclusive prefix sums, in place (DEVICE; unsigned 32-bit sums); scratch: DEVICE,
+// scan_scratch_ints(n) words
+size_t scan_scratch_ints(int64_t n);
+hipError_t exclusive_scan_u32(hipStream_t st, uint32_t *data, int64_t n, uint32_t *scratch);
 hipError_t fill_zero(hipStream_t st, void *p, int64_t n);   // n 32-bit words, by a kernel
 // validation of a matrix: bits ORed into *flags (DEVICE): 1 row offsets not 0 .. nnz ascending, 2 column id out of
 // range, 4 column ids of a row not strictly ascending.  check_idx needs offsets that passed check_ptr.

@@ -6,37 +6,37 @@
 
 namespace als {
 
-// ---- exclusive prefix sum of int32, in place ---------------------------------------------------
+// ---- exclusive prefix sum of 32-bit counts, in place (unsigned: sums up to 2^32 - 1) -----------------
 constexpr int kScanThreads = 256, kScanItems = 8, kScanBlock = kScanThreads * kScanItems;
 
-__global__ __launch_bounds__(kScanThreads) void k_scan_block(int32_t *__restrict__ data, int64_t n,
-                                                             int32_t *__restrict__ block_sums) {
-    __shared__ int32_t wave_tot[kScanThreads / 64];
+__global__ __launch_bounds__(kScanThreads) void k_scan_block(uint32_t *__restrict__ data, int64_t n,
+                                                             uint32_t *__restrict__ block_sums) {
+    __shared__ uint32_t wave_tot[kScanThreads / 64];
     const int64_t base = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
-    int32_t v[kScanItems];
-    int32_t sum = 0;
+    uint32_t v[kScanItems];
+    uint32_t sum = 0;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
-        v[q] = (base + q < n) ? data[base + q] : 0;
+        v[q] = (base + q < n) ? data[base + q] : 0u;
         sum += v[q];
     }
     // inclusive scan of `sum` across the wavefront
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int32_t inc = sum;
+    uint32_t inc = sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const int32_t t = __shfl_up(inc, o);
+        const uint32_t t = (uint32_t)__shfl_up((int)inc, o);
         if (lane >= o) inc += t;
     }
     if (lane == 63) wave_tot[w] = inc;
     __syncthreads();
-    int32_t woff = 0, total = 0;
+    uint32_t woff = 0, total = 0;
 #pragma unroll
     for (int q = 0; q < kScanThreads / 64; ++q) {
         if (q < w) woff += wave_tot[q];
         total += wave_tot[q];
     }
-    int32_t run = woff + inc - sum;
+    uint32_t run = woff + inc - sum;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q) {
         if (base + q < n) data[base + q] = run;
@@ -45,16 +45,16 @@ __global__ __launch_bounds__(kScanThreads) void k_scan_block(int32_t *__restrict
     if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(kScanThreads) void k_scan_add(int32_t *__restrict__ data, int64_t n,
-                                                           const int32_t *__restrict__ block_offsets) {
-    const int32_t off = block_offsets[blockIdx.x];
+__global__ __launch_bounds__(kScanThreads) void k_scan_add(uint32_t *__restrict__ data, int64_t n,
+                                                           const uint32_t *__restrict__ block_offsets) {
+    const uint32_t off = block_offsets[blockIdx.x];
     const int64_t base = (int64_t)blockIdx.x * kScanBlock + (int64_t)threadIdx.x * kScanItems;
 #pragma unroll
     for (int q = 0; q < kScanItems; ++q)
         if (base + q < n) data[base + q] += off;
 }
 
-static size_t scan_scratch_ints(int64_t n) {
+size_t scan_scratch_ints(int64_t n) {
     size_t total = 0;
     while (n > 1) {
         n = (n + kScanBlock - 1) / kScanBlock;
@@ -64,16 +64,21 @@ static size_t scan_scratch_ints(int64_t n) {
     return total + 1;
 }
 
-static hipError_t exclusive_scan(hipStream_t st, int32_t *data, int64_t n, int32_t *scratch) {
+hipError_t exclusive_scan_u32(hipStream_t st, uint32_t *data, int64_t n, uint32_t *scratch) {
     if (n <= 0) return hipSuccess;
     const int64_t nb = (n + kScanBlock - 1) / kScanBlock;
     hipLaunchKernelGGL(k_scan_block, dim3((unsigned)nb), dim3(kScanThreads), 0, st, data, n, scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || nb == 1) return e;
-    e = exclusive_scan(st, scratch, nb, scratch + nb);
+    e = exclusive_scan_u32(st, scratch, nb, scratch + nb);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_scan_add, dim3((unsigned)nb), dim3(kScanThreads), 0, st, data, n, scratch);
     return hipGetLastError();
+}
+
+// (the counts of the plans are non-negative int32: same bits)
+static hipError_t exclusive_scan(hipStream_t st, int32_t *data, int64_t n, int32_t *scratch) {
+    return exclusive_scan_u32(st, reinterpret_cast<uint32_t *>(data), n, reinterpret_cast<uint32_t *>(scratch));
 }
 
 size_t plan_scratch_bytes(int64_t nrows, int nclass) {

@@ -1,10 +1,10 @@
 // Compressed columns of R from its compressed rows: the CSC that "Update Theta" (eq. (3)) walks.
-// A stable radix sort of the stored entries by column id (rocPRIM, a library primitive for a step
-// that is not on the per-sweep path) keeps the rows of every column ascending, so the result is
-// the canonical CSC and is reproducible bit for bit.
+// A stable sort of the stored entries by column id keeps the rows of every column ascending, so the result is the
+// canonical CSC and is reproducible bit for bit.  The sort is a least-significant-digit radix sort of (column id,
+// position of the entry) pairs, one to three passes of up to 11 bits: per pass a digit histogram of every tile, one
+// prefix sum over (digit, tile), and a scatter in which one wavefront walks its tile in order and ranks equal digits
+// with ballots (no atomics whose order could matter).  Off the per-sweep path: once per matrix.
 #include <cstring>
-
-#include <rocprim/rocprim.hpp>
 
 #include "als_internal.h"
 
@@ -21,9 +21,61 @@ __device__ __forceinline__ int64_t row_of_entry(const PtrT *__restrict__ ptr, in
     return lo;
 }
 
-__global__ __launch_bounds__(256) void k_iota_u32(uint32_t *__restrict__ p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = (uint32_t)i;
+constexpr int kMaxDigitBits = 11;
+constexpr int64_t kMinTile = 2048;            // keys per tile, a power of two, doubled until ...
+constexpr int64_t kMaxCounts = 1ll << 25;     // ... (tiles x digits) stays below this many counters (128 MB)
+
+// counts[d * ntiles + t] = number of keys of tile t whose digit (bits shift .. shift+bits-1) is d
+__global__ __launch_bounds__(256) void k_digit_hist(const uint32_t *__restrict__ keys, int64_t n, int64_t tile, int shift,
+                                                    int bits, int64_t ntiles, uint32_t *__restrict__ counts) {
+    __shared__ uint32_t cnt[1 << kMaxDigitBits];
+    const int nd = 1 << bits;
+    for (int d = threadIdx.x; d < nd; d += 256) cnt[d] = 0u;
+    __syncthreads();
+    const int64_t t = blockIdx.x, lo = t * tile, hi = lo + tile < n ? lo + tile : n;
+    for (int64_t q = lo + threadIdx.x; q < hi; q += 256) atomicAdd(&cnt[(keys[q] >> shift) & (uint32_t)(nd - 1)], 1u);
+    __syncthreads();
+    for (int d = threadIdx.x; d < nd; d += 256) counts[(int64_t)d * ntiles + t] = cnt[d];
+}
+
+// One wavefront per tile.  offsets[d * ntiles + t]: where the keys of tile t with digit d start in the output (the
+// prefix sums of the counts).  The wavefront takes its keys 64 at a time, in order; lanes with the same digit find
+// each other with one ballot per digit bit, and the lower lanes of such a group come first: the pass is stable.
+// vals == nullptr: the value of a key is its position (first pass).
+__global__ __launch_bounds__(64) void k_digit_scatter(const uint32_t *__restrict__ keys, const uint32_t *__restrict__ vals,
+                                                      int64_t n, int64_t tile, int shift, int bits, int64_t ntiles,
+                                                      const uint32_t *__restrict__ offsets,
+                                                      uint32_t *__restrict__ keys_out, uint32_t *__restrict__ vals_out) {
+    __shared__ uint32_t next[1 << kMaxDigitBits];   // next free output position of every digit, for this tile
+    const int lane = threadIdx.x, nd = 1 << bits;
+    const int64_t t = blockIdx.x, lo = t * tile, hi = lo + tile < n ? lo + tile : n;
+    for (int d = lane; d < nd; d += 64) next[d] = offsets[(int64_t)d * ntiles + t];
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int64_t q0 = lo; q0 < hi; q0 += 64) {
+        const int64_t q = q0 + lane;
+        const bool ok = q < hi;
+        const uint32_t key = ok ? keys[q] : 0u;
+        const uint32_t val = ok ? (vals ? vals[q] : (uint32_t)q) : 0u;
+        const uint32_t d = (key >> shift) & (uint32_t)(nd - 1);
+        unsigned long long same = __ballot(ok);
+        for (int k = 0; k < bits; ++k) {
+            const bool bit = ((d >> k) & 1u) != 0u;
+            const unsigned long long m = __ballot(bit);
+            same &= bit ? m : ~m;
+        }
+        // (one wavefront: its LDS reads and writes are performed in program order, so every lane of a group has read
+        // next[d] before the first lane of the group moves it on)
+        uint32_t base = 0u;
+        if (ok) base = next[d];
+        const uint32_t rank = (uint32_t)__popcll(same & below);
+        if (ok) {
+            keys_out[base + rank] = key;
+            vals_out[base + rank] = val;
+            if (rank == 0u) next[d] = base + (uint32_t)__popcll(same);
+        }
+        __syncthreads();   // (a single wavefront: orders the LDS write above before the next round's reads)
+    }
 }
 
 template <typename PtrT>
@@ -54,34 +106,43 @@ __global__ __launch_bounds__(256) void k_column_starts(const uint32_t *__restric
 template <typename PtrT>
 static hipError_t transpose_t(hipStream_t st, int64_t nrows, int64_t ncols, int64_t nnz, const PtrT *ptr,
                               const int32_t *idx, const float *val, PtrT *cptr, int32_t *cidx, float *cval) {
-    hipError_t e;
-    uint32_t *keys_out = nullptr, *vals_in = nullptr, *vals_out = nullptr;
-    void *temp = nullptr;
-    size_t temp_bytes = 0;
-    unsigned end_bit = 1;
-    while (end_bit < 32 && (1ll << end_bit) < ncols) ++end_bit;
-    const uint32_t *keys_in = reinterpret_cast<const uint32_t *>(idx);
+    hipError_t e = hipSuccess;
+    uint32_t *keys[2] = {nullptr, nullptr}, *vals[2] = {nullptr, nullptr}, *counts = nullptr;
     auto cleanup = [&]() {
-        (void)hipFree(keys_out); (void)hipFree(vals_in); (void)hipFree(vals_out); (void)hipFree(temp);
+        for (int k = 0; k < 2; ++k) { (void)hipFree(keys[k]); (void)hipFree(vals[k]); }
+        (void)hipFree(counts);
     };
+    int key_bits = 1;   // bits of the largest column id
+    while (key_bits < 32 && (1ll << key_bits) < ncols) ++key_bits;
+    const int npass = (key_bits + kMaxDigitBits - 1) / kMaxDigitBits, bits = (key_bits + npass - 1) / npass;
+    const uint32_t *sorted_cols = nullptr;
     if (nnz > 0) {
-        if ((e = hipMalloc(&keys_out, sizeof(uint32_t) * nnz)) != hipSuccess) { cleanup(); return e; }
-        if ((e = hipMalloc(&vals_in, sizeof(uint32_t) * nnz)) != hipSuccess) { cleanup(); return e; }
-        if ((e = hipMalloc(&vals_out, sizeof(uint32_t) * nnz)) != hipSuccess) { cleanup(); return e; }
-        e = rocprim::radix_sort_pairs(nullptr, temp_bytes, keys_in, keys_out, vals_in, vals_out, (size_t)nnz, 0u,
-                                      end_bit, st);
-        if (e != hipSuccess) { cleanup(); return e; }
-        if ((e = hipMalloc(&temp, temp_bytes ? temp_bytes : 16)) != hipSuccess) { cleanup(); return e; }
-        const unsigned nb = (unsigned)((nnz + 255) / 256);
-        hipLaunchKernelGGL(k_iota_u32, dim3(nb), dim3(256), 0, st, vals_in, nnz);
-        e = rocprim::radix_sort_pairs(temp, temp_bytes, keys_in, keys_out, vals_in, vals_out, (size_t)nnz, 0u,
-                                      end_bit, st);
-        if (e != hipSuccess) { cleanup(); return e; }
-        hipLaunchKernelGGL((k_gather_entries<PtrT>), dim3(nb), dim3(256), 0, st, ptr, nrows, nnz, vals_out, val,
+        int64_t tile = kMinTile;
+        while ((((nnz + tile - 1) / tile) << bits) > kMaxCounts) tile *= 2;
+        const int64_t ntiles = (nnz + tile - 1) / tile, ncount = ntiles << bits;
+        for (int k = 0; k < (npass > 1 ? 2 : 1); ++k) {
+            if ((e = hipMalloc(&keys[k], sizeof(uint32_t) * nnz)) != hipSuccess) { cleanup(); return e; }
+            if ((e = hipMalloc(&vals[k], sizeof(uint32_t) * nnz)) != hipSuccess) { cleanup(); return e; }
+        }
+        if ((e = hipMalloc(&counts, sizeof(uint32_t) * (ncount + scan_scratch_ints(ncount)))) != hipSuccess) { cleanup(); return e; }
+        const uint32_t *kin = reinterpret_cast<const uint32_t *>(idx), *vin = nullptr;   // first pass: value = position
+        for (int p = 0; p < npass; ++p) {
+            uint32_t *kout = keys[p & 1], *vout = vals[p & 1];
+            hipLaunchKernelGGL(k_digit_hist, dim3((unsigned)ntiles), dim3(256), 0, st, kin, nnz, tile, p * bits, bits, ntiles, counts);
+            if ((e = hipGetLastError()) != hipSuccess) { cleanup(); return e; }
+            if ((e = exclusive_scan_u32(st, counts, ncount, counts + ncount)) != hipSuccess) { cleanup(); return e; }
+            hipLaunchKernelGGL(k_digit_scatter, dim3((unsigned)ntiles), dim3(64), 0, st, kin, vin, nnz, tile, p * bits, bits, ntiles,
+                               counts, kout, vout);
+            if ((e = hipGetLastError()) != hipSuccess) { cleanup(); return e; }
+            kin = kout;
+            vin = vout;
+        }
+        sorted_cols = kin;
+        hipLaunchKernelGGL((k_gather_entries<PtrT>), dim3((unsigned)((nnz + 255) / 256)), dim3(256), 0, st, ptr, nrows, nnz, vin, val,
                            cidx, cval);
     }
     hipLaunchKernelGGL((k_column_starts<PtrT>), dim3((unsigned)((ncols + 1 + 255) / 256)), dim3(256), 0, st,
-                       keys_out, nnz, ncols, cptr);
+                       sorted_cols, nnz, ncols, cptr);
     e = hipGetLastError();
     hipError_t e2 = hipStreamSynchronize(st);  // the temporaries are freed below
     cleanup();

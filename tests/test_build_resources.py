@@ -28,7 +28,7 @@ def test_build_refuses_a_kernel_that_spills(tmp_path):
 
 
 def test_no_kernel_spills_or_uses_scratch(res):
-    # the library's own kernels (namespace als); rocPRIM's sort kernels use a little scratch by design
+    # every kernel of the library lives in namespace als
     bad = {k: v for k, v in res.items() if k.startswith("_ZN3als") and (v["spill"] or v["scratch"])}
     assert not bad, bad
 
