@@ -269,7 +269,8 @@ def test_large_square_five_sweeps_follow_the_stored_oracle_trajectory():
     """Large-square at full size (1,000,990 x 624,961, 252.8M entries, ratings 0..100, lambda = 1): the exact mode
     follows the stored fp64 trajectory (tests/golden/large_square_trajectory.json, written by the oracle alone) sweep
     by sweep, and CG(6) -- the mode this configuration names -- ends within 2e-3 of the exact oracle's training RMSE
-    after the 5 sweeps, with fp32 and with bf16 factor inputs (fp32 accumulate)."""
+    after the 5 sweeps, with fp32 and with bf16 factor inputs (fp32 accumulate); the routes through 16-bit parts of fp32
+    factors are held to the same bars."""
     import paper_1808_03843_amd as P
     gold = _golden("large_square")
     assert gold is not None
@@ -281,6 +282,11 @@ def test_large_square_five_sweeps_follow_the_stored_oracle_trajectory():
         ("exact", dict(solver=P.SOLVER_CHOLESKY), None),
         ("CG(6)", dict(solver=P.SOLVER_CG, cg_iters=6), None),
         ("CG(6) bf16 inputs", dict(solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.BF16), torch.bfloat16),
+        # fp32 factors on the 16-bit matrix cores (ratings up to 100: the rating operand of the two-part route is not
+        # scaled): the exact solver is held to the stored trajectory like the fp32 path
+        ("exact, three bf16 parts", dict(solver=P.SOLVER_CHOLESKY, factor_dtype=P.F32X3), None),
+        ("exact, two fp16 parts", dict(solver=P.SOLVER_CHOLESKY, factor_dtype=P.F32X2), None),
+        ("CG(6), two fp16 parts", dict(solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.F32X2), None),
     ])
 
 

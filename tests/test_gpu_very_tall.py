@@ -167,4 +167,29 @@ def _very_tall(P, _sub_csr, _rel):
         r16 = rh
     ah.synchronize()
     ah.close()
+    # fp32 factors on the 16-bit matrix cores (two fp16 parts after a power-of-two scaling): the sampled rows against
+    # double-precision Algorithm 1 at the bar of the fp32 path, then one timed sweep.  The column side gathers the
+    # 20 GB X with 64-bit row addresses.
+    a2 = P.Als(w.f, solver=P.SOLVER_CG, cg_iters=6, factor_dtype=P.F32X2)
+    T2 = torch.from_numpy(Ts_host).to(dev)
+    Xb = X.clone()
+    Xb[sel] = torch.from_numpy(warm_rows).to(dev)
+    a2.update_rows(csr, T2, w.lam, Xb)
+    a2.synchronize()
+    ref = oracle.update_rows_cg(sptr, sidx, sval, Ts_host, w.lam, warm_rows, fs=6)
+    err = _rel(Xb[sel].cpu().numpy(), ref)
+    print(f"very_tall rows, two fp16 parts: {len(rows)} sampled, CG(6) vs double Algorithm 1 max {err.max():.2e}", flush=True)
+    assert err.max() <= 2e-3
+    del Xb, T2
+    torch.cuda.synchronize()
+    t0 = time.time()
+    a2.update_rows(csr, T, w.lam, X)
+    a2.update_cols(csc, X, w.lam, T)
+    torch.cuda.synchronize()
+    dt = time.time() - t0
+    r2 = als.rmse(csr, X, T)
+    print(f"very_tall sweep 8 (two fp16 parts): {dt:.3f} s, training rmse {r2:.5f}", flush=True)
+    assert r2 < r16 + 2e-3
+    a2.synchronize()
+    a2.close()
     als.close()
