@@ -107,7 +107,10 @@ def main():
     ap.add_argument("--solver", default="cg", choices=["cg", "cholesky"])
     ap.add_argument("--herm-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage of the partial Gram matrices that go through slots (Section 4.2); bf16 needs --solver cg")
-    ap.add_argument("--no-reduced", action="store_true", help="skip the extra timing with bf16 factor inputs")
+    ap.add_argument("--no-reduced", action="store_true", help="skip the extra timings in the other input modes")
+    ap.add_argument("--dense-short-rows", action="store_true",
+                    help="rows with fewer than 64 entries build A_u too (the paper's route for every row) instead of "
+                         "running Algorithm 1 on their gathered rows")
     ap.add_argument("--test-frac", type=float, default=0.0,
                     help="hold out this fraction of the entries (seeded), fit on the rest and report the held-out RMSE "
                          "per sweep and the time to come within 0.2 %% of its best value (protocol of Section 5.2)")
@@ -161,7 +164,8 @@ def main():
     ftorch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16, "f32x3": torch.float32, "f32x2": torch.float32}[args.factor_dtype]
     in_fp32 = args.factor_dtype in ("f32", "f32x3", "f32x2")   # the gathered factor is the fp32 matrix itself
     als = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
-                profile=True, factor_dtype=fcode, herm_dtype=P.BF16 if args.herm_dtype == "bf16" else P.F32)
+                profile=True, factor_dtype=fcode, herm_dtype=P.BF16 if args.herm_dtype == "bf16" else P.F32,
+                dense_short_rows=args.dense_short_rows)
     csr = P.SparseMatrix.from_host(a.nrows, a.ncols, a.ptr, a.idx, a.val, device=dev)
     csc = als.csr_to_csc(csr)
     X0, T0 = W.init_factors(w)
@@ -191,6 +195,7 @@ def main():
     fused_ms, fused_n = als.kernel_time(P.K_FUSED)
     solve_ms, solve_n = als.kernel_time(P.K_SOLVE)
     gram_ms, gram_n = als.kernel_time(P.K_GRAM)
+    short_ms, short_n = als.kernel_time(P.K_SHORT)
     als.synchronize()
     ev = P.Als(w.f, profile=True)
     ev.rmse(csr, X, T)                       # first call builds the plan of the matrix
@@ -203,7 +208,7 @@ def main():
     K = args.steps
     log(f"[bench] {K} sweeps in {elapsed:.3f} s; rmse {rmse:.5f}; per sweep: k_hermitian {herm_ms / K:.2f} ms "
         f"({herm_n // K} launches), k_hermitian_cg {fused_ms / K:.2f} ms ({fused_n // K}), "
-        f"slot solve {solve_ms / K:.2f} ms ({solve_n // K}); rmse kernel {rmse_ms:.2f} ms ({rmse_gbps:.0f} GB/s gathered)"
+        f"k_cg_gathered {short_ms / K:.2f} ms ({short_n // K}), slot solve {solve_ms / K:.2f} ms ({solve_n // K}); rmse kernel {rmse_ms:.2f} ms ({rmse_gbps:.0f} GB/s gathered)"
         + (f", gram {gram_ms / K:.2f} ms ({gram_n // K}); implicit cost {als.implicit_loss(csr, X, T, w.lam, args.implicit):.6e}"
            if args.implicit is not None else ""))
 
@@ -214,9 +219,13 @@ def main():
     deg_r = np.diff(a.ptr)
     deg_c = np.bincount(a.idx, minlength=w.n)
     nnz_fit = int(a.nnz)   # entries the factors are fitted on (all of them unless --test-frac)
-    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if fused_n > 0 else 2 * nnz_fit
+    nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if (fused_n > 0 or short_n > 0) else 2 * nnz_fit
+    # rows with fewer than 64 entries run Algorithm 1 on their gathered rows and never form A_u (k_cg_gathered): their
+    # entries are no get_hermitian work and are left out of its flops
+    short_rows = int((deg_r < 64).sum() + (deg_c < 64).sum()) if short_n > 0 else 0
+    nnz_short = int(deg_r[deg_r < 64].sum() + deg_c[deg_c < 64].sum()) if short_n > 0 else 0
     per_entry = w.f * (w.f + 1)
-    flops_sweep = 2.0 * nnz_fit * per_entry
+    flops_sweep = (2.0 * nnz_fit - nnz_short) * per_entry
     herm_s = (herm_ms + fused_ms) * 1e-3 / K
     achieved = flops_sweep / herm_s / 1e12          # all get_hermitian launches of a sweep together
     launches = (herm_n + fused_n) // K
@@ -225,7 +234,7 @@ def main():
     for name, what, ms, n, entries in (
             ("k_hermitian", "get_hermitian of the work items of rows with >= chunk entries, into slots", herm_ms, herm_n, nnz_slot),
             ("k_hermitian_cg", "get_hermitian fused with the solver (rows shorter than a chunk); its whole time is charged "
-                               "to get_hermitian", fused_ms, fused_n, 2 * nnz_fit - nnz_slot)):
+                               "to get_hermitian", fused_ms, fused_n, 2 * nnz_fit - nnz_slot - nnz_short)):
         if n <= 0:
             continue
         per_launch = entries / (n / K)
@@ -234,6 +243,16 @@ def main():
         kernels[name] = {"what": what, "tflops": tf, "frac": tf / PEAK_FP32_MFMA_TFLOPS, "ms_per_sweep": ms / K,
                          "launches_per_sweep": n // K, "avg_launch_ms": avg_ms, "entries_per_launch": per_launch,
                          "entries_per_sweep": entries}
+    short = None
+    if short_n > 0:
+        # Algorithm 1 on the gathered rows: per row (f_s + 1) products of 4 n_u f + 2 f flops and b_u (2 n_u f), on the
+        # vector ALUs
+        fl = (args.cg_iters + 1) * (4.0 * nnz_short * w.f + 2.0 * w.f * short_rows) + 2.0 * nnz_short * w.f
+        short = {"what": "Algorithm 1 on the gathered rows of rows with fewer than 64 entries, A_u never formed "
+                         "(A_u p = G^T (G p) + lambda n_u p)", "bound": "alu", "ms_per_sweep": short_ms / K,
+                 "launches_per_sweep": short_n // K, "rows_per_sweep": short_rows, "entries_per_sweep": nnz_short,
+                 "systems_per_s": short_rows / (short_ms / K * 1e-3), "tflops": fl / (short_ms / K * 1e-3) / 1e12,
+                 "frac_of_fp32_vector_peak": fl / (short_ms / K * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS}
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_sweep"])   # the kernel that takes most of the sweep
     d = kernels[dom]
     traffic, traffic_source = measured_traffic(w, args, chunk, dom)
@@ -248,7 +267,7 @@ def main():
                 "all_get_hermitian": {"achieved": achieved, "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                                       "ms_per_sweep": (herm_ms + fused_ms) / K, "launches_per_sweep": launches,
                                       "flops_per_sweep": flops_sweep},
-                **kernels}
+                **kernels, **({"k_cg_gathered": short} if short else {})}
     if args.factor_dtype in ("f32x3", "f32x2"):
         # fp32 values as 16-bit parts on the 16-bit matrix cores: the numerator stays the algorithmic flops of the
         # fp32 Gram matrix, the denominator is the peak of the instruction that runs, the 16-bit dense MFMA peak
@@ -314,6 +333,10 @@ def main():
         modes = [("bf16_factor_inputs", P.BF16, torch.bfloat16,
                   "gathered factor rounded to bf16 each half-sweep (conversion timed), v_mfma_f32_16x16x32_bf16 with fp32 "
                   "accumulate, fp32 solver and output")]
+        if solver == P.SOLVER_CG and w.f <= 128 and not args.dense_short_rows:
+            modes.append(("every_row_builds_A_u", P.F32, None,
+                          "dense_short_rows = 1: rows with fewer than 64 entries also go through get_hermitian and the "
+                          "dense Algorithm 1, as in the paper"))
         if w.f <= 128:
             modes.insert(0, ("f32x3_factor_inputs", P.F32X3, None,
                              "fp32 factor cut into three bf16 parts in registers, six products per pair on "
@@ -324,7 +347,7 @@ def main():
                              "of the fp32 path"))
         for key, code, tdt, note in modes:
             a2 = P.Als(w.f, solver=solver, cg_iters=args.cg_iters, chunk=args.chunk, batch_slots=args.batch_slots,
-                       factor_dtype=code)
+                       factor_dtype=code, dense_short_rows=key == "every_row_builds_A_u")
             X2, T2 = X.clone(), T.clone()
 
             def sweep2():

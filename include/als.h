@@ -115,6 +115,11 @@ typedef struct als_config {
     size_t workspace_bytes;
     int64_t workspace_max_rows;
     int64_t workspace_max_nnz;
+    int32_t dense_short_rows; /* 0 (default): with ALS_SOLVER_CG, explicit feedback and f <= 128, rows with fewer than
+                                 64 stored entries run Algorithm 1 on the gathered theta_v themselves,
+                                 A_u p = G^T (G p) + lambda n_u p, and never form A_u (2 n_u f instead of f^2
+                                 multiply-adds per product, no get_hermitian; the iterates differ from the dense
+                                 ones by rounding order only).  1: every row builds A_u, as in the paper         */
 } als_config;
 
 /* Bytes of workspace a context with this configuration needs for matrices of at most max_rows rows (the larger
@@ -257,7 +262,8 @@ int als_drop_plans(als_ctx *ctx);
 #define ALS_K_PLAN 3
 #define ALS_K_FUSED 4 /* get_hermitian and Algorithm 1 in one kernel (rows shorter than chunk, CG solver) */
 #define ALS_K_GRAM 5  /* Theta^T Theta of the implicit update (Section 5.6)                                   */
-#define ALS_K_COUNT 6
+#define ALS_K_SHORT 6 /* Algorithm 1 on the gathered rows, without A_u (rows with fewer than 64 entries)          */
+#define ALS_K_COUNT 7
 
 /* With config.profile = 1: total milliseconds and number of launches of one
  * kernel class since the last als_profile_reset, measured with HIP events on

@@ -18,7 +18,7 @@ ALS_OK, ALS_EINVAL, ALS_EHIP, ALS_ENUMERIC, ALS_ENOMEM = 0, -1, -2, -3, -4
 SOLVER_CHOLESKY, SOLVER_CG = 0, 1
 F32, BF16, F16, F32X3, F32X2 = 0, 1, 2, 3, 4
 PEAK_MFMA_F32, PEAK_MFMA_BF16, PEAK_MFMA_F16, PEAK_COPY = 0, 1, 2, 3   # ids of als_measure_peak
-K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM = 0, 1, 2, 3, 4, 5
+K_HERMITIAN, K_SOLVE, K_RMSE, K_PLAN, K_FUSED, K_GRAM, K_SHORT = 0, 1, 2, 3, 4, 5, 6
 
 EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
@@ -40,7 +40,8 @@ class AlsConfig(ctypes.Structure):
                 ("device", ctypes.c_int32), ("stream", ctypes.c_void_p), ("chunk", ctypes.c_int32),
                 ("batch_slots", ctypes.c_int64), ("profile", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
-                ("workspace_max_rows", ctypes.c_int64), ("workspace_max_nnz", ctypes.c_int64)]
+                ("workspace_max_rows", ctypes.c_int64), ("workspace_max_nnz", ctypes.c_int64),
+                ("dense_short_rows", ctypes.c_int32)]
 
 
 _lib = None
@@ -135,8 +136,10 @@ class Als:
     def __init__(self, f: int, solver: int = SOLVER_CHOLESKY, cg_iters: int = 6, cg_eps: float = 0.0,
                  device: int = 0, stream: Optional[int] = None, chunk: int = 0, batch_slots: int = 0,
                  profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32,
-                 workspace_rows: int = 0, workspace_nnz: int = 0, library: Optional[ctypes.CDLL] = None):
-        """workspace_rows / workspace_nnz > 0: the library works in a torch-allocated workspace sized for matrices of
+                 workspace_rows: int = 0, workspace_nnz: int = 0, library: Optional[ctypes.CDLL] = None,
+                 dense_short_rows: bool = False):
+        """dense_short_rows: rows with fewer than 64 entries also build A_u (see als_config in include/als.h).
+        workspace_rows / workspace_nnz > 0: the library works in a torch-allocated workspace sized for matrices of
         at most that many rows and stored entries, and allocates no device memory itself.
         library: another build of the library from load_library(path) (default: the in-tree build)."""
         self._lib = library if library is not None else load_library()
@@ -144,6 +147,7 @@ class Als:
             stream = torch.cuda.current_stream(device).cuda_stream
         self.cfg = AlsConfig(f, solver, cg_iters, cg_eps, factor_dtype, herm_dtype, device, stream, chunk, batch_slots,
                              1 if profile else 0)
+        self.cfg.dense_short_rows = 1 if dense_short_rows else 0
         self.workspace = None
         if workspace_rows > 0 or workspace_nnz > 0:
             need = self._lib.als_workspace_bytes(ctypes.byref(self.cfg), workspace_rows, workspace_nnz)

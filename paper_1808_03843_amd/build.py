@@ -13,7 +13,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 # tests/test_gpu_drained.py compares it with the production library bit for bit
 LIB_DRAINED = os.path.join(HERE, "libals_gfx950_drained.so")
 OBJ_DIR_DRAINED = os.path.join(HERE, "_build_drained")
-SOURCES = ["api.hip", "hermitian.hip", "hermitian_x3.hip", "hermitian_x2.hip", "wide.hip", "wide_ldlt.hip", "wide_ldlt_bf16.hip", "wide_ldlt_f16.hip", "wide_ldlt_implicit.hip", "implicit.hip", "implicit16.hip", "dual.hip", "solve.hip", "plan.hip", "metrics.hip", "transpose.hip", "peaks.hip"]
+SOURCES = ["api.hip", "hermitian.hip", "hermitian_x3.hip", "hermitian_x2.hip", "wide.hip", "wide_ldlt.hip", "wide_ldlt_bf16.hip", "wide_ldlt_f16.hip", "wide_ldlt_implicit.hip", "implicit.hip", "implicit16.hip", "dual.hip", "cg_short.hip", "solve.hip", "plan.hip", "metrics.hip", "transpose.hip", "peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -1,0 +1,225 @@
+// Algorithm 1 (CGSolve, Section 4.1) for rows with fewer than 64 stored entries, without forming A_u.
+// Algorithm 1 touches A_u only through the products A_u p, and with G the n_u x f matrix of the gathered theta_v
+//     A_u p = G^T (G p) + lambda n_u p            (eq. (2): A_u = sum theta_v theta_v^T + lambda n_u I),
+// 2 n_u f multiply-adds instead of f^2 -- and no get_hermitian at all (n_u f^2 multiply-adds) -- when G stays in
+// registers.  The paper always builds the f x f matrix; on Netflix-shaped data more than half of the rows have fewer
+// than 64 entries, and for those the build and the dense products are most of the work.  Same iteration, same
+// stopping rules and guards as cg_tiles (tiles.h); the products differ from the dense ones by rounding order only.
+//
+// One wavefront per row.  Lane (i, kq) holds, for the entries 4j + kq (j = 0 .. 15), the features that lane i holds
+// of every tile in the other kernels (feature_of: registers q = 0 .. NT-1), i.e. G[j][q]; vectors are in the column
+// layout of cg_tiles (register q of lane (i, kq) = v[feature_of(q, i)], the same in the four lane rows).
+//   t = G p:      per entry the lane's partial dot product, summed over the 16 lanes of its lane row;
+//   y = G^T t:    per feature the sum over the lane's entries, then over the four lane rows.
+// Steps j beyond the row's last entry are skipped (a wavefront-uniform branch), so the cost follows n_u.
+// 16-bit factor rows are widened on load: the products are those of the fp32 path on the rounded factor.
+#include "hermitian_kernels.h"
+
+namespace als {
+
+constexpr int kShortSteps = 16;   // steps of 4 entries: rows of up to 63 entries (degree classes below 7)
+
+// the features of lane i (all tiles) of row c of the factor matrix, as fp32
+template <int F, int ET>
+__device__ __forceinline__ void gather_lane_features(const void *__restrict__ Theta, int c, int i, float (&g)[tiles_1d(F)]) {
+    constexpr int NT = tiles_1d(F), N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
+    static_assert(4 * N4 + 2 * N2 + N1 == NT);
+    constexpr int ES = ET == ALS_F32 ? 4 : 2;
+    const char *row = reinterpret_cast<const char *>(Theta) + (int64_t)c * (F * ES);
+#pragma unroll
+    for (int q = 0; q < N4; ++q) {   // features 64q + 4i .. + 3
+        if constexpr (ET == ALS_F32) {
+            const v4f v = *reinterpret_cast<const v4f *>(row + 4 * (64 * q + 4 * i));
+            g[4 * q] = v[0]; g[4 * q + 1] = v[1]; g[4 * q + 2] = v[2]; g[4 * q + 3] = v[3];
+        } else {
+            const uint2 w = *reinterpret_cast<const uint2 *>(row + 2 * (64 * q + 4 * i));
+            g[4 * q] = widen_lo<ET>(w.x); g[4 * q + 1] = widen_hi<ET>(w.x);
+            g[4 * q + 2] = widen_lo<ET>(w.y); g[4 * q + 3] = widen_hi<ET>(w.y);
+        }
+    }
+    if constexpr (N2 > 0) {          // features 64 N4 + 2i, + 1
+        if constexpr (ET == ALS_F32) {
+            const float2 v = *reinterpret_cast<const float2 *>(row + 4 * (64 * N4 + 2 * i));
+            g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
+        } else {
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(row + 2 * (64 * N4 + 2 * i));
+            g[4 * N4] = widen_lo<ET>(w); g[4 * N4 + 1] = widen_hi<ET>(w);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {   // feature 64 N4 + 32 N2 + 16k + i, if there is one
+        const int ft = 64 * N4 + 32 * N2 + 16 * k + i;
+        float v = 0.f;
+        if (ft < F) {
+            if constexpr (ET == ALS_F32) v = *reinterpret_cast<const float *>(row + 4 * ft);
+            else v = widen_lo<ET>((uint32_t)*reinterpret_cast<const unsigned short *>(row + 2 * ft));
+        }
+        g[4 * N4 + 2 * N2 + k] = v;
+    }
+}
+
+template <int F, typename PtrT, int ET>
+__global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
+                                                    const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                    const float *__restrict__ val, const void *__restrict__ Theta,
+                                                    float lambda, int fs, float eps, float *__restrict__ Xout,
+                                                    int *__restrict__ status) {
+    constexpr int NT = tiles_1d(F), NJ = kShortSteps;
+    const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
+    const int row = perm[pos0 + blockIdx.x];
+    const int64_t s0 = (int64_t)ptr[row];
+    // fewer than 4 NJ by the caller's choice of rows; clamped so that a plan built from other row offsets cannot make
+    // the kernel read more than it holds
+    int n = (int)((int64_t)ptr[row + 1] - s0);
+    n = __builtin_amdgcn_readfirstlane(n < 0 ? 0 : (n > 4 * NJ ? 4 * NJ : n));
+    float *xg = Xout + (int64_t)row * F;
+    if (n == 0) {
+        store_zero_vec<F>(xg);
+        return;
+    }
+    const int nj = (n + 3) >> 2;   // steps that hold an entry
+
+    // the gathered rows and their ratings; entries beyond the end count as zero rows
+    float G[NJ][NT], rt[NJ];
+#pragma unroll
+    for (int j0 = 0; j0 < NJ; j0 += 4) {
+#pragma unroll
+        for (int j = j0; j < j0 + 4; ++j) {
+            rt[j] = 0.f;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) G[j][q] = 0.f;
+        }
+        if (j0 < nj) {   // four steps at a time: their loads are in flight together
+            int col[4];
+            bool ok[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int e = 4 * (j0 + d) + kq;
+                ok[d] = e < n;
+                const int64_t at = s0 + (ok[d] ? e : 0);
+                col[d] = idx[at];
+                rt[j0 + d] = ok[d] ? val[at] : 0.f;
+            }
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                float g[NT];
+                gather_lane_features<F, ET>(Theta, col[d], i, g);
+#pragma unroll
+                for (int q = 0; q < NT; ++q) G[j0 + d][q] = ok[d] ? g[q] : 0.f;
+            }
+        }
+    }
+
+    // b_u = G^T r_u (get_bias, Section 2 step (i))
+    float b[NT], x[NT];
+    {
+        float s[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) s[q] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            if (j < nj) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) s[q] = fmaf(rt[j], G[j][q], s[q]);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = colsum4(s[q]);
+    }
+    load_vec<F>(xg, x);   // warm start
+
+    const float reg = lambda * (float)n;
+    auto matvec = [&](const float (&p)[NT], float (&ap)[NT]) {
+        float y[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) y[q] = 0.f;
+#pragma unroll
+        for (int j0 = 0; j0 < NJ; j0 += 2)
+            if (j0 < nj) {   // (two steps per branch: a step without entries holds zeros)
+                float t[2];
+#pragma unroll
+                for (int d = 0; d < 2; ++d) {
+                    t[d] = 0.f;
+#pragma unroll
+                    for (int q = 0; q < NT; ++q) t[d] = fmaf(G[j0 + d][q], p[q], t[d]);
+                }
+#pragma unroll
+                for (int d = 0; d < 2; ++d) t[d] = rowsum16(t[d]);   // theta_v . p of entry 4j + kq
+#pragma unroll
+                for (int d = 0; d < 2; ++d)
+#pragma unroll
+                    for (int q = 0; q < NT; ++q) y[q] = fmaf(G[j0 + d][q], t[d], y[q]);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) ap[q] = fmaf(reg, p[q], colsum4(y[q]));
+    };
+    auto dot = [&](const float (&u)[NT], const float (&v)[NT]) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) s = fmaf(u[q], v[q], s);
+        return rowsum16(s);   // the 4 lane rows hold the same values
+    };
+
+    // Algorithm 1, as in cg_tiles
+    float r[NT], p[NT], ap[NT];
+    matvec(x, ap);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        r[q] = b[q] - ap[q];
+        p[q] = r[q];
+    }
+    float rs_old = dot(r, r);
+    if (rs_old > 0.f) {
+        for (int it = 0; it < fs; ++it) {
+            matvec(p, ap);
+            const float pap = dot(p, ap);
+            if (!(pap > 0.f) || !isfinite(pap)) break;
+            const float alpha = rs_old / pap;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                x[q] = fmaf(alpha, p[q], x[q]);
+                r[q] = fmaf(-alpha, ap[q], r[q]);
+            }
+            const float rs_new = dot(r, r);
+            if (sqrtf(rs_new) < eps) break;
+            const float beta = rs_new / rs_old;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) p[q] = fmaf(beta, p[q], r[q]);
+            rs_old = rs_new;
+        }
+    }
+    store_vec<F>(xg, x, status);
+}
+
+template <int F, typename PtrT>
+static hipError_t cg_gathered_f(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
+                                const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
+                                float *Xout, int *status) {
+    const dim3 grid((unsigned)npos), block(64);
+#define LAUNCH(E)                                                                                                        \
+    hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
+                       lambda, fs, eps, Xout, status)
+    if (et == ALS_F32) LAUNCH(ALS_F32); else if (et == ALS_BF16) LAUNCH(ALS_BF16); else LAUNCH(ALS_F16);
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_cg_gathered(int f, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+                              const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
+                              int fs, float eps, float *Xout, int *status) {
+    if (npos <= 0) return hipSuccess;
+    if (et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) return hipErrorInvalidValue;
+#define CALL(FF)                                                                                                       \
+    (ptr64 ? cg_gathered_f<FF, int64_t>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
+           : cg_gathered_f<FF, int32_t>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
+    switch (f) {
+        case 16: return CALL(16);
+        case 32: return CALL(32);
+        case 64: return CALL(64);
+        case 100: return CALL(100);
+        case 128: return CALL(128);
+        default: return hipErrorInvalidValue;
+    }
+#undef CALL
+}
+
+}  // namespace als

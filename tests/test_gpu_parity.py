@@ -783,10 +783,15 @@ def test_kernel_times_are_recorded_when_profiling_is_on(P):
     X = torch.zeros((w.m, w.f), device="cuda:0")
     als.update_rows(sp, _dev(T0), w.lam, X)
     als.rmse(sp, X, _dev(T0))
-    for kid in (P.K_HERMITIAN, P.K_SOLVE, P.K_FUSED, P.K_RMSE, P.K_PLAN):
+    # (chunk = 64: rows of 64 entries or more go through slots, every other row runs Algorithm 1 on its gathered rows)
+    for kid in (P.K_HERMITIAN, P.K_SOLVE, P.K_SHORT, P.K_RMSE, P.K_PLAN):
         ms, launches = als.kernel_time(kid)
         assert launches >= 1 and ms > 0.0, kid
-    assert als.kernel_time(P.K_GRAM) == (0.0, 0)
+    assert als.kernel_time(P.K_GRAM) == (0.0, 0) and als.kernel_time(P.K_FUSED) == (0.0, 0)
+    dense = P.Als(w.f, solver=P.SOLVER_CG, chunk=64, profile=True, dense_short_rows=True)   # every row builds A_u
+    dense.update_rows(sp, _dev(T0), w.lam, X)
+    assert dense.kernel_time(P.K_FUSED)[1] >= 1 and dense.kernel_time(P.K_SHORT) == (0.0, 0)
+    dense.close()
     als.profile_reset()
     assert als.kernel_time(P.K_HERMITIAN) == (0.0, 0)
     with pytest.raises(P.AlsError):
