@@ -17,7 +17,6 @@
 
 namespace als {
 
-constexpr int kShortSteps = 16;   // steps of 4 entries: rows of up to 63 entries (degree classes below 7)
 
 // the features of lane i (all tiles) of row c of the factor matrix, as fp32
 template <int F, int ET>
@@ -58,13 +57,16 @@ __device__ __forceinline__ void gather_lane_features(const void *__restrict__ Th
     }
 }
 
-template <int F, typename PtrT, int ET>
+// NJ: steps of 4 entries the wavefront holds (4, 8 or 16: rows with fewer than 16, 32, 64 entries).  The shorter
+// variants need fewer registers, so more wavefronts share a SIMD and hide the chain of dependent loads (row id, row
+// offsets, column ids, factor rows) that a row of a dozen entries mostly consists of.
+template <int F, typename PtrT, int ET, int NJ>
 __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
                                                     const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                     const float *__restrict__ val, const void *__restrict__ Theta,
                                                     float lambda, int fs, float eps, float *__restrict__ Xout,
                                                     int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F), NJ = kShortSteps;
+    constexpr int NT = tiles_1d(F);
     const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
     const int row = perm[pos0 + blockIdx.x];
     const int64_t s0 = (int64_t)ptr[row];
@@ -79,33 +81,37 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
     }
     const int nj = (n + 3) >> 2;   // steps that hold an entry
 
+    // Column ids and ratings: lane l fetches those of entry l (one coalesced load each), then every lane picks up
+    // those of its own entries 4j + kq through the LDS crossbar -- one memory round trip for the whole row, so that the
+    // gathers below can all be in flight together (loads complete in order: a second round of id loads behind the
+    // first gathers would wait for them).
+    const bool mine = lane < n;
+    const int64_t at = s0 + (mine ? lane : 0);
+    const int my_col = idx[at];                      // (entries beyond the end: the row's first column, masked below)
+    const float my_r = mine ? val[at] : 0.f;
     // the gathered rows and their ratings; entries beyond the end count as zero rows
     float G[NJ][NT], rt[NJ];
+    int col[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int src = 4 * (4 * j + kq);            // byte address of lane 4j + kq
+        col[j] = __builtin_amdgcn_ds_bpermute(src, my_col);
+        rt[j] = bperm(src, my_r);
+    }
 #pragma unroll
     for (int j0 = 0; j0 < NJ; j0 += 4) {
 #pragma unroll
-        for (int j = j0; j < j0 + 4; ++j) {
-            rt[j] = 0.f;
+        for (int j = j0; j < j0 + 4; ++j)
 #pragma unroll
             for (int q = 0; q < NT; ++q) G[j][q] = 0.f;
-        }
-        if (j0 < nj) {   // four steps at a time: their loads are in flight together
-            int col[4];
-            bool ok[4];
+        if (j0 < nj) {   // (four steps per branch)
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                const int e = 4 * (j0 + d) + kq;
-                ok[d] = e < n;
-                const int64_t at = s0 + (ok[d] ? e : 0);
-                col[d] = idx[at];
-                rt[j0 + d] = ok[d] ? val[at] : 0.f;
-            }
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
+                const bool ok = 4 * (j0 + d) + kq < n;
                 float g[NT];
-                gather_lane_features<F, ET>(Theta, col[d], i, g);
+                gather_lane_features<F, ET>(Theta, col[j0 + d], i, g);
 #pragma unroll
-                for (int q = 0; q < NT; ++q) G[j0 + d][q] = ok[d] ? g[q] : 0.f;
+                for (int q = 0; q < NT; ++q) G[j0 + d][q] = ok ? g[q] : 0.f;
             }
         }
     }
@@ -190,27 +196,28 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
     store_vec<F>(xg, x, status);
 }
 
-template <int F, typename PtrT>
+template <int F, typename PtrT, int NJ>
 static hipError_t cg_gathered_f(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
                                 const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
                                 float *Xout, int *status) {
     const dim3 grid((unsigned)npos), block(64);
 #define LAUNCH(E)                                                                                                        \
-    hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
+    hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E, NJ>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
                        lambda, fs, eps, Xout, status)
     if (et == ALS_F32) LAUNCH(ALS_F32); else if (et == ALS_BF16) LAUNCH(ALS_BF16); else LAUNCH(ALS_F16);
 #undef LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_cg_gathered(int f, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
+hipError_t launch_cg_gathered(int f, int steps, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
                               const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
                               int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    if (et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) return hipErrorInvalidValue;
-#define CALL(FF)                                                                                                       \
-    (ptr64 ? cg_gathered_f<FF, int64_t>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status) \
-           : cg_gathered_f<FF, int32_t>(et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status))
+    if ((et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) || (steps != 4 && steps != 8 && steps != 16)) return hipErrorInvalidValue;
+#define ARGS et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status
+#define CALL_P(FF, PP) \
+    (steps == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : steps == 8 ? cg_gathered_f<FF, PP, 8>(ARGS) : cg_gathered_f<FF, PP, 16>(ARGS))
+#define CALL(FF) (ptr64 ? CALL_P(FF, int64_t) : CALL_P(FF, int32_t))
     switch (f) {
         case 16: return CALL(16);
         case 32: return CALL(32);
@@ -220,6 +227,8 @@ hipError_t launch_cg_gathered(int f, bool ptr64, int et, hipStream_t st, const i
         default: return hipErrorInvalidValue;
     }
 #undef CALL
+#undef CALL_P
+#undef ARGS
 }
 
 }  // namespace als
