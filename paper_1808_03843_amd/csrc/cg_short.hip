@@ -57,16 +57,15 @@ __device__ __forceinline__ void gather_lane_features(const void *__restrict__ Th
     }
 }
 
-// NJ: steps of 4 entries the wavefront holds (4, 8 or 16: rows with fewer than 16, 32, 64 entries).  The shorter
-// variants need fewer registers, so more wavefronts share a SIMD and hide the chain of dependent loads (row id, row
-// offsets, column ids, factor rows) that a row of a dozen entries mostly consists of.
-template <int F, typename PtrT, int ET, int NJ>
+constexpr int kShortSteps = 16;   // steps the registers of a wavefront hold
+
+template <int F, typename PtrT, int ET>
 __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
                                                     const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                     const float *__restrict__ val, const void *__restrict__ Theta,
                                                     float lambda, int fs, float eps, float *__restrict__ Xout,
                                                     int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F);
+    constexpr int NT = tiles_1d(F), NJ = kShortSteps;
     const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
     const int row = perm[pos0 + blockIdx.x];
     const int64_t s0 = (int64_t)ptr[row];
@@ -196,27 +195,194 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
     store_vec<F>(xg, x, status);
 }
 
-template <int F, typename PtrT, int NJ>
+// The same for rows of fewer than 64 / R entries, R = 2 or 4 of them per wavefront: a row of a dozen entries leaves
+// most of a wavefront's lanes idle in the steps above, and what does not depend on n_u (the reductions over the lane
+// rows, the dot products, the vector updates, the divisions: about 110 of the vector instructions of an iteration)
+// is then paid once per R rows.  Row slot rs = kq / (4 / R) of the wavefront takes row pos0 + R * blockIdx + rs
+// (none beyond pos_end); its 4 / R lane rows hold the entries (4 / R) j + kq % (4 / R), j = 0 .. 15.  Everything that
+// is wavefront-uniform above (n_u, the row's pointers, lambda n_u, the scalars of Algorithm 1, its stopping tests) is
+// a per-lane value here, the same in the lanes of a row slot; a row that has stopped keeps its x (select), the loop
+// ends when every row of the wavefront has stopped.
+template <int F, typename PtrT, int ET, int R>
+__global__ __launch_bounds__(64) void k_cg_gathered_packed(const int32_t *__restrict__ perm, int64_t pos0, int64_t pos_end,
+                                                           const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                           const float *__restrict__ val, const void *__restrict__ Theta,
+                                                           float lambda, int fs, float eps, float *__restrict__ Xout,
+                                                           int *__restrict__ status) {
+    static_assert(R == 2 || R == 4);
+    constexpr int NT = tiles_1d(F), NJ = kShortSteps, EPS = 4 / R, CAP = NJ * EPS;   // entries per step and per row
+    const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
+    const int rs = kq / EPS, sub = kq % EPS;
+    const int64_t pos = pos0 + (int64_t)R * blockIdx.x + rs;
+    const bool valid = pos < pos_end;
+    const int row = perm[valid ? pos : pos0];
+    const int64_t s0 = (int64_t)ptr[row];
+    int n = (int)((int64_t)ptr[row + 1] - s0);   // fewer than CAP by the caller's choice of rows (clamped: see above)
+    n = !valid ? 0 : (n < 0 ? 0 : (n > CAP ? CAP : n));
+    float *xg = Xout + (int64_t)row * F;
+    // steps that hold an entry of some row of the wavefront (uniform)
+    int nmax = 0;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+        const int nk = __builtin_amdgcn_readlane(n, 16 * EPS * k);
+        nmax = nk > nmax ? nk : nmax;
+    }
+    const int nj = (nmax + EPS - 1) / EPS;
+
+    // column ids and ratings: lane l of a row slot fetches those of entry l of its row, then every lane picks up those
+    // of its own entries
+    const int lr = lane - 16 * EPS * rs;             // lane within the row slot, 0 .. 16 EPS - 1
+    const bool mine = lr < n;
+    const int64_t at = s0 + (mine ? lr : 0);
+    const int my_col = (valid && n > 0) ? idx[at] : 0;   // (no entry: row 0 of the factor, masked below)
+    const float my_r = mine ? val[at] : 0.f;
+    float G[NJ][NT], rt[NJ];
+    int col[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int src = 4 * (16 * EPS * rs + EPS * j + sub);
+        col[j] = __builtin_amdgcn_ds_bpermute(src, my_col);
+        rt[j] = bperm(src, my_r);
+    }
+#pragma unroll
+    for (int j0 = 0; j0 < NJ; j0 += 4) {
+#pragma unroll
+        for (int j = j0; j < j0 + 4; ++j)
+#pragma unroll
+            for (int q = 0; q < NT; ++q) G[j][q] = 0.f;
+        if (j0 < nj) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const bool ok = EPS * (j0 + d) + sub < n;
+                float g[NT];
+                gather_lane_features<F, ET>(Theta, col[j0 + d], i, g);
+#pragma unroll
+                for (int q = 0; q < NT; ++q) G[j0 + d][q] = ok ? g[q] : 0.f;
+            }
+        }
+    }
+    // sum over the lane rows of a row slot (R = 4: one lane row, nothing to add)
+    auto slotsum = [&](float v) { return R == 2 ? v + __shfl_xor(v, 16) : v; };
+
+    float b[NT], x[NT];
+    {
+        float s[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) s[q] = 0.f;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            if (j < nj) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) s[q] = fmaf(rt[j], G[j][q], s[q]);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) b[q] = slotsum(s[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {   // warm start; a row without entries gets x = 0
+        const int ft = feature_of(F, q, i);
+        x[q] = (ft >= 0 && n > 0) ? xg[ft] : 0.f;
+    }
+
+    const float reg = lambda * (float)n;
+    auto matvec = [&](const float (&p)[NT], float (&ap)[NT]) {
+        float y[NT];
+#pragma unroll
+        for (int q = 0; q < NT; ++q) y[q] = 0.f;
+#pragma unroll
+        for (int j0 = 0; j0 < NJ; j0 += 2)
+            if (j0 < nj) {
+                float t[2];
+#pragma unroll
+                for (int d = 0; d < 2; ++d) {
+                    t[d] = 0.f;
+#pragma unroll
+                    for (int q = 0; q < NT; ++q) t[d] = fmaf(G[j0 + d][q], p[q], t[d]);
+                }
+#pragma unroll
+                for (int d = 0; d < 2; ++d) t[d] = rowsum16(t[d]);
+#pragma unroll
+                for (int d = 0; d < 2; ++d)
+#pragma unroll
+                    for (int q = 0; q < NT; ++q) y[q] = fmaf(G[j0 + d][q], t[d], y[q]);
+            }
+#pragma unroll
+        for (int q = 0; q < NT; ++q) ap[q] = fmaf(reg, p[q], slotsum(y[q]));
+    };
+    auto dot = [&](const float (&u)[NT], const float (&v)[NT]) {
+        float s = 0.f;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) s = fmaf(u[q], v[q], s);
+        return rowsum16(s);   // the lane rows of a row slot hold the same values
+    };
+
+    // Algorithm 1 with per-row stopping
+    float r[NT], p[NT], ap[NT];
+    matvec(x, ap);
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        r[q] = b[q] - ap[q];
+        p[q] = r[q];
+    }
+    float rs_old = dot(r, r);
+    bool live = n > 0 && rs_old > 0.f;
+    for (int it = 0; it < fs; ++it) {
+        if (__ballot(live) == 0ull) break;
+        matvec(p, ap);
+        const float pap = dot(p, ap);
+        live = live && pap > 0.f && isfinite(pap);
+        const float alpha = live ? rs_old / pap : 0.f;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            x[q] = live ? fmaf(alpha, p[q], x[q]) : x[q];
+            r[q] = fmaf(-alpha, ap[q], r[q]);
+        }
+        const float rs_new = dot(r, r);
+        live = live && !(sqrtf(rs_new) < eps);
+        const float beta = live ? rs_new / rs_old : 0.f;
+#pragma unroll
+        for (int q = 0; q < NT; ++q) p[q] = fmaf(beta, p[q], r[q]);
+        rs_old = live ? rs_new : rs_old;
+    }
+    bool bad = false;
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        const int ft = feature_of(F, q, i);
+        if (valid && sub == 0 && ft >= 0) {
+            xg[ft] = x[q];
+            bad |= !isfinite(x[q]);
+        }
+    }
+    if (bad) atomicOr(status, kStatusNonFinite);
+}
+
+// rows: rows per wavefront (1, 2, 4)
+template <int F, typename PtrT, int ROWS>
 static hipError_t cg_gathered_f(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
                                 const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
                                 float *Xout, int *status) {
-    const dim3 grid((unsigned)npos), block(64);
-#define LAUNCH(E)                                                                                                        \
-    hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E, NJ>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
-                       lambda, fs, eps, Xout, status)
-    if (et == ALS_F32) LAUNCH(ALS_F32); else if (et == ALS_BF16) LAUNCH(ALS_BF16); else LAUNCH(ALS_F16);
+    const dim3 grid((unsigned)((npos + ROWS - 1) / ROWS)), block(64);
+#define LAUNCH(E)                                                                                                           \
+    if constexpr (ROWS == 1)                                                                                                \
+        hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
+                           lambda, fs, eps, Xout, status);                                                                  \
+    else                                                                                                                    \
+        hipLaunchKernelGGL((k_cg_gathered_packed<F, PtrT, E, ROWS>), grid, block, 0, st, perm, pos0, pos0 + npos,           \
+                           (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status)
+    if (et == ALS_F32) { LAUNCH(ALS_F32); } else if (et == ALS_BF16) { LAUNCH(ALS_BF16); } else { LAUNCH(ALS_F16); }
 #undef LAUNCH
     return hipGetLastError();
 }
 
-hipError_t launch_cg_gathered(int f, int steps, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
-                              const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
-                              int fs, float eps, float *Xout, int *status) {
+hipError_t launch_cg_gathered(int f, int rows_per_wave, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0,
+                              int64_t npos, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
+                              float lambda, int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    if ((et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) || (steps != 4 && steps != 8 && steps != 16)) return hipErrorInvalidValue;
+    if ((et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) || (rows_per_wave != 1 && rows_per_wave != 2 && rows_per_wave != 4))
+        return hipErrorInvalidValue;
 #define ARGS et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status
 #define CALL_P(FF, PP) \
-    (steps == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : steps == 8 ? cg_gathered_f<FF, PP, 8>(ARGS) : cg_gathered_f<FF, PP, 16>(ARGS))
+    (rows_per_wave == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : rows_per_wave == 2 ? cg_gathered_f<FF, PP, 2>(ARGS) : cg_gathered_f<FF, PP, 1>(ARGS))
 #define CALL(FF) (ptr64 ? CALL_P(FF, int64_t) : CALL_P(FF, int32_t))
     switch (f) {
         case 16: return CALL(16);
