@@ -2,9 +2,11 @@
 // In implicit mode (Section 5.6) the per-entry term is c (p - d)^2 - d^2 with d = x_u^T theta_v,
 // p = [r > 0], c = 1 + alpha max(r, 0): the part of the all-pairs cost that depends on the stored entries.
 // One wavefront per work item (the same row chunks as the update), 4 stored entries per step with
-// 16 lanes sharing one dot product; fp32 dots, fp64 accumulation of the squared errors, per-item
-// partial sums added in item order by a single block (deterministic).
-#include "als_internal.h"
+// 16 lanes sharing one dot product (each lane fetches its features of a theta row with one 16-, one 8- and one 4-byte
+// load, as in the update kernels); the rows of four steps are in flight together and the column ids of the next four
+// arrive meanwhile; fp32 dots, fp64 accumulation of the squared errors, per-item partial sums added in item order by
+// a single block (deterministic).
+#include "tiles.h"
 
 namespace als {
 
@@ -15,7 +17,7 @@ __global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row
                                             const float *__restrict__ val, const float *__restrict__ X,
                                             const float *__restrict__ Theta, float alpha,
                                             double *__restrict__ partial) {
-    constexpr int NT = tiles_1d(F);
+    constexpr int NT = tiles_1d(F), G = 4;   // G steps of 4 entries are in flight together
     const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
     const int64_t t = blockIdx.x;
     const int row = task_row[t];
@@ -24,31 +26,53 @@ __global__ __launch_bounds__(64) void k_sse(const int32_t *__restrict__ task_row
     const int64_t s0 = rs + (int64_t)ch * chunk;
     const int64_t s1 = (s0 + chunk < re) ? s0 + chunk : re;
     const int len = s1 > s0 ? (int)(s1 - s0) : 0;   // >= 1 with the plan of this matrix; 0 reads nothing
+    // x_u with the lane -> feature map of the gathers (16-, 8- and 4-byte loads per lane)
     float xr[NT];
 #pragma unroll
-    for (int q = 0; q < NT; ++q) xr[q] = (16 * q + i < F) ? X[(int64_t)row * F + 16 * q + i] : 0.f;
-    double acc = 0.0;
-    for (int e0 = 0; e0 < len; e0 += 4) {
-        const int e = e0 + kq;
-        const bool ok = e < len;
-        const int c = idx[s0 + (ok ? e : len - 1)];
-        const float r = val[s0 + (ok ? e : len - 1)];
-        const float *p = Theta + (int64_t)c * F;
-        float d = 0.f;
+    for (int q = 0; q < NT; ++q) {
+        const int ft = feature_of(F, q, i);
+        xr[q] = ft >= 0 ? X[(int64_t)row * F + ft] : 0.f;
+    }
+    // column ids and ratings of a group of 16 entries: step d of the group holds entry 4d + kq
+    auto load_entries = [&](int e0, int (&c)[G], float (&r)[G]) {
 #pragma unroll
-        for (int q = 0; q < NT; ++q) {
-            const int feat = 16 * q + i;
-            d = fmaf(xr[q], p[feat < F ? feat : F - 1], d);
+        for (int d = 0; d < G; ++d) {
+            const int e = e0 + 4 * d + kq;
+            const int64_t at = s0 + (e < len ? e : len - 1);
+            c[d] = idx[at];
+            r[d] = val[at];
+        }
+    };
+    double acc = 0.0;
+    int cn[G];
+    float rn[G];
+    if (len > 0) load_entries(0, cn, rn);
+    for (int e0 = 0; e0 < len; e0 += 4 * G) {
+        int c[G];
+        float r[G], g[G][NT];
+#pragma unroll
+        for (int d = 0; d < G; ++d) {
+            c[d] = cn[d];
+            r[d] = rn[d];
         }
 #pragma unroll
-        for (int o = 1; o < 16; o <<= 1) d += __shfl_xor(d, o);
-        if constexpr (MODE == kImplicit) {
-            const double rp = r > 0.f ? (double)r : 0.0, dd = (double)d;
-            const double pe = (r > 0.f ? 1.0 : 0.0) - dd;
-            if (ok && i == 0) acc += (1.0 + (double)alpha * rp) * pe * pe - dd * dd;
-        } else {
-            const float err = r - d;
-            if (ok && i == 0) acc += (double)err * (double)err;
+        for (int d = 0; d < G; ++d) gather_lane_features<F, ALS_F32>(Theta, c[d], i, g[d]);
+        if (e0 + 4 * G < len) load_entries(e0 + 4 * G, cn, rn);   // of the next group, while the rows arrive
+#pragma unroll
+        for (int d = 0; d < G; ++d) {
+            const bool ok = e0 + 4 * d + kq < len;
+            float dot = 0.f;
+#pragma unroll
+            for (int q = 0; q < NT; ++q) dot = fmaf(xr[q], g[d][q], dot);
+            dot = rowsum16(dot);
+            if constexpr (MODE == kImplicit) {
+                const double rp = r[d] > 0.f ? (double)r[d] : 0.0, dd = (double)dot;
+                const double pe = (r[d] > 0.f ? 1.0 : 0.0) - dd;
+                if (ok && i == 0) acc += (1.0 + (double)alpha * rp) * pe * pe - dd * dd;
+            } else {
+                const float err = r[d] - dot;
+                if (ok && i == 0) acc += (double)err * (double)err;
+            }
         }
     }
     acc += __shfl_xor(acc, 16);

@@ -198,6 +198,47 @@ __device__ __forceinline__ float widen_hi(uint32_t w) {   // high 16 bits of w
     else return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16));
 }
 
+// The features of lane i (register q: feature_of(F, q, i), filler lanes 0) of row c of the factor matrix, as fp32, with
+// the widest loads the feature map allows and a 64-bit row address.  For the kernels that keep gathered rows as
+// plain fp32 registers (Algorithm 1 on the gathered rows, the RMSE).
+template <int F, int ET>
+__device__ __forceinline__ void gather_lane_features(const void *__restrict__ Theta, int c, int i, float (&g)[tiles_1d(F)]) {
+    constexpr int NT = tiles_1d(F), N4 = loads16(F), N2 = loads8(F), N1 = loads4(F);
+    static_assert(4 * N4 + 2 * N2 + N1 == NT);
+    constexpr int ES = ET == ALS_F32 ? 4 : 2;
+    const char *row = reinterpret_cast<const char *>(Theta) + (int64_t)c * (F * ES);
+#pragma unroll
+    for (int q = 0; q < N4; ++q) {   // features 64q + 4i .. + 3
+        if constexpr (ET == ALS_F32) {
+            const v4f v = *reinterpret_cast<const v4f *>(row + 4 * (64 * q + 4 * i));
+            g[4 * q] = v[0]; g[4 * q + 1] = v[1]; g[4 * q + 2] = v[2]; g[4 * q + 3] = v[3];
+        } else {
+            const uint2 w = *reinterpret_cast<const uint2 *>(row + 2 * (64 * q + 4 * i));
+            g[4 * q] = widen_lo<ET>(w.x); g[4 * q + 1] = widen_hi<ET>(w.x);
+            g[4 * q + 2] = widen_lo<ET>(w.y); g[4 * q + 3] = widen_hi<ET>(w.y);
+        }
+    }
+    if constexpr (N2 > 0) {          // features 64 N4 + 2i, + 1
+        if constexpr (ET == ALS_F32) {
+            const float2 v = *reinterpret_cast<const float2 *>(row + 4 * (64 * N4 + 2 * i));
+            g[4 * N4] = v.x; g[4 * N4 + 1] = v.y;
+        } else {
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(row + 2 * (64 * N4 + 2 * i));
+            g[4 * N4] = widen_lo<ET>(w); g[4 * N4 + 1] = widen_hi<ET>(w);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < N1; ++k) {   // feature 64 N4 + 32 N2 + 16k + i, if there is one
+        const int ft = 64 * N4 + 32 * N2 + 16 * k + i;
+        float v = 0.f;
+        if (ft < F) {
+            if constexpr (ET == ALS_F32) v = *reinterpret_cast<const float *>(row + 4 * ft);
+            else v = widen_lo<ET>((uint32_t)*reinterpret_cast<const unsigned short *>(row + 2 * ft));
+        }
+        g[4 * N4 + 2 * N2 + k] = v;
+    }
+}
+
 // ROWS: the wavefront accumulates the tile rows of this set only (acc[tiles_below(ROWS, R) + C]); the
 // default is the whole triangle.  WANT_B: also produce b_u, for the tile rows of the set.
 // MODE: kExplicit as described above.  kImplicit (Section 5.6): the entry (u, v) enters A_u with weight
