@@ -29,14 +29,20 @@ def _matrix(rng, n, m, chunk, implicit):
     return deg, ptr, idx, val
 
 
-@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
 def test_random_half_sweeps(seed):
     import paper_1808_03843_amd as P
     rng = np.random.default_rng(seed)
+    # seeds from 3 on also draw the routes of fp32 factors through 16-bit parts and the switch that sends rows with
+    # fewer than 64 entries through get_hermitian (the earlier seeds keep their cases)
+    wide_choice = seed >= 3
     for case in range(60):
         f = int(rng.choice([16, 32, 64, 100, 128, 256]))
         solver = int(rng.choice([P.SOLVER_CG, P.SOLVER_CHOLESKY]))
-        dt = str(rng.choice(["f32", "f32", "bf16", "f16"]))
+        dt = str(rng.choice(["f32", "f32x3", "f32x2", "bf16", "f16"] if wide_choice else ["f32", "f32", "bf16", "f16"]))
+        if dt in ("f32x3", "f32x2") and f == 256:
+            dt = "f32"   # those routes exist for f <= 128
+        dense_short = bool(wide_choice and rng.random() < 0.3)
         chunk = int(rng.choice([64, 128, 256, 1024, 4096]))
         implicit = dt == "f32" and rng.random() < 0.3
         herm16 = (not implicit) and solver == P.SOLVER_CG and rng.random() < 0.2 and (f != 256 or dt == "f32")
@@ -49,15 +55,17 @@ def test_random_half_sweeps(seed):
         batch = int(rng.choice([0, 8, 64]))
         deg, ptr, idx, val = _matrix(rng, n, m, chunk, implicit)
         tag = (f"seed {seed} case {case}: f={f} solver={solver} {dt} chunk={chunk} implicit={implicit} bf16 slots={herm16} "
+               f"dense_short_rows={dense_short} "
                f"ptr64={p64} n={n} m={m} lambda={lam} f_s={fs} batch_slots={batch} max degree {deg.max()}")
         print(tag, flush=True)
         Theta = W.random_factors(n, f, seed=1000 * seed + case, scale=0.3)
         warm = W.random_factors(m, f, seed=1000 * seed + case + 500, scale=0.05)
-        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[dt]
+        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16),
+                     "f32x3": (torch.float32, P.F32X3), "f32x2": (torch.float32, P.F32X2)}[dt]
         Td = torch.from_numpy(Theta).cuda().to(tdt)
         Th = Td.to(torch.float32).cpu().numpy()
         als = P.Als(f, solver=solver, cg_iters=fs, chunk=chunk, batch_slots=batch, factor_dtype=code,
-                    herm_dtype=P.BF16 if herm16 else P.F32)
+                    herm_dtype=P.BF16 if herm16 else P.F32, dense_short_rows=dense_short)
         sp = P.SparseMatrix.from_host(m, n, ptr, idx, val, ptr64=p64)
         als.check_matrix(sp)
         X = torch.from_numpy(warm.copy()).cuda()
@@ -94,7 +102,8 @@ def test_random_side_entry_points():
         print(tag, flush=True)
         Theta = W.random_factors(n, f, seed=case + 1, scale=0.3)
         Xf = W.random_factors(m, f, seed=case + 77, scale=0.3)
-        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16)}[dt]
+        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16),
+                     "f32x3": (torch.float32, P.F32X3), "f32x2": (torch.float32, P.F32X2)}[dt]
         Td = torch.from_numpy(Theta).cuda().to(tdt)
         Th = Td.to(torch.float32).cpu().numpy()
         als = P.Als(f, chunk=chunk, factor_dtype=code)
