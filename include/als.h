@@ -144,7 +144,9 @@ const char *als_last_error(const als_ctx *ctx);
 /* "Update X" (eq. (2)): for every row u of csr, builds A_u, b_u from Theta
  * (DEVICE, ncols x f, config's factor_dtype) and writes x_u into X (DEVICE,
  * nrows x f float).  With ALS_SOLVER_CG, X is also an input: row u of X is the
- * warm start of Algorithm 1.  Rows with n_u = 0 get x_u = 0.  f must equal the
+ * warm start of Algorithm 1 (rows with fewer than 64 entries then run it on
+ * their gathered theta_v without forming A_u, unless dense_short_rows is set:
+ * see als_config).  Rows with n_u = 0 get x_u = 0.  f must equal the
  * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD).
  * The first call on a matrix (identified by its ptr, nrows, nnz) builds its work plan and sizes the work
  * buffers: it waits for the stream and, without a caller's workspace, allocates.  Later calls on the same matrix
