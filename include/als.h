@@ -115,7 +115,7 @@ typedef struct als_config {
     size_t workspace_bytes;
     int64_t workspace_max_rows;
     int64_t workspace_max_nnz;
-    int32_t dense_short_rows; /* 0 (default): with ALS_SOLVER_CG, explicit feedback and f <= 128, rows with fewer than
+    int32_t dense_short_rows; /* 0 (default): with ALS_SOLVER_CG and explicit feedback, rows with fewer than
                                  64 stored entries run Algorithm 1 on the gathered theta_v themselves,
                                  A_u p = G^T (G p) + lambda n_u p, and never form A_u (2 n_u f instead of f^2
                                  multiply-adds per product, no get_hermitian; the iterates differ from the dense

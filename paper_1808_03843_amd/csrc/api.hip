@@ -524,16 +524,17 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
             }
         }
     }
-    // Algorithm 1, explicit feedback, one-wavefront widths: rows with fewer than 64 entries (classes below 7, the tail
-    // of perm) iterate on the gathered rows themselves and never form A_u (cg_short.hip)
-    if (cg && !implicit && one_wave && !ctx->cfg.dense_short_rows) {
+    // Algorithm 1, explicit feedback: rows with fewer than 64 entries (classes below 7, the tail of perm) iterate on
+    // the gathered rows themselves and never form A_u (cg_short.hip)
+    if (cg && !implicit && !ctx->cfg.dense_short_rows) {
         const int et = fp32_in_memory(ctx->cfg.factor_dtype) ? ALS_F32 : ctx->cfg.factor_dtype;
-        // one launch per group of classes, shortest rows first: fewer than 16, 32, 64 entries as 4, 2, 1 rows per wavefront
-        for (int c = 5; c <= 7; ++c) {
+        // one launch per group of classes, shortest rows first: fewer than 16, 32, 64 entries as 4, 2, 1 rows per
+        // wavefront (f = 256: one row per pair of wavefronts throughout)
+        for (int c = one_wave ? 5 : 7; c <= 7; ++c) {
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
             if (lo < fused_end) {
                 Timed t(ctx, ALS_K_SHORT);
-                rc = in_pieces(lo, fused_end - lo, max_workgroups(64), [&](int64_t pos0, int64_t npos) {
+                rc = in_pieces(lo, fused_end - lo, max_workgroups(one_wave ? 64 : 128), [&](int64_t pos0, int64_t npos) {
                     HIP_TRY(ctx, launch_cg_gathered(f, 1 << (7 - c), p64, et, ctx->stream, p->perm, pos0, npos, a->ptr, a->idx,
                                                     a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
                     return (int)ALS_OK;

@@ -20,25 +20,35 @@ namespace als {
 
 constexpr int kShortSteps = 16;   // steps the registers of a wavefront hold
 
-template <int F, typename PtrT, int ET>
-__global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
-                                                    const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
-                                                    const float *__restrict__ val, const void *__restrict__ Theta,
-                                                    float lambda, int fs, float eps, float *__restrict__ Xout,
-                                                    int *__restrict__ status) {
-    constexpr int NT = tiles_1d(F), NJ = kShortSteps;
-    const int lane = threadIdx.x, i = lane & 15, kq = lane >> 4;
+// W: wavefronts that share a row (1; 2 at f = 256, where the 64 entries of a row are 256 registers per lane).  The
+// entries are dealt out in blocks of 64 / W; every wavefront holds all vectors and runs the whole iteration, and
+// the partial sums of G^T t meet through LDS: one barrier per product (two buffers used in turn -- a wavefront can
+// only reach the write of product k+2 after every wavefront has passed the barrier of product k+1, i.e. has finished
+// reading the buffer of product k).  The sums are formed in the same order everywhere, so the wavefronts of a row
+// hold identical vectors and take the same branches.
+template <int F, typename PtrT, int ET, int W>
+__global__ __launch_bounds__(64 * W) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
+                                                        const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
+                                                        const float *__restrict__ val, const void *__restrict__ Theta,
+                                                        float lambda, int fs, float eps, float *__restrict__ Xout,
+                                                        int *__restrict__ status) {
+    static_assert(W == 1 || W == 2);
+    constexpr int NT = tiles_1d(F), NJ = kShortSteps / W, CAPW = 4 * NJ;   // steps and entries of one wavefront
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, i = lane & 15, kq = lane >> 4;
     const int row = perm[pos0 + blockIdx.x];
-    const int64_t s0 = (int64_t)ptr[row];
-    // fewer than 4 NJ by the caller's choice of rows; clamped so that a plan built from other row offsets cannot make
+    const int64_t r0 = (int64_t)ptr[row];
+    // fewer than 64 by the caller's choice of rows; clamped so that a plan built from other row offsets cannot make
     // the kernel read more than it holds
-    int n = (int)((int64_t)ptr[row + 1] - s0);
-    n = __builtin_amdgcn_readfirstlane(n < 0 ? 0 : (n > 4 * NJ ? 4 * NJ : n));
+    int nrow = (int)((int64_t)ptr[row + 1] - r0);
+    nrow = __builtin_amdgcn_readfirstlane(nrow < 0 ? 0 : (nrow > 4 * kShortSteps ? 4 * kShortSteps : nrow));
     float *xg = Xout + (int64_t)row * F;
-    if (n == 0) {
+    if (nrow == 0) {   // (the whole workgroup leaves here, before any barrier)
         store_zero_vec<F>(xg);
         return;
     }
+    // this wavefront's entries: CAPW * wv .. of the row
+    const int64_t s0 = r0 + CAPW * wv;
+    const int n = __builtin_amdgcn_readfirstlane(nrow - CAPW * wv < 0 ? 0 : (nrow - CAPW * wv > CAPW ? CAPW : nrow - CAPW * wv));
     const int nj = (n + 3) >> 2;   // steps that hold an entry
 
     // Column ids and ratings: lane l fetches those of entry l (one coalesced load each), then every lane picks up
@@ -46,7 +56,7 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
     // gathers below can all be in flight together (loads complete in order: a second round of id loads behind the
     // first gathers would wait for them).
     const bool mine = lane < n;
-    const int64_t at = s0 + (mine ? lane : 0);
+    const int64_t at = mine ? s0 + lane : r0;
     const int my_col = idx[at];                      // (entries beyond the end: the row's first column, masked below)
     const float my_r = mine ? val[at] : 0.f;
     // the gathered rows and their ratings; entries beyond the end count as zero rows
@@ -76,24 +86,47 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
         }
     }
 
+    // Sum of a per-lane partial vector over the four lane rows and, with W > 1, over the wavefronts of the row
+    __shared__ float xch[W > 1 ? 2 * W * 16 * NT : 1];
+    int buf = 0;
+    auto allsum = [&](float (&y)[NT]) {
+#pragma unroll
+        for (int q = 0; q < NT; ++q) y[q] = colsum4(y[q]);
+        if constexpr (W > 1) {
+            float *mine_out = xch + (buf * W + wv) * 16 * NT + i * NT;
+            if (kq == 0) {
+#pragma unroll
+                for (int q = 0; q < NT; ++q) mine_out[q] = y[q];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < NT; ++q) y[q] = 0.f;
+#pragma unroll
+            for (int k = 0; k < W; ++k) {   // the same order in every wavefront
+                const float *part = xch + (buf * W + k) * 16 * NT + i * NT;
+#pragma unroll
+                for (int q = 0; q < NT; ++q) y[q] += part[q];
+            }
+            buf ^= 1;
+        }
+    };
+
     // b_u = G^T r_u (get_bias, Section 2 step (i))
     float b[NT], x[NT];
     {
-        float s[NT];
 #pragma unroll
-        for (int q = 0; q < NT; ++q) s[q] = 0.f;
+        for (int q = 0; q < NT; ++q) b[q] = 0.f;
 #pragma unroll
         for (int j = 0; j < NJ; ++j)
             if (j < nj) {
 #pragma unroll
-                for (int q = 0; q < NT; ++q) s[q] = fmaf(rt[j], G[j][q], s[q]);
+                for (int q = 0; q < NT; ++q) b[q] = fmaf(rt[j], G[j][q], b[q]);
             }
-#pragma unroll
-        for (int q = 0; q < NT; ++q) b[q] = colsum4(s[q]);
+        allsum(b);
     }
     load_vec<F>(xg, x);   // warm start
 
-    const float reg = lambda * (float)n;
+    const float reg = lambda * (float)nrow;
     auto matvec = [&](const float (&p)[NT], float (&ap)[NT]) {
         float y[NT];
 #pragma unroll
@@ -115,8 +148,9 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
 #pragma unroll
                     for (int q = 0; q < NT; ++q) y[q] = fmaf(G[j0 + d][q], t[d], y[q]);
             }
+        allsum(y);
 #pragma unroll
-        for (int q = 0; q < NT; ++q) ap[q] = fmaf(reg, p[q], colsum4(y[q]));
+        for (int q = 0; q < NT; ++q) ap[q] = fmaf(reg, p[q], y[q]);
     };
     auto dot = [&](const float (&u)[NT], const float (&v)[NT]) {
         float s = 0.f;
@@ -153,7 +187,7 @@ __global__ __launch_bounds__(64) void k_cg_gathered(const int32_t *__restrict__ 
             rs_old = rs_new;
         }
     }
-    store_vec<F>(xg, x, status);
+    if (wv == 0) store_vec<F>(xg, x, status);
 }
 
 // The same for rows of fewer than 64 / R entries, R = 2 or 4 of them per wavefront: a row of a dozen entries leaves
@@ -322,11 +356,12 @@ template <int F, typename PtrT, int ROWS>
 static hipError_t cg_gathered_f(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
                                 const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
                                 float *Xout, int *status) {
-    const dim3 grid((unsigned)((npos + ROWS - 1) / ROWS)), block(64);
+    constexpr int W = F > 128 ? 2 : 1;   // wavefronts per row of the one-row kernel
+    const dim3 grid((unsigned)((npos + ROWS - 1) / ROWS)), block(ROWS == 1 ? 64 * W : 64);
 #define LAUNCH(E)                                                                                                           \
     if constexpr (ROWS == 1)                                                                                                \
-        hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, Theta, \
-                           lambda, fs, eps, Xout, status);                                                                  \
+        hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E, W>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val,     \
+                           Theta, lambda, fs, eps, Xout, status);                                                           \
     else                                                                                                                    \
         hipLaunchKernelGGL((k_cg_gathered_packed<F, PtrT, E, ROWS>), grid, block, 0, st, perm, pos0, pos0 + npos,           \
                            (const PtrT *)ptr, idx, val, Theta, lambda, fs, eps, Xout, status)
@@ -344,6 +379,9 @@ hipError_t launch_cg_gathered(int f, int rows_per_wave, bool ptr64, int et, hipS
 #define ARGS et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status
 #define CALL_P(FF, PP) \
     (rows_per_wave == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : rows_per_wave == 2 ? cg_gathered_f<FF, PP, 2>(ARGS) : cg_gathered_f<FF, PP, 1>(ARGS))
+    if (f == 256)   // one row per workgroup of two wavefronts only
+        return rows_per_wave != 1 ? hipErrorInvalidValue
+                                  : (ptr64 ? cg_gathered_f<256, int64_t, 1>(ARGS) : cg_gathered_f<256, int32_t, 1>(ARGS));
 #define CALL(FF) (ptr64 ? CALL_P(FF, int64_t) : CALL_P(FF, int32_t))
     switch (f) {
         case 16: return CALL(16);

@@ -38,8 +38,8 @@ def _matrix(seed, ncols):
     return degrees, ptr, idx, val
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16", "f32x3", "f32x2"])
-@pytest.mark.parametrize("f", [16, 32, 64, 100, 128])
+@pytest.mark.parametrize("f,dtype", [(f, d) for f in (16, 32, 64, 100, 128, 256) for d in ("f32", "bf16", "f16", "f32x3", "f32x2")
+                                     if f <= 128 or d in ("f32", "bf16", "f16")])   # (the routes through 16-bit parts: f <= 128)
 def test_short_rows_follow_double_precision_algorithm_1(P, f, dtype):
     ncols, lam = 900, 0.2
     degrees, ptr, idx, val = _matrix(100 + f, ncols)
