@@ -93,19 +93,21 @@ __global__ __launch_bounds__(64 * W) void k_cg_gathered(const int32_t *__restric
 #pragma unroll
         for (int q = 0; q < NT; ++q) y[q] = colsum4(y[q]);
         if constexpr (W > 1) {
-            float *mine_out = xch + (buf * W + wv) * 16 * NT + i * NT;
+            // (element (q, i) at q * 16 + i: the 16 lanes of a lane row touch consecutive words, the four lane rows
+            // read the same ones)
+            float *mine_out = xch + (buf * W + wv) * 16 * NT + i;
             if (kq == 0) {
 #pragma unroll
-                for (int q = 0; q < NT; ++q) mine_out[q] = y[q];
+                for (int q = 0; q < NT; ++q) mine_out[16 * q] = y[q];
             }
             __syncthreads();
 #pragma unroll
             for (int q = 0; q < NT; ++q) y[q] = 0.f;
 #pragma unroll
             for (int k = 0; k < W; ++k) {   // the same order in every wavefront
-                const float *part = xch + (buf * W + k) * 16 * NT + i * NT;
+                const float *part = xch + (buf * W + k) * 16 * NT + i;
 #pragma unroll
-                for (int q = 0; q < NT; ++q) y[q] += part[q];
+                for (int q = 0; q < NT; ++q) y[q] += part[16 * q];
             }
             buf ^= 1;
         }
