@@ -256,6 +256,35 @@ def test_index_work_is_bit_exact(P):
         als.close()
 
 
+@pytest.mark.parametrize("ncols", [1, 2, 2048, 2049, 70_000, 5_000_000, 40_000_000])
+def test_csr_to_csc_over_the_digit_widths_of_the_column_ids(P, ncols):
+    """The transpose is a radix sort of the column ids in one to three passes of up to 11 bits: column counts on both
+    sides of the 11-bit and 22-bit boundaries, heavy columns (every row hits column 0), empty rows, ties that must
+    keep their row order, against the oracle's transpose bit for bit."""
+    rng = np.random.default_rng(ncols % 1000 + 5)
+    m = 3000
+    deg = rng.integers(0, min(ncols, 40) + 1, m)
+    deg[rng.random(m) < 0.1] = 0
+    rows = []
+    for d in deg:
+        c = rng.choice(ncols, d, replace=False) if ncols <= 100_000 else np.unique(rng.integers(0, ncols, d))
+        if d > 0 and rng.random() < 0.7:
+            c = np.unique(np.concatenate([[0, ncols - 1], c]))   # two columns that most rows share
+        rows.append(np.sort(c))
+    ptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])]).astype(np.int64)
+    idx = np.concatenate(rows + [np.zeros(0, np.int64)]).astype(np.int32)
+    val = rng.standard_normal(len(idx)).astype(np.float32)
+    als = P.Als(16)
+    for ptr64 in (False, True):
+        sp = P.SparseMatrix.from_host(m, ncols, ptr, idx, val, ptr64=ptr64)
+        t = als.csr_to_csc(sp)
+        cptr, cidx, cval = oracle.csr_to_csc(m, ncols, ptr, idx, val)
+        assert np.array_equal(t.ptr.cpu().numpy(), cptr)
+        assert np.array_equal(t.idx.cpu().numpy(), cidx)
+        assert np.array_equal(t.val.cpu().numpy(), cval)
+    als.close()
+
+
 def test_bad_arguments_are_errors_not_crashes(P):
     with pytest.raises(P.AlsError):
         P.Als(17)
