@@ -152,7 +152,8 @@ const char *als_last_error(const als_ctx *ctx);
  * buffers: it waits for the stream and, without a caller's workspace, allocates.  Later calls on the same matrix
  * only enqueue kernels on the context's stream (no allocation, no wait, no memset), so they may be captured in a
  * HIP graph; the same holds for als_update_cols and the implicit variants.  Errors found by the kernels (a non-positive pivot, a
- * non-finite solution) are reported by the next als_synchronize. */
+ * non-finite solution) are reported by the next als_synchronize.  A row whose A_u, b_u or warm start is not finite (a NaN or
+ * an overflow in the gathered factor) gets NaN with ALS_SOLVER_CG and is reported the same way. */
 int als_update_rows(als_ctx *ctx, const als_sparse *csr, const void *Theta, float lambda, int f, float *X);
 
 /* "Update Theta" (eq. (3)): the same computation with csc = compressed columns

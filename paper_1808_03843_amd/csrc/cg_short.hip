@@ -170,7 +170,11 @@ __global__ __launch_bounds__(64 * W) void k_cg_gathered(const int32_t *__restric
         p[q] = r[q];
     }
     float rs_old = dot(r, r);
-    if (rs_old > 0.f) {
+    if (rs_old != 0.f && !(rs_old > 0.f && isfinite(rs_old))) {   // non-finite input: the row gets NaN, reported by the store
+#pragma unroll
+        for (int q = 0; q < NT; ++q) x[q] = __builtin_nanf("");
+    }
+    if (rs_old > 0.f && isfinite(rs_old)) {
         for (int it = 0; it < fs; ++it) {
             matvec(p, ap);
             const float pap = dot(p, ap);
@@ -322,7 +326,11 @@ __global__ __launch_bounds__(64) void k_cg_gathered_packed(const int32_t *__rest
         p[q] = r[q];
     }
     float rs_old = dot(r, r);
-    bool live = n > 0 && rs_old > 0.f;
+    bool live = n > 0 && rs_old > 0.f && isfinite(rs_old);
+    if (n > 0 && !live && rs_old != 0.f) {   // non-finite input: the row gets NaN, reported by the store
+#pragma unroll
+        for (int q = 0; q < NT; ++q) x[q] = __builtin_nanf("");
+    }
     for (int it = 0; it < fs; ++it) {
         if (__ballot(live) == 0ull) break;
         matvec(p, ap);

@@ -617,7 +617,15 @@ __device__ __forceinline__ void cg_tiles(const v4f (&acc)[tiles_tri(F)], const f
         p[q] = r[q];
     }
     float rs_old = dot(r, r);
-    if (!(rs_old > 0.f)) return;
+    if (!(rs_old > 0.f) || !isfinite(rs_old)) {
+        // r = 0: x solves the system already.  Anything else here is a non-finite A_u, b_u or warm start: the row
+        // gets that value instead of silently keeping its warm start, and the store reports it
+        if (rs_old != 0.f) {
+#pragma unroll
+            for (int q = 0; q < NT; ++q) x[q] = __builtin_nanf("");   // NaN
+        }
+        return;
+    }
     for (int it = 0; it < fs; ++it) {
         matvec(p, ap);
         const float pap = dot(p, ap);

@@ -111,7 +111,8 @@ __device__ __forceinline__ void cg_wide(const v4f (&acc)[tiles_tri(F) / NW], Wid
     float r = own ? bsrc[tid] - ax : 0.f;
     float p = r;
     float rs_old = wide_sum<NW>(r * r, sh.red, turn);
-    if (rs_old > 0.f) {
+    if (rs_old != 0.f && !(rs_old > 0.f && isfinite(rs_old))) x = __builtin_nanf("");   // non-finite input: NaN, reported below
+    if (rs_old > 0.f && isfinite(rs_old)) {
         for (int it = 0; it < fs; ++it) {
             const float ap = matvec(p);
             const float pap = wide_sum<NW>(p * ap, sh.red, turn);

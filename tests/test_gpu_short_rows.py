@@ -98,3 +98,34 @@ def test_short_rows_in_a_whole_cg_run_match_the_dense_route(P):
     print(f"mid_small CG(6): rmse {rm[False]:.6f} (short rows on their gathered rows), {rm[True]:.6f} (every row builds A_u), "
           f"exact oracle {hist[-1]['rmse']:.6f}")
     assert abs(rm[False] - rm[True]) <= 1e-4 and abs(rm[False] - hist[-1]["rmse"]) <= 2e-3
+
+
+@pytest.mark.parametrize("solver", ["cg", "cholesky"])
+def test_a_non_finite_factor_entry_is_reported_by_every_route(P, solver):
+    """A NaN in one factor row reaches rows of every length (short rows on their gathered rows, fused rows, split rows):
+    the next als_synchronize reports ALS_ENUMERIC, the rows that do not gather it are unharmed."""
+    f, ncols, lam = 100, 600, 0.2
+    degrees, ptr, idx, val = _matrix(3, ncols)
+    degrees = np.concatenate([degrees, [500]])                       # one row that is split at chunk = 256
+    rng = np.random.default_rng(8)
+    idx = np.concatenate([idx, np.sort(rng.choice(ncols, 500, replace=False)).astype(np.int32)])
+    val = np.concatenate([val, rng.integers(1, 6, 500).astype(np.float32)])
+    ptr = np.concatenate([[0], np.cumsum(degrees)]).astype(np.int64)
+    Theta = W.random_factors(ncols, f, seed=2, scale=0.4)
+    bad_col = 17
+    Theta[bad_col, 5] = np.nan
+    warm = W.random_factors(len(degrees), f, seed=4, scale=0.05)
+    hit = np.array([bad_col in idx[ptr[u]:ptr[u + 1]] for u in range(len(degrees))])
+    assert hit[degrees < 64].any() and hit[(degrees >= 64) & (degrees < 256)].any() and hit[-1]
+    als = P.Als(f, solver=P.SOLVER_CG if solver == "cg" else P.SOLVER_CHOLESKY, cg_iters=6, chunk=256)
+    sp = P.SparseMatrix.from_host(len(degrees), ncols, ptr, idx, val)
+    X = _dev(warm.copy())
+    als.update_rows(sp, _dev(Theta), lam, X)
+    with pytest.raises(P.AlsError) as info:
+        als.synchronize()
+    assert info.value.code == P.ALS_ENUMERIC
+    got = X.cpu().numpy()
+    clean = (~hit) & (degrees > 0)
+    assert np.isfinite(got[clean]).all() and not np.isfinite(got[hit]).all(axis=1).any()
+    als.synchronize()          # the report clears the status word
+    als.close()
