@@ -69,6 +69,7 @@ typedef struct als_sparse {
     const float *val;   /* nnz ratings                                                 */
 } als_sparse;
 
+/* Zero the whole struct first (memset or = {0}) and then set fields: 0 is the default of every optional field. */
 typedef struct als_config {
     int32_t f;            /* number of latent features; supported: 16, 32, 64, 100, 128, 256            */
     int32_t solver;       /* ALS_SOLVER_*                                                                */
