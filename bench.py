@@ -220,10 +220,11 @@ def main():
     deg_c = np.bincount(a.idx, minlength=w.n)
     nnz_fit = int(a.nnz)   # entries the factors are fitted on (all of them unless --test-frac)
     nnz_slot = int(deg_r[deg_r >= chunk].sum() + deg_c[deg_c >= chunk].sum()) if (fused_n > 0 or short_n > 0) else 2 * nnz_fit
-    # rows with fewer than 64 entries run Algorithm 1 on their gathered rows and never form A_u (k_cg_gathered): their
+    # short rows run Algorithm 1 on their gathered rows and never form A_u (k_cg_gathered): their
     # entries are no get_hermitian work and are left out of its flops
-    short_rows = int((deg_r < 64).sum() + (deg_c < 64).sum()) if short_n > 0 else 0
-    nnz_short = int(deg_r[deg_r < 64].sum() + deg_c[deg_c < 64].sum()) if short_n > 0 else 0
+    short_limit = als.short_row_limit()   # 64, or 128 on the fp32 MFMA path at f = 100 / 128; 0: no such rows
+    short_rows = int((deg_r < short_limit).sum() + (deg_c < short_limit).sum()) if short_n > 0 else 0
+    nnz_short = int(deg_r[deg_r < short_limit].sum() + deg_c[deg_c < short_limit].sum()) if short_n > 0 else 0
     per_entry = w.f * (w.f + 1)
     flops_sweep = (2.0 * nnz_fit - nnz_short) * per_entry
     herm_s = (herm_ms + fused_ms) * 1e-3 / K
@@ -248,7 +249,7 @@ def main():
         # Algorithm 1 on the gathered rows: per row (f_s + 1) products of 4 n_u f + 2 f flops and b_u (2 n_u f), on the
         # vector ALUs
         fl = (args.cg_iters + 1) * (4.0 * nnz_short * w.f + 2.0 * w.f * short_rows) + 2.0 * nnz_short * w.f
-        short = {"what": "Algorithm 1 on the gathered rows of rows with fewer than 64 entries, A_u never formed "
+        short = {"what": f"Algorithm 1 on the gathered rows of rows with fewer than {short_limit} entries, A_u never formed "
                          "(A_u p = G^T (G p) + lambda n_u p)", "bound": "alu", "ms_per_sweep": short_ms / K,
                  "launches_per_sweep": short_n // K, "rows_per_sweep": short_rows, "entries_per_sweep": nnz_short,
                  "systems_per_s": short_rows / (short_ms / K * 1e-3), "tflops": fl / (short_ms / K * 1e-3) / 1e12,

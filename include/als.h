@@ -117,7 +117,7 @@ typedef struct als_config {
     int64_t workspace_max_rows;
     int64_t workspace_max_nnz;
     int32_t dense_short_rows; /* 0 (default): with ALS_SOLVER_CG and explicit feedback, rows with fewer than
-                                 64 stored entries run Algorithm 1 on the gathered theta_v themselves,
+                                 64 stored entries (128: see als_short_row_limit) run Algorithm 1 on the gathered theta_v themselves,
                                  A_u p = G^T (G p) + lambda n_u p, and never form A_u (2 n_u f instead of f^2
                                  multiply-adds per product, no get_hermitian; the iterates differ from the dense
                                  ones by rounding order only).  1: every row builds A_u, as in the paper         */
@@ -145,7 +145,7 @@ const char *als_last_error(const als_ctx *ctx);
 /* "Update X" (eq. (2)): for every row u of csr, builds A_u, b_u from Theta
  * (DEVICE, ncols x f, config's factor_dtype) and writes x_u into X (DEVICE,
  * nrows x f float).  With ALS_SOLVER_CG, X is also an input: row u of X is the
- * warm start of Algorithm 1 (rows with fewer than 64 entries then run it on
+ * warm start of Algorithm 1 (rows with fewer than 64 or 128 entries then run it on
  * their gathered theta_v without forming A_u, unless dense_short_rows is set:
  * see als_config).  Rows with n_u = 0 get x_u = 0.  f must equal the
  * config's f; lambda >= 0 (lambda > 0 or n_u >= f is needed for A_u to be SPD).
@@ -251,6 +251,12 @@ int als_check_matrix(als_ctx *ctx, const als_sparse *a);
 #define ALS_PEAK_MFMA_F16 2  /* v_mfma_f32_16x16x32_f16  */
 #define ALS_PEAK_COPY 3
 int als_measure_peak(als_ctx *ctx, int what, double *rate_out);
+
+/* Rows (of als_update_rows / als_update_cols, explicit feedback) with fewer stored entries than the value returned run
+ * Algorithm 1 on their gathered theta_v and never form A_u (see dense_short_rows in als_config): 64, or 128 with
+ * ALS_F32 factors at f = 100 and f = 128; 0 when no row does (exact solver, dense_short_rows = 1, NULL).  For
+ * callers that account for get_hermitian work. */
+int als_short_row_limit(const als_ctx *ctx);
 
 /* Forgets the cached work plans (waits for the stream first).  A plan is keyed on a matrix's ptr address, nrows
  * and nnz and holds its degree classes and work items, so the arrays of a matrix must stay unchanged between

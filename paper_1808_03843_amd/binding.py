@@ -24,7 +24,7 @@ EXPORTS = [
     "als_create", "als_destroy", "als_last_error", "als_update_rows", "als_update_cols", "als_rmse",
     "als_hermitian", "als_bin_rows", "als_csr_to_csc", "als_synchronize", "als_kernel_time",
     "als_profile_reset", "als_drop_plans", "als_check_matrix", "als_measure_peak", "als_update_rows_implicit", "als_update_cols_implicit", "als_implicit_loss", "als_gram",
-    "als_gram_static", "als_workspace_bytes",
+    "als_gram_static", "als_workspace_bytes", "als_short_row_limit",
 ]
 
 
@@ -74,6 +74,7 @@ def _declare(lib: ctypes.CDLL) -> ctypes.CDLL:
     lib.als_drop_plans.argtypes = [vp]
     lib.als_check_matrix.argtypes = [vp, sp]
     lib.als_measure_peak.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
+    lib.als_short_row_limit.argtypes = [vp]
     return lib
 
 
@@ -279,6 +280,10 @@ class Als:
     def check_matrix(self, sp: "SparseMatrix"):
         """Raise AlsError unless ptr, the range of the column ids and their order inside every row are sound."""
         self._check(self._lib.als_check_matrix(self._ctx, ctypes.byref(sp.desc)))
+
+    def short_row_limit(self) -> int:
+        """Rows with fewer stored entries than this run Algorithm 1 on their gathered rows (0: none)."""
+        return int(self._lib.als_short_row_limit(self._ctx))
 
     def measure_peak(self, what: int) -> float:
         """Sustained rate of the device: what = 0 / 1 / 2 MFMA fp32 / bf16 / fp16 (flop/s), 3 streaming copy (B/s)."""

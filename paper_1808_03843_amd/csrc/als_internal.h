@@ -121,8 +121,8 @@ hipError_t launch_hermitian_cg_x2(int f, bool ptr64, bool wide, int solver, hipS
 
 // cg_short.hip: Algorithm 1 on the gathered rows themselves (A_u p = G^T (G p) + lambda n_u p), one wavefront per
 // row, or 2 or 4 rows per wavefront, for the rows perm[pos0 .. pos0+npos) which must have fewer than
-// 64 / rows_per_wave entries (f = 256: rows_per_wave = 1, two wavefronts per row).  et: ALS_F32 / ALS_BF16 / ALS_F16,
-// the element type in memory
+// 64 / rows_per_wave entries (f = 256: rows_per_wave = 1, two wavefronts per row); rows_per_wave = -2 (f <= 128): two
+// wavefronts per row, fewer than 128 entries.  et: ALS_F32 / ALS_BF16 / ALS_F16, the element type in memory
 hipError_t launch_cg_gathered(int f, int rows_per_wave, bool ptr64, int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos,
                               const void *ptr, const int32_t *idx, const float *val, const void *Theta, float lambda,
                               int fs, float eps, float *Xout, int *status);

@@ -78,6 +78,15 @@ constexpr bool kTaskOrder = ALS_TASK_ORDER != 0;   // band order of the work ite
 #endif
 constexpr bool kDualExact = ALS_DUAL_EXACT != 0;   // dual-form exact solve of rows with n_u < f (dual.hip)
 
+// Rows with fewer stored entries than this run Algorithm 1 on their gathered rows (cg_short.hip) instead of building
+// A_u; 0: no row does.  64 entries fit the registers of one wavefront (two at f = 256).  On the fp32 MFMA path at
+// f >= 100, where building A_u is the expensive part, rows of 64 .. 127 entries go the same way with two wavefronts
+// per row (Mid shape: 19.1 -> 18.7 ms per sweep; with 16-bit matrix cores or a narrower A_u the dense route is as fast).
+int short_row_limit(const als_config &c) {
+    if (c.solver != ALS_SOLVER_CG || c.dense_short_rows) return 0;
+    return (c.factor_dtype == ALS_F32 && (c.f == 100 || c.f == 128)) ? 128 : 64;
+}
+
 struct TimedLaunch { hipEvent_t a, b; int kernel; };
 }  // namespace
 
@@ -530,12 +539,14 @@ int update(als_ctx *ctx, const als_sparse *a, const void *G, float lambda, int f
         const int et = fp32_in_memory(ctx->cfg.factor_dtype) ? ALS_F32 : ctx->cfg.factor_dtype;
         // one launch per group of classes, shortest rows first: fewer than 16, 32, 64 entries as 4, 2, 1 rows per
         // wavefront (f = 256: one row per pair of wavefronts throughout)
-        for (int c = one_wave ? 5 : 7; c <= 7; ++c) {
+        // c = 8: rows of 64 .. 127 entries, two wavefronts per row, where short_row_limit says so
+        const int cmax = short_row_limit(ctx->cfg) > 64 ? 8 : 7;
+        for (int c = one_wave ? 5 : 7; c <= cmax; ++c) {
             const int64_t lo = p->rows_ge[c] > slot_rows ? p->rows_ge[c] : slot_rows;
             if (lo < fused_end) {
                 Timed t(ctx, ALS_K_SHORT);
-                rc = in_pieces(lo, fused_end - lo, max_workgroups(one_wave ? 64 : 128), [&](int64_t pos0, int64_t npos) {
-                    HIP_TRY(ctx, launch_cg_gathered(f, 1 << (7 - c), p64, et, ctx->stream, p->perm, pos0, npos, a->ptr, a->idx,
+                rc = in_pieces(lo, fused_end - lo, max_workgroups(128), [&](int64_t pos0, int64_t npos) {
+                    HIP_TRY(ctx, launch_cg_gathered(f, c == 8 ? -2 : 1 << (7 - c), p64, et, ctx->stream, p->perm, pos0, npos, a->ptr, a->idx,
                                                     a->val, G, lambda, ctx->cfg.cg_iters, ctx->cfg.cg_eps, Out, ctx->status));
                     return (int)ALS_OK;
                 });
@@ -1134,6 +1145,8 @@ int als_drop_plans(als_ctx *ctx) {
 int als_check_matrix(als_ctx *ctx, const als_sparse *a) {
     return guarded(ctx, [&] { return als_check_matrix_impl(ctx, a); });
 }
+
+int als_short_row_limit(const als_ctx *ctx) { return ctx ? short_row_limit(ctx->cfg) : 0; }
 
 int als_measure_peak(als_ctx *ctx, int what, double *rate_out) {
     return guarded(ctx, [&] { return als_measure_peak_impl(ctx, what, rate_out); });

@@ -26,21 +26,22 @@ constexpr int kShortSteps = 16;   // steps the registers of a wavefront hold
 // only reach the write of product k+2 after every wavefront has passed the barrier of product k+1, i.e. has finished
 // reading the buffer of product k).  The sums are formed in the same order everywhere, so the wavefronts of a row
 // hold identical vectors and take the same branches.
-template <int F, typename PtrT, int ET, int W>
+// NJ: steps of 4 entries one wavefront holds (16; 8 at f = 256): rows of fewer than 4 NJ W entries.
+template <int F, typename PtrT, int ET, int W, int NJ>
 __global__ __launch_bounds__(64 * W) void k_cg_gathered(const int32_t *__restrict__ perm, int64_t pos0,
                                                         const PtrT *__restrict__ ptr, const int32_t *__restrict__ idx,
                                                         const float *__restrict__ val, const void *__restrict__ Theta,
                                                         float lambda, int fs, float eps, float *__restrict__ Xout,
                                                         int *__restrict__ status) {
     static_assert(W == 1 || W == 2);
-    constexpr int NT = tiles_1d(F), NJ = kShortSteps / W, CAPW = 4 * NJ;   // steps and entries of one wavefront
+    constexpr int NT = tiles_1d(F), CAPW = 4 * NJ;   // entries of one wavefront
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, i = lane & 15, kq = lane >> 4;
     const int row = perm[pos0 + blockIdx.x];
     const int64_t r0 = (int64_t)ptr[row];
-    // fewer than 64 by the caller's choice of rows; clamped so that a plan built from other row offsets cannot make
-    // the kernel read more than it holds
+    // fewer than CAPW * W by the caller's choice of rows; clamped so that a plan built from other row offsets cannot
+    // make the kernel read more than it holds
     int nrow = (int)((int64_t)ptr[row + 1] - r0);
-    nrow = __builtin_amdgcn_readfirstlane(nrow < 0 ? 0 : (nrow > 4 * kShortSteps ? 4 * kShortSteps : nrow));
+    nrow = __builtin_amdgcn_readfirstlane(nrow < 0 ? 0 : (nrow > CAPW * W ? CAPW * W : nrow));
     float *xg = Xout + (int64_t)row * F;
     if (nrow == 0) {   // (the whole workgroup leaves here, before any barrier)
         store_zero_vec<F>(xg);
@@ -366,11 +367,14 @@ template <int F, typename PtrT, int ROWS>
 static hipError_t cg_gathered_f(int et, hipStream_t st, const int32_t *perm, int64_t pos0, int64_t npos, const void *ptr,
                                 const int32_t *idx, const float *val, const void *Theta, float lambda, int fs, float eps,
                                 float *Xout, int *status) {
-    constexpr int W = F > 128 ? 2 : 1;   // wavefronts per row of the one-row kernel
-    const dim3 grid((unsigned)((npos + ROWS - 1) / ROWS)), block(ROWS == 1 ? 64 * W : 64);
+    // ROWS: 4, 2, 1 rows per wavefront; -2: two wavefronts per row (rows of 64 .. 127 entries, f <= 128).  At f = 256 a
+    // wavefront holds 8 steps, so ROWS == 1 already means two wavefronts per row.
+    constexpr int W = (F > 128 || ROWS == -2) ? 2 : 1, NJ = F > 128 ? kShortSteps / 2 : kShortSteps;
+    constexpr int PER = ROWS > 0 ? ROWS : 1;
+    const dim3 grid((unsigned)((npos + PER - 1) / PER)), block(ROWS > 1 ? 64 : 64 * W);
 #define LAUNCH(E)                                                                                                           \
-    if constexpr (ROWS == 1)                                                                                                \
-        hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E, W>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val,     \
+    if constexpr (ROWS <= 1)                                                                                                \
+        hipLaunchKernelGGL((k_cg_gathered<F, PtrT, E, W, NJ>), grid, block, 0, st, perm, pos0, (const PtrT *)ptr, idx, val, \
                            Theta, lambda, fs, eps, Xout, status);                                                           \
     else                                                                                                                    \
         hipLaunchKernelGGL((k_cg_gathered_packed<F, PtrT, E, ROWS>), grid, block, 0, st, perm, pos0, pos0 + npos,           \
@@ -384,11 +388,13 @@ hipError_t launch_cg_gathered(int f, int rows_per_wave, bool ptr64, int et, hipS
                               int64_t npos, const void *ptr, const int32_t *idx, const float *val, const void *Theta,
                               float lambda, int fs, float eps, float *Xout, int *status) {
     if (npos <= 0) return hipSuccess;
-    if ((et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) || (rows_per_wave != 1 && rows_per_wave != 2 && rows_per_wave != 4))
+    if ((et != ALS_F32 && et != ALS_BF16 && et != ALS_F16) ||
+        (rows_per_wave != 1 && rows_per_wave != 2 && rows_per_wave != 4 && rows_per_wave != -2))
         return hipErrorInvalidValue;
 #define ARGS et, st, perm, pos0, npos, ptr, idx, val, Theta, lambda, fs, eps, Xout, status
 #define CALL_P(FF, PP) \
-    (rows_per_wave == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : rows_per_wave == 2 ? cg_gathered_f<FF, PP, 2>(ARGS) : cg_gathered_f<FF, PP, 1>(ARGS))
+    (rows_per_wave == 4 ? cg_gathered_f<FF, PP, 4>(ARGS) : rows_per_wave == 2 ? cg_gathered_f<FF, PP, 2>(ARGS)   \
+     : rows_per_wave == 1 ? cg_gathered_f<FF, PP, 1>(ARGS) : cg_gathered_f<FF, PP, -2>(ARGS))
     if (f == 256)   // one row per workgroup of two wavefronts only
         return rows_per_wave != 1 ? hipErrorInvalidValue
                                   : (ptr64 ? cg_gathered_f<256, int64_t, 1>(ARGS) : cg_gathered_f<256, int32_t, 1>(ARGS));

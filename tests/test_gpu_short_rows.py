@@ -1,5 +1,5 @@
-"""Rows with fewer than 64 stored entries under the CG solver: Algorithm 1 (Section 4.1) runs on the gathered theta_v
-themselves, A_u p = G^T (G p) + lambda n_u p, and A_u is never formed.  Same iteration as the dense route, so every row
+"""Rows with fewer than 64 stored entries (128 with fp32 factors at f = 100 and 128) under the CG solver: Algorithm 1
+(Section 4.1) runs on the gathered theta_v themselves, A_u p = G^T (G p) + lambda n_u p, and A_u is never formed.  Same iteration as the dense route, so every row
 is held to the double-precision Algorithm 1 of the oracle (same warm start, same f_s) at the bar of the dense route,
 and the two routes must agree to fp32 rounding."""
 import numpy as np
@@ -60,6 +60,7 @@ def test_short_rows_follow_double_precision_algorithm_1(P, f, dtype):
             als.synchronize()
             short_launches = als.kernel_time(P.K_SHORT)[1]
             assert (short_launches == 0) == dense
+            assert als.short_row_limit() == (0 if dense else 128 if (dtype == "f32" and f in (100, 128)) else 64)
             out[dense] = X.cpu().numpy()
             als.close()
         live = degrees > 0
