@@ -81,8 +81,8 @@ def cpu_baseline(w, a_host, stride):
 TRAFFIC_SOURCE = "profiles/k_hermitian_mid_f100_cg6_counters.txt"
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
     ("mid", 100, "cg", 6, "f32", 4096): {
-        "k_hermitian": ((3.281e5 + 1.042e7) * 2048 + (2.86e5 + 5.569e5) * 1024) / 2,
-        "k_hermitian_cg": ((2.319e6 + 3.544e6) * 2048 + (8.416e4 + 5012) * 1024) / 2,
+        "k_hermitian": ((3.282e5 + 1.043e7) * 2048 + (2.86e5 + 5.569e5) * 1024) / 2,
+        "k_hermitian_cg": ((1.937e6 + 3.546e6) * 2048 + (4.125e4 + 5012) * 1024) / 2,
     },
 }
 

@@ -139,7 +139,7 @@ class Als:
                  profile: bool = False, factor_dtype: int = F32, herm_dtype: int = F32,
                  workspace_rows: int = 0, workspace_nnz: int = 0, library: Optional[ctypes.CDLL] = None,
                  dense_short_rows: bool = False):
-        """dense_short_rows: rows with fewer than 64 entries also build A_u (see als_config in include/als.h).
+        """dense_short_rows: every row builds A_u, also the short ones (see als_config in include/als.h).
         workspace_rows / workspace_nnz > 0: the library works in a torch-allocated workspace sized for matrices of
         at most that many rows and stored entries, and allocates no device memory itself.
         library: another build of the library from load_library(path) (default: the in-tree build)."""
