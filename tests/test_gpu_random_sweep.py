@@ -49,9 +49,10 @@ def test_random_half_sweeps(seed):
         p64 = bool(rng.random() < 0.3)
         n, m = int(rng.integers(300, 6000)), int(rng.integers(20, 300))
         lam = float(rng.choice([0.05, 0.3, 1.0]))
-        # Algorithm 1 is compared row by row while it is still converging; on the well-conditioned implicit systems
-        # 40 iterations reach the exact solution, which is what the oracle has there
-        fs = 40 if implicit else int(rng.choice([3, 6]))
+        # Algorithm 1 is compared row by row while it is still converging, against the same iteration in double
+        # precision (with few columns Theta^T Theta is ill-conditioned and no fixed iteration count reaches the exact
+        # solution, so the exact oracle cannot be the reference of the implicit CG cases either)
+        fs = 6 if implicit else int(rng.choice([3, 6]))
         batch = int(rng.choice([0, 8, 64]))
         deg, ptr, idx, val = _matrix(rng, n, m, chunk, implicit)
         tag = (f"seed {seed} case {case}: f={f} solver={solver} {dt} chunk={chunk} implicit={implicit} bf16 slots={herm16} "
@@ -69,9 +70,19 @@ def test_random_half_sweeps(seed):
         sp = P.SparseMatrix.from_host(m, n, ptr, idx, val, ptr64=p64)
         als.check_matrix(sp)
         X = torch.from_numpy(warm.copy()).cuda()
-        if implicit:
+        rows = np.flatnonzero(deg > 0)
+        if implicit and solver == P.SOLVER_CHOLESKY:
             als.update_rows_implicit(sp, Td, lam, 2.0, X)
-            ref, tol = oracle.implicit_update_rows(ptr, idx, val, Th, lam, 2.0), (1e-4 if solver == P.SOLVER_CHOLESKY else 5e-3)
+            ref, tol = oracle.implicit_update_rows(ptr, idx, val, Th, lam, 2.0), 1e-4
+        elif implicit:
+            als.update_rows_implicit(sp, Td, lam, 2.0, X)
+            # the definition sums over every column: a sample of rows (shortest, longest, evenly spaced between)
+            rows = rows[np.argsort(deg[rows], kind="stable")]
+            rows = np.unique(rows[np.linspace(0, len(rows) - 1, min(len(rows), 8)).astype(np.int64)])
+            ref, tol = np.zeros((m, f)), 2e-3
+            for u in rows:
+                A, b = oracle.implicit_normal_eq(idx[ptr[u]:ptr[u + 1]], val[ptr[u]:ptr[u + 1]], Th, lam, 2.0)
+                ref[u], _ = oracle.cg(A, warm[u], b, fs)
         else:
             als.update_rows(sp, Td, lam, X)
             if solver == P.SOLVER_CHOLESKY:
@@ -81,10 +92,9 @@ def test_random_half_sweeps(seed):
         als.synchronize()
         got = X.cpu().numpy()
         als.close()
-        live = deg > 0
-        assert not got[~live].any(), tag
-        err = _rel(got[live], ref[live])
-        assert err.max() <= tol, (tag, float(err.max()), int(deg[live][err.argmax()]))
+        assert not got[deg == 0].any(), tag
+        err = _rel(got[rows], ref[rows])
+        assert err.max() <= tol, (tag, float(err.max()), int(deg[rows][err.argmax()]))
 
 
 def test_random_side_entry_points():
