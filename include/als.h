@@ -79,6 +79,10 @@ typedef struct als_config {
                              (Theta in als_update_rows, X in als_update_cols).  16-bit elements are multiplied
                              on the 16-bit matrix cores with fp32 accumulation (exact products, so the sums
                              are those of the widened values); solvers and the written factor stay fp32.
+                             The rating rides along as three 16-bit parts: exact to 2^-24 of it with ALS_BF16;
+                             with ALS_F16 to 2^-24 of max(|r_uv|, 1), the spacing of the smallest fp16 numbers
+                             being 2^-24 (ratings and counts of 1 and more, as in Sections 5.1 and 5.6, lose
+                             nothing; a rating of 0.02 carries a relative error of up to 3e-6 into b_u).
                              ALS_F32X3: the gathered matrix is fp32 as with ALS_F32, but get_hermitian and get_bias
                              run on the 16-bit matrix cores: every value is cut into three bf16 parts that add up
                              to it exactly, and a product is the sum of the six part products that matter (what is

@@ -12,7 +12,8 @@
 // repacked with one byte-permute per register.
 //
 // b_u rides along: the rating is split into three 16-bit parts (hi + mid + lo = the fp32 rating up to 2^-24, or
-// better).  When f is not a multiple of 16, three spare lanes of the last tile (features f, f+1, f+2 of the
+// better; fp16 parts cannot go below the spacing 2^-24 of the smallest fp16 numbers, so with fp16 factors that bound
+// is an absolute one for |r_uv| < 1).  When f is not a multiple of 16, three spare lanes of the last tile (features f, f+1, f+2 of the
 // padded row) carry them, so rows f .. f+2 of the accumulated matrix add up to b_u; they and the remaining
 // padding are zeroed at the end.  When f is a multiple of 16 there is no spare lane: the parts form an operand of
 // their own (lanes 0..2, the others zero) and one more row of NT tiles is accumulated, whose rows 0..2 add up to

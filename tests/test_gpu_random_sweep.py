@@ -127,7 +127,9 @@ def test_random_side_entry_points():
             Ao, bo = oracle.normal_eq(idx[s:e], val[s:e], Th, 0.07)
             d = np.sqrt(max(1, e - s))
             assert np.abs(A[k] - Ao).max() <= 2e-6 * max(np.abs(Ao).max(), 1e-30) * d, (tag, r0 + k)
-            assert np.abs(b[k] - bo).max() <= 2e-6 * max(np.abs(bo).max(), 1e-30) * d + 1e-30, (tag, r0 + k)
+            # (fp16 factors: the parts of a rating stop at the spacing 2^-24 of the smallest fp16 numbers)
+            floor = 2.0 ** -24 * np.abs(Th[idx[s:e]]).sum(0).max() if dt == "f16" and e > s else 0.0
+            assert np.abs(b[k] - bo).max() <= 2e-6 * max(np.abs(bo).max(), 1e-30) * d + floor + 1e-30, (tag, r0 + k)
             assert np.array_equal(A[k], A[k].T), (tag, r0 + k)
         perm, start = als.bin_rows(sp, 12)
         po, so = oracle.bin_rows(ptr, 12)
