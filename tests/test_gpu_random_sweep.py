@@ -97,6 +97,72 @@ def test_random_half_sweeps(seed):
         assert err.max() <= tol, (tag, float(err.max()), int(deg[rows][err.argmax()]))
 
 
+def _tailed_matrix(rng, n, m, mean, chunk):
+    """Heavy-tailed degrees (Pareto, as in the rating data sets of Section 5.1: most rows short, a few long), 5 % empty
+    rows, and rows planted at the boundaries of the kernels; no duplicate column in a row."""
+    deg = np.minimum(np.floor(rng.pareto(1.3, m) * mean * 0.4).astype(np.int64), n)
+    deg[rng.random(m) < 0.05] = 0
+    planted = [1, 15, 16, 31, 32, 63, 64, 65, 127, 128, 129, 255, 256, chunk - 1, chunk, chunk + 1, 3 * chunk + 2]
+    deg[rng.integers(0, m, 40)] = np.minimum(rng.choice(planted, 40), n)
+    ptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    idx = np.empty(int(ptr[-1]), np.int32)
+    perm = rng.permutation(n).astype(np.int32)
+    for u in np.flatnonzero(deg):   # a window of a fixed permutation of the columns, from a random start
+        idx[ptr[u]:ptr[u + 1]] = np.sort(perm[(int(rng.integers(0, n)) + np.arange(deg[u])) % n])
+    val = rng.integers(1, 6, int(ptr[-1])).astype(np.float32)
+    return deg, ptr, idx, val
+
+
+@pytest.mark.parametrize("block", [0, 1, 2, 3])
+def test_random_half_sweeps_over_thousands_of_rows(block):
+    """Thousands of rows with heavy-tailed degrees: many launches' worth of short rows (the packed and the two-wavefront
+    routes of Algorithm 1 on gathered rows), several batches of split rows, both entry points of the half-sweep."""
+    import paper_1808_03843_amd as P
+    for seed in range(10 * block, 10 * block + 10):
+        rng = np.random.default_rng(7000 + seed)
+        f = int(rng.choice([16, 32, 64, 100, 128, 256]))
+        solver = int(rng.choice([P.SOLVER_CG, P.SOLVER_CG, P.SOLVER_CHOLESKY]))
+        dt = str(rng.choice(["f32", "f32x3", "f32x2", "bf16", "f16"]))
+        if dt in ("f32x3", "f32x2") and f == 256:
+            dt = "f32"
+        dense_short = bool(rng.random() < 0.2)
+        chunk = int(rng.choice([64, 256, 1024, 4096]))
+        p64 = bool(rng.random() < 0.3)
+        n = int(rng.integers(200, 20000))
+        mean = float(rng.choice([3, 10, 30, 80, 200]))
+        m = int(min(30000, max(50, (150_000 if f == 256 else 600_000) / mean)))
+        deg, ptr, idx, val = _tailed_matrix(rng, n, m, mean, chunk)
+        lam, fs = float(rng.choice([0.05, 0.3])), int(rng.choice([3, 6]))
+        batch = int(rng.choice([0, 8, 64]))
+        cols = bool(rng.random() < 0.5)
+        tag = (f"seed {seed}: f={f} solver={solver} {dt} chunk={chunk} dense_short_rows={dense_short} ptr64={p64} n={n} m={m} "
+               f"entries={ptr[-1]} lambda={lam} f_s={fs} batch_slots={batch} {'update_cols' if cols else 'update_rows'} "
+               f"max degree {deg.max()}")
+        print(tag, flush=True)
+        Theta = W.random_factors(n, f, seed=seed, scale=0.3)
+        warm = W.random_factors(m, f, seed=seed + 500, scale=0.05)
+        tdt, code = {"f32": (torch.float32, P.F32), "bf16": (torch.bfloat16, P.BF16), "f16": (torch.float16, P.F16),
+                     "f32x3": (torch.float32, P.F32X3), "f32x2": (torch.float32, P.F32X2)}[dt]
+        Td = torch.from_numpy(Theta).cuda().to(tdt)
+        Th = Td.to(torch.float32).cpu().numpy()
+        als = P.Als(f, solver=solver, cg_iters=fs, chunk=chunk, batch_slots=batch, factor_dtype=code, dense_short_rows=dense_short)
+        sp = P.SparseMatrix.from_host(m, n, ptr, idx, val, ptr64=p64)
+        als.check_matrix(sp)
+        X = torch.from_numpy(warm.copy()).cuda()
+        (als.update_cols if cols else als.update_rows)(sp, Td, lam, X)   # the same operation under its two names
+        als.synchronize()
+        got = X.cpu().numpy()
+        als.close()
+        if solver == P.SOLVER_CHOLESKY:
+            ref, tol = oracle.update_rows(ptr, idx, val, Th, lam), 1e-4
+        else:
+            ref, tol = oracle.update_rows_cg(ptr, idx, val, Th, lam, warm, fs=fs), 2e-3
+        live = deg > 0
+        assert not got[~live].any(), tag
+        err = _rel(got[live], ref[live])
+        assert err.max() <= tol, (tag, float(err.max()), int(deg[live][err.argmax()]))
+
+
 def test_random_side_entry_points():
     import paper_1808_03843_amd as P
     rng = np.random.default_rng(5)
